@@ -1,0 +1,123 @@
+/*
+ * dmr_qlinear: the linear layer of a step routed by Dynamic Mixed-Precision Routing, for MI355X.
+ *
+ * The router of the paper picks, per decision step, which copy of the model serves the step
+ * (Sec. 3, Eq. 1): the bf16 high-precision copy or the low-precision copy whose Linear layers
+ * (all except lm_head, App. E "Per-cell configuration") hold 4-bit weights and take 16-bit
+ * activations (Sec. 5.1 "Experimental Models and Precision").  A step routed low calls
+ * dmr_qlinear_forward for each such layer, a step routed high calls dmr_qlinear_bf16_forward;
+ * their cost ratio is the T_high / T_low of the paper's cost model (Sec. 4.3, Eq. 9), and App. B
+ * locates that cost in streaming the weights from memory once per generated token.
+ *
+ * Quantised format at this boundary (the paper leaves it open; this is the build's reading):
+ *   qweight  uint32 [N][K/8]   code q[n][8i+j] (0..15) in bits [4j,4j+4) of word i of row n
+ *   scales   bf16   [N][K/g]   finite, > 0
+ *   zeros    bf16   [N][K/g]   an integer code 0..15 held in bf16
+ *   w^[n][k] = (q[n][k] - zeros[n][k/g]) * scales[n][k/g],   g = 128
+ *
+ * General conventions
+ *   - Every pointer named d_* is DEVICE memory owned by the caller; the library never allocates
+ *     or frees device memory.  Arrays are row-major and contiguous.  bf16 travels as uint16_t.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls enqueue work on
+ *     it and return without synchronising; buffers must stay valid until that work is done.
+ *   - Errors come back as a dmr_status_t; nothing throws or aborts.  All argument checks happen
+ *     before the first HIP call, so a rejected call has touched nothing.  A failed launch
+ *     returns DMR_ERR_HIP.
+ *   - Shapes: K % 128 == 0, N % 16 == 0, g == 128, M >= 0 (M == 0 is DMR_OK and launches
+ *     nothing).  Device pointers must be 16-byte aligned.  No bias, no activation function.
+ *   - Non-finite activations are outside the contract.
+ *   - Two calls that share an output or workspace buffer must not overlap in time.
+ */
+#ifndef DMR_QLINEAR_H
+#define DMR_QLINEAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dmr_qlinear dmr_qlinear_t; /* opaque, lives in host memory */
+
+typedef enum {
+    DMR_OK = 0,
+    DMR_ERR_NULL = 1,        /* a required pointer is NULL                              */
+    DMR_ERR_SHAPE = 2,       /* a dimension is negative, zero or not a permitted multiple */
+    DMR_ERR_ALIGN = 3,       /* a device pointer is not 16-byte aligned                  */
+    DMR_ERR_WORKSPACE = 4,   /* storage or workspace buffer smaller than the size query  */
+    DMR_ERR_UNSUPPORTED = 5, /* a valid request this build has no kernel for (g != 128)  */
+    DMR_ERR_HIP = 6          /* the HIP runtime refused a launch                         */
+} dmr_status_t;
+
+typedef enum {
+    DMR_OUT_BF16 = 0, /* y is bf16 [M][N], rounded to nearest even from the fp32 accumulator */
+    DMR_OUT_FP32 = 1  /* y is fp32 [M][N], the accumulator itself                            */
+} dmr_out_t;
+
+/* Bytes of device memory a layer needs for its re-tiled weights, scales and zero points
+ * (dmr_qlinear_create's d_storage).  0 if the shape is not supported. */
+size_t dmr_qlinear_storage_bytes(int64_t K, int64_t N, int32_t g);
+
+/* Bytes of scratch a forward call of this shape needs (d_ws); may be 0, and then d_ws may be
+ * NULL.  Valid for both the INT4 and the bf16 forward. */
+size_t dmr_qlinear_workspace_bytes(int64_t M, int64_t K, int64_t N);
+
+/*
+ * Prepare one low-precision Linear layer (a layer of the W4A16 copy, Sec. 5.1 / App. E): re-tile
+ * the canonical arrays into d_storage in the order the kernels stream them.  One-off per layer,
+ * integer only.  The canonical arrays may be released once the stream work has completed;
+ * d_storage must outlive the handle.  *out receives a host-side handle.
+ */
+dmr_status_t dmr_qlinear_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32_t g,
+                                const uint32_t *d_qweight, /* [N][K/8]  */
+                                const uint16_t *d_scales,  /* bf16 [N][K/g] */
+                                const uint16_t *d_zeros,   /* bf16 [N][K/g] */
+                                void *d_storage, size_t storage_bytes, void *stream);
+
+/* The layer's weights as bf16 [N][K]: RNE_bf16((q - z) * s), exactly one correct answer. */
+dmr_status_t dmr_qlinear_dequantize(const dmr_qlinear_t *layer, uint16_t *d_w_bf16, void *stream);
+
+/*
+ * A step routed to the low-precision copy (Sec. 3, Eq. 1 with r_t = low):
+ *   y[m][n] = sum_k x[m][k] * (q[n][k] - z[n][k/g]) * s[n][k/g]
+ * with the dequantisation fused into the product and fp32 accumulation.  d_x is bf16 [M][K];
+ * d_y is [M][N] of the type `out` names.  M <= 64 takes the weight-streaming path (decode, a
+ * group of parallel rollouts), larger M the tiled MFMA path (prefill of a long prompt, App. B).
+ */
+dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x, int64_t M,
+                                 void *d_y, dmr_out_t out, void *d_ws, size_t ws_bytes,
+                                 void *stream);
+
+/*
+ * The same layer in the bf16 high-precision copy (Sec. 5.1; a step with r_t = high):
+ *   y[m][n] = sum_k x[m][k] * W[n][k],  W bf16 [N][K], fp32 accumulation.
+ * This is the denominator of the T_high / T_low ratio (Eq. 9).  Needs no handle.
+ */
+dmr_status_t dmr_qlinear_bf16_forward(const uint16_t *d_w, const uint16_t *d_x, int64_t M,
+                                      int64_t K, int64_t N, void *d_y, dmr_out_t out, void *d_ws,
+                                      size_t ws_bytes, void *stream);
+
+/*
+ * Offline step that produces the low-precision copy (App. E names AWQ/GPTQ; this is plain
+ * asymmetric round-to-nearest, which yields the same format): fp32 weights [N][K] to canonical
+ * qweight / scales / zeros.  Per (row, group): lo = min(w, 0), hi = max(w, 0),
+ * s = RNE_bf16(float((hi - lo) / 15)) (1 if that is 0), z = clamp(rint(-lo / s), 0, 15),
+ * q = clamp(rint(w / s) + z, 0, 15), divisions and rint in fp64 with the stored bf16 s.
+ */
+dmr_status_t dmr_qlinear_quantize(int64_t K, int64_t N, int32_t g, const float *d_w,
+                                  uint32_t *d_qweight, uint16_t *d_scales, uint16_t *d_zeros,
+                                  void *stream);
+
+/* Release the host handle (NULL is allowed).  Device memory is the caller's and is untouched. */
+void dmr_qlinear_destroy(dmr_qlinear_t *layer);
+
+/* Shape of a handle (for bindings); any out pointer may be NULL. */
+dmr_status_t dmr_qlinear_shape(const dmr_qlinear_t *layer, int64_t *K, int64_t *N, int32_t *g);
+
+const char *dmr_status_string(dmr_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DMR_QLINEAR_H */

@@ -1,0 +1,16 @@
+"""MI355X-native W4A16 / bf16 linear layer of a Dynamic-Mixed-Precision-Routing step.
+
+The product is ``libdmr_qlinear.so`` (hand-written gfx950 kernels behind the C ABI declared in
+``include/dmr_qlinear.h``); this package holds its sources, its build step, a thin binding with
+the same names, and the seeded input generators.
+"""
+from .binding import (DMR_OUT_BF16, DMR_OUT_FP32, DmrError, Layer, dmr_qlinear_bf16_forward,
+                      dmr_qlinear_create, dmr_qlinear_dequantize, dmr_qlinear_destroy,
+                      dmr_qlinear_forward, dmr_qlinear_quantize, dmr_qlinear_storage_bytes,
+                      dmr_qlinear_workspace_bytes)
+
+__all__ = [
+    "DMR_OUT_BF16", "DMR_OUT_FP32", "DmrError", "Layer", "dmr_qlinear_bf16_forward",
+    "dmr_qlinear_create", "dmr_qlinear_dequantize", "dmr_qlinear_destroy", "dmr_qlinear_forward",
+    "dmr_qlinear_quantize", "dmr_qlinear_storage_bytes", "dmr_qlinear_workspace_bytes",
+]

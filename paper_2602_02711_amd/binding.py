@@ -1,0 +1,215 @@
+"""Python binding of ``include/dmr_qlinear.h``: argument marshalling only.
+
+Every function has the name and meaning of the C entry point it calls; tensors are torch
+tensors used as device memory (PyTorch supplies allocation and streams, nothing else) and all
+arithmetic happens in the HIP kernels of ``libdmr_qlinear.so``.  There is no fallback: if the
+library is missing or a call is refused, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdmr_qlinear.so")
+
+DMR_OK = 0
+DMR_ERR_NULL, DMR_ERR_SHAPE, DMR_ERR_ALIGN, DMR_ERR_WORKSPACE, DMR_ERR_UNSUPPORTED, DMR_ERR_HIP = range(1, 7)
+DMR_OUT_BF16, DMR_OUT_FP32 = 0, 1
+
+EXPORTS = (
+    "dmr_qlinear_storage_bytes", "dmr_qlinear_workspace_bytes", "dmr_qlinear_create",
+    "dmr_qlinear_dequantize", "dmr_qlinear_forward", "dmr_qlinear_bf16_forward",
+    "dmr_qlinear_quantize", "dmr_qlinear_destroy", "dmr_qlinear_shape", "dmr_status_string",
+)
+
+
+class DmrError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        text = lib().dmr_status_string(status).decode()
+        super().__init__(f"{where}: {text} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library, with prototypes set.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+        L = ctypes.CDLL(LIB_PATH)
+        i64, i32, vp, sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t
+        L.dmr_qlinear_storage_bytes.restype = sz
+        L.dmr_qlinear_storage_bytes.argtypes = [i64, i64, i32]
+        L.dmr_qlinear_workspace_bytes.restype = sz
+        L.dmr_qlinear_workspace_bytes.argtypes = [i64, i64, i64]
+        L.dmr_qlinear_create.restype = ctypes.c_int
+        L.dmr_qlinear_create.argtypes = [ctypes.POINTER(vp), i64, i64, i32, vp, vp, vp, vp, sz, vp]
+        L.dmr_qlinear_dequantize.restype = ctypes.c_int
+        L.dmr_qlinear_dequantize.argtypes = [vp, vp, vp]
+        L.dmr_qlinear_forward.restype = ctypes.c_int
+        L.dmr_qlinear_forward.argtypes = [vp, vp, i64, vp, ctypes.c_int, vp, sz, vp]
+        L.dmr_qlinear_bf16_forward.restype = ctypes.c_int
+        L.dmr_qlinear_bf16_forward.argtypes = [vp, vp, i64, i64, i64, vp, ctypes.c_int, vp, sz, vp]
+        L.dmr_qlinear_quantize.restype = ctypes.c_int
+        L.dmr_qlinear_quantize.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp]
+        L.dmr_qlinear_destroy.restype = None
+        L.dmr_qlinear_destroy.argtypes = [vp]
+        L.dmr_qlinear_shape.restype = ctypes.c_int
+        L.dmr_qlinear_shape.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i32)]
+        L.dmr_status_string.restype = ctypes.c_char_p
+        L.dmr_status_string.argtypes = [ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def _check(status: int, where: str) -> None:
+    if status != DMR_OK:
+        raise DmrError(status, where)
+
+
+def _dev(t: torch.Tensor, name: str, dtypes) -> int:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a tensor in device memory")
+    if t.dtype not in dtypes:
+        raise TypeError(f"{name} has dtype {t.dtype}, expected one of {dtypes}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+_BF16 = (torch.bfloat16, torch.int16, torch.uint16)
+_U32 = (torch.int32, torch.uint32)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream)
+
+
+def _out_code(dtype) -> int:
+    if dtype == torch.bfloat16:
+        return DMR_OUT_BF16
+    if dtype == torch.float32:
+        return DMR_OUT_FP32
+    raise TypeError("output dtype must be torch.bfloat16 or torch.float32")
+
+
+class Layer:
+    """Host handle of one quantised Linear layer plus the storage tensor it points into."""
+
+    def __init__(self, handle: int, storage: torch.Tensor, K: int, N: int, g: int):
+        self.handle, self.storage, self.K, self.N, self.g = handle, storage, K, N, g
+
+    def __del__(self):
+        dmr_qlinear_destroy(self)
+
+
+def dmr_qlinear_storage_bytes(K: int, N: int, g: int = 128) -> int:
+    return int(lib().dmr_qlinear_storage_bytes(K, N, g))
+
+
+def dmr_qlinear_workspace_bytes(M: int, K: int, N: int) -> int:
+    return int(lib().dmr_qlinear_workspace_bytes(M, K, N))
+
+
+def dmr_qlinear_create(qweight: torch.Tensor, scales: torch.Tensor, zeros: torch.Tensor, g: int = 128,
+                       storage: torch.Tensor | None = None, stream=None) -> Layer:
+    pq = _dev(qweight, "qweight", _U32)
+    ps = _dev(scales, "scales", _BF16)
+    pz = _dev(zeros, "zeros", _BF16)
+    N, K8 = qweight.shape
+    K = K8 * 8
+    if g <= 0 or K % g or tuple(scales.shape) != (N, K // g) or tuple(zeros.shape) != (N, K // g):
+        raise ValueError("scales and zeros must be [N][K/g]")
+    need = dmr_qlinear_storage_bytes(K, N, g)
+    if storage is None:
+        storage = torch.empty(max(need, 16), dtype=torch.uint8, device=qweight.device)
+    pst = _dev(storage, "storage", (torch.uint8,))
+    handle = ctypes.c_void_p()
+    _check(lib().dmr_qlinear_create(ctypes.byref(handle), K, N, g, pq, ps, pz, pst, storage.numel(),
+                                    _stream(stream)), "dmr_qlinear_create")
+    return Layer(handle.value, storage, K, N, g)
+
+
+def dmr_qlinear_dequantize(layer: Layer, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty((layer.N, layer.K), dtype=torch.bfloat16, device=layer.storage.device)
+    po = _dev(out, "out", _BF16)
+    if tuple(out.shape) != (layer.N, layer.K):
+        raise ValueError("out must be [N][K]")
+    _check(lib().dmr_qlinear_dequantize(layer.handle, po, _stream(stream)), "dmr_qlinear_dequantize")
+    return out
+
+
+def _workspace(workspace):
+    if workspace is None:
+        return None, 0
+    return _dev(workspace, "workspace", (torch.uint8,)), workspace.numel()
+
+
+def dmr_qlinear_forward(layer: Layer, x: torch.Tensor, out: torch.Tensor | None = None,
+                        out_dtype=torch.bfloat16, workspace: torch.Tensor | None = None,
+                        stream=None) -> torch.Tensor:
+    px = _dev(x, "x", _BF16)
+    if x.dim() != 2 or x.shape[1] != layer.K:
+        raise ValueError("x must be [M][K]")
+    M = x.shape[0]
+    if out is None:
+        out = torch.empty((M, layer.N), dtype=out_dtype, device=x.device)
+    po = _dev(out, "out", (torch.bfloat16, torch.float32))
+    if tuple(out.shape) != (M, layer.N):
+        raise ValueError("out must be [M][N]")
+    pw, wbytes = _workspace(workspace)
+    _check(lib().dmr_qlinear_forward(layer.handle, px, M, po, _out_code(out.dtype), pw, wbytes,
+                                     _stream(stream)), "dmr_qlinear_forward")
+    return out
+
+
+def dmr_qlinear_bf16_forward(w: torch.Tensor, x: torch.Tensor, out: torch.Tensor | None = None,
+                             out_dtype=torch.bfloat16, workspace: torch.Tensor | None = None,
+                             stream=None) -> torch.Tensor:
+    pw_ = _dev(w, "w", _BF16)
+    px = _dev(x, "x", _BF16)
+    N, K = w.shape
+    if x.dim() != 2 or x.shape[1] != K:
+        raise ValueError("x must be [M][K]")
+    M = x.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=x.device)
+    po = _dev(out, "out", (torch.bfloat16, torch.float32))
+    if tuple(out.shape) != (M, N):
+        raise ValueError("out must be [M][N]")
+    pws, wbytes = _workspace(workspace)
+    _check(lib().dmr_qlinear_bf16_forward(pw_, px, M, K, N, po, _out_code(out.dtype), pws, wbytes,
+                                          _stream(stream)), "dmr_qlinear_bf16_forward")
+    return out
+
+
+def dmr_qlinear_quantize(w: torch.Tensor, g: int = 128, stream=None):
+    """fp32 [N][K] in device memory -> (qweight int32 [N][K/8], scales bf16, zeros bf16 [N][K/g])."""
+    pw_ = _dev(w, "w", (torch.float32,))
+    N, K = w.shape
+    if g <= 0 or K % g or K % 8:
+        raise ValueError("K must be a multiple of g and of 8")
+    qweight = torch.empty((N, K // 8), dtype=torch.int32, device=w.device)
+    scales = torch.empty((N, K // g), dtype=torch.bfloat16, device=w.device)
+    zeros = torch.empty((N, K // g), dtype=torch.bfloat16, device=w.device)
+    _check(lib().dmr_qlinear_quantize(K, N, g, pw_, qweight.data_ptr(), scales.data_ptr(),
+                                      zeros.data_ptr(), _stream(stream)), "dmr_qlinear_quantize")
+    return qweight, scales, zeros
+
+
+def dmr_qlinear_destroy(layer: Layer) -> None:
+    handle, layer.handle = getattr(layer, "handle", None), None
+    if handle and _lib is not None:
+        _lib.dmr_qlinear_destroy(handle)

@@ -1,0 +1,156 @@
+// C ABI of dmr_qlinear.h: argument checks (all before the first HIP call), the host handle, and
+// the choice of kernel by M.  No device memory is allocated here or anywhere in the library.
+#include <new>
+
+#include "common.hpp"
+
+struct dmr_qlinear {
+    int64_t K, N;
+    int32_t g;
+    const uint4 *wt;
+    const uint32_t *sz;
+};
+
+namespace {
+
+constexpr int64_t kSkinnyMaxM = 64;
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+dmr_status_t check_shape(int64_t K, int64_t N, int32_t g) {
+    if (K <= 0 || N <= 0 || g <= 0) return DMR_ERR_SHAPE;
+    if (g != dmr::kGroup) return (K % g == 0) ? DMR_ERR_UNSUPPORTED : DMR_ERR_SHAPE;
+    if (K % dmr::kGroup != 0 || N % dmr::kTileRows != 0) return DMR_ERR_SHAPE;
+    // block and element indices are formed in 64 bits; the grid's x dimension is 32 bits
+    if (N / dmr::kTileRows > 0x7FFFFFFF || K > (int64_t(1) << 31) || N > (int64_t(1) << 31))
+        return DMR_ERR_SHAPE;
+    return DMR_OK;
+}
+
+dmr_status_t hip_status(hipError_t e) { return e == hipSuccess ? DMR_OK : DMR_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+size_t dmr_qlinear_storage_bytes(int64_t K, int64_t N, int32_t g) {
+    if (check_shape(K, N, g) != DMR_OK) return 0;
+    return dmr::weight_region_bytes(K, N) + dmr::sz_region_bytes(K, N);
+}
+
+size_t dmr_qlinear_workspace_bytes(int64_t M, int64_t K, int64_t N) {
+    (void)M; (void)K; (void)N;
+    return 0;   // every reduction of this build stays inside a workgroup
+}
+
+dmr_status_t dmr_qlinear_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32_t g,
+                                const uint32_t *d_qweight, const uint16_t *d_scales,
+                                const uint16_t *d_zeros, void *d_storage, size_t storage_bytes,
+                                void *stream) {
+    if (!out) return DMR_ERR_NULL;
+    *out = nullptr;
+    const dmr_status_t shape = check_shape(K, N, g);
+    if (shape != DMR_OK) return shape;
+    if (!d_qweight || !d_scales || !d_zeros || !d_storage) return DMR_ERR_NULL;
+    if (!aligned16(d_qweight) || !aligned16(d_scales) || !aligned16(d_zeros) || !aligned16(d_storage))
+        return DMR_ERR_ALIGN;
+    if (storage_bytes < dmr_qlinear_storage_bytes(K, N, g)) return DMR_ERR_WORKSPACE;
+
+    dmr_qlinear *h = new (std::nothrow) dmr_qlinear;
+    if (!h) return DMR_ERR_NULL;
+    h->K = K;
+    h->N = N;
+    h->g = g;
+    uint8_t *base = static_cast<uint8_t *>(d_storage);
+    h->wt = reinterpret_cast<const uint4 *>(base);
+    h->sz = reinterpret_cast<const uint32_t *>(base + dmr::weight_region_bytes(K, N));
+    const hipError_t e = dmr::launch_retile(K, N, d_qweight, d_scales, d_zeros,
+                                            reinterpret_cast<uint4 *>(base),
+                                            reinterpret_cast<uint32_t *>(base + dmr::weight_region_bytes(K, N)),
+                                            static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) {
+        delete h;
+        return DMR_ERR_HIP;
+    }
+    *out = h;
+    return DMR_OK;
+}
+
+dmr_status_t dmr_qlinear_dequantize(const dmr_qlinear_t *layer, uint16_t *d_w_bf16, void *stream) {
+    if (!layer || !d_w_bf16) return DMR_ERR_NULL;
+    if (!aligned16(d_w_bf16)) return DMR_ERR_ALIGN;
+    const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz};
+    return hip_status(dmr::launch_dequantize(L, d_w_bf16, static_cast<hipStream_t>(stream)));
+}
+
+dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x, int64_t M, void *d_y,
+                                 dmr_out_t out, void *d_ws, size_t ws_bytes, void *stream) {
+    if (!layer) return DMR_ERR_NULL;
+    if (M < 0 || M > (int64_t(1) << 22)) return DMR_ERR_SHAPE;
+    if (out != DMR_OUT_BF16 && out != DMR_OUT_FP32) return DMR_ERR_UNSUPPORTED;
+    if (M == 0) return DMR_OK;
+    if (!d_x || !d_y) return DMR_ERR_NULL;
+    if (!aligned16(d_x) || !aligned16(d_y) || (d_ws && !aligned16(d_ws))) return DMR_ERR_ALIGN;
+    const size_t need = dmr_qlinear_workspace_bytes(M, layer->K, layer->N);
+    if (need > 0 && (!d_ws || ws_bytes < need)) return DMR_ERR_WORKSPACE;
+    const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz};
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool f32 = out == DMR_OUT_FP32;
+    if (M <= kSkinnyMaxM) return hip_status(dmr::launch_w4_skinny(L, d_x, M, d_y, f32, s));
+    return hip_status(dmr::launch_w4_gemm(L, d_x, M, d_y, f32, s));
+}
+
+dmr_status_t dmr_qlinear_bf16_forward(const uint16_t *d_w, const uint16_t *d_x, int64_t M, int64_t K,
+                                      int64_t N, void *d_y, dmr_out_t out, void *d_ws, size_t ws_bytes,
+                                      void *stream) {
+    const dmr_status_t shape = check_shape(K, N, dmr::kGroup);
+    if (shape != DMR_OK) return shape;
+    if (M < 0 || M > (int64_t(1) << 22)) return DMR_ERR_SHAPE;
+    if (out != DMR_OUT_BF16 && out != DMR_OUT_FP32) return DMR_ERR_UNSUPPORTED;
+    if (M == 0) return DMR_OK;
+    if (!d_w || !d_x || !d_y) return DMR_ERR_NULL;
+    if (!aligned16(d_w) || !aligned16(d_x) || !aligned16(d_y) || (d_ws && !aligned16(d_ws)))
+        return DMR_ERR_ALIGN;
+    const size_t need = dmr_qlinear_workspace_bytes(M, K, N);
+    if (need > 0 && (!d_ws || ws_bytes < need)) return DMR_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool f32 = out == DMR_OUT_FP32;
+    if (M <= kSkinnyMaxM) return hip_status(dmr::launch_bf16_skinny(d_w, d_x, M, K, N, d_y, f32, s));
+    return hip_status(dmr::launch_bf16_gemm(d_w, d_x, M, K, N, d_y, f32, s));
+}
+
+dmr_status_t dmr_qlinear_quantize(int64_t K, int64_t N, int32_t g, const float *d_w, uint32_t *d_qweight,
+                                  uint16_t *d_scales, uint16_t *d_zeros, void *stream) {
+    const dmr_status_t shape = check_shape(K, N, g);
+    if (shape != DMR_OK) return shape;
+    if (!d_w || !d_qweight || !d_scales || !d_zeros) return DMR_ERR_NULL;
+    if (!aligned16(d_w) || !aligned16(d_qweight) || !aligned16(d_scales) || !aligned16(d_zeros))
+        return DMR_ERR_ALIGN;
+    return hip_status(dmr::launch_quantize(K, N, d_w, d_qweight, d_scales, d_zeros,
+                                           static_cast<hipStream_t>(stream)));
+}
+
+void dmr_qlinear_destroy(dmr_qlinear_t *layer) { delete layer; }
+
+dmr_status_t dmr_qlinear_shape(const dmr_qlinear_t *layer, int64_t *K, int64_t *N, int32_t *g) {
+    if (!layer) return DMR_ERR_NULL;
+    if (K) *K = layer->K;
+    if (N) *N = layer->N;
+    if (g) *g = layer->g;
+    return DMR_OK;
+}
+
+const char *dmr_status_string(dmr_status_t status) {
+    switch (status) {
+        case DMR_OK: return "ok";
+        case DMR_ERR_NULL: return "a required pointer is NULL";
+        case DMR_ERR_SHAPE: return "bad shape";
+        case DMR_ERR_ALIGN: return "device pointer not 16-byte aligned";
+        case DMR_ERR_WORKSPACE: return "storage or workspace buffer too small";
+        case DMR_ERR_UNSUPPORTED: return "unsupported configuration";
+        case DMR_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

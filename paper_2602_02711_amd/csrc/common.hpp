@@ -1,0 +1,83 @@
+// Shared declarations of the gfx950 kernels behind dmr_qlinear.h.
+//
+// Internal ("streaming") layout of a quantised layer, written once by the re-tiling kernel:
+//
+//   weights: a 1 KiB block per (row tile T = n / 16, group G = k / 128), blocks ordered
+//            [T][G], so a wave that walks along k for its 16 rows reads one contiguous stream.
+//            Inside a block, lane l = 16 c + j of a wavefront owns 16 bytes at offset 16 l:
+//            row n = 16 T + j, the 32 weights k = 128 G + 32 c + 8 t + p (t = word 0..3,
+//            p = 0..7).  Within a word, position p sits in nibble (p >> 1) + 4 (p & 1), so that
+//            ((word >> 4 i) & 0x000F000F) | 0x43004300 is the bf16 pair (128 + q[p = 2 i],
+//            128 + q[p = 2 i + 1]): one MFMA B-operand register, k-consecutive like the
+//            activations.
+//   sz:      after the weights, one uint32 per (T, G, j): low half = bf16 scale s, high half =
+//            bf16 of -(128 + z) (exact: 128..143 needs 8 significant bits).
+//
+// With D = sum_k x_k (128 + q_k) and X = sum_k x_k over one group, the group's contribution to
+// an output is  s * (D - (128 + z) * X): the zero point and the scale cost two FMAs per group
+// instead of work per weight, and D, X come out of the matrix cores.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/dmr_qlinear.h"
+
+namespace dmr {
+
+constexpr int kGroup = 128;      // weights per (scale, zero) along k
+constexpr int kTileRows = 16;    // rows of one streaming block
+constexpr int kBlockBytes = 1024;
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+union Frag {
+    uint4 u;
+    uint32_t w[4];
+    bf16x8 v;
+};
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) {
+    return __uint_as_float(bits16 << 16);
+}
+
+// fp32 -> bf16 bits, round to nearest even (v_cvt_pk_bf16_f32 on gfx950).
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    return (uint16_t)(pack_bf16x2(f, 0.0f) & 0xFFFFu);
+}
+
+// Position p (0..7) of a streaming-layout word -> nibble index.
+__host__ __device__ __forceinline__ int nibble_of_position(int p) { return (p >> 1) + 4 * (p & 1); }
+
+struct LayerView {
+    int64_t K, N;
+    const uint4 *wt;       // streaming weight blocks
+    const uint32_t *sz;    // streaming scale / zero words
+};
+
+inline size_t weight_region_bytes(int64_t K, int64_t N) { return (size_t)N * (size_t)K / 2; }
+inline size_t sz_region_bytes(int64_t K, int64_t N) { return (size_t)N * (size_t)(K / kGroup) * 4; }
+
+// Kernel launchers (each returns hipGetLastError() after its launch).
+hipError_t launch_retile(int64_t K, int64_t N, const uint32_t *qweight, const uint16_t *scales,
+                         const uint16_t *zeros, uint4 *wt, uint32_t *sz, hipStream_t stream);
+hipError_t launch_dequantize(const LayerView &L, uint16_t *w_bf16, hipStream_t stream);
+hipError_t launch_quantize(int64_t K, int64_t N, const float *w, uint32_t *qweight,
+                           uint16_t *scales, uint16_t *zeros, hipStream_t stream);
+hipError_t launch_w4_skinny(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+                            hipStream_t stream);
+hipError_t launch_bf16_skinny(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
+                              void *y, bool out_f32, hipStream_t stream);
+hipError_t launch_w4_gemm(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+                          hipStream_t stream);
+hipError_t launch_bf16_gemm(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
+                            void *y, bool out_f32, hipStream_t stream);
+
+}  // namespace dmr

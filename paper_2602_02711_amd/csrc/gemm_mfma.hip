@@ -1,0 +1,195 @@
+// Tiled MFMA GEMM for prefill-sized M (a long prompt: few-shot prefix plus the whole history),
+// y[M][N] = x[M][K] . W[N][K]^T with fp32 accumulation.  Two weight sources share the kernel:
+// bf16 weights read as they are, and INT4 streaming blocks dequantised to bf16 on their way
+// into LDS (RNE_bf16((q - z) s), the same value dequantize produces).
+//
+// Workgroup tile 128 (m) x 128 (n) x 64 (k), 4 wavefronts in a 2 x 2 grid, each owning a 64 x 64
+// patch as 2 x 2 tiles of v_mfma_f32_32x32x16_bf16.  Global loads for step i+1 are issued into
+// registers before the MFMAs of step i.  LDS rows are padded by 16 bytes so that the 16-byte
+// operand reads of 32 consecutive rows fall in distinct banks.
+//
+// Operand layout of a 32x32x16 MFMA: lane l supplies row (l % 32), k = 8 (l / 32) .. + 7 of A and
+// of B; accumulator register r of lane l is (A row 8 (r / 4) + 4 (l / 32) + r % 4, B row l % 32).
+#include "common.hpp"
+
+namespace dmr {
+
+namespace {
+
+constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int LDS_STRIDE = BK + 8;   // bf16 elements per padded LDS row (144 bytes)
+
+template <bool W4>
+struct Prefetch {
+    uint4 xa[4];
+    uint4 wb[4];       // bf16 source: 4 x 16 bytes; INT4 source: wb[0] = 32 packed weights
+    uint32_t szw;
+};
+
+template <bool W4>
+__device__ __forceinline__ void load_global(Prefetch<W4> &p, const void *__restrict__ wsrc,
+                                            const uint32_t *__restrict__ sz,
+                                            const uint16_t *__restrict__ x, int64_t M, int64_t K,
+                                            int64_t N, int64_t m0, int64_t n0, int64_t k0, int tid) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int idx = tid + 256 * i;
+        const int row = idx >> 3, chunk = idx & 7;
+        const int64_t m = m0 + row;
+        p.xa[i] = (m < M) ? *reinterpret_cast<const uint4 *>(x + m * K + k0 + chunk * 8)
+                          : make_uint4(0, 0, 0, 0);
+    }
+    if (W4) {
+        // 8 row tiles x 32 lanes: the half of each 1 KiB block that covers this 64-wide k step
+        const int64_t groups = K / kGroup;
+        const int64_t G = k0 / kGroup;
+        const int half = (int)((k0 % kGroup) / 64);
+        const int64_t T = n0 / kTileRows + (tid >> 5);
+        const int l = half * 32 + (tid & 31);
+        if (T * kTileRows < N) {
+            p.wb[0] = reinterpret_cast<const uint4 *>(wsrc)[(T * groups + G) * 64 + l];
+            p.szw = sz[(T * groups + G) * kTileRows + (l & 15)];
+        } else {
+            p.wb[0] = make_uint4(0, 0, 0, 0);
+            p.szw = 0xC3000000u;   // s = 0, -(128 + z) = -128: contributes zeros
+        }
+    } else {
+        const uint16_t *w = reinterpret_cast<const uint16_t *>(wsrc);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = tid + 256 * i;
+            const int row = idx >> 3, chunk = idx & 7;
+            const int64_t n = n0 + row;
+            p.wb[i] = (n < N) ? *reinterpret_cast<const uint4 *>(w + n * K + k0 + chunk * 8)
+                              : make_uint4(0, 0, 0, 0);
+        }
+    }
+}
+
+template <bool W4>
+__device__ __forceinline__ void store_lds(const Prefetch<W4> &p, uint16_t *As, uint16_t *Bs, int tid) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int idx = tid + 256 * i;
+        const int row = idx >> 3, chunk = idx & 7;
+        *reinterpret_cast<uint4 *>(As + row * LDS_STRIDE + chunk * 8) = p.xa[i];
+    }
+    if (W4) {
+        const int l = tid & 31;                       // lane within the half block
+        const int row = (tid >> 5) * kTileRows + (l & 15);
+        const int kofs = (l >> 4) * 32;               // 0 or 32 inside the 64-wide step
+        const float s = __uint_as_float(p.szw << 16);
+        const float czs = __uint_as_float(p.szw & 0xFFFF0000u) * s;   // -(128 + z) s, exact
+        const uint32_t words[4] = {p.wb[0].x, p.wb[0].y, p.wb[0].z, p.wb[0].w};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            uint32_t o[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                // (128 + q) as fp32 straight from the bf16 magic pair, then one exact FMA each
+                const uint32_t pair = ((words[t] >> (4 * i)) & 0x000F000Fu) | 0x43004300u;
+                const float lo = fmaf(__uint_as_float(pair << 16), s, czs);
+                const float hi = fmaf(__uint_as_float(pair & 0xFFFF0000u), s, czs);
+                o[i] = pack_bf16x2(lo, hi);
+            }
+            *reinterpret_cast<uint4 *>(Bs + row * LDS_STRIDE + kofs + t * 8) =
+                make_uint4(o[0], o[1], o[2], o[3]);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = tid + 256 * i;
+            const int row = idx >> 3, chunk = idx & 7;
+            *reinterpret_cast<uint4 *>(Bs + row * LDS_STRIDE + chunk * 8) = p.wb[i];
+        }
+    }
+}
+
+template <bool W4, bool OUT_F32>
+__global__ __launch_bounds__(256) void gemm_kernel(const void *__restrict__ wsrc,
+                                                   const uint32_t *__restrict__ sz,
+                                                   const uint16_t *__restrict__ x,
+                                                   void *__restrict__ y, int64_t M, int64_t K,
+                                                   int64_t N) {
+    __shared__ __attribute__((aligned(16))) uint16_t As[BM * LDS_STRIDE];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * LDS_STRIDE];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int64_t n0 = (int64_t)blockIdx.x * BN;
+    const int64_t m0 = (int64_t)blockIdx.y * BM;
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    Prefetch<W4> pre;
+    load_global<W4>(pre, wsrc, sz, x, M, K, N, m0, n0, 0, tid);
+    for (int64_t k0 = 0; k0 < K; k0 += BK) {
+        store_lds<W4>(pre, As, Bs, tid);
+        __syncthreads();
+        if (k0 + BK < K) load_global<W4>(pre, wsrc, sz, x, M, K, N, m0, n0, k0 + BK, tid);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            Frag a[2], b[2];
+            const int kk = ks * 16 + (lane >> 5) * 8;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                a[i].u = *reinterpret_cast<const uint4 *>(As + (wm * 64 + i * 32 + (lane & 31)) * LDS_STRIDE + kk);
+                b[i].u = *reinterpret_cast<const uint4 *>(Bs + (wn * 64 + i * 32 + (lane & 31)) * LDS_STRIDE + kk);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int64_t n = n0 + wn * 64 + j * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (m < M && n < N) {
+                    if (OUT_F32)
+                        reinterpret_cast<float *>(y)[m * N + n] = acc[i][j][r];
+                    else
+                        reinterpret_cast<uint16_t *>(y)[m * N + n] = f32_to_bf16(acc[i][j][r]);
+                }
+            }
+        }
+}
+
+template <bool W4>
+hipError_t launch(const void *wsrc, const uint32_t *sz, const uint16_t *x, int64_t M, int64_t K,
+                  int64_t N, void *y, bool out_f32, hipStream_t stream) {
+    const dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
+    if (out_f32)
+        hipLaunchKernelGGL((gemm_kernel<W4, true>), grid, dim3(256), 0, stream, wsrc, sz, x, y, M, K, N);
+    else
+        hipLaunchKernelGGL((gemm_kernel<W4, false>), grid, dim3(256), 0, stream, wsrc, sz, x, y, M, K, N);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_w4_gemm(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+                          hipStream_t stream) {
+    return launch<true>(L.wt, L.sz, x, M, L.K, L.N, y, out_f32, stream);
+}
+
+hipError_t launch_bf16_gemm(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
+                            void *y, bool out_f32, hipStream_t stream) {
+    return launch<false>(w, nullptr, x, M, K, N, y, out_f32, stream);
+}
+
+}  // namespace dmr

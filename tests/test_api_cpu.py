@@ -1,0 +1,95 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, answers the size queries, and rejects bad arguments before touching HIP."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_02711_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000001000        # a 16-byte aligned address that is never dereferenced by a rejected call
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return binding.lib()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "dmr_qlinear.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(dmr_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_size_queries(lib):
+    # 0.5 byte per weight + 4 bytes per (row, group of 128)
+    assert lib.dmr_qlinear_storage_bytes(4096, 4096, 128) == 4096 * 4096 // 2 + 4096 * 32 * 4
+    assert lib.dmr_qlinear_storage_bytes(1024, 1024, 128) == 1024 * 512 + 1024 * 8 * 4
+    assert lib.dmr_qlinear_storage_bytes(1000, 1024, 128) == 0
+    assert lib.dmr_qlinear_storage_bytes(1024, 1000, 128) == 0
+    assert lib.dmr_qlinear_storage_bytes(1024, 1024, 64) == 0
+    assert lib.dmr_qlinear_workspace_bytes(1, 4096, 4096) % 16 == 0
+
+
+def test_status_strings(lib):
+    seen = {lib.dmr_status_string(i) for i in range(7)}
+    assert len(seen) == 7 and all(s for s in seen)
+    assert lib.dmr_status_string(99)
+
+
+def _create(lib, K, N, g, q=FAKE, s=FAKE, z=FAKE, st=FAKE, st_bytes=1 << 40, out=True):
+    h = ctypes.c_void_p(0xDEAD)
+    rc = lib.dmr_qlinear_create(ctypes.byref(h) if out else None, K, N, g, q, s, z, st, st_bytes, None)
+    return rc, h.value
+
+
+def test_create_rejects_bad_arguments_without_touching_hip(lib):
+    assert _create(lib, 1024, 1024, 128, out=False)[0] == binding.DMR_ERR_NULL
+    for K, N, g, want in [(0, 1024, 128, binding.DMR_ERR_SHAPE), (1024, -16, 128, binding.DMR_ERR_SHAPE),
+                          (1000, 1024, 128, binding.DMR_ERR_SHAPE), (1024, 1000, 128, binding.DMR_ERR_SHAPE),
+                          (1024, 1024, 0, binding.DMR_ERR_SHAPE), (1024, 1024, 100, binding.DMR_ERR_SHAPE),
+                          (1024, 1024, 64, binding.DMR_ERR_UNSUPPORTED),
+                          (1024, 1024, 1024, binding.DMR_ERR_UNSUPPORTED)]:
+        rc, h = _create(lib, K, N, g)
+        assert rc == want, (K, N, g)
+        assert h is None                       # *out is cleared on failure
+    assert _create(lib, 1024, 1024, 128, q=None)[0] == binding.DMR_ERR_NULL
+    assert _create(lib, 1024, 1024, 128, s=None)[0] == binding.DMR_ERR_NULL
+    assert _create(lib, 1024, 1024, 128, z=None)[0] == binding.DMR_ERR_NULL
+    assert _create(lib, 1024, 1024, 128, st=None)[0] == binding.DMR_ERR_NULL
+    assert _create(lib, 1024, 1024, 128, q=FAKE + 4)[0] == binding.DMR_ERR_ALIGN
+    assert _create(lib, 1024, 1024, 128, st=FAKE + 8)[0] == binding.DMR_ERR_ALIGN
+    need = lib.dmr_qlinear_storage_bytes(1024, 1024, 128)
+    assert _create(lib, 1024, 1024, 128, st_bytes=need - 1)[0] == binding.DMR_ERR_WORKSPACE
+
+
+def test_forward_and_friends_reject_bad_arguments(lib):
+    assert lib.dmr_qlinear_forward(None, FAKE, 1, FAKE, 0, None, 0, None) == binding.DMR_ERR_NULL
+    assert lib.dmr_qlinear_dequantize(None, FAKE, None) == binding.DMR_ERR_NULL
+    assert lib.dmr_qlinear_shape(None, None, None, None) == binding.DMR_ERR_NULL
+    lib.dmr_qlinear_destroy(None)             # NULL-safe
+    bf = lib.dmr_qlinear_bf16_forward
+    assert bf(FAKE, FAKE, 1, 1000, 1024, FAKE, 0, None, 0, None) == binding.DMR_ERR_SHAPE
+    assert bf(FAKE, FAKE, -1, 1024, 1024, FAKE, 0, None, 0, None) == binding.DMR_ERR_SHAPE
+    assert bf(FAKE, FAKE, 1, 1024, 1024, FAKE, 7, None, 0, None) == binding.DMR_ERR_UNSUPPORTED
+    assert bf(FAKE, FAKE, 0, 1024, 1024, FAKE, 0, None, 0, None) == binding.DMR_OK   # M == 0: nothing to do
+    assert bf(None, FAKE, 1, 1024, 1024, FAKE, 0, None, 0, None) == binding.DMR_ERR_NULL
+    assert bf(FAKE, None, 1, 1024, 1024, FAKE, 0, None, 0, None) == binding.DMR_ERR_NULL
+    assert bf(FAKE, FAKE, 1, 1024, 1024, None, 0, None, 0, None) == binding.DMR_ERR_NULL
+    assert bf(FAKE, FAKE + 2, 1, 1024, 1024, FAKE, 0, None, 0, None) == binding.DMR_ERR_ALIGN
+    qz = lib.dmr_qlinear_quantize
+    assert qz(1024, 1024, 128, None, FAKE, FAKE, FAKE, None) == binding.DMR_ERR_NULL
+    assert qz(1024, 1024, 32, FAKE, FAKE, FAKE, FAKE, None) == binding.DMR_ERR_UNSUPPORTED
+    assert qz(1024, 8, 128, FAKE, FAKE, FAKE, FAKE, None) == binding.DMR_ERR_SHAPE
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    with pytest.raises(TypeError):
+        binding.dmr_qlinear_bf16_forward(torch.zeros(16, 128, dtype=torch.bfloat16),
+                                         torch.zeros(1, 128, dtype=torch.bfloat16))
