@@ -120,7 +120,7 @@ int oracle_quantize(int64_t K, int64_t N, int64_t g, const float *w,
             double s = oracle_bf16_to_f64(sb);
             if (s == 0.0) { s = 1.0; sb = 0x3F80; }
             double z = nearbyint(-(double)lo / s);
-            if (z < 0.0) z = 0.0;
+            if (z <= 0.0) z = 0.0;          /* also turns the -0 of an all-positive group into code 0 */
             if (z > 15.0) z = 15.0;
             for (int64_t i = 0; i < g; ++i) {
                 double c = nearbyint((double)wg[i] / s) + z;

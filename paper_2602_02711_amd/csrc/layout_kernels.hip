@@ -130,7 +130,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(int64_t K, int64_t N,
         s_bits = 0x3F80u;
     }
     double z = rint(-(double)lo / s);
-    z = fmin(fmax(z, 0.0), 15.0);
+    z = (z > 0.0) ? fmin(z, 15.0) : 0.0;   // code 0 is +0 also when -lo / s is -0
     uint32_t packed = 0;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {

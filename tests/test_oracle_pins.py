@@ -345,6 +345,7 @@ def test_quantizer_degenerate_groups():
     assert np.all(q[0] == 0) and np.all(orc.bf16_to_f64(s)[0] == 1.0) and np.all(orc.bf16_to_f64(z)[0] == 0)
     assert np.all(q[1, :8] == 15) and orc.bf16_to_f64(s)[1, 0] == 0.2001953125 and orc.bf16_to_f64(z)[1, 0] == 0
     assert np.array_equal(orc.dequantize_exact(orc.pack(q), s, z, 8)[0], np.zeros(16))
+    assert np.all(z == 0x0000)                       # the zero point 0 is +0, never -0
 
 
 def test_threads_do_not_change_results():
