@@ -141,16 +141,31 @@ def test_power_of_two_scales_small_integer_activations_are_exact(M):
 
 
 @pytest.mark.parametrize("M", [1, 64, 130])
-def test_zero_point_only_weights_give_exact_zero(M):
+def test_zero_point_only_weights_give_zero(M):
+    # q == z everywhere, so w^ == 0 and y == 0.  With small-integer activations every partial sum
+    # is exact and all paths must return exactly 0.  With Gaussian activations the tiled path
+    # (per-weight dequantisation) is still exactly 0; the streaming path forms
+    # sum x (128+q) - (128+z) sum x from two separately rounded fp32 sums, so it is only required
+    # to stay four orders of magnitude below the size of an ordinary output (the 1e-2 bar is 100x
+    # looser still).
     rng = np.random.default_rng(60)
     K, N = 512, 64
     zc = rng.integers(0, 16, size=(N, K // G))
     q = np.repeat(zc, G, axis=1).astype(np.uint8)
-    s = synth.to_bf16_bits(np.abs(synth.weights_f32(61, N, K // G)) + np.float32(1e-3))
+    s_f32 = np.abs(synth.weights_f32(61, N, K // G)) + np.float32(1e-3)
+    s = synth.to_bf16_bits(s_f32)
     z = orc.f64_to_bf16(zc.astype(np.float64))
+    layer = make_layer(orc.pack(q), s, z)
+    xi = orc.f64_to_bf16(rng.integers(-8, 9, size=(M, K)).astype(np.float64))
+    y_int = dmr.dmr_qlinear_forward(layer, bf16_dev(xi), out_dtype=torch.float32)
+    assert torch.count_nonzero(y_int).item() == 0
     x = synth.activations_bf16(62, M, K)
-    y32 = dmr.dmr_qlinear_forward(make_layer(orc.pack(q), s, z), bf16_dev(x), out_dtype=torch.float32)
-    assert torch.count_nonzero(y32).item() == 0
+    y32 = dmr.dmr_qlinear_forward(layer, bf16_dev(x), out_dtype=torch.float32)
+    if M > 64:
+        assert torch.count_nonzero(y32).item() == 0
+    else:
+        ordinary = float(s_f32.mean()) * 4.6 * np.sqrt(K)     # rms of x . w^ for codes spread over 0..15
+        assert float(y32.abs().max()) <= 1e-4 * ordinary
 
 
 def test_forward_is_deterministic_and_m0_is_a_no_op():
