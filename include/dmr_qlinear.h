@@ -109,6 +109,15 @@ dmr_status_t dmr_qlinear_quantize(int64_t K, int64_t N, int32_t g, const float *
                                   uint32_t *d_qweight, uint16_t *d_scales, uint16_t *d_zeros,
                                   void *stream);
 
+/*
+ * Measurement aid, not part of a routed step: read `bytes` (a multiple of 16) of d_buf once with
+ * 128-bit loads from `blocks` workgroups of 256 threads and leave one word per thread in d_sink
+ * (blocks * 256 words).  Timing it over a buffer much larger than the caches gives the HBM read
+ * rate that App. B's "constrained by memory bandwidth" refers to on this chip.
+ */
+dmr_status_t dmr_probe_hbm_read(const void *d_buf, size_t bytes, uint32_t *d_sink, int32_t blocks,
+                                void *stream);
+
 /* Release the host handle (NULL is allowed).  Device memory is the caller's and is untouched. */
 void dmr_qlinear_destroy(dmr_qlinear_t *layer);
 

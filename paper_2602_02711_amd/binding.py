@@ -23,6 +23,7 @@ EXPORTS = (
     "dmr_qlinear_storage_bytes", "dmr_qlinear_workspace_bytes", "dmr_qlinear_create",
     "dmr_qlinear_dequantize", "dmr_qlinear_forward", "dmr_qlinear_bf16_forward",
     "dmr_qlinear_quantize", "dmr_qlinear_destroy", "dmr_qlinear_shape", "dmr_status_string",
+    "dmr_probe_hbm_read",
 )
 
 
@@ -63,6 +64,8 @@ def lib() -> ctypes.CDLL:
         L.dmr_qlinear_destroy.argtypes = [vp]
         L.dmr_qlinear_shape.restype = ctypes.c_int
         L.dmr_qlinear_shape.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i32)]
+        L.dmr_probe_hbm_read.restype = ctypes.c_int
+        L.dmr_probe_hbm_read.argtypes = [vp, sz, vp, i32, vp]
         L.dmr_status_string.restype = ctypes.c_char_p
         L.dmr_status_string.argtypes = [ctypes.c_int]
         _lib = L
@@ -207,6 +210,14 @@ def dmr_qlinear_quantize(w: torch.Tensor, g: int = 128, stream=None):
     _check(lib().dmr_qlinear_quantize(K, N, g, pw_, qweight.data_ptr(), scales.data_ptr(),
                                       zeros.data_ptr(), _stream(stream)), "dmr_qlinear_quantize")
     return qweight, scales, zeros
+
+
+def dmr_probe_hbm_read(buf: torch.Tensor, sink: torch.Tensor, blocks: int, stream=None) -> None:
+    pb = _dev(buf, "buf", (torch.uint8,))
+    ps = _dev(sink, "sink", (torch.int32, torch.uint32))
+    if sink.numel() < blocks * 256:
+        raise ValueError("sink needs blocks * 256 words")
+    _check(lib().dmr_probe_hbm_read(pb, buf.numel(), ps, blocks, _stream(stream)), "dmr_probe_hbm_read")
 
 
 def dmr_qlinear_destroy(layer: Layer) -> None:

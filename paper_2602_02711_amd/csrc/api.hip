@@ -96,6 +96,10 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
     const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz};
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool f32 = out == DMR_OUT_FP32;
+    if (M == 1) {
+        const hipError_t e = dmr::launch_w4_gemv(L, d_x, d_y, f32, s);
+        if (e != hipErrorInvalidValue) return hip_status(e);   // else: shape outside its range
+    }
     if (M <= kSkinnyMaxM) return hip_status(dmr::launch_w4_skinny(L, d_x, M, d_y, f32, s));
     return hip_status(dmr::launch_w4_gemm(L, d_x, M, d_y, f32, s));
 }
@@ -128,6 +132,14 @@ dmr_status_t dmr_qlinear_quantize(int64_t K, int64_t N, int32_t g, const float *
         return DMR_ERR_ALIGN;
     return hip_status(dmr::launch_quantize(K, N, d_w, d_qweight, d_scales, d_zeros,
                                            static_cast<hipStream_t>(stream)));
+}
+
+dmr_status_t dmr_probe_hbm_read(const void *d_buf, size_t bytes, uint32_t *d_sink, int32_t blocks,
+                                void *stream) {
+    if (!d_buf || !d_sink) return DMR_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0 || blocks <= 0 || blocks > (1 << 20)) return DMR_ERR_SHAPE;
+    if (!aligned16(d_buf) || !aligned16(d_sink)) return DMR_ERR_ALIGN;
+    return hip_status(dmr::launch_hbm_read_probe(d_buf, bytes, d_sink, blocks, static_cast<hipStream_t>(stream)));
 }
 
 void dmr_qlinear_destroy(dmr_qlinear_t *layer) { delete layer; }

@@ -1,0 +1,34 @@
+// Measurement aid: a read-only stream over a buffer with 128-bit loads, to learn the HBM read
+// rate this chip actually sustains (the ceiling the decode kernels are judged against).
+#include "common.hpp"
+
+namespace dmr {
+
+__global__ __launch_bounds__(256) void hbm_read_probe_kernel(const uint4 *__restrict__ buf, size_t n16,
+                                                             uint32_t *__restrict__ sink) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t acc = 0;
+    for (; i + 7 * stride < n16; i += 8 * stride) {
+        uint4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = buf[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    for (; i < n16; i += stride) {
+        const uint4 v = buf[i];
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    // one store per thread keeps the loads alive without adding measurable traffic
+    sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = acc;
+}
+
+hipError_t launch_hbm_read_probe(const void *buf, size_t bytes, uint32_t *sink, int blocks,
+                                 hipStream_t stream) {
+    hipLaunchKernelGGL(hbm_read_probe_kernel, dim3(blocks), dim3(256), 0, stream,
+                       reinterpret_cast<const uint4 *>(buf), bytes / 16, sink);
+    return hipGetLastError();
+}
+
+}  // namespace dmr
