@@ -53,6 +53,14 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
     return (uint16_t)(pack_bf16x2(f, 0.0f) & 0xFFFFu);
 }
 
+// Streaming (read-once) loads: keep weight traffic from displacing the activations in the caches.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream(const uint4 *p) {
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint32_t load_stream(const uint32_t *p) { return __builtin_nontemporal_load(p); }
+
 // Position p (0..7) of a streaming-layout word -> nibble index.
 __host__ __device__ __forceinline__ int nibble_of_position(int p) { return (p >> 1) + 4 * (p & 1); }
 

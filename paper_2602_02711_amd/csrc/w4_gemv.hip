@@ -1,17 +1,19 @@
 // W4A16 decode GEMV (M == 1): the kernel behind "one generated token streams every weight once".
 //
-// Work split.  A workgroup owns the row tiles blockIdx.x, blockIdx.x + gridDim.x, ...; its S
-// wavefronts split the groups along k once (wave w owns groups [g0, g1)) and keep that slice of
-// x in wave-private LDS for the whole kernel.  Each wave walks the flattened list of
-// (tile, group) blocks it owns through a register ring of P outstanding 1 KiB block loads, so
-// the HBM stream never drains between tiles.  Partial sums meet in LDS once, at the end, and are
-// added in wave order (deterministic).
+// Work split.  A workgroup has S x TW wavefronts: wave (s, tw) owns the k slice s of S (groups
+// [g0, g1)) and, of the TW adjacent row tiles the workgroup visits per step, tile tw; steps
+// advance by gridDim.x * TW tiles.  x is staged once per workgroup in LDS.  Each wave walks the
+// flattened list of (tile, group) blocks it owns through a register ring of P outstanding 1 KiB
+// block loads, so the HBM stream never drains between tiles.  With S > 1 the partial sums meet in
+// LDS once, at the end, and are added in slice order (deterministic, no float atomics).
 //
 // Per block: 3 shifts + 4 v_and_or_b32 per packed word turn nibbles into bf16 (128 + q) pairs,
 // four 16x16x32 MFMAs contract them with x (row 0 of the A operand; the other 15 rows repeat it
 // and are ignored), four more against all-ones give sum(x) in the same accumulator slot, and
 //     acc += s * (D - (128 + z) * X)
 // applies zero point and scale once per group.
+#include <cstdlib>
+
 #include "common.hpp"
 
 namespace dmr {
@@ -19,6 +21,7 @@ namespace dmr {
 namespace {
 
 constexpr uint32_t kOnes = 0x3F803F80u;    // bf16 pair (1.0, 1.0)
+constexpr int kMaxXLoads = 8;              // x staging: up to 8 uint4 per thread
 
 // (a & mask) | c in one VALU instruction; mask rides the scalar operand slot.
 __device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) {
@@ -32,39 +35,46 @@ struct Item {
     uint32_t szw;
 };
 
-template <int P, bool OUT_F32>
+template <int P, bool NTW, bool NTS>
 __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__ wt,
                                                        const uint32_t *__restrict__ sz,
                                                        const uint16_t *__restrict__ x,
                                                        void *__restrict__ y, int groups, int tiles,
-                                                       int slice_uint4 /* LDS uint4 per wave slice */) {
-    extern __shared__ uint4 smem[];
+                                                       int S, int nT_max, int out_f32) {
+    extern __shared__ uint4 smem[];          // x (16 uint4 per group), then red[nT_max][TW][S][16]
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, lives in an SGPR
-    const int S = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform (SGPR)
+    const int nw = blockDim.x >> 6;
+    const int TW = nw / S;
+    const int s = wave % S, tw = wave / S;
     const int c = lane >> 4, j = lane & 15;
-    const int g0 = (groups * wave) / S;
-    const int GW = (groups * (wave + 1)) / S - g0;
-    const int nT = (tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int g0 = (groups * s) / S;
+    const int GW = (groups * (s + 1)) / S - g0;
+    const int t_first = (int)blockIdx.x * TW + tw;
+    const int t_step = (int)gridDim.x * TW;
+    const int nT = t_first < tiles ? (tiles - t_first + t_step - 1) / t_step : 0;
     const int items = nT * GW;
 
-    // wave-private copy of x[128 g0 .. 128 g1): 16 uint4 per group
-    uint4 *xs = smem + wave * slice_uint4;
-    {
-        const uint4 *src = reinterpret_cast<const uint4 *>(x) + (int64_t)g0 * 16;
-        for (int i = lane; i < GW * 16; i += 64) xs[i] = src[i];
+    // x -> registers now (oldest loads), -> LDS after the first weight loads have been issued
+    uint4 xreg[kMaxXLoads];
+    const int x16 = groups * 16;
+#pragma unroll
+    for (int u = 0; u < kMaxXLoads; ++u) {
+        const int i = (int)threadIdx.x + u * (int)blockDim.x;
+        xreg[u] = reinterpret_cast<const uint4 *>(x)[i < x16 ? i : 0];
     }
-    float *red = reinterpret_cast<float *>(smem + S * slice_uint4);   // [nT][S][16]
 
-    // Issue pointer (it, ig) walks (tile slot, group in slice) and saturates at the last block,
+    // Issue pointer (it, ig) walks (tile step, group in slice) and saturates at the last block,
     // so every issue is unconditional (the waitcnt bookkeeping stays exact); a wave whose item
     // count is not a multiple of P re-reads its last block up to P - 1 times from cache.
     int it = 0, ig = 0, issued = 0;
     Item ring[P];
     auto issue = [&](Item &dst) {
-        const int64_t block = (int64_t)((int)blockIdx.x + it * (int)gridDim.x) * groups + (g0 + ig);
-        dst.w = wt[block * 64 + lane];
-        dst.szw = sz[block * kTileRows + j];
+        const int64_t block = (int64_t)(t_first + it * t_step) * groups + (g0 + ig);
+        const uint4 *pw = wt + block * 64 + lane;
+        const uint32_t *ps = sz + block * kTileRows + j;
+        dst.w = NTW ? load_stream(pw) : *pw;
+        dst.szw = NTS ? load_stream(ps) : *ps;
         if (issued + 1 < items) {
             ++issued;
             if (++ig == GW) {
@@ -73,7 +83,19 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
             }
         }
     };
+    if (items > 0) {
+#pragma unroll
+        for (int p = 0; p < P; ++p) issue(ring[p]);
+    }
+#pragma unroll
+    for (int u = 0; u < kMaxXLoads; ++u) {
+        const int i = (int)threadIdx.x + u * (int)blockDim.x;
+        if (i < x16) smem[i] = xreg[u];
+    }
+    __syncthreads();
 
+    const uint4 *xs = smem + g0 * 16;
+    float *red = reinterpret_cast<float *>(smem + x16);
     Frag ones;
     ones.u = make_uint4(kOnes, kOnes, kOnes, kOnes);
     const uint32_t mask = 0x000F000Fu, magic = 0x43004300u;
@@ -96,11 +118,21 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
             d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t].v, b.v, d, 0, 0, 0);
             xsum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t].v, ones.v, xsum, 0, 0, 0);
         }
-        const float s = __uint_as_float(cur.szw << 16);
+        const float sc = __uint_as_float(cur.szw << 16);
         const float cz = __uint_as_float(cur.szw & 0xFFFF0000u);   // -(128 + z)
-        acc = fmaf(s, fmaf(cz, xsum[0], d[0]), acc);
+        acc = fmaf(sc, fmaf(cz, xsum[0], d[0]), acc);
         if (++cg == GW) {
-            if (lane < 16) red[(ct * S + wave) * 16 + lane] = acc;
+            if (lane < 16) {
+                if (S > 1) {
+                    red[((ct * TW + tw) * S + s) * 16 + lane] = acc;
+                } else {
+                    const int64_t n = (int64_t)(t_first + ct * t_step) * kTileRows + lane;
+                    if (out_f32)
+                        reinterpret_cast<float *>(y)[n] = acc;
+                    else
+                        reinterpret_cast<uint16_t *>(y)[n] = f32_to_bf16(acc);
+                }
+            }
             acc = 0.f;
             cg = 0;
             ++ct;
@@ -108,8 +140,6 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
     };
 
     if (items > 0) {
-#pragma unroll
-        for (int p = 0; p < P; ++p) issue(ring[p]);
         int base = 0;
         for (; base + P < items; base += P) {
 #pragma unroll
@@ -123,17 +153,44 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
         for (int p = 0; p < P; ++p)
             if (base + p < items) compute(ring[p]);
     }
+    if (S == 1) return;
+
     __syncthreads();
-    for (int e = threadIdx.x; e < nT * 16; e += blockDim.x) {
-        const int slot = e >> 4, col = e & 15;
-        float sum = 0.f;
-        for (int s = 0; s < S; ++s) sum += red[(slot * S + s) * 16 + col];
-        const int64_t n = (int64_t)((int)blockIdx.x + slot * (int)gridDim.x) * kTileRows + col;
-        if (OUT_F32)
-            reinterpret_cast<float *>(y)[n] = sum;
-        else
-            reinterpret_cast<uint16_t *>(y)[n] = f32_to_bf16(sum);
+    for (int e = threadIdx.x; e < nT_max * TW * 16; e += blockDim.x) {
+        const int col = e & 15, slot = e >> 4;            // slot = step * TW + tile lane
+        const int tile = (int)blockIdx.x * TW + (slot % TW) + (slot / TW) * t_step;
+        if (tile < tiles) {
+            float sum = 0.f;
+            for (int q = 0; q < S; ++q) sum += red[(slot * S + q) * 16 + col];
+            const int64_t n = (int64_t)tile * kTileRows + col;
+            if (out_f32)
+                reinterpret_cast<float *>(y)[n] = sum;
+            else
+                reinterpret_cast<uint16_t *>(y)[n] = f32_to_bf16(sum);
+        }
     }
+}
+
+int env_int(const char *name, int fallback) {
+    const char *v = std::getenv(name);
+    return (v && *v) ? std::atoi(v) : fallback;
+}
+
+struct GemvPlan {
+    int S, TW, grid;
+};
+
+// Launch shape from (groups, tiles), after a sweep of (S, TW, grid, P) on MI355X at the four
+// decoder shapes: up to two workgroups' worth of tiles per CU runs as one workgroup of 16 k
+// slices per tile; beyond that, 8 slices and two workgroups per CU, each looping over tiles.
+GemvPlan plan_for(int groups, int tiles, int cus) {
+    GemvPlan p;
+    p.TW = 1;
+    p.S = tiles <= 2 * cus ? 16 : 8;
+    while (p.S > groups) p.S >>= 1;
+    const int resident = cus * (16 / p.S);
+    p.grid = tiles < resident ? tiles : resident;
+    return p;
 }
 
 }  // namespace
@@ -151,48 +208,39 @@ hipError_t launch_w4_gemv(const LayerView &L, const uint16_t *x, void *y, bool o
         else
             cus = 256;
     }
-    // A CU holds 16 of these wavefronts.  With S waves per workgroup, cus * 16 / S workgroups are
-    // resident at once; take the largest S (most k slices, shortest per-wave stream) whose grid
-    // still fits in one round, then a grid that divides the tile count when one exists.
-    int S = 16;
-    while (S > groups) S >>= 1;
-    while (S > 4 && tiles > cus && tiles < 2 * cus && tiles > cus * (16 / S)) S >>= 1;
-    int grid = tiles < cus * (16 / S) ? tiles : cus * (16 / S);
-    if (tiles > grid) {
-        for (int gsz = grid; gsz >= grid / 2; --gsz)
-            if (tiles % gsz == 0) {
-                grid = gsz;
-                break;
-            }
-    }
-    const int nT = (tiles + grid - 1) / grid;
-    const int gw_max = (groups + S - 1) / S;
-    const int slice_uint4 = gw_max * 16;
-    const size_t lds = (size_t)S * slice_uint4 * sizeof(uint4) + (size_t)nT * S * 16 * sizeof(float);
+    GemvPlan plan = plan_for(groups, tiles, cus);
+    // sweep overrides (unset in production)
+    plan.S = env_int("DMR_GEMV_S", plan.S);
+    plan.TW = env_int("DMR_GEMV_TW", plan.TW);
+    plan.grid = env_int("DMR_GEMV_GRID", plan.grid);
+    const int ntw = env_int("DMR_GEMV_NTW", 1), nts = env_int("DMR_GEMV_NTS", 1);
+    if (plan.S < 1 || plan.TW < 1 || plan.S * plan.TW > 16 || plan.S > groups || plan.grid < 1)
+        return hipErrorInvalidValue;
+    const int nw = plan.S * plan.TW;
+    if (groups * 16 > kMaxXLoads * nw * 64) return hipErrorInvalidValue;   // x staging capacity
+    const int t_step = plan.grid * plan.TW;
+    const int nT_max = (tiles + t_step - 1) / t_step;
+    const int gw_max = (groups + plan.S - 1) / plan.S;
+    const size_t lds = (size_t)groups * 16 * sizeof(uint4) +
+                       (plan.S > 1 ? (size_t)nT_max * nw * 16 * sizeof(float) : 0);
     if (lds > 64 * 1024) return hipErrorInvalidValue;   // caller falls back to the general kernel
-    // Ring depth: the P in 4..8 that wastes the fewest re-reads (largest on ties); short streams
-    // take P = items.
-    const int items_max = nT * gw_max;
+
+    // Ring depth: four blocks in flight per wave measured best (more costs registers, hence
+    // resident waves); shorter streams take their whole length.
+    const int items_max = nT_max * gw_max;
     int P = items_max < 4 ? items_max : 4;
-    if (items_max >= 4) {
-        int best_waste = 1 << 30;
-        for (int cand = 4; cand <= 8; ++cand) {
-            const int waste = (items_max + cand - 1) / cand * cand - items_max;
-            if (waste <= best_waste) {
-                best_waste = waste;
-                P = cand;
-            }
-        }
-    }
-    const dim3 g(grid), b(S * 64);
-#define DMR_GEMV_CASE(PP)                                                                              \
-    case PP:                                                                                           \
-        if (out_f32)                                                                                   \
-            hipLaunchKernelGGL((w4_gemv_kernel<PP, true>), g, b, lds, stream, L.wt, L.sz, x, y, groups, \
-                               tiles, slice_uint4);                                                    \
-        else                                                                                           \
-            hipLaunchKernelGGL((w4_gemv_kernel<PP, false>), g, b, lds, stream, L.wt, L.sz, x, y, groups, \
-                               tiles, slice_uint4);                                                    \
+    P = env_int("DMR_GEMV_P", P);
+    const dim3 g(plan.grid), b(nw * 64);
+    const int of = out_f32 ? 1 : 0;
+#define DMR_GEMV_LAUNCH(PP, A, B)                                                                     \
+    hipLaunchKernelGGL((w4_gemv_kernel<PP, A, B>), g, b, lds, stream, L.wt, L.sz, x, y, groups, tiles, \
+                       plan.S, nT_max, of)
+#define DMR_GEMV_CASE(PP)                                                                             \
+    case PP:                                                                                          \
+        if (ntw && nts) DMR_GEMV_LAUNCH(PP, true, true);                                              \
+        else if (ntw) DMR_GEMV_LAUNCH(PP, true, false);                                               \
+        else if (nts) DMR_GEMV_LAUNCH(PP, false, true);                                               \
+        else DMR_GEMV_LAUNCH(PP, false, false);                                                       \
         break;
     switch (P) {
         DMR_GEMV_CASE(1) DMR_GEMV_CASE(2) DMR_GEMV_CASE(3) DMR_GEMV_CASE(4) DMR_GEMV_CASE(5)
@@ -200,6 +248,7 @@ hipError_t launch_w4_gemv(const LayerView &L, const uint16_t *x, void *y, bool o
         default: return hipErrorInvalidValue;
     }
 #undef DMR_GEMV_CASE
+#undef DMR_GEMV_LAUNCH
     return hipGetLastError();
 }
 

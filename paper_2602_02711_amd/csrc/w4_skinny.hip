@@ -33,7 +33,7 @@ __device__ __forceinline__ void load_group(GroupRegs<MT> &r, const uint4 *__rest
                                            const uint16_t *__restrict__ x, int64_t block, int lane,
                                            int64_t M, int64_t K, int64_t k0) {
     const int c = lane >> 4, j = lane & 15;
-    r.w = wt[block * 64 + lane];
+    r.w = load_stream(wt + block * 64 + lane);
     r.szw = sz[block * kTileRows + j];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
