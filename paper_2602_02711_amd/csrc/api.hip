@@ -119,6 +119,10 @@ dmr_status_t dmr_qlinear_bf16_forward(const uint16_t *d_w, const uint16_t *d_x, 
     if (need > 0 && (!d_ws || ws_bytes < need)) return DMR_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool f32 = out == DMR_OUT_FP32;
+    if (M == 1) {
+        const hipError_t e = dmr::launch_bf16_gemv(d_w, d_x, K, N, d_y, f32, s);
+        if (e != hipErrorInvalidValue) return hip_status(e);   // else: K outside its range
+    }
     if (M <= kSkinnyMaxM) return hip_status(dmr::launch_bf16_skinny(d_w, d_x, M, K, N, d_y, f32, s));
     return hip_status(dmr::launch_bf16_gemm(d_w, d_x, M, K, N, d_y, f32, s));
 }
