@@ -153,6 +153,14 @@ def main():
         })
         log(f"[bench] {per_shape[-1]}")
 
+    # HBM traffic of the dominant kernel, from the committed rocprofv3 counter summary (offline runs
+    # of this same command under --pmc FETCH_SIZE / WRITE_SIZE); null when no summary is present.
+    traffic = None
+    traffic_file = os.path.join(ROOT, "profiles", "decode_sweep_w4_gemv_traffic.json")
+    if os.path.exists(traffic_file):
+        with open(traffic_file) as fh:
+            traffic = json.load(fh).get("traffic")
+
     result = {
         "metric": "INT4 W4A16 linear achieved HBM GB/s at M=1 and speedup vs bf16 linear",
         "value": round(value, 1),
@@ -182,13 +190,13 @@ def main():
         "us_per_decode_sweep": round(wall_ms * 1e3, 2),
         "per_shape": per_shape,
         "roofline": {
-            "kernel": "w4_skinny_kernel<1,false> (INT4 weight-streaming MFMA GEMV)",
+            "kernel": "w4_gemv_kernel (INT4 weight-streaming MFMA GEMV, all four shapes of a step)",
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": None,
+            "traffic": None if traffic is None else round(traffic),
             "bytes_per_launch": step_bytes // launches,
             "avg_launch_us": round(ev_ms * 1e3 / launches, 3),
         },
