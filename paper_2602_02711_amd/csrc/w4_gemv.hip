@@ -21,7 +21,6 @@ namespace dmr {
 namespace {
 
 constexpr uint32_t kOnes = 0x3F803F80u;    // bf16 pair (1.0, 1.0)
-constexpr int kMaxXLoads = 8;              // x staging: up to 8 uint4 per thread
 
 // (a & mask) | c in one VALU instruction; mask rides the scalar operand slot.
 __device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) {
@@ -35,31 +34,31 @@ struct Item {
     uint32_t szw;
 };
 
-template <int P, bool NTW, bool NTS>
+template <int P, int XL>
 __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__ wt,
                                                        const uint32_t *__restrict__ sz,
                                                        const uint16_t *__restrict__ x,
                                                        void *__restrict__ y, int groups, int tiles,
-                                                       int S, int nT_max, int out_f32) {
+                                                       int lgS, int lgTW, int nT_max, int out_f32) {
     extern __shared__ uint4 smem[];          // x (16 uint4 per group), then red[nT_max][TW][S][16]
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform (SGPR)
-    const int nw = blockDim.x >> 6;
-    const int TW = nw / S;
-    const int s = wave % S, tw = wave / S;
+    const int S = 1 << lgS, TW = 1 << lgTW;
+    const int s = wave & (S - 1), tw = wave >> lgS;
     const int c = lane >> 4, j = lane & 15;
-    const int g0 = (groups * s) / S;
-    const int GW = (groups * (s + 1)) / S - g0;
-    const int t_first = (int)blockIdx.x * TW + tw;
-    const int t_step = (int)gridDim.x * TW;
-    const int nT = t_first < tiles ? (tiles - t_first + t_step - 1) / t_step : 0;
+    const int g0 = (groups * s) >> lgS;
+    const int GW = ((groups * (s + 1)) >> lgS) - g0;
+    const int t_first = ((int)blockIdx.x << lgTW) + tw;
+    const int t_step = (int)gridDim.x << lgTW;
+    // tiles go round-robin over the grid: a wave gets nT_max of them, or one fewer
+    const int nT = nT_max - ((t_first + (nT_max - 1) * t_step >= tiles) ? 1 : 0);
     const int items = nT * GW;
 
     // x -> registers now (oldest loads), -> LDS after the first weight loads have been issued
-    uint4 xreg[kMaxXLoads];
+    uint4 xreg[XL];
     const int x16 = groups * 16;
 #pragma unroll
-    for (int u = 0; u < kMaxXLoads; ++u) {
+    for (int u = 0; u < XL; ++u) {
         const int i = (int)threadIdx.x + u * (int)blockDim.x;
         xreg[u] = reinterpret_cast<const uint4 *>(x)[i < x16 ? i : 0];
     }
@@ -71,10 +70,8 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
     Item ring[P];
     auto issue = [&](Item &dst) {
         const int64_t block = (int64_t)(t_first + it * t_step) * groups + (g0 + ig);
-        const uint4 *pw = wt + block * 64 + lane;
-        const uint32_t *ps = sz + block * kTileRows + j;
-        dst.w = NTW ? load_stream(pw) : *pw;
-        dst.szw = NTS ? load_stream(ps) : *ps;
+        dst.w = load_stream(wt + block * 64 + lane);
+        dst.szw = load_stream(sz + block * kTileRows + j);
         if (issued + 1 < items) {
             ++issued;
             if (++ig == GW) {
@@ -88,7 +85,7 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
         for (int p = 0; p < P; ++p) issue(ring[p]);
     }
 #pragma unroll
-    for (int u = 0; u < kMaxXLoads; ++u) {
+    for (int u = 0; u < XL; ++u) {
         const int i = (int)threadIdx.x + u * (int)blockDim.x;
         if (i < x16) smem[i] = xreg[u];
     }
@@ -123,8 +120,8 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
         acc = fmaf(sc, fmaf(cz, xsum[0], d[0]), acc);
         if (++cg == GW) {
             if (lane < 16) {
-                if (S > 1) {
-                    red[((ct * TW + tw) * S + s) * 16 + lane] = acc;
+                if (lgS > 0) {
+                    red[((((ct << lgTW) + tw) << lgS) + s) * 16 + lane] = acc;
                 } else {
                     const int64_t n = (int64_t)(t_first + ct * t_step) * kTileRows + lane;
                     if (out_f32)
@@ -153,20 +150,23 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
         for (int p = 0; p < P; ++p)
             if (base + p < items) compute(ring[p]);
     }
-    if (S == 1) return;
+    if (lgS == 0) return;
 
+    // Cross-slice sum: thread e = (slot, column, slice) with the slice index fastest, so the S
+    // partials of one output sit in S adjacent lanes and fold in a fixed xor tree.
     __syncthreads();
-    for (int e = threadIdx.x; e < nT_max * TW * 16; e += blockDim.x) {
-        const int col = e & 15, slot = e >> 4;            // slot = step * TW + tile lane
-        const int tile = (int)blockIdx.x * TW + (slot % TW) + (slot / TW) * t_step;
-        if (tile < tiles) {
-            float sum = 0.f;
-            for (int q = 0; q < S; ++q) sum += red[(slot * S + q) * 16 + col];
+    const int total = (nT_max << (lgTW + lgS)) * 16;
+    for (int e = threadIdx.x; e < total; e += blockDim.x) {
+        const int q = e & (S - 1), col = (e >> lgS) & 15, slot = e >> (lgS + 4);
+        float v = red[((slot << lgS) + q) * 16 + col];
+        for (int m = S >> 1; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+        const int tile = ((int)blockIdx.x << lgTW) + (slot & (TW - 1)) + (slot >> lgTW) * t_step;
+        if (q == 0 && tile < tiles) {
             const int64_t n = (int64_t)tile * kTileRows + col;
             if (out_f32)
-                reinterpret_cast<float *>(y)[n] = sum;
+                reinterpret_cast<float *>(y)[n] = v;
             else
-                reinterpret_cast<uint16_t *>(y)[n] = f32_to_bf16(sum);
+                reinterpret_cast<uint16_t *>(y)[n] = f32_to_bf16(v);
         }
     }
 }
@@ -213,11 +213,17 @@ hipError_t launch_w4_gemv(const LayerView &L, const uint16_t *x, void *y, bool o
     plan.S = env_int("DMR_GEMV_S", plan.S);
     plan.TW = env_int("DMR_GEMV_TW", plan.TW);
     plan.grid = env_int("DMR_GEMV_GRID", plan.grid);
-    const int ntw = env_int("DMR_GEMV_NTW", 1), nts = env_int("DMR_GEMV_NTS", 1);
-    if (plan.S < 1 || plan.TW < 1 || plan.S * plan.TW > 16 || plan.S > groups || plan.grid < 1)
+    auto log2_exact = [](int v) {
+        int l = 0;
+        while ((1 << l) < v) ++l;
+        return (1 << l) == v ? l : -1;
+    };
+    const int lgS = log2_exact(plan.S), lgTW = log2_exact(plan.TW);
+    if (lgS < 0 || lgTW < 0 || plan.S * plan.TW > 16 || plan.S > groups || plan.grid < 1)
         return hipErrorInvalidValue;
     const int nw = plan.S * plan.TW;
-    if (groups * 16 > kMaxXLoads * nw * 64) return hipErrorInvalidValue;   // x staging capacity
+    const int xl_need = (groups * 16 + nw * 64 - 1) / (nw * 64);   // x staging loads per thread
+    if (xl_need > 8) return hipErrorInvalidValue;
     const int t_step = plan.grid * plan.TW;
     const int nT_max = (tiles + t_step - 1) / t_step;
     const int gw_max = (groups + plan.S - 1) / plan.S;
@@ -232,19 +238,18 @@ hipError_t launch_w4_gemv(const LayerView &L, const uint16_t *x, void *y, bool o
     P = env_int("DMR_GEMV_P", P);
     const dim3 g(plan.grid), b(nw * 64);
     const int of = out_f32 ? 1 : 0;
-#define DMR_GEMV_LAUNCH(PP, A, B)                                                                     \
-    hipLaunchKernelGGL((w4_gemv_kernel<PP, A, B>), g, b, lds, stream, L.wt, L.sz, x, y, groups, tiles, \
-                       plan.S, nT_max, of)
-#define DMR_GEMV_CASE(PP)                                                                             \
-    case PP:                                                                                          \
-        if (ntw && nts) DMR_GEMV_LAUNCH(PP, true, true);                                              \
-        else if (ntw) DMR_GEMV_LAUNCH(PP, true, false);                                               \
-        else if (nts) DMR_GEMV_LAUNCH(PP, false, true);                                               \
-        else DMR_GEMV_LAUNCH(PP, false, false);                                                       \
+#define DMR_GEMV_LAUNCH(PP, XX)                                                                        \
+    hipLaunchKernelGGL((w4_gemv_kernel<PP, XX>), g, b, lds, stream, L.wt, L.sz, x, y, groups, tiles, lgS, \
+                       lgTW, nT_max, of)
+#define DMR_GEMV_CASE(PP)                                                                              \
+    case PP:                                                                                           \
+        if (xl_need <= 1) DMR_GEMV_LAUNCH(PP, 1);                                                      \
+        else if (xl_need <= 2) DMR_GEMV_LAUNCH(PP, 2);                                                 \
+        else if (xl_need <= 4) DMR_GEMV_LAUNCH(PP, 4);                                                 \
+        else DMR_GEMV_LAUNCH(PP, 8);                                                                   \
         break;
     switch (P) {
-        DMR_GEMV_CASE(1) DMR_GEMV_CASE(2) DMR_GEMV_CASE(3) DMR_GEMV_CASE(4) DMR_GEMV_CASE(5)
-        DMR_GEMV_CASE(6) DMR_GEMV_CASE(7) DMR_GEMV_CASE(8)
+        DMR_GEMV_CASE(1) DMR_GEMV_CASE(2) DMR_GEMV_CASE(3) DMR_GEMV_CASE(4)
         default: return hipErrorInvalidValue;
     }
 #undef DMR_GEMV_CASE
