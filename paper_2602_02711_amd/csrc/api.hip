@@ -100,6 +100,10 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
         const hipError_t e = dmr::launch_w4_gemv(L, d_x, d_y, f32, s);
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: shape outside its range
     }
+    if (M >= 2 && M <= 16) {
+        const hipError_t e = dmr::launch_w4_stream(L, d_x, M, d_y, f32, s);
+        if (e != hipErrorInvalidValue) return hip_status(e);   // else: activations do not fit LDS
+    }
     if (M <= kSkinnyMaxM) return hip_status(dmr::launch_w4_skinny(L, d_x, M, d_y, f32, s));
     return hip_status(dmr::launch_w4_gemm(L, d_x, M, d_y, f32, s));
 }

@@ -85,6 +85,9 @@ hipError_t launch_w4_gemv(const LayerView &L, const uint16_t *x, void *y, bool o
 // M == 1 bf16 kernel; hipErrorInvalidValue (nothing launched) for K beyond its range.
 hipError_t launch_bf16_gemv(const uint16_t *w, const uint16_t *x, int64_t K, int64_t N, void *y,
                             bool out_f32, hipStream_t stream);
+// 2 <= M <= 16 streaming kernel; hipErrorInvalidValue (nothing launched) when the activations do not fit LDS.
+hipError_t launch_w4_stream(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+                            hipStream_t stream);
 hipError_t launch_hbm_read_probe(const void *buf, size_t bytes, uint32_t *sink, int blocks,
                                  hipStream_t stream);
 hipError_t launch_w4_skinny(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,

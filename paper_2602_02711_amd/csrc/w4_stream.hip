@@ -1,0 +1,206 @@
+// W4A16 streaming kernel for 2 <= M <= 16: a small group of parallel rollouts each taking one
+// low-precision step.  Same structure as the M == 1 GEMV (S k slices x TW tiles of wavefronts per
+// workgroup, a register ring of P outstanding 1 KiB block loads per wave, nibble -> bf16 unpack,
+// 16x16x32 MFMAs, group-wise zero point and scale), with three differences:
+//   - all M activation rows are staged in LDS (row stride padded by 16 bytes so that the 16
+//     operand rows of a wave fall in distinct banks); lanes of rows >= M re-read row M - 1 and
+//     their results are never stored;
+//   - the accumulator is the whole 16 x 16 MFMA tile (4 registers per lane);
+//   - the cross-slice sum happens at every tile step through one reused LDS buffer, bracketed by
+//     two barriers.  Every wave executes the same nT_max * GW_max item slots and therefore the same
+//     number of barriers whatever its share of the work: slots beyond a wave's work re-read its last
+//     block from cache and skip the arithmetic.
+#include "common.hpp"
+
+namespace dmr {
+
+namespace {
+
+constexpr uint32_t kOnes = 0x3F803F80u;    // bf16 pair (1.0, 1.0)
+
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) {
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(c));
+    return r;
+}
+
+struct Item {
+    uint4 w;
+    uint32_t szw;
+};
+
+template <int P>
+__global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict__ wt,
+                                                         const uint32_t *__restrict__ sz,
+                                                         const uint16_t *__restrict__ x,
+                                                         void *__restrict__ y, int M, int64_t N,
+                                                         int groups, int tiles, int lgS, int lgTW,
+                                                         int nT_max, int gw_max, int out_f32) {
+    extern __shared__ uint4 smem[];   // x rows [M][groups * 16 + 1] uint4, then red[TW][S][4][64] floats
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int S = 1 << lgS, TW = 1 << lgTW;
+    const int s = wave & (S - 1), tw = wave >> lgS;
+    const int c = lane >> 4, j = lane & 15;
+    const int g0 = (groups * s) >> lgS;
+    const int GW = ((groups * (s + 1)) >> lgS) - g0;          // 0 <= GW <= gw_max
+    const int t_first = ((int)blockIdx.x << lgTW) + tw;
+    const int t_step = (int)gridDim.x << lgTW;
+    const int slots = nT_max * gw_max;                          // the same for every wave
+    const int x16 = groups * 16, row_stride = x16 + 1;
+
+    // Slot (step, gi) -> block to load, clamped into this wave's valid range (or to the matrix's last
+    // tile if it owns none): every load is unconditional and in bounds.
+    int is = 0, ig = 0;   // issue pointer
+    Item ring[P];
+    auto issue = [&](Item &dst) {
+        int tile = t_first + is * t_step;
+        tile = tile < tiles ? tile : tiles - 1;
+        int g = g0 + (ig < GW ? ig : GW - 1);
+        g = g < 0 ? 0 : (g < groups ? g : groups - 1);
+        const int64_t block = (int64_t)tile * groups + g;
+        dst.w = load_stream(wt + block * 64 + lane);
+        dst.szw = load_stream(sz + block * kTileRows + j);
+        if (++ig == gw_max) {
+            ig = 0;
+            if (is + 1 < nT_max) ++is;      // saturate at the last step
+        }
+    };
+#pragma unroll
+    for (int p = 0; p < P; ++p) issue(ring[p]);
+
+    // stage the M activation rows
+    for (int r = 0; r < M; ++r)
+        for (int i = threadIdx.x; i < x16; i += blockDim.x)
+            smem[r * row_stride + i] = reinterpret_cast<const uint4 *>(x)[(int64_t)r * x16 + i];
+    __syncthreads();
+
+    float *red = reinterpret_cast<float *>(smem + M * row_stride);
+    const uint4 *xrow = smem + (j < M ? j : M - 1) * row_stride + c * 4;
+    Frag ones;
+    ones.u = make_uint4(kOnes, kOnes, kOnes, kOnes);
+    const uint32_t mask = 0x000F000Fu, magic = 0x43004300u;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    int cs = 0, cg = 0;   // consume pointer: (tile step, slot within step)
+
+    auto consume = [&](const Item &cur) {
+        const int tile = t_first + cs * t_step;
+        if (cg < GW && tile < tiles) {
+            const uint4 *xp = xrow + (g0 + cg) * 16;
+            Frag a[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) a[t].u = xp[t];
+            const uint32_t words[4] = {cur.w.x, cur.w.y, cur.w.z, cur.w.w};
+            f32x4 d = {0.f, 0.f, 0.f, 0.f}, xsum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                Frag b;
+                b.w[0] = and_or(words[t], mask, magic);
+                b.w[1] = and_or(words[t] >> 4, mask, magic);
+                b.w[2] = and_or(words[t] >> 8, mask, magic);
+                b.w[3] = and_or(words[t] >> 12, mask, magic);
+                d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t].v, b.v, d, 0, 0, 0);
+                xsum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t].v, ones.v, xsum, 0, 0, 0);
+            }
+            const float sc = __uint_as_float(cur.szw << 16);
+            const float cz = __uint_as_float(cur.szw & 0xFFFF0000u);   // -(128 + z)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[r] = fmaf(sc, fmaf(cz, xsum[r], d[r]), acc[r]);
+        }
+        if (++cg == gw_max) {
+            // tile step finished: every wave arrives here exactly once per step
+#pragma unroll
+            for (int r = 0; r < 4; ++r) red[(((tw << lgS) + s) * 4 + r) * 64 + lane] = acc[r];
+            __syncthreads();
+            const int total = (TW << lgS) * 256;
+            for (int e = threadIdx.x; e < total; e += blockDim.x) {
+                const int q = e & (S - 1), l = (e >> lgS) & 63, r = (e >> (lgS + 6)) & 3,
+                          w2 = e >> (lgS + 8);
+                float v = red[(((w2 << lgS) + q) * 4 + r) * 64 + l];
+                for (int m = S >> 1; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+                const int t2 = ((int)blockIdx.x << lgTW) + w2 + cs * t_step;
+                const int row = (l >> 4) * 4 + r;
+                if (q == 0 && t2 < tiles && row < M) {
+                    const int64_t o = (int64_t)row * N + (int64_t)t2 * kTileRows + (l & 15);
+                    if (out_f32)
+                        reinterpret_cast<float *>(y)[o] = v;
+                    else
+                        reinterpret_cast<uint16_t *>(y)[o] = f32_to_bf16(v);
+                }
+            }
+            __syncthreads();
+            acc = f32x4{0.f, 0.f, 0.f, 0.f};
+            cg = 0;
+            ++cs;
+        }
+    };
+
+    int base = 0;
+    for (; base + P < slots; base += P) {
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const Item cur = ring[p];
+            issue(ring[p]);
+            consume(cur);
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+        if (base + p < slots) consume(ring[p]);
+}
+
+}  // namespace
+
+hipError_t launch_w4_stream(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+                            hipStream_t stream) {
+    if (M < 2 || M > 16) return hipErrorInvalidValue;
+    const int groups = (int)(L.K / kGroup);
+    const int tiles = (int)(L.N / kTileRows);
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            cus = v;
+        else
+            cus = 256;
+    }
+    int S = 16;
+    while (S > groups) S >>= 1;
+    const int TW = 16 / S;
+    int lgS = 0, lgTW = 0;
+    while ((1 << lgS) < S) ++lgS;
+    while ((1 << lgTW) < TW) ++lgTW;
+    const int nw = S * TW;
+    const int wgs_needed = (tiles + TW - 1) / TW;
+    const int grid = wgs_needed < cus ? wgs_needed : cus;
+    const int t_step = grid * TW;
+    const int nT_max = (tiles + t_step - 1) / t_step;
+    const int gw_max = (groups + S - 1) / S;
+    const size_t lds = (size_t)M * (groups * 16 + 1) * sizeof(uint4) + (size_t)nw * 4 * 64 * sizeof(float);
+    if (lds > 160 * 1024) return hipErrorInvalidValue;   // activations do not fit: general kernel
+    const int slots = nT_max * gw_max;
+    const int P = slots < 4 ? slots : 4;
+    const int of = out_f32 ? 1 : 0;
+    const int iM = (int)M;
+    static bool attr_set[5] = {false, false, false, false, false};
+#define DMR_STREAM_CASE(PP)                                                                             \
+    case PP: {                                                                                          \
+        if (!attr_set[PP]) {                                                                            \
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_stream_kernel<PP>), \
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); \
+            if (e != hipSuccess) return e;                                                              \
+            attr_set[PP] = true;                                                                        \
+        }                                                                                               \
+        hipLaunchKernelGGL((w4_stream_kernel<PP>), dim3(grid), dim3(nw * 64), lds, stream, L.wt, L.sz, x, y, \
+                           iM, L.N, groups, tiles, lgS, lgTW, nT_max, gw_max, of);                      \
+    } break;
+    switch (P) {
+        DMR_STREAM_CASE(1) DMR_STREAM_CASE(2) DMR_STREAM_CASE(3) DMR_STREAM_CASE(4)
+        default: return hipErrorInvalidValue;
+    }
+#undef DMR_STREAM_CASE
+    return hipGetLastError();
+}
+
+}  // namespace dmr
