@@ -10,11 +10,18 @@
 //     two barriers.  Every wave executes the same nT_max * GW_max item slots and therefore the same
 //     number of barriers whatever its share of the work: slots beyond a wave's work re-read its last
 //     block from cache and skip the arithmetic.
+#include <cstdlib>
+
 #include "common.hpp"
 
 namespace dmr {
 
 namespace {
+
+int env_int(const char *name, int fallback) {
+    const char *v = std::getenv(name);
+    return (v && *v) ? std::atoi(v) : fallback;
+}
 
 constexpr uint32_t kOnes = 0x3F803F80u;    // bf16 pair (1.0, 1.0)
 
@@ -36,7 +43,7 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
                                                          void *__restrict__ y, int M, int64_t N,
                                                          int groups, int tiles, int lgS, int lgTW,
                                                          int nT_max, int gw_max, int out_f32) {
-    extern __shared__ uint4 smem[];   // x rows [M][groups * 16 + 1] uint4, then red[TW][S][4][64] floats
+    extern __shared__ uint4 smem[];   // x rows [M][groups * 16 + 1] uint4, then red[TW][S][64] float4
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int S = 1 << lgS, TW = 1 << lgTW;
@@ -109,26 +116,50 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
         }
         if (++cg == gw_max) {
             // tile step finished: every wave arrives here exactly once per step
+            if (lgS == 0) {
+                // one slice: the wave owns the whole k range, its tile goes straight to memory
+                if (tile < tiles) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) red[(((tw << lgS) + s) * 4 + r) * 64 + lane] = acc[r];
-            __syncthreads();
-            const int total = (TW << lgS) * 256;
-            for (int e = threadIdx.x; e < total; e += blockDim.x) {
-                const int q = e & (S - 1), l = (e >> lgS) & 63, r = (e >> (lgS + 6)) & 3,
-                          w2 = e >> (lgS + 8);
-                float v = red[(((w2 << lgS) + q) * 4 + r) * 64 + l];
-                for (int m = S >> 1; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-                const int t2 = ((int)blockIdx.x << lgTW) + w2 + cs * t_step;
-                const int row = (l >> 4) * 4 + r;
-                if (q == 0 && t2 < tiles && row < M) {
-                    const int64_t o = (int64_t)row * N + (int64_t)t2 * kTileRows + (l & 15);
-                    if (out_f32)
-                        reinterpret_cast<float *>(y)[o] = v;
-                    else
-                        reinterpret_cast<uint16_t *>(y)[o] = f32_to_bf16(v);
+                    for (int r = 0; r < 4; ++r) {
+                        const int row = (lane >> 4) * 4 + r;
+                        if (row < M) {
+                            const int64_t o = (int64_t)row * N + (int64_t)tile * kTileRows + (lane & 15);
+                            if (out_f32)
+                                reinterpret_cast<float *>(y)[o] = acc[r];
+                            else
+                                reinterpret_cast<uint16_t *>(y)[o] = f32_to_bf16(acc[r]);
+                        }
+                    }
                 }
+            } else {
+                reinterpret_cast<f32x4 *>(red)[((tw << lgS) + s) * 64 + lane] = acc;
+                __syncthreads();
+                // wave w2 < TW adds the S partial tiles of tile lane w2 in slice order
+                if (wave < TW) {
+                    const f32x4 *part = reinterpret_cast<const f32x4 *>(red) + ((wave << lgS) * 64 + lane);
+                    f32x4 v = part[0];
+                    for (int q = 1; q < S; ++q) {
+                        const f32x4 u = part[q * 64];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[r] += u[r];
+                    }
+                    const int t2 = ((int)blockIdx.x << lgTW) + wave + cs * t_step;
+                    if (t2 < tiles) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const int row = (lane >> 4) * 4 + r;
+                            if (row < M) {
+                                const int64_t o = (int64_t)row * N + (int64_t)t2 * kTileRows + (lane & 15);
+                                if (out_f32)
+                                    reinterpret_cast<float *>(y)[o] = v[r];
+                                else
+                                    reinterpret_cast<uint16_t *>(y)[o] = f32_to_bf16(v[r]);
+                            }
+                        }
+                    }
+                }
+                __syncthreads();
             }
-            __syncthreads();
             acc = f32x4{0.f, 0.f, 0.f, 0.f};
             cg = 0;
             ++cs;
@@ -165,25 +196,67 @@ hipError_t launch_w4_stream(const LayerView &L, const uint16_t *x, int64_t M, vo
         else
             cus = 256;
     }
-    int S = 16;
-    while (S > groups) S >>= 1;
-    const int TW = 16 / S;
+    // Choose (waves per workgroup, k slices S, tile lanes TW = waves / S).  The activations' LDS
+    // footprint limits how many workgroups a CU holds.
+    const size_t xbytes = (size_t)M * (groups * 16 + 1) * sizeof(uint4);
+    // Measured on MI355X (sweep over waves per workgroup, S, ring depth at M = 2..16): few, long k
+    // slices win once there are several tiles per CU; one tile per CU wants all 16 slices.
+    int best_nw, best_S;
+    if (tiles >= 4 * cus) {
+        best_nw = 8;
+        best_S = 2;
+    } else if (tiles > cus) {
+        best_nw = 8;
+        best_S = 4;
+    } else {
+        best_nw = 16;
+        best_S = 16;
+    }
+    while (best_S > groups) best_S >>= 1;
+    int best_grid = 0;
+    {
+        const int TWc = best_nw / best_S;
+        const size_t lds_c = xbytes + (best_S > 1 ? (size_t)best_nw * 64 * sizeof(f32x4) : 0);
+        if (lds_c > 160 * 1024) {
+            best_nw = 0;
+        } else {
+            int per_cu = (int)((160 * 1024) / lds_c);
+            if (per_cu > 16 / best_nw) per_cu = 16 / best_nw;
+            const int wgs = (tiles + TWc - 1) / TWc;
+            best_grid = wgs < per_cu * cus ? wgs : per_cu * cus;
+        }
+    }
+    if (best_nw == 0) return hipErrorInvalidValue;   // activations do not fit LDS: general kernel
+    // sweep overrides (unset in production)
+    const int nw = env_int("DMR_STREAM_NW", best_nw), S = env_int("DMR_STREAM_S", best_S);
+    if (nw < 1 || nw > 16 || S < 1 || S > nw || S > groups || (nw & (nw - 1)) || (S & (S - 1)))
+        return hipErrorInvalidValue;
+    const int TW = nw / S;
+    int grid = best_grid;
+    if (nw != best_nw || S != best_S) {
+        const size_t lds_o = xbytes + (S > 1 ? (size_t)nw * 64 * sizeof(f32x4) : 0);
+        if (lds_o > 160 * 1024) return hipErrorInvalidValue;
+        int per_cu = (int)((160 * 1024) / lds_o);
+        if (per_cu > 16 / nw) per_cu = 16 / nw;
+        const int wgs = (tiles + TW - 1) / TW;
+        grid = wgs < per_cu * cus ? wgs : per_cu * cus;
+    }
+    grid = env_int("DMR_STREAM_GRID", grid);
+    if (grid < 1) return hipErrorInvalidValue;
     int lgS = 0, lgTW = 0;
     while ((1 << lgS) < S) ++lgS;
     while ((1 << lgTW) < TW) ++lgTW;
-    const int nw = S * TW;
-    const int wgs_needed = (tiles + TW - 1) / TW;
-    const int grid = wgs_needed < cus ? wgs_needed : cus;
     const int t_step = grid * TW;
     const int nT_max = (tiles + t_step - 1) / t_step;
     const int gw_max = (groups + S - 1) / S;
-    const size_t lds = (size_t)M * (groups * 16 + 1) * sizeof(uint4) + (size_t)nw * 4 * 64 * sizeof(float);
-    if (lds > 160 * 1024) return hipErrorInvalidValue;   // activations do not fit: general kernel
+    const size_t lds = xbytes + (S > 1 ? (size_t)nw * 64 * sizeof(f32x4) : 0);
     const int slots = nT_max * gw_max;
-    const int P = slots < 4 ? slots : 4;
+    int P = slots < 4 ? slots : 4;
+    P = env_int("DMR_STREAM_P", P);
+    if (P > slots) P = slots;
     const int of = out_f32 ? 1 : 0;
     const int iM = (int)M;
-    static bool attr_set[5] = {false, false, false, false, false};
+    static bool attr_set[9] = {false, false, false, false, false, false, false, false, false};
 #define DMR_STREAM_CASE(PP)                                                                             \
     case PP: {                                                                                          \
         if (!attr_set[PP]) {                                                                            \
@@ -197,6 +270,7 @@ hipError_t launch_w4_stream(const LayerView &L, const uint16_t *x, int64_t M, vo
     } break;
     switch (P) {
         DMR_STREAM_CASE(1) DMR_STREAM_CASE(2) DMR_STREAM_CASE(3) DMR_STREAM_CASE(4)
+        DMR_STREAM_CASE(5) DMR_STREAM_CASE(6) DMR_STREAM_CASE(7) DMR_STREAM_CASE(8)
         default: return hipErrorInvalidValue;
     }
 #undef DMR_STREAM_CASE
