@@ -105,6 +105,7 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: activations do not fit LDS
     }
     if (M <= kSkinnyMaxM) return hip_status(dmr::launch_w4_skinny(L, d_x, M, d_y, f32, s));
+    if (dmr::gemm_big_applies(M, L.N)) return hip_status(dmr::launch_w4_gemm_big(L, d_x, M, d_y, f32, s));
     return hip_status(dmr::launch_w4_gemm(L, d_x, M, d_y, f32, s));
 }
 
@@ -128,6 +129,7 @@ dmr_status_t dmr_qlinear_bf16_forward(const uint16_t *d_w, const uint16_t *d_x, 
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: K outside its range
     }
     if (M <= kSkinnyMaxM) return hip_status(dmr::launch_bf16_skinny(d_w, d_x, M, K, N, d_y, f32, s));
+    if (dmr::gemm_big_applies(M, N)) return hip_status(dmr::launch_bf16_gemm_big(d_w, d_x, M, K, N, d_y, f32, s));
     return hip_status(dmr::launch_bf16_gemm(d_w, d_x, M, K, N, d_y, f32, s));
 }
 
