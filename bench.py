@@ -40,6 +40,82 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def full_step(args, dmr, synth, torch, dev):
+    """All Linear layers of one decode step of a 32-layer 7B-class decoder: 32 x {qkv, attn_out,
+    gate_up, down} in INT4 (or bf16 for the twin) plus the bf16 lm_head, 129 launches on one stream,
+    each layer with its own weights and buffers (4.76 GB INT4 step, 15.0 GB bf16 step)."""
+    G, M, LAYERS = synth.GROUP, args.m, 32
+    gen = torch.Generator(device=dev)
+    t0 = time.time()
+    int4_layers, bf16_layers, xs, ys = [], [], {}, {}
+    for li in range(LAYERS):
+        for si, (name, K, N) in enumerate(synth.LAYER_SHAPES):
+            gen.manual_seed(synth.seed_for(4, si, 0, layer=li))
+            w = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02
+            qw, s, z = dmr.dmr_qlinear_quantize(w, G)
+            int4_layers.append((name, dmr.dmr_qlinear_create(qw, s, z, G)))
+            bf16_layers.append((name, w.to(torch.bfloat16)))
+            del w, qw, s, z
+    for si, (name, K, N) in enumerate(synth.LAYER_SHAPES + (synth.LM_HEAD,)):
+        gen.manual_seed(synth.seed_for(4, si, 1))
+        xs[name] = torch.randn((M, K), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        ys[name] = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    name, K, N = synth.LM_HEAD
+    gen.manual_seed(synth.seed_for(4, 4, 0))
+    lm_head = (torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+    torch.cuda.synchronize()
+    log(f"[bench] 129 layers resident after {time.time() - t0:.1f}s")
+    stream = torch.cuda.Stream()
+
+    def step(low: bool):
+        for i in range(len(int4_layers)):
+            nm = int4_layers[i][0]
+            if low:
+                dmr.dmr_qlinear_forward(int4_layers[i][1], xs[nm], out=ys[nm])
+            else:
+                dmr.dmr_qlinear_bf16_forward(bf16_layers[i][1], xs[nm], out=ys[nm])
+        dmr.dmr_qlinear_bf16_forward(lm_head, xs["lm_head"], out=ys["lm_head"])     # lm_head stays bf16
+
+    def timed(low: bool):
+        with torch.cuda.stream(stream):
+            for _ in range(args.warmup):
+                step(low)
+            stream.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                for _ in range(args.steps):
+                    step(low)
+            for _ in range(2):
+                graph.replay()
+            stream.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t_start = time.perf_counter()
+            e0.record(stream)
+            graph.replay()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t_start) * 1e3 / args.steps, e0.elapsed_time(e1) / args.steps
+
+    lm_bytes = bf16_bytes(synth.LM_HEAD[1], synth.LM_HEAD[2], M)
+    b4 = LAYERS * sum(int4_bytes(K, N, M) for _, K, N in synth.LAYER_SHAPES) + lm_bytes
+    b16 = LAYERS * sum(bf16_bytes(K, N, M) for _, K, N in synth.LAYER_SHAPES) + lm_bytes
+    w4, e4 = timed(True)
+    w16, e16 = timed(False)
+    result = {
+        "metric": "full decode step over all Linear layers, aggregate HBM GB/s (INT4 copy) and speedup vs bf16 copy",
+        "value": round(b4 / (w4 * 1e-3) / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(w4, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"full decode step, 32 layers x (qkv, attn_out, gate_up, down) INT4 g128 + bf16 "
+                               f"lm_head 4096x128256, M={M}, 129 launches per step, hip-graph replay",
+                   "algorithmic_bytes_per_step": b4},
+        "us_per_step_int4": round(e4 * 1e3, 1), "us_per_step_bf16": round(e16 * 1e3, 1),
+        "bf16_GBps": round(b16 / (w16 * 1e-3) / 1e9, 1), "speedup_vs_bf16": round(w16 / w4, 3),
+        "frac_hbm_peak_int4": round(b4 / (w4 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+    }
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,6 +124,10 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly from Python instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--workload", choices=("decode_sweep", "full_step"), default="decode_sweep",
+                    help="decode_sweep (default, the headline metric) or full_step: all 129 Linear layers of "
+                         "a 32-layer 7B-class decoder per step")
+    ap.add_argument("--m", type=int, default=1, help="rows of activations for --workload full_step")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -63,6 +143,8 @@ def main():
         sys.exit("bench.py: no GPU visible")
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.workload == "full_step":
+        return full_step(args, dmr, synth, torch, dev)
     G = synth.GROUP
     M = 1
 

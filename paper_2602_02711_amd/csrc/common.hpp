@@ -61,6 +61,19 @@ __device__ __forceinline__ uint4 load_stream(const uint4 *p) {
 }
 __device__ __forceinline__ uint32_t load_stream(const uint32_t *p) { return __builtin_nontemporal_load(p); }
 
+// Sum over each aligned group of 16 lanes (a DPP "row"), result in every lane: four rotate-and-add
+// steps on the VALU, no LDS round trip.
+template <int N>
+__device__ __forceinline__ float row_ror_add(float v) {
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+    v = row_ror_add<8>(v);
+    v = row_ror_add<4>(v);
+    v = row_ror_add<2>(v);
+    return row_ror_add<1>(v);
+}
+
 // Position p (0..7) of a streaming-layout word -> nibble index.
 __host__ __device__ __forceinline__ int nibble_of_position(int p) { return (p >> 1) + 4 * (p & 1); }
 

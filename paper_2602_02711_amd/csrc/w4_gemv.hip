@@ -9,9 +9,10 @@
 //
 // Per block: 3 shifts + 4 v_and_or_b32 per packed word turn nibbles into bf16 (128 + q) pairs,
 // four 16x16x32 MFMAs contract them with x (row 0 of the A operand; the other 15 rows repeat it
-// and are ignored), four more against all-ones give sum(x) in the same accumulator slot, and
+// and are ignored), and
 //     acc += s * (D - (128 + z) * X)
-// applies zero point and scale once per group.
+// applies zero point and scale once per group; X = sum of the group's 128 activations is formed
+// once per workgroup while x is staged and kept in LDS beside it.
 #include <cstdlib>
 
 #include "common.hpp"
@@ -20,7 +21,6 @@ namespace dmr {
 
 namespace {
 
-constexpr uint32_t kOnes = 0x3F803F80u;    // bf16 pair (1.0, 1.0)
 
 // (a & mask) | c in one VALU instruction; mask rides the scalar operand slot.
 __device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) {
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
                                                        const uint16_t *__restrict__ x,
                                                        void *__restrict__ y, int groups, int tiles,
                                                        int lgS, int lgTW, int nT_max, int out_f32) {
-    extern __shared__ uint4 smem[];          // x (16 uint4 per group), then red[nT_max][TW][S][16]
+    extern __shared__ uint4 smem[];          // x (16 uint4 per group), X[groups], red[nT_max][TW][S][16]
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform (SGPR)
     const int S = 1 << lgS, TW = 1 << lgTW;
@@ -84,27 +84,36 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
 #pragma unroll
         for (int p = 0; p < P; ++p) issue(ring[p]);
     }
+    float *xsum_lds = reinterpret_cast<float *>(smem + x16);                 // X[group]
+    float *red = xsum_lds + ((groups + 3) & ~3);
 #pragma unroll
     for (int u = 0; u < XL; ++u) {
         const int i = (int)threadIdx.x + u * (int)blockDim.x;
-        if (i < x16) smem[i] = xreg[u];
+        // 16 consecutive threads hold one group's 128 activations: sum them (fp32, fixed order)
+        float part = 0.f;
+        const uint32_t xw[4] = {xreg[u].x, xreg[u].y, xreg[u].z, xreg[u].w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) part += __uint_as_float(xw[q] << 16) + __uint_as_float(xw[q] & 0xFFFF0000u);
+        part = row16_sum(part);
+        if (i < x16) {
+            smem[i] = xreg[u];
+            if ((i & 15) == 0) xsum_lds[i >> 4] = part;
+        }
     }
     __syncthreads();
 
     const uint4 *xs = smem + g0 * 16;
-    float *red = reinterpret_cast<float *>(smem + x16);
-    Frag ones;
-    ones.u = make_uint4(kOnes, kOnes, kOnes, kOnes);
     const uint32_t mask = 0x000F000Fu, magic = 0x43004300u;
     float acc = 0.f;
     int ct = 0, cg = 0;
     auto compute = [&](const Item &cur) {
         const uint4 *xp = xs + cg * 16 + c * 4;
+        const float xg = xsum_lds[g0 + cg];
         Frag a[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) a[t].u = xp[t];
         const uint32_t words[4] = {cur.w.x, cur.w.y, cur.w.z, cur.w.w};
-        f32x4 d = {0.f, 0.f, 0.f, 0.f}, xsum = {0.f, 0.f, 0.f, 0.f};
+        f32x4 d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             Frag b;
@@ -113,11 +122,10 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
             b.w[2] = and_or(words[t] >> 8, mask, magic);
             b.w[3] = and_or(words[t] >> 12, mask, magic);
             d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t].v, b.v, d, 0, 0, 0);
-            xsum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t].v, ones.v, xsum, 0, 0, 0);
         }
         const float sc = __uint_as_float(cur.szw << 16);
         const float cz = __uint_as_float(cur.szw & 0xFFFF0000u);   // -(128 + z)
-        acc = fmaf(sc, fmaf(cz, xsum[0], d[0]), acc);
+        acc = fmaf(sc, fmaf(cz, xg, d[0]), acc);
         if (++cg == GW) {
             if (lane < 16) {
                 if (lgS > 0) {
@@ -227,7 +235,7 @@ hipError_t launch_w4_gemv(const LayerView &L, const uint16_t *x, void *y, bool o
     const int t_step = plan.grid * plan.TW;
     const int nT_max = (tiles + t_step - 1) / t_step;
     const int gw_max = (groups + plan.S - 1) / plan.S;
-    const size_t lds = (size_t)groups * 16 * sizeof(uint4) +
+    const size_t lds = (size_t)groups * 16 * sizeof(uint4) + (size_t)((groups + 3) & ~3) * sizeof(float) +
                        (plan.S > 1 ? (size_t)nT_max * nw * 16 * sizeof(float) : 0);
     if (lds > 64 * 1024) return hipErrorInvalidValue;   // caller falls back to the general kernel
 
