@@ -116,6 +116,82 @@ def full_step(args, dmr, synth, torch, dev):
     print(json.dumps(result), flush=True)
 
 
+def mixed_step(args, dmr, synth, torch, dev):
+    """One decision step of a group of G = 16 parallel rollouts of which the router sends a fraction rho
+    to the bf16 copy and the rest to the INT4 copy (Sec. 4.3: group sampling; Eq. 7: budget rho): the two
+    copies' Linear layers run concurrently on two streams.  Reports step time against rho and against
+    the linear per-token cost model of Eq. 9 fitted to the two pure cases."""
+    G_ROLL, LAYERS, G = 16, 32, synth.GROUP
+    gen = torch.Generator(device=dev)
+    int4_layers, bf16_layers = [], []
+    for li in range(LAYERS):
+        for si, (name, K, N) in enumerate(synth.LAYER_SHAPES):
+            gen.manual_seed(synth.seed_for(4, si, 0, layer=li))
+            w = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02
+            qw, s, z = dmr.dmr_qlinear_quantize(w, G)
+            int4_layers.append((name, dmr.dmr_qlinear_create(qw, s, z, G)))
+            bf16_layers.append((name, w.to(torch.bfloat16)))
+            del w, qw, s, z
+    xs = {}
+    for si, (name, K, N) in enumerate(synth.LAYER_SHAPES):
+        gen.manual_seed(synth.seed_for(4, si, 1))
+        xs[name] = torch.randn((G_ROLL, K), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    ys = {name: torch.empty((G_ROLL, N), dtype=torch.bfloat16, device=dev) for name, K, N in synth.LAYER_SHAPES}
+    torch.cuda.synchronize()
+    s_low, s_high = torch.cuda.Stream(), torch.cuda.Stream()      # both at the default priority
+
+    def step(m_high):
+        m_low = G_ROLL - m_high
+        s_high.wait_stream(s_low)                                  # fork
+        if m_low:
+            with torch.cuda.stream(s_low):
+                for name, layer in int4_layers:
+                    dmr.dmr_qlinear_forward(layer, xs[name][:m_low], out=ys[name][:m_low])
+        if m_high:
+            with torch.cuda.stream(s_high):
+                for name, wb in bf16_layers:
+                    dmr.dmr_qlinear_bf16_forward(wb, xs[name][m_low:], out=ys[name][m_low:])
+        s_low.wait_stream(s_high)                                  # join
+
+    def timed(m_high):
+        with torch.cuda.stream(s_low):
+            for _ in range(args.warmup):
+                step(m_high)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=s_low):
+                for _ in range(args.steps):
+                    step(m_high)
+            for _ in range(2):
+                graph.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(s_low)
+            graph.replay()
+            e1.record(s_low)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / args.steps
+
+    rows = []
+    for rho in (0.0, 0.2, 0.4, 0.7, 1.0):
+        m_high = int(round(rho * G_ROLL))
+        rows.append({"rho": rho, "m_high": m_high, "m_low": G_ROLL - m_high, "us_per_step": round(timed(m_high), 1)})
+        log(f"[bench] {rows[-1]}")
+    t_low, t_high = rows[0]["us_per_step"] / G_ROLL, rows[-1]["us_per_step"] / G_ROLL
+    for r in rows:
+        r["eq9_linear_model_us"] = round(r["m_low"] * t_low + r["m_high"] * t_high, 1)
+    result = {
+        "metric": "mixed routed decision step of 16 rollouts: us per step vs high-precision budget rho",
+        "value": rows[1]["us_per_step"], "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": rows[1]["us_per_step"] / 1e3, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "32 layers x (qkv, attn_out, gate_up, down), 16 rollouts split by rho between the "
+                               "bf16 copy (stream A) and the INT4 copy (stream B); value is rho = 0.2"},
+        "by_rho": rows,
+    }
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -124,7 +200,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly from Python instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
-    ap.add_argument("--workload", choices=("decode_sweep", "full_step"), default="decode_sweep",
+    ap.add_argument("--workload", choices=("decode_sweep", "full_step", "mixed_step"), default="decode_sweep",
                     help="decode_sweep (default, the headline metric) or full_step: all 129 Linear layers of "
                          "a 32-layer 7B-class decoder per step")
     ap.add_argument("--m", type=int, default=1, help="rows of activations for --workload full_step")
@@ -145,6 +221,8 @@ def main():
     torch.cuda.set_device(dev)
     if args.workload == "full_step":
         return full_step(args, dmr, synth, torch, dev)
+    if args.workload == "mixed_step":
+        return mixed_step(args, dmr, synth, torch, dev)
     G = synth.GROUP
     M = 1
 

@@ -59,8 +59,9 @@ typedef enum {
  * (dmr_qlinear_create's d_storage).  0 if the shape is not supported. */
 size_t dmr_qlinear_storage_bytes(int64_t K, int64_t N, int32_t g);
 
-/* Bytes of scratch a forward call of this shape needs (d_ws); may be 0, and then d_ws may be
- * NULL.  Valid for both the INT4 and the bf16 forward. */
+/* Bytes of scratch dmr_qlinear_forward needs for this shape (d_ws); may be 0, and then d_ws may be
+ * NULL.  Non-zero only for 16 < M <= 64, where the activations are re-ordered once per call.  The
+ * bf16 forward never needs any. */
 size_t dmr_qlinear_workspace_bytes(int64_t M, int64_t K, int64_t N);
 
 /*

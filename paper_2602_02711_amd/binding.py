@@ -172,6 +172,9 @@ def dmr_qlinear_forward(layer: Layer, x: torch.Tensor, out: torch.Tensor | None 
     po = _dev(out, "out", (torch.bfloat16, torch.float32))
     if tuple(out.shape) != (M, layer.N):
         raise ValueError("out must be [M][N]")
+    need = dmr_qlinear_workspace_bytes(M, layer.K, layer.N)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)    # device memory only
     pw, wbytes = _workspace(workspace)
     _check(lib().dmr_qlinear_forward(layer.handle, px, M, po, _out_code(out.dtype), pw, wbytes,
                                      _stream(stream)), "dmr_qlinear_forward")

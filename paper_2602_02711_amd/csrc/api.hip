@@ -39,8 +39,10 @@ size_t dmr_qlinear_storage_bytes(int64_t K, int64_t N, int32_t g) {
 }
 
 size_t dmr_qlinear_workspace_bytes(int64_t M, int64_t K, int64_t N) {
-    (void)M; (void)K; (void)N;
-    return 0;   // every reduction of this build stays inside a workgroup
+    (void)N;
+    if (M <= 0 || K <= 0 || K % dmr::kGroup != 0) return 0;
+    // only the 16 < M <= 64 INT4 path stages anything outside LDS: its re-ordered activations
+    return dmr::w4_skinny2_workspace_bytes(M, K);
 }
 
 dmr_status_t dmr_qlinear_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32_t g,
@@ -104,6 +106,7 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
         const hipError_t e = dmr::launch_w4_stream(L, d_x, M, d_y, f32, s);
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: activations do not fit LDS
     }
+    if (M > 16 && M <= kSkinnyMaxM) return hip_status(dmr::launch_w4_skinny2(L, d_x, M, d_y, f32, d_ws, s));
     if (M <= kSkinnyMaxM) return hip_status(dmr::launch_w4_skinny(L, d_x, M, d_y, f32, s));
     if (dmr::gemm_big_applies(M, L.N)) return hip_status(dmr::launch_w4_gemm_big(L, d_x, M, d_y, f32, s));
     return hip_status(dmr::launch_w4_gemm(L, d_x, M, d_y, f32, s));
@@ -120,8 +123,7 @@ dmr_status_t dmr_qlinear_bf16_forward(const uint16_t *d_w, const uint16_t *d_x, 
     if (!d_w || !d_x || !d_y) return DMR_ERR_NULL;
     if (!aligned16(d_w) || !aligned16(d_x) || !aligned16(d_y) || (d_ws && !aligned16(d_ws)))
         return DMR_ERR_ALIGN;
-    const size_t need = dmr_qlinear_workspace_bytes(M, K, N);
-    if (need > 0 && (!d_ws || ws_bytes < need)) return DMR_ERR_WORKSPACE;
+    (void)ws_bytes;   // the bf16 path needs no workspace
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool f32 = out == DMR_OUT_FP32;
     if (M == 1) {

@@ -101,6 +101,10 @@ hipError_t launch_bf16_gemv(const uint16_t *w, const uint16_t *x, int64_t K, int
 // 2 <= M <= 16 streaming kernel; hipErrorInvalidValue (nothing launched) when the activations do not fit LDS.
 hipError_t launch_w4_stream(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
                             hipStream_t stream);
+// 16 < M <= 64: activation pre-pass into `ws` (w4_skinny2_workspace_bytes), then the streaming kernel.
+size_t w4_skinny2_workspace_bytes(int64_t M, int64_t K);
+hipError_t launch_w4_skinny2(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+                             void *ws, hipStream_t stream);
 hipError_t launch_hbm_read_probe(const void *buf, size_t bytes, uint32_t *sink, int blocks,
                                  hipStream_t stream);
 hipError_t launch_w4_skinny(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,

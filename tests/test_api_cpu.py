@@ -33,7 +33,12 @@ def test_size_queries(lib):
     assert lib.dmr_qlinear_storage_bytes(1000, 1024, 128) == 0
     assert lib.dmr_qlinear_storage_bytes(1024, 1000, 128) == 0
     assert lib.dmr_qlinear_storage_bytes(1024, 1024, 64) == 0
-    assert lib.dmr_qlinear_workspace_bytes(1, 4096, 4096) % 16 == 0
+    assert lib.dmr_qlinear_workspace_bytes(1, 4096, 4096) == 0
+    assert lib.dmr_qlinear_workspace_bytes(16, 4096, 4096) == 0
+    # 16 < M <= 64: activations in MFMA operand order (4 KiB per group and row tile) + their group sums
+    assert lib.dmr_qlinear_workspace_bytes(64, 4096, 4096) == 32 * 4 * (4096 + 64)
+    assert lib.dmr_qlinear_workspace_bytes(17, 4096, 4096) == 32 * 2 * (4096 + 64)
+    assert lib.dmr_qlinear_workspace_bytes(65, 4096, 4096) == 0
 
 
 def test_status_strings(lib):
