@@ -67,6 +67,18 @@ def _load():
         lib.oracle_bf16_forward.argtypes = [i64, i64, i64, vp, vp, vp, i32]
         lib.oracle_bf16_forward_sampled.restype = i32
         lib.oracle_bf16_forward_sampled.argtypes = [i64, i64, i64, vp, vp, i64, vp, vp, vp]
+        lib.oracle_quantize_bits.restype = i32
+        lib.oracle_quantize_bits.argtypes = [i64, i64, i64, i32, vp, vp, vp, vp]
+        lib.oracle_pack3.restype = i32
+        lib.oracle_pack3.argtypes = [i64, i64, vp, vp]
+        lib.oracle_unpack3.restype = i32
+        lib.oracle_unpack3.argtypes = [i64, i64, vp, vp]
+        lib.oracle_dequantize_exact_bits.restype = i32
+        lib.oracle_dequantize_exact_bits.argtypes = [i64, i64, i64, i32, vp, vp, vp, vp]
+        lib.oracle_dequantize_bits.restype = i32
+        lib.oracle_dequantize_bits.argtypes = [i64, i64, i64, i32, vp, vp, vp, vp]
+        lib.oracle_forward_bits.restype = i32
+        lib.oracle_forward_bits.argtypes = [i64, i64, i64, i32, i64, vp, vp, vp, vp, vp, i32]
         lib.oracle_max_threads.restype = i32
         lib.oracle_max_threads.argtypes = []
         _lib = lib
@@ -217,3 +229,67 @@ def bf16_forward_sampled(w_bits, x_bits, ms, ns) -> np.ndarray:
     _check(_load().oracle_bf16_forward_sampled(K, N, M, _p(w_bits), _p(x_bits), ms.size, _p(ms),
                                                _p(ns), _p(out)), "oracle_bf16_forward_sampled")
     return out
+
+
+# ---- 3-bit variant (W3A16 group-128): 32 codes per three words ---------------------------------
+
+def quantize_bits(w, g: int, bits: int):
+    w = _arr(w, np.float32)
+    N, K = w.shape
+    q = np.empty((N, K), dtype=np.uint8)
+    s = np.empty((N, K // g), dtype=np.uint16)
+    z = np.empty((N, K // g), dtype=np.uint16)
+    _check(_load().oracle_quantize_bits(K, N, g, bits, _p(w), _p(q), _p(s), _p(z)), "oracle_quantize_bits")
+    return q, s, z
+
+
+def pack3(q) -> np.ndarray:
+    q = _arr(q, np.uint8)
+    N, K = q.shape
+    out = np.empty((N, K // 32 * 3), dtype=np.uint32)
+    _check(_load().oracle_pack3(K, N, _p(q), _p(out)), "oracle_pack3")
+    return out
+
+
+def unpack3(qweight) -> np.ndarray:
+    qweight = _arr(qweight, np.uint32)
+    N, W = qweight.shape
+    K = W // 3 * 32
+    out = np.empty((N, K), dtype=np.uint8)
+    _check(_load().oracle_unpack3(K, N, _p(qweight), _p(out)), "oracle_unpack3")
+    return out
+
+
+def _qsz3(qweight, s, z, g):
+    qweight = _arr(qweight, np.uint32)
+    N, W = qweight.shape
+    K = W // 3 * 32
+    return qweight, _arr(s, np.uint16, (N, K // g)), _arr(z, np.uint16, (N, K // g)), N, K
+
+
+def dequantize_exact3(qweight, s, z, g: int) -> np.ndarray:
+    qweight, s, z, N, K = _qsz3(qweight, s, z, g)
+    out = np.empty((N, K), dtype=np.float64)
+    _check(_load().oracle_dequantize_exact_bits(K, N, g, 3, _p(qweight), _p(s), _p(z), _p(out)),
+           "oracle_dequantize_exact_bits")
+    return out
+
+
+def dequantize3(qweight, s, z, g: int) -> np.ndarray:
+    qweight, s, z, N, K = _qsz3(qweight, s, z, g)
+    out = np.empty((N, K), dtype=np.uint16)
+    _check(_load().oracle_dequantize_bits(K, N, g, 3, _p(qweight), _p(s), _p(z), _p(out)),
+           "oracle_dequantize_bits")
+    return out
+
+
+def forward3(qweight, s, z, g: int, x_bits, threads: int = 1):
+    qweight, s, z, N, K = _qsz3(qweight, s, z, g)
+    x_bits = _arr(x_bits, np.uint16)
+    M = x_bits.shape[0]
+    if x_bits.shape != (M, K):
+        raise ValueError("x must be [M][K]")
+    y = np.zeros((M, N), dtype=np.float64)
+    used = _check(_load().oracle_forward_bits(K, N, g, 3, M, _p(qweight), _p(s), _p(z), _p(x_bits), _p(y),
+                                              int(threads)), "oracle_forward_bits")
+    return y, used

@@ -14,6 +14,11 @@
  *
  *   - codes q[n][k] in 0..15, eight per 32-bit word along k, code j of a word in bits
  *     [4j, 4j+4)                                                 ("canonical packing")
+ *   - the 3-bit variant (the W3A16 group-128 cell of Sec. 5.1 / App. E, for which the paper had
+ *     no kernel and projected T_W3 = T_W4 / 1.15 in App. A): codes 0..7, 32 per three 32-bit
+ *     words along k, code j in bits [3j, 3j+3) of the 96-bit little-endian number formed by the
+ *     three words; everything else is the same with 7 in place of 15.  Functions that take
+ *     `bits` accept 3 or 4.
  *   - one bf16 scale s[n][G] and one bf16 zero point z[n][G] (an integer code 0..15 held
  *     in bf16) per group G = k / g of g consecutive k
  *   - w^[n][k] = (q[n][k] - z[n][G]) * s[n][G]                     (exact in fp64)
@@ -102,10 +107,11 @@ static int bad_shape(int64_t K, int64_t N, int64_t g)
  * actually stored (already rounded to bf16), so codes are the best ones for that scale.
  * q: uint8 [N][K] (one code per byte), s and z: bf16 bits [N][K/g].
  */
-int oracle_quantize(int64_t K, int64_t N, int64_t g, const float *w,
-                    uint8_t *q, uint16_t *s_bits, uint16_t *z_bits)
+int oracle_quantize_bits(int64_t K, int64_t N, int64_t g, int bits, const float *w,
+                         uint8_t *q, uint16_t *s_bits, uint16_t *z_bits)
 {
-    if (bad_shape(K, N, g) || !w || !q || !s_bits || !z_bits) return -1;
+    if (bad_shape(K, N, g) || (bits != 3 && bits != 4) || !w || !q || !s_bits || !z_bits) return -1;
+    const double qmax = (double)((1 << bits) - 1);     /* 15 or 7 */
     const int64_t groups = K / g;
     for (int64_t n = 0; n < N; ++n) {
         for (int64_t G = 0; G < groups; ++G) {
@@ -115,17 +121,17 @@ int oracle_quantize(int64_t K, int64_t N, int64_t g, const float *w,
                 if (wg[i] < lo) lo = wg[i];
                 if (wg[i] > hi) hi = wg[i];
             }
-            float s32 = (float)(((double)hi - (double)lo) / 15.0);
+            float s32 = (float)(((double)hi - (double)lo) / qmax);
             uint16_t sb = oracle_f32_to_bf16(s32);
             double s = oracle_bf16_to_f64(sb);
             if (s == 0.0) { s = 1.0; sb = 0x3F80; }
             double z = nearbyint(-(double)lo / s);
             if (z <= 0.0) z = 0.0;          /* also turns the -0 of an all-positive group into code 0 */
-            if (z > 15.0) z = 15.0;
+            if (z > qmax) z = qmax;
             for (int64_t i = 0; i < g; ++i) {
                 double c = nearbyint((double)wg[i] / s) + z;
                 if (c < 0.0) c = 0.0;
-                if (c > 15.0) c = 15.0;
+                if (c > qmax) c = qmax;
                 q[n * K + G * g + i] = (uint8_t)c;
             }
             s_bits[n * groups + G] = sb;
@@ -133,6 +139,12 @@ int oracle_quantize(int64_t K, int64_t N, int64_t g, const float *w,
         }
     }
     return 0;
+}
+
+int oracle_quantize(int64_t K, int64_t N, int64_t g, const float *w,
+                    uint8_t *q, uint16_t *s_bits, uint16_t *z_bits)
+{
+    return oracle_quantize_bits(K, N, g, 4, w, q, s_bits, z_bits);
 }
 
 /* ---- canonical packing -------------------------------------------------------------- */
@@ -163,17 +175,114 @@ int oracle_unpack(int64_t K, int64_t N, const uint32_t *qweight, uint8_t *q)
     return 0;
 }
 
+/* 3-bit: q uint8 [N][K] (0..7) -> qweight uint32 [N][3K/32]; K % 32 == 0.  Code j of a run of 32
+ * occupies bits [3j, 3j+3) of the 96-bit number word0 + 2^32 word1 + 2^64 word2. */
+int oracle_pack3(int64_t K, int64_t N, const uint8_t *q, uint32_t *qweight)
+{
+    if (K <= 0 || N <= 0 || (K % 32) != 0 || !q || !qweight) return -1;
+    const int64_t wpr = K / 32 * 3;      /* words per row */
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t i = 0; i < wpr; ++i) qweight[n * wpr + i] = 0;
+        for (int64_t k = 0; k < K; ++k) {
+            uint8_t c = q[n * K + k];
+            if (c > 7) return -2;
+            for (int b = 0; b < 3; ++b) {
+                int64_t bit = (k / 32) * 96 + 3 * (k % 32) + b;     /* position in the row's bit stream */
+                if ((c >> b) & 1) qweight[n * wpr + bit / 32] |= (uint32_t)1 << (bit % 32);
+            }
+        }
+    }
+    return 0;
+}
+
+static int code3(const uint32_t *row_words, int64_t k)
+{
+    int c = 0;
+    for (int b = 0; b < 3; ++b) {
+        int64_t bit = (k / 32) * 96 + 3 * (k % 32) + b;
+        c |= (int)((row_words[bit / 32] >> (bit % 32)) & 1u) << b;
+    }
+    return c;
+}
+
+int oracle_unpack3(int64_t K, int64_t N, const uint32_t *qweight, uint8_t *q)
+{
+    if (K <= 0 || N <= 0 || (K % 32) != 0 || !q || !qweight) return -1;
+    const int64_t wpr = K / 32 * 3;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) q[n * K + k] = (uint8_t)code3(qweight + n * wpr, k);
+    return 0;
+}
+
 /* ---- dequantisation ----------------------------------------------------------------- */
+
+static double weight_exact_bits(int64_t K, int64_t g, int bits, const uint32_t *qweight,
+                                const uint16_t *s_bits, const uint16_t *z_bits,
+                                int64_t n, int64_t k)
+{
+    const int64_t groups = K / g;
+    int code = bits == 4 ? (int)((qweight[n * (K / 8) + k / 8] >> (4 * (k % 8))) & 0xFu)
+                         : code3(qweight + n * (K / 32 * 3), k);
+    double s = oracle_bf16_to_f64(s_bits[n * groups + k / g]);
+    double z = oracle_bf16_to_f64(z_bits[n * groups + k / g]);
+    return ((double)code - z) * s;
+}
 
 static double weight_exact(int64_t K, int64_t g, const uint32_t *qweight,
                            const uint16_t *s_bits, const uint16_t *z_bits,
                            int64_t n, int64_t k)
 {
-    const int64_t groups = K / g;
-    int code = (int)((qweight[n * (K / 8) + k / 8] >> (4 * (k % 8))) & 0xFu);
-    double s = oracle_bf16_to_f64(s_bits[n * groups + k / g]);
-    double z = oracle_bf16_to_f64(z_bits[n * groups + k / g]);
-    return ((double)code - z) * s;
+    return weight_exact_bits(K, g, 4, qweight, s_bits, z_bits, n, k);
+}
+
+static int bad_shape_bits(int64_t K, int64_t N, int64_t g, int bits)
+{
+    if (bits == 4) return bad_shape(K, N, g);
+    return bits != 3 || K <= 0 || N <= 0 || g <= 0 || (K % 32) != 0 || (K % g) != 0;
+}
+
+/* 3- or 4-bit versions of the three functions below (same definitions, `bits` picks the packing). */
+int oracle_dequantize_exact_bits(int64_t K, int64_t N, int64_t g, int bits, const uint32_t *qweight,
+                                 const uint16_t *s_bits, const uint16_t *z_bits, double *w_hat)
+{
+    if (bad_shape_bits(K, N, g, bits) || !qweight || !s_bits || !z_bits || !w_hat) return -1;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k)
+            w_hat[n * K + k] = weight_exact_bits(K, g, bits, qweight, s_bits, z_bits, n, k);
+    return 0;
+}
+
+int oracle_dequantize_bits(int64_t K, int64_t N, int64_t g, int bits, const uint32_t *qweight,
+                           const uint16_t *s_bits, const uint16_t *z_bits, uint16_t *w_bf16)
+{
+    if (bad_shape_bits(K, N, g, bits) || !qweight || !s_bits || !z_bits || !w_bf16) return -1;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k)
+            w_bf16[n * K + k] =
+                oracle_f64_to_bf16(weight_exact_bits(K, g, bits, qweight, s_bits, z_bits, n, k));
+    return 0;
+}
+
+int oracle_forward_bits(int64_t K, int64_t N, int64_t g, int bits, int64_t M, const uint32_t *qweight,
+                        const uint16_t *s_bits, const uint16_t *z_bits, const uint16_t *x_bits,
+                        double *y, int threads)
+{
+    if (bad_shape_bits(K, N, g, bits) || M < 0 || !qweight || !s_bits || !z_bits || (M && (!x_bits || !y)))
+        return -1;
+    int used = 1;
+#ifdef _OPENMP
+    if (threads > 1) used = threads;
+#pragma omp parallel for num_threads(used) schedule(static)
+#endif
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t m = 0; m < M; ++m) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += oracle_bf16_to_f64(x_bits[m * K + k]) *
+                       weight_exact_bits(K, g, bits, qweight, s_bits, z_bits, n, k);
+            y[m * N + n] = acc;
+        }
+    return used;
 }
 
 /* w^ as fp64 [N][K] (the mathematical weight; exact). */

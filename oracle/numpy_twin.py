@@ -70,3 +70,32 @@ def forward_group_sums(qweight, s_bits, z_bits, g, x_bits):
 
 def bf16_forward(w_bits, x_bits):
     return np.einsum("mk,nk->mn", bf16_bits_to_f64(x_bits), bf16_bits_to_f64(w_bits))
+
+
+# ---- 3-bit variant, written independently of the C code: the row is one little-endian bit stream
+
+
+def unpack3(qweight):
+    qweight = np.ascontiguousarray(qweight, dtype="<u4")
+    N = qweight.shape[0]
+    bits = np.unpackbits(qweight.view(np.uint8).reshape(N, -1), axis=1, bitorder="little")
+    fields = bits.reshape(N, -1, 3).astype(np.uint8)
+    return fields[:, :, 0] | (fields[:, :, 1] << 1) | (fields[:, :, 2] << 2)
+
+
+def pack3(q):
+    q = np.asarray(q, dtype=np.uint8)
+    N = q.shape[0]
+    bits = np.stack([(q >> b) & 1 for b in range(3)], axis=2).reshape(N, -1)
+    return np.packbits(bits, axis=1, bitorder="little").view("<u4").reshape(N, -1)
+
+
+def dequantize_exact3(qweight, s_bits, z_bits, g):
+    q = unpack3(qweight).astype(np.float64)
+    s = np.repeat(bf16_bits_to_f64(s_bits), g, axis=1)
+    z = np.repeat(bf16_bits_to_f64(z_bits), g, axis=1)
+    return (q - z) * s
+
+
+def forward3(qweight, s_bits, z_bits, g, x_bits):
+    return np.einsum("mk,nk->mn", bf16_bits_to_f64(x_bits), dequantize_exact3(qweight, s_bits, z_bits, g))

@@ -367,3 +367,62 @@ def test_synth_is_seeded_and_shaped():
     x = synth.activations_bf16(synth.seed_for(1, 2, 1), 2, 4096)
     assert x.dtype == np.uint16 and abs(float(orc.bf16_to_f64(x).std()) - 1.0) < 0.05
     assert len({synth.seed_for(c, s, r) for c, s, r in itertools.product(range(5), range(4), range(2))}) == 40
+
+
+# ------------------------------------------------------------------ 3-bit variant (W3A16 g128)
+
+def test_w3_handworked_packing(golden):
+    gd = golden("handworked_w3_pack.txt")
+    q = np.stack([_f(gd[f"q_row{r}"]) for r in range(3)]).astype(np.uint8)
+    words = orc.pack3(q)
+    for r in range(3):
+        assert np.array_equal(words[r].astype(np.uint64), _h(gd[f"words_row{r}"])), r
+    assert np.array_equal(orc.unpack3(words), q)
+
+
+def test_w3_pack_bijection_and_twin():
+    rng = np.random.default_rng(31)
+    q = rng.integers(0, 8, size=(11, 160), dtype=np.uint8)
+    words = orc.pack3(q)
+    assert words.shape == (11, 15)
+    assert np.array_equal(orc.unpack3(words), q)
+    assert np.array_equal(twin.pack3(q), words)
+    assert np.array_equal(twin.unpack3(words), q)
+    raw = rng.integers(0, 2 ** 32, size=(5, 9), dtype=np.uint64).astype(np.uint32)
+    assert np.array_equal(orc.pack3(orc.unpack3(raw)), raw)
+    bad = q.copy()
+    bad[0, 3] = 8
+    with pytest.raises(ValueError):
+        orc.pack3(bad)
+
+
+def test_w3_quantizer_dequantize_forward():
+    N, K, g, M = 24, 256, 128, 3
+    w = synth.weights_f32(41, N, K)
+    q, s, z = orc.quantize_bits(w, g, 3)
+    assert q.max() <= 7
+    zf, sf = orc.bf16_to_f64(z), np.repeat(orc.bf16_to_f64(s), g, axis=1)
+    assert np.all((zf >= 0) & (zf <= 7) & (zf == np.rint(zf)))
+    words = orc.pack3(q)
+    w_hat = orc.dequantize_exact3(words, s, z, g)
+    # closed form: half a step (steps are range / 7 now), plus the clamped excess
+    unclamped = np.rint(w.astype(np.float64) / sf) + np.repeat(zf, g, axis=1)
+    excess = np.maximum(unclamped - 7, 0) + np.maximum(-unclamped, 0)
+    assert np.all(np.abs(w_hat - w) <= sf * (0.5 + excess) * (1 + 1e-12))
+    assert np.array_equal(w_hat, twin.dequantize_exact3(words, s, z, g))
+    assert np.array_equal(orc.dequantize3(words, s, z, g), twin.f32_to_bf16_bits(w_hat.astype(np.float32)))
+    x = synth.activations_bf16(42, M, K)
+    y, _ = orc.forward3(words, s, z, g, x)
+    yt = twin.forward3(words, s, z, g, x)
+    assert np.max(np.abs(y - yt)) <= 1e-12 * np.sqrt(np.mean(yt ** 2)) * np.sqrt(K)
+    # integer special case: z = 4, s = 1 -> x . (q - 4)^T in int64
+    rng = np.random.default_rng(43)
+    xi = rng.integers(-8, 9, size=(M, K))
+    one = orc.f64_to_bf16(np.ones((N, K // g)))
+    four = orc.f64_to_bf16(np.full((N, K // g), 4.0))
+    yi, _ = orc.forward3(words, one, four, g, orc.f64_to_bf16(xi.astype(np.float64)))
+    assert np.array_equal(yi, (xi @ (q.astype(np.int64) - 4).T).astype(np.float64))
+    # the 4-bit entry point is the bits = 4 case of the general one
+    q4a, s4a, z4a = orc.quantize(w, g)
+    q4b, s4b, z4b = orc.quantize_bits(w, g, 4)
+    assert np.array_equal(q4a, q4b) and np.array_equal(s4a, s4b) and np.array_equal(z4a, z4b)
