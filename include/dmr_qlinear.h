@@ -111,6 +111,29 @@ dmr_status_t dmr_qlinear_quantize(int64_t K, int64_t N, int32_t g, const float *
                                   void *stream);
 
 /*
+ * The 3-bit variant of the low-precision copy: the paper's W3A16 group-128 cell (Sec. 5.1, App. E),
+ * which it could only run fake-quantised and whose cost it projected as T_W4 / 1.15 (App. A).  Format:
+ * codes 0..7, 32 per three words along k (code j in bits [3j, 3j+3) of the 96-bit little-endian run),
+ * qweight3 uint32 [N][3K/32]; scales and zeros as for 4 bits, zero points 0..7.  The handle these
+ * calls return is used with dmr_qlinear_dequantize / _forward / _destroy like a 4-bit one.  M = 1
+ * runs a native weight-streaming kernel; M > 1 dequantises the layer into d_ws
+ * (dmr_qlinear_w3_workspace_bytes) and takes the bf16 path.
+ */
+size_t dmr_qlinear_w3_storage_bytes(int64_t K, int64_t N, int32_t g);
+size_t dmr_qlinear_w3_workspace_bytes(int64_t M, int64_t K, int64_t N);
+dmr_status_t dmr_qlinear_w3_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32_t g,
+                                   const uint32_t *d_qweight3, /* [N][3K/32] */
+                                   const uint16_t *d_scales,   /* bf16 [N][K/g] */
+                                   const uint16_t *d_zeros,    /* bf16 [N][K/g] */
+                                   void *d_storage, size_t storage_bytes, void *stream);
+/* Round-to-nearest quantiser of the 3-bit format: as dmr_qlinear_quantize with 7 in place of 15. */
+dmr_status_t dmr_qlinear_quantize_w3(int64_t K, int64_t N, int32_t g, const float *d_w,
+                                     uint32_t *d_qweight3, uint16_t *d_scales, uint16_t *d_zeros,
+                                     void *stream);
+/* 4 or 3: which format a handle holds (0 for NULL). */
+int32_t dmr_qlinear_bits(const dmr_qlinear_t *layer);
+
+/*
  * Measurement aid, not part of a routed step: read `bytes` (a multiple of 16) of d_buf once with
  * 128-bit loads from `blocks` workgroups of 256 threads and leave one word per thread in d_sink
  * (blocks * 256 words).  Timing it over a buffer much larger than the caches gives the HBM read

@@ -23,7 +23,8 @@ EXPORTS = (
     "dmr_qlinear_storage_bytes", "dmr_qlinear_workspace_bytes", "dmr_qlinear_create",
     "dmr_qlinear_dequantize", "dmr_qlinear_forward", "dmr_qlinear_bf16_forward",
     "dmr_qlinear_quantize", "dmr_qlinear_destroy", "dmr_qlinear_shape", "dmr_status_string",
-    "dmr_probe_hbm_read",
+    "dmr_probe_hbm_read", "dmr_qlinear_w3_storage_bytes", "dmr_qlinear_w3_workspace_bytes",
+    "dmr_qlinear_w3_create", "dmr_qlinear_quantize_w3", "dmr_qlinear_bits",
 )
 
 
@@ -64,6 +65,16 @@ def lib() -> ctypes.CDLL:
         L.dmr_qlinear_destroy.argtypes = [vp]
         L.dmr_qlinear_shape.restype = ctypes.c_int
         L.dmr_qlinear_shape.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i32)]
+        L.dmr_qlinear_w3_storage_bytes.restype = sz
+        L.dmr_qlinear_w3_storage_bytes.argtypes = [i64, i64, i32]
+        L.dmr_qlinear_w3_workspace_bytes.restype = sz
+        L.dmr_qlinear_w3_workspace_bytes.argtypes = [i64, i64, i64]
+        L.dmr_qlinear_w3_create.restype = ctypes.c_int
+        L.dmr_qlinear_w3_create.argtypes = [ctypes.POINTER(vp), i64, i64, i32, vp, vp, vp, vp, sz, vp]
+        L.dmr_qlinear_quantize_w3.restype = ctypes.c_int
+        L.dmr_qlinear_quantize_w3.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp]
+        L.dmr_qlinear_bits.restype = i32
+        L.dmr_qlinear_bits.argtypes = [vp]
         L.dmr_probe_hbm_read.restype = ctypes.c_int
         L.dmr_probe_hbm_read.argtypes = [vp, sz, vp, i32, vp]
         L.dmr_status_string.restype = ctypes.c_char_p
@@ -110,8 +121,8 @@ def _out_code(dtype) -> int:
 class Layer:
     """Host handle of one quantised Linear layer plus the storage tensor it points into."""
 
-    def __init__(self, handle: int, storage: torch.Tensor, K: int, N: int, g: int):
-        self.handle, self.storage, self.K, self.N, self.g = handle, storage, K, N, g
+    def __init__(self, handle: int, storage: torch.Tensor, K: int, N: int, g: int, bits: int = 4):
+        self.handle, self.storage, self.K, self.N, self.g, self.bits = handle, storage, K, N, g, bits
 
     def __del__(self):
         dmr_qlinear_destroy(self)
@@ -172,7 +183,8 @@ def dmr_qlinear_forward(layer: Layer, x: torch.Tensor, out: torch.Tensor | None 
     po = _dev(out, "out", (torch.bfloat16, torch.float32))
     if tuple(out.shape) != (M, layer.N):
         raise ValueError("out must be [M][N]")
-    need = dmr_qlinear_workspace_bytes(M, layer.K, layer.N)
+    need = (dmr_qlinear_w3_workspace_bytes(M, layer.K, layer.N) if layer.bits == 3
+            else dmr_qlinear_workspace_bytes(M, layer.K, layer.N))
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)    # device memory only
     pw, wbytes = _workspace(workspace)
@@ -212,6 +224,49 @@ def dmr_qlinear_quantize(w: torch.Tensor, g: int = 128, stream=None):
     zeros = torch.empty((N, K // g), dtype=torch.bfloat16, device=w.device)
     _check(lib().dmr_qlinear_quantize(K, N, g, pw_, qweight.data_ptr(), scales.data_ptr(),
                                       zeros.data_ptr(), _stream(stream)), "dmr_qlinear_quantize")
+    return qweight, scales, zeros
+
+
+def dmr_qlinear_w3_storage_bytes(K: int, N: int, g: int = 128) -> int:
+    return int(lib().dmr_qlinear_w3_storage_bytes(K, N, g))
+
+
+def dmr_qlinear_w3_workspace_bytes(M: int, K: int, N: int) -> int:
+    return int(lib().dmr_qlinear_w3_workspace_bytes(M, K, N))
+
+
+def dmr_qlinear_w3_create(qweight3: torch.Tensor, scales: torch.Tensor, zeros: torch.Tensor, g: int = 128,
+                          storage: torch.Tensor | None = None, stream=None) -> Layer:
+    pq = _dev(qweight3, "qweight3", _U32)
+    ps = _dev(scales, "scales", _BF16)
+    pz = _dev(zeros, "zeros", _BF16)
+    N, W = qweight3.shape
+    if W % 3:
+        raise ValueError("qweight3 must be [N][3K/32]")
+    K = W // 3 * 32
+    if g <= 0 or K % g or tuple(scales.shape) != (N, K // g) or tuple(zeros.shape) != (N, K // g):
+        raise ValueError("scales and zeros must be [N][K/g]")
+    need = dmr_qlinear_w3_storage_bytes(K, N, g)
+    if storage is None:
+        storage = torch.empty(max(need, 16), dtype=torch.uint8, device=qweight3.device)
+    pst = _dev(storage, "storage", (torch.uint8,))
+    handle = ctypes.c_void_p()
+    _check(lib().dmr_qlinear_w3_create(ctypes.byref(handle), K, N, g, pq, ps, pz, pst, storage.numel(),
+                                       _stream(stream)), "dmr_qlinear_w3_create")
+    return Layer(handle.value, storage, K, N, g, bits=3)
+
+
+def dmr_qlinear_quantize_w3(w: torch.Tensor, g: int = 128, stream=None):
+    """fp32 [N][K] in device memory -> (qweight3 int32 [N][3K/32], scales bf16, zeros bf16 [N][K/g])."""
+    pw_ = _dev(w, "w", (torch.float32,))
+    N, K = w.shape
+    if g <= 0 or K % g or K % 32:
+        raise ValueError("K must be a multiple of g and of 32")
+    qweight = torch.empty((N, K // 32 * 3), dtype=torch.int32, device=w.device)
+    scales = torch.empty((N, K // g), dtype=torch.bfloat16, device=w.device)
+    zeros = torch.empty((N, K // g), dtype=torch.bfloat16, device=w.device)
+    _check(lib().dmr_qlinear_quantize_w3(K, N, g, pw_, qweight.data_ptr(), scales.data_ptr(),
+                                         zeros.data_ptr(), _stream(stream)), "dmr_qlinear_quantize_w3")
     return qweight, scales, zeros
 
 

@@ -7,7 +7,9 @@
 struct dmr_qlinear {
     int64_t K, N;
     int32_t g;
-    const uint4 *wt;
+    int32_t bits;           // 4, or 3 for the W3A16 variant
+    const uint4 *wt;        // 4-bit streaming blocks
+    const uint32_t *wt3;    // 3-bit streaming blocks
     const uint32_t *sz;
 };
 
@@ -63,6 +65,8 @@ dmr_status_t dmr_qlinear_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32
     h->K = K;
     h->N = N;
     h->g = g;
+    h->bits = 4;
+    h->wt3 = nullptr;
     uint8_t *base = static_cast<uint8_t *>(d_storage);
     h->wt = reinterpret_cast<const uint4 *>(base);
     h->sz = reinterpret_cast<const uint32_t *>(base + dmr::weight_region_bytes(K, N));
@@ -78,9 +82,68 @@ dmr_status_t dmr_qlinear_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32
     return DMR_OK;
 }
 
+size_t dmr_qlinear_w3_storage_bytes(int64_t K, int64_t N, int32_t g) {
+    if (check_shape(K, N, g) != DMR_OK) return 0;
+    return dmr::weight3_region_bytes(K, N) + dmr::sz_region_bytes(K, N);
+}
+
+size_t dmr_qlinear_w3_workspace_bytes(int64_t M, int64_t K, int64_t N) {
+    if (M <= 1 || K <= 0 || N <= 0) return 0;
+    return (size_t)N * (size_t)K * 2;   // M > 1: the layer is dequantised to bf16 there first
+}
+
+dmr_status_t dmr_qlinear_w3_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32_t g,
+                                   const uint32_t *d_qweight3, const uint16_t *d_scales,
+                                   const uint16_t *d_zeros, void *d_storage, size_t storage_bytes,
+                                   void *stream) {
+    if (!out) return DMR_ERR_NULL;
+    *out = nullptr;
+    const dmr_status_t shape = check_shape(K, N, g);
+    if (shape != DMR_OK) return shape;
+    if (!d_qweight3 || !d_scales || !d_zeros || !d_storage) return DMR_ERR_NULL;
+    if (!aligned16(d_qweight3) || !aligned16(d_scales) || !aligned16(d_zeros) || !aligned16(d_storage))
+        return DMR_ERR_ALIGN;
+    if (storage_bytes < dmr_qlinear_w3_storage_bytes(K, N, g)) return DMR_ERR_WORKSPACE;
+    dmr_qlinear *h = new (std::nothrow) dmr_qlinear;
+    if (!h) return DMR_ERR_NULL;
+    h->K = K;
+    h->N = N;
+    h->g = g;
+    h->bits = 3;
+    h->wt = nullptr;
+    uint8_t *base = static_cast<uint8_t *>(d_storage);
+    h->wt3 = reinterpret_cast<const uint32_t *>(base);
+    h->sz = reinterpret_cast<const uint32_t *>(base + dmr::weight3_region_bytes(K, N));
+    const hipError_t e = dmr::launch_retile3(K, N, d_qweight3, d_scales, d_zeros,
+                                             reinterpret_cast<uint32_t *>(base),
+                                             reinterpret_cast<uint32_t *>(base + dmr::weight3_region_bytes(K, N)),
+                                             static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) {
+        delete h;
+        return DMR_ERR_HIP;
+    }
+    *out = h;
+    return DMR_OK;
+}
+
+dmr_status_t dmr_qlinear_quantize_w3(int64_t K, int64_t N, int32_t g, const float *d_w, uint32_t *d_qweight3,
+                                     uint16_t *d_scales, uint16_t *d_zeros, void *stream) {
+    const dmr_status_t shape = check_shape(K, N, g);
+    if (shape != DMR_OK) return shape;
+    if (!d_w || !d_qweight3 || !d_scales || !d_zeros) return DMR_ERR_NULL;
+    if (!aligned16(d_w) || !aligned16(d_qweight3) || !aligned16(d_scales) || !aligned16(d_zeros))
+        return DMR_ERR_ALIGN;
+    return hip_status(dmr::launch_quantize3(K, N, d_w, d_qweight3, d_scales, d_zeros,
+                                            static_cast<hipStream_t>(stream)));
+}
+
 dmr_status_t dmr_qlinear_dequantize(const dmr_qlinear_t *layer, uint16_t *d_w_bf16, void *stream) {
     if (!layer || !d_w_bf16) return DMR_ERR_NULL;
     if (!aligned16(d_w_bf16)) return DMR_ERR_ALIGN;
+    if (layer->bits == 3) {
+        const dmr::LayerView3 L3{layer->K, layer->N, layer->wt3, layer->sz};
+        return hip_status(dmr::launch_dequantize3(L3, d_w_bf16, static_cast<hipStream_t>(stream)));
+    }
     const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz};
     return hip_status(dmr::launch_dequantize(L, d_w_bf16, static_cast<hipStream_t>(stream)));
 }
@@ -93,11 +156,25 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
     if (M == 0) return DMR_OK;
     if (!d_x || !d_y) return DMR_ERR_NULL;
     if (!aligned16(d_x) || !aligned16(d_y) || (d_ws && !aligned16(d_ws))) return DMR_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool f32 = out == DMR_OUT_FP32;
+    if (layer->bits == 3) {
+        const dmr::LayerView3 L3{layer->K, layer->N, layer->wt3, layer->sz};
+        if (M == 1) {
+            const hipError_t e = dmr::launch_w3_gemv(L3, d_x, d_y, f32, s);
+            if (e != hipErrorInvalidValue) return hip_status(e);
+        }
+        // M > 1 (or a shape outside the GEMV's range): dequantise into the workspace, then the bf16 path
+        const size_t need3 = (size_t)layer->N * (size_t)layer->K * 2;
+        if (!d_ws || ws_bytes < need3) return DMR_ERR_WORKSPACE;
+        const hipError_t e = dmr::launch_dequantize3(L3, static_cast<uint16_t *>(d_ws), s);
+        if (e != hipSuccess) return DMR_ERR_HIP;
+        return dmr_qlinear_bf16_forward(static_cast<const uint16_t *>(d_ws), d_x, M, layer->K, layer->N, d_y, out,
+                                        nullptr, 0, stream);
+    }
     const size_t need = dmr_qlinear_workspace_bytes(M, layer->K, layer->N);
     if (need > 0 && (!d_ws || ws_bytes < need)) return DMR_ERR_WORKSPACE;
     const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz};
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const bool f32 = out == DMR_OUT_FP32;
     if (M == 1) {
         const hipError_t e = dmr::launch_w4_gemv(L, d_x, d_y, f32, s);
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: shape outside its range
@@ -155,6 +232,8 @@ dmr_status_t dmr_probe_hbm_read(const void *d_buf, size_t bytes, uint32_t *d_sin
 }
 
 void dmr_qlinear_destroy(dmr_qlinear_t *layer) { delete layer; }
+
+int32_t dmr_qlinear_bits(const dmr_qlinear_t *layer) { return layer ? layer->bits : 0; }
 
 dmr_status_t dmr_qlinear_shape(const dmr_qlinear_t *layer, int64_t *K, int64_t *N, int32_t *g) {
     if (!layer) return DMR_ERR_NULL;

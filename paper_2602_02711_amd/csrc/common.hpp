@@ -83,6 +83,13 @@ struct LayerView {
     const uint32_t *sz;    // streaming scale / zero words
 };
 
+struct LayerView3 {       // 3-bit variant: 64 lanes x 3 words per block
+    int64_t K, N;
+    const uint32_t *wt;
+    const uint32_t *sz;
+};
+
+inline size_t weight3_region_bytes(int64_t K, int64_t N) { return (size_t)N * (size_t)K / 32 * 12; }
 inline size_t weight_region_bytes(int64_t K, int64_t N) { return (size_t)N * (size_t)K / 2; }
 inline size_t sz_region_bytes(int64_t K, int64_t N) { return (size_t)N * (size_t)(K / kGroup) * 4; }
 
@@ -105,6 +112,12 @@ hipError_t launch_w4_stream(const LayerView &L, const uint16_t *x, int64_t M, vo
 size_t w4_skinny2_workspace_bytes(int64_t M, int64_t K);
 hipError_t launch_w4_skinny2(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
                              void *ws, hipStream_t stream);
+hipError_t launch_retile3(int64_t K, int64_t N, const uint32_t *qweight, const uint16_t *scales,
+                          const uint16_t *zeros, uint32_t *wt, uint32_t *sz, hipStream_t stream);
+hipError_t launch_dequantize3(const LayerView3 &L, uint16_t *w_bf16, hipStream_t stream);
+hipError_t launch_quantize3(int64_t K, int64_t N, const float *w, uint32_t *qweight, uint16_t *scales,
+                            uint16_t *zeros, hipStream_t stream);
+hipError_t launch_w3_gemv(const LayerView3 &L, const uint16_t *x, void *y, bool out_f32, hipStream_t stream);
 hipError_t launch_hbm_read_probe(const void *buf, size_t bytes, uint32_t *sink, int blocks,
                                  hipStream_t stream);
 hipError_t launch_w4_skinny(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,

@@ -1,0 +1,293 @@
+// W3A16 (group 128) decode GEMV, M == 1: the native 3-bit kernel the paper did not have (its W3 cell
+// ran fake-quantised and its cost was projected as T_W4 / 1.15, App. A).  Same structure as the
+// 4-bit GEMV (S k slices x TW tiles of wavefronts, x and its group sums staged in LDS, a register
+// ring of outstanding block loads, bf16 MFMA 16x16x32, deterministic LDS reduction); a block is
+// 64 lanes x 12 bytes = 768 bytes (0.40625 bytes per weight with scale and zero point).
+//
+// Streaming layout of a lane's three words (32 weights k = 32 c + i): operand register r = i / 2
+// (the pair i = 2r, 2r + 1, low and high half).  For r < 15 the two 3-bit codes sit in field r % 5
+// of word r / 5: bits [3f, 3f+3) of the low half and of the high half, so one shift and one
+// v_and_or_b32 (mask 0x00070007, or 0x43004300) give the bf16 pair (128 + q, 128 + q).  Each half
+// keeps one spare bit (15 and 31); the three low spare bits are code 30, the three high ones code
+// 31 (register 15).
+#include <cstdlib>
+
+#include "common.hpp"
+
+namespace dmr {
+
+namespace {
+
+
+// (a & mask) | c in one VALU instruction; mask rides the scalar operand slot.
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) {
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(c));
+    return r;
+}
+
+struct Item {
+    uint32_t w0, w1, w2;
+    uint32_t szw;
+};
+
+// Operand register r (0..15) of a lane's three words.
+template <int R>
+__device__ __forceinline__ uint32_t pair_reg(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t mask,
+                                             uint32_t magic) {
+    if (R < 15) {
+        const uint32_t w = (R / 5 == 0) ? w0 : (R / 5 == 1 ? w1 : w2);
+        return and_or(w >> (3 * (R % 5)), mask, magic);
+    }
+    uint32_t v = (w0 >> 15) & 0x00010001u;
+    v = and_or(w1 >> 14, 0x00020002u, v);
+    v = and_or(w2 >> 13, 0x00040004u, v);
+    return v | magic;
+}
+
+template <int P, int XL>
+__global__ __launch_bounds__(1024) void w3_gemv_kernel(const uint32_t *__restrict__ wt,
+                                                       const uint32_t *__restrict__ sz,
+                                                       const uint16_t *__restrict__ x,
+                                                       void *__restrict__ y, int groups, int tiles,
+                                                       int lgS, int lgTW, int nT_max, int out_f32) {
+    extern __shared__ uint4 smem[];          // x (16 uint4 per group), X[groups], red[nT_max][TW][S][16]
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform (SGPR)
+    const int S = 1 << lgS, TW = 1 << lgTW;
+    const int s = wave & (S - 1), tw = wave >> lgS;
+    const int c = lane >> 4, j = lane & 15;
+    const int g0 = (groups * s) >> lgS;
+    const int GW = ((groups * (s + 1)) >> lgS) - g0;
+    const int t_first = ((int)blockIdx.x << lgTW) + tw;
+    const int t_step = (int)gridDim.x << lgTW;
+    // tiles go round-robin over the grid: a wave gets nT_max of them, or one fewer
+    const int nT = nT_max - ((t_first + (nT_max - 1) * t_step >= tiles) ? 1 : 0);
+    const int items = nT * GW;
+
+    // x -> registers now (oldest loads), -> LDS after the first weight loads have been issued
+    uint4 xreg[XL];
+    const int x16 = groups * 16;
+#pragma unroll
+    for (int u = 0; u < XL; ++u) {
+        const int i = (int)threadIdx.x + u * (int)blockDim.x;
+        xreg[u] = reinterpret_cast<const uint4 *>(x)[i < x16 ? i : 0];
+    }
+
+    // Issue pointer (it, ig) walks (tile step, group in slice) and saturates at the last block,
+    // so every issue is unconditional (the waitcnt bookkeeping stays exact); a wave whose item
+    // count is not a multiple of P re-reads its last block up to P - 1 times from cache.
+    int it = 0, ig = 0, issued = 0;
+    Item ring[P];
+    auto issue = [&](Item &dst) {
+        const int64_t block = (int64_t)(t_first + it * t_step) * groups + (g0 + ig);
+        const uint32_t *pw = wt + (block * 64 + lane) * 3;
+        dst.w0 = load_stream(pw);
+        dst.w1 = load_stream(pw + 1);
+        dst.w2 = load_stream(pw + 2);
+        dst.szw = load_stream(sz + block * kTileRows + j);
+        if (issued + 1 < items) {
+            ++issued;
+            if (++ig == GW) {
+                ig = 0;
+                ++it;
+            }
+        }
+    };
+    if (items > 0) {
+#pragma unroll
+        for (int p = 0; p < P; ++p) issue(ring[p]);
+    }
+    float *xsum_lds = reinterpret_cast<float *>(smem + x16);                 // X[group]
+    float *red = xsum_lds + ((groups + 3) & ~3);
+#pragma unroll
+    for (int u = 0; u < XL; ++u) {
+        const int i = (int)threadIdx.x + u * (int)blockDim.x;
+        // 16 consecutive threads hold one group's 128 activations: sum them (fp32, fixed order)
+        float part = 0.f;
+        const uint32_t xw[4] = {xreg[u].x, xreg[u].y, xreg[u].z, xreg[u].w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) part += __uint_as_float(xw[q] << 16) + __uint_as_float(xw[q] & 0xFFFF0000u);
+        part = row16_sum(part);
+        if (i < x16) {
+            smem[i] = xreg[u];
+            if ((i & 15) == 0) xsum_lds[i >> 4] = part;
+        }
+    }
+    __syncthreads();
+
+    const uint4 *xs = smem + g0 * 16;
+    const uint32_t mask = 0x00070007u, magic = 0x43004300u;
+    float acc = 0.f;
+    int ct = 0, cg = 0;
+    auto compute = [&](const Item &cur) {
+        const uint4 *xp = xs + cg * 16 + c * 4;
+        const float xg = xsum_lds[g0 + cg];
+        Frag a[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) a[t].u = xp[t];
+        f32x4 d = {0.f, 0.f, 0.f, 0.f};
+        Frag b;
+        b.w[0] = pair_reg<0>(cur.w0, cur.w1, cur.w2, mask, magic);
+        b.w[1] = pair_reg<1>(cur.w0, cur.w1, cur.w2, mask, magic);
+        b.w[2] = pair_reg<2>(cur.w0, cur.w1, cur.w2, mask, magic);
+        b.w[3] = pair_reg<3>(cur.w0, cur.w1, cur.w2, mask, magic);
+        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[0].v, b.v, d, 0, 0, 0);
+        b.w[0] = pair_reg<4>(cur.w0, cur.w1, cur.w2, mask, magic);
+        b.w[1] = pair_reg<5>(cur.w0, cur.w1, cur.w2, mask, magic);
+        b.w[2] = pair_reg<6>(cur.w0, cur.w1, cur.w2, mask, magic);
+        b.w[3] = pair_reg<7>(cur.w0, cur.w1, cur.w2, mask, magic);
+        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[1].v, b.v, d, 0, 0, 0);
+        b.w[0] = pair_reg<8>(cur.w0, cur.w1, cur.w2, mask, magic);
+        b.w[1] = pair_reg<9>(cur.w0, cur.w1, cur.w2, mask, magic);
+        b.w[2] = pair_reg<10>(cur.w0, cur.w1, cur.w2, mask, magic);
+        b.w[3] = pair_reg<11>(cur.w0, cur.w1, cur.w2, mask, magic);
+        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[2].v, b.v, d, 0, 0, 0);
+        b.w[0] = pair_reg<12>(cur.w0, cur.w1, cur.w2, mask, magic);
+        b.w[1] = pair_reg<13>(cur.w0, cur.w1, cur.w2, mask, magic);
+        b.w[2] = pair_reg<14>(cur.w0, cur.w1, cur.w2, mask, magic);
+        b.w[3] = pair_reg<15>(cur.w0, cur.w1, cur.w2, mask, magic);
+        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[3].v, b.v, d, 0, 0, 0);
+        const float sc = __uint_as_float(cur.szw << 16);
+        const float cz = __uint_as_float(cur.szw & 0xFFFF0000u);   // -(128 + z)
+        acc = fmaf(sc, fmaf(cz, xg, d[0]), acc);
+        if (++cg == GW) {
+            if (lane < 16) {
+                if (lgS > 0) {
+                    red[((((ct << lgTW) + tw) << lgS) + s) * 16 + lane] = acc;
+                } else {
+                    const int64_t n = (int64_t)(t_first + ct * t_step) * kTileRows + lane;
+                    if (out_f32)
+                        reinterpret_cast<float *>(y)[n] = acc;
+                    else
+                        reinterpret_cast<uint16_t *>(y)[n] = f32_to_bf16(acc);
+                }
+            }
+            acc = 0.f;
+            cg = 0;
+            ++ct;
+        }
+    };
+
+    if (items > 0) {
+        int base = 0;
+        for (; base + P < items; base += P) {
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                const Item cur = ring[p];
+                issue(ring[p]);
+                compute(cur);
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+            if (base + p < items) compute(ring[p]);
+    }
+    if (lgS == 0) return;
+
+    // Cross-slice sum: thread e = (slot, column, slice) with the slice index fastest, so the S
+    // partials of one output sit in S adjacent lanes and fold in a fixed xor tree.
+    __syncthreads();
+    const int total = (nT_max << (lgTW + lgS)) * 16;
+    for (int e = threadIdx.x; e < total; e += blockDim.x) {
+        const int q = e & (S - 1), col = (e >> lgS) & 15, slot = e >> (lgS + 4);
+        float v = red[((slot << lgS) + q) * 16 + col];
+        for (int m = S >> 1; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+        const int tile = ((int)blockIdx.x << lgTW) + (slot & (TW - 1)) + (slot >> lgTW) * t_step;
+        if (q == 0 && tile < tiles) {
+            const int64_t n = (int64_t)tile * kTileRows + col;
+            if (out_f32)
+                reinterpret_cast<float *>(y)[n] = v;
+            else
+                reinterpret_cast<uint16_t *>(y)[n] = f32_to_bf16(v);
+        }
+    }
+}
+
+int env_int(const char *name, int fallback) {
+    const char *v = std::getenv(name);
+    return (v && *v) ? std::atoi(v) : fallback;
+}
+
+struct GemvPlan {
+    int S, TW, grid;
+};
+
+// Launch shape from (groups, tiles), after a sweep of (S, TW, grid, P) on MI355X at the four
+// decoder shapes: up to two workgroups' worth of tiles per CU runs as one workgroup of 16 k
+// slices per tile; beyond that, 8 slices and two workgroups per CU, each looping over tiles.
+GemvPlan plan_for(int groups, int tiles, int cus) {
+    GemvPlan p;
+    p.TW = 1;
+    p.S = tiles <= 2 * cus ? 16 : 8;
+    while (p.S > groups) p.S >>= 1;
+    const int resident = cus * (16 / p.S);
+    p.grid = tiles < resident ? tiles : resident;
+    return p;
+}
+
+}  // namespace
+
+hipError_t launch_w3_gemv(const LayerView3 &L, const uint16_t *x, void *y, bool out_f32,
+                          hipStream_t stream) {
+    const int groups = (int)(L.K / kGroup);
+    const int tiles = (int)(L.N / kTileRows);
+    static int cus = 0;   // compute units of the (single) device, asked once
+    if (cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            cus = v;
+        else
+            cus = 256;
+    }
+    GemvPlan plan = plan_for(groups, tiles, cus);
+    // sweep overrides (unset in production)
+    plan.S = env_int("DMR_GEMV3_S", plan.S);
+    plan.TW = env_int("DMR_GEMV3_TW", plan.TW);
+    plan.grid = env_int("DMR_GEMV3_GRID", plan.grid);
+    auto log2_exact = [](int v) {
+        int l = 0;
+        while ((1 << l) < v) ++l;
+        return (1 << l) == v ? l : -1;
+    };
+    const int lgS = log2_exact(plan.S), lgTW = log2_exact(plan.TW);
+    if (lgS < 0 || lgTW < 0 || plan.S * plan.TW > 16 || plan.S > groups || plan.grid < 1)
+        return hipErrorInvalidValue;
+    const int nw = plan.S * plan.TW;
+    const int xl_need = (groups * 16 + nw * 64 - 1) / (nw * 64);   // x staging loads per thread
+    if (xl_need > 8) return hipErrorInvalidValue;
+    const int t_step = plan.grid * plan.TW;
+    const int nT_max = (tiles + t_step - 1) / t_step;
+    const int gw_max = (groups + plan.S - 1) / plan.S;
+    const size_t lds = (size_t)groups * 16 * sizeof(uint4) + (size_t)((groups + 3) & ~3) * sizeof(float) +
+                       (plan.S > 1 ? (size_t)nT_max * nw * 16 * sizeof(float) : 0);
+    if (lds > 64 * 1024) return hipErrorInvalidValue;   // caller falls back to the general kernel
+
+    // Ring depth: four blocks in flight per wave measured best (more costs registers, hence
+    // resident waves); shorter streams take their whole length.
+    const int items_max = nT_max * gw_max;
+    int P = items_max < 4 ? items_max : 4;
+    P = env_int("DMR_GEMV3_P", P);
+    const dim3 g(plan.grid), b(nw * 64);
+    const int of = out_f32 ? 1 : 0;
+#define DMR_GEMV3_LAUNCH(PP, XX)                                                                        \
+    hipLaunchKernelGGL((w3_gemv_kernel<PP, XX>), g, b, lds, stream, L.wt, L.sz, x, y, groups, tiles, lgS, \
+                       lgTW, nT_max, of)
+#define DMR_GEMV3_CASE(PP)                                                                              \
+    case PP:                                                                                           \
+        if (xl_need <= 1) DMR_GEMV3_LAUNCH(PP, 1);                                                      \
+        else if (xl_need <= 2) DMR_GEMV3_LAUNCH(PP, 2);                                                 \
+        else if (xl_need <= 4) DMR_GEMV3_LAUNCH(PP, 4);                                                 \
+        else DMR_GEMV3_LAUNCH(PP, 8);                                                                   \
+        break;
+    switch (P) {
+        DMR_GEMV3_CASE(1) DMR_GEMV3_CASE(2) DMR_GEMV3_CASE(3) DMR_GEMV3_CASE(4)
+        default: return hipErrorInvalidValue;
+    }
+#undef DMR_GEMV3_CASE
+#undef DMR_GEMV3_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace dmr
