@@ -76,6 +76,18 @@ dmr_status_t dmr_qlinear_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32
                                 const uint16_t *d_zeros,   /* bf16 [N][K/g] */
                                 void *d_storage, size_t storage_bytes, void *stream);
 
+/*
+ * The paper's literal W4A16 setting, "default per-channel grouping" (App. E "Per-cell configuration"):
+ * symmetric INT4 with one bf16 scale per output row and the fixed zero point 8,
+ *   w^[n][k] = (q[n][k] - 8) * scales[n].
+ * d_scales is bf16 [N].  The handle behaves like a group-wise one (g reported as K); in this build
+ * the row scale is replicated into the per-group stream, so storage and traffic are those of g = 128.
+ */
+dmr_status_t dmr_qlinear_create_per_channel(dmr_qlinear_t **out, int64_t K, int64_t N,
+                                            const uint32_t *d_qweight, /* [N][K/8] */
+                                            const uint16_t *d_scales,  /* bf16 [N] */
+                                            void *d_storage, size_t storage_bytes, void *stream);
+
 /* The layer's weights as bf16 [N][K]: RNE_bf16((q - z) * s), exactly one correct answer. */
 dmr_status_t dmr_qlinear_dequantize(const dmr_qlinear_t *layer, uint16_t *d_w_bf16, void *stream);
 

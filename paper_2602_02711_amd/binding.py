@@ -24,7 +24,7 @@ EXPORTS = (
     "dmr_qlinear_dequantize", "dmr_qlinear_forward", "dmr_qlinear_bf16_forward",
     "dmr_qlinear_quantize", "dmr_qlinear_destroy", "dmr_qlinear_shape", "dmr_status_string",
     "dmr_probe_hbm_read", "dmr_qlinear_w3_storage_bytes", "dmr_qlinear_w3_workspace_bytes",
-    "dmr_qlinear_w3_create", "dmr_qlinear_quantize_w3", "dmr_qlinear_bits",
+    "dmr_qlinear_w3_create", "dmr_qlinear_quantize_w3", "dmr_qlinear_bits", "dmr_qlinear_create_per_channel",
 )
 
 
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.dmr_qlinear_w3_create.argtypes = [ctypes.POINTER(vp), i64, i64, i32, vp, vp, vp, vp, sz, vp]
         L.dmr_qlinear_quantize_w3.restype = ctypes.c_int
         L.dmr_qlinear_quantize_w3.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp]
+        L.dmr_qlinear_create_per_channel.restype = ctypes.c_int
+        L.dmr_qlinear_create_per_channel.argtypes = [ctypes.POINTER(vp), i64, i64, vp, vp, vp, sz, vp]
         L.dmr_qlinear_bits.restype = i32
         L.dmr_qlinear_bits.argtypes = [vp]
         L.dmr_probe_hbm_read.restype = ctypes.c_int
@@ -225,6 +227,25 @@ def dmr_qlinear_quantize(w: torch.Tensor, g: int = 128, stream=None):
     _check(lib().dmr_qlinear_quantize(K, N, g, pw_, qweight.data_ptr(), scales.data_ptr(),
                                       zeros.data_ptr(), _stream(stream)), "dmr_qlinear_quantize")
     return qweight, scales, zeros
+
+
+def dmr_qlinear_create_per_channel(qweight: torch.Tensor, scales: torch.Tensor,
+                                   storage: torch.Tensor | None = None, stream=None) -> Layer:
+    """Symmetric per-channel INT4: qweight [N][K/8], one bf16 scale per row, zero point 8."""
+    pq = _dev(qweight, "qweight", _U32)
+    ps = _dev(scales, "scales", _BF16)
+    N, K8 = qweight.shape
+    K = K8 * 8
+    if scales.numel() != N:
+        raise ValueError("scales must hold one value per row")
+    need = dmr_qlinear_storage_bytes(K, N, 128)
+    if storage is None:
+        storage = torch.empty(max(need, 16), dtype=torch.uint8, device=qweight.device)
+    pst = _dev(storage, "storage", (torch.uint8,))
+    handle = ctypes.c_void_p()
+    _check(lib().dmr_qlinear_create_per_channel(ctypes.byref(handle), K, N, pq, ps, pst, storage.numel(),
+                                                _stream(stream)), "dmr_qlinear_create_per_channel")
+    return Layer(handle.value, storage, K, N, K)
 
 
 def dmr_qlinear_w3_storage_bytes(K: int, N: int, g: int = 128) -> int:

@@ -73,7 +73,38 @@ dmr_status_t dmr_qlinear_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32
     const hipError_t e = dmr::launch_retile(K, N, d_qweight, d_scales, d_zeros,
                                             reinterpret_cast<uint4 *>(base),
                                             reinterpret_cast<uint32_t *>(base + dmr::weight_region_bytes(K, N)),
-                                            static_cast<hipStream_t>(stream));
+                                            false, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) {
+        delete h;
+        return DMR_ERR_HIP;
+    }
+    *out = h;
+    return DMR_OK;
+}
+
+dmr_status_t dmr_qlinear_create_per_channel(dmr_qlinear_t **out, int64_t K, int64_t N,
+                                            const uint32_t *d_qweight, const uint16_t *d_scales,
+                                            void *d_storage, size_t storage_bytes, void *stream) {
+    if (!out) return DMR_ERR_NULL;
+    *out = nullptr;
+    const dmr_status_t shape = check_shape(K, N, dmr::kGroup);
+    if (shape != DMR_OK) return shape;
+    if (!d_qweight || !d_scales || !d_storage) return DMR_ERR_NULL;
+    if (!aligned16(d_qweight) || !aligned16(d_scales) || !aligned16(d_storage)) return DMR_ERR_ALIGN;
+    if (storage_bytes < dmr_qlinear_storage_bytes(K, N, dmr::kGroup)) return DMR_ERR_WORKSPACE;
+    dmr_qlinear *h = new (std::nothrow) dmr_qlinear;
+    if (!h) return DMR_ERR_NULL;
+    h->K = K;
+    h->N = N;
+    h->g = (int32_t)K;      // one group spans the whole row
+    h->bits = 4;
+    h->wt3 = nullptr;
+    uint8_t *base = static_cast<uint8_t *>(d_storage);
+    h->wt = reinterpret_cast<const uint4 *>(base);
+    h->sz = reinterpret_cast<const uint32_t *>(base + dmr::weight_region_bytes(K, N));
+    const hipError_t e = dmr::launch_retile(K, N, d_qweight, d_scales, nullptr, reinterpret_cast<uint4 *>(base),
+                                            reinterpret_cast<uint32_t *>(base + dmr::weight_region_bytes(K, N)),
+                                            true, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) {
         delete h;
         return DMR_ERR_HIP;
@@ -185,7 +216,8 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
     }
     if (M > 16 && M <= kSkinnyMaxM) return hip_status(dmr::launch_w4_skinny2(L, d_x, M, d_y, f32, d_ws, s));
     if (M <= kSkinnyMaxM) return hip_status(dmr::launch_w4_skinny(L, d_x, M, d_y, f32, s));
-    if (dmr::gemm_big_applies(M, L.N)) return hip_status(dmr::launch_w4_gemm_big(L, d_x, M, d_y, f32, s));
+    // the INT4 GEMM keeps weights exact (integer codes in the MFMA, scale per group in fp32); only the
+    // 128 x 128 kernel has room for its per-group accumulators
     return hip_status(dmr::launch_w4_gemm(L, d_x, M, d_y, f32, s));
 }
 

@@ -95,7 +95,8 @@ inline size_t sz_region_bytes(int64_t K, int64_t N) { return (size_t)N * (size_t
 
 // Kernel launchers (each returns hipGetLastError() after its launch).
 hipError_t launch_retile(int64_t K, int64_t N, const uint32_t *qweight, const uint16_t *scales,
-                         const uint16_t *zeros, uint4 *wt, uint32_t *sz, hipStream_t stream);
+                         const uint16_t *zeros, uint4 *wt, uint32_t *sz, bool per_channel,
+                         hipStream_t stream);
 hipError_t launch_dequantize(const LayerView &L, uint16_t *w_bf16, hipStream_t stream);
 hipError_t launch_quantize(int64_t K, int64_t N, const float *w, uint32_t *qweight,
                            uint16_t *scales, uint16_t *zeros, hipStream_t stream);

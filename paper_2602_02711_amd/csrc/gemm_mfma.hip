@@ -1,7 +1,10 @@
 // Tiled MFMA GEMM for prefill-sized M (a long prompt: few-shot prefix plus the whole history),
 // y[M][N] = x[M][K] . W[N][K]^T with fp32 accumulation.  Two weight sources share the kernel:
-// bf16 weights read as they are, and INT4 streaming blocks dequantised to bf16 on their way
-// into LDS (RNE_bf16((q - z) s), the same value dequantize produces).
+// bf16 weights read as they are, and INT4 streaming blocks whose codes go into LDS as the exact
+// small integers (q - z) (exact in bf16); the MFMAs of one group of 128 k accumulate into a
+// per-group tile that is folded into the result with the group's scale in fp32,
+//     acc += s[n][G] * D_G,
+// so no weight is ever rounded: the prefill path is as accurate as the decode path.
 //
 // Workgroup tile 128 (m) x 128 (n) x 64 (k), 4 wavefronts in a 2 x 2 grid, each owning a 64 x 64
 // patch as 2 x 2 tiles of v_mfma_f32_32x32x16_bf16.  Global loads for step i+1 are issued into
@@ -78,18 +81,18 @@ __device__ __forceinline__ void store_lds(const Prefetch<W4> &p, uint16_t *As, u
         const int l = tid & 31;                       // lane within the half block
         const int row = (tid >> 5) * kTileRows + (l & 15);
         const int kofs = (l >> 4) * 32;               // 0 or 32 inside the 64-wide step
-        const float s = __uint_as_float(p.szw << 16);
-        const float czs = __uint_as_float(p.szw & 0xFFFF0000u) * s;   // -(128 + z) s, exact
+        const float cz = __uint_as_float(p.szw & 0xFFFF0000u);   // -(128 + z)
         const uint32_t words[4] = {p.wb[0].x, p.wb[0].y, p.wb[0].z, p.wb[0].w};
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             uint32_t o[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                // (128 + q) as fp32 straight from the bf16 magic pair, then one exact FMA each
+                // (128 + q) as fp32 straight from the bf16 magic pair; adding -(128 + z) leaves the
+                // integer q - z in [-15, 15], which bf16 holds exactly
                 const uint32_t pair = ((words[t] >> (4 * i)) & 0x000F000Fu) | 0x43004300u;
-                const float lo = fmaf(__uint_as_float(pair << 16), s, czs);
-                const float hi = fmaf(__uint_as_float(pair & 0xFFFF0000u), s, czs);
+                const float lo = __uint_as_float(pair << 16) + cz;
+                const float hi = __uint_as_float(pair & 0xFFFF0000u) + cz;
                 o[i] = pack_bf16x2(lo, hi);
             }
             *reinterpret_cast<uint4 *>(Bs + row * LDS_STRIDE + kofs + t * 8) =
@@ -106,7 +109,7 @@ __device__ __forceinline__ void store_lds(const Prefetch<W4> &p, uint16_t *As, u
 }
 
 template <bool W4, bool OUT_F32>
-__global__ __launch_bounds__(256) void gemm_kernel(const void *__restrict__ wsrc,
+__global__ __launch_bounds__(256, 2) void gemm_kernel(const void *__restrict__ wsrc,
                                                    const uint32_t *__restrict__ sz,
                                                    const uint16_t *__restrict__ x,
                                                    void *__restrict__ y, int64_t M, int64_t K,
@@ -127,12 +130,38 @@ __global__ __launch_bounds__(256) void gemm_kernel(const void *__restrict__ wsrc
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
+    // INT4: per-group accumulators and this lane's two weight rows (one per n tile)
+    f32x16 grp[2][2];
+    if (W4) {
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) grp[a][b][r] = 0.f;
+    }
+    const int64_t groups = K / kGroup;
+    int64_t srow[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int64_t n = n0 + wn * 64 + j * 32 + (lane & 31);
+        const int64_t nc = n < N ? n : N - 1;                         // clamped: never stored
+        srow[j] = ((nc / kTileRows) * groups) * kTileRows + (nc % kTileRows);   // sz index of (row, G = 0)
+    }
+
     Prefetch<W4> pre;
     load_global<W4>(pre, wsrc, sz, x, M, K, N, m0, n0, 0, tid);
     for (int64_t k0 = 0; k0 < K; k0 += BK) {
         store_lds<W4>(pre, As, Bs, tid);
         __syncthreads();
         if (k0 + BK < K) load_global<W4>(pre, wsrc, sz, x, M, K, N, m0, n0, k0 + BK, tid);
+        float gscale[2] = {0.f, 0.f};
+        const bool group_end = W4 && ((k0 + BK) % kGroup == 0);
+        if (group_end) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                gscale[j] = __uint_as_float(sz[srow[j] + (k0 / kGroup) * kTileRows] << 16);
+        }
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             Frag a[2], b[2];
@@ -145,8 +174,23 @@ __global__ __launch_bounds__(256) void gemm_kernel(const void *__restrict__ wsrc
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    if (W4)
+                        grp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, grp[i][j], 0, 0, 0);
+                    else
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, acc[i][j], 0, 0, 0);
+                }
+        }
+        if (group_end) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
                 for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, acc[i][j], 0, 0, 0);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        acc[i][j][r] = fmaf(gscale[j], grp[i][j][r], acc[i][j][r]);
+                        grp[i][j][r] = 0.f;
+                    }
         }
         __syncthreads();
     }

@@ -13,7 +13,7 @@ __global__ __launch_bounds__(256) void retile_kernel(int64_t K, int64_t N,
                                                      const uint16_t *__restrict__ scales,
                                                      const uint16_t *__restrict__ zeros,
                                                      uint4 *__restrict__ wt,
-                                                     uint32_t *__restrict__ sz) {
+                                                     uint32_t *__restrict__ sz, int per_channel) {
     const int64_t groups = K / kGroup;
     const int64_t slot = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t slots = N * K / 32;
@@ -36,19 +36,21 @@ __global__ __launch_bounds__(256) void retile_kernel(int64_t K, int64_t N,
     }
     wt[slot] = make_uint4(out[0], out[1], out[2], out[3]);
     if (c == 0) {
-        const uint32_t s_bits = scales[n * groups + G];
-        const float z = bf16_bits_to_f32(zeros[n * groups + G]);
+        // per-channel symmetric layers carry one scale per row and the fixed zero point 8
+        const uint32_t s_bits = per_channel ? scales[n] : scales[n * groups + G];
+        const float z = per_channel ? 8.0f : bf16_bits_to_f32(zeros[n * groups + G]);
         const uint32_t cz_bits = __float_as_uint(-(128.0f + z)) >> 16;   // exact in bf16
         sz[block * kTileRows + j] = s_bits | (cz_bits << 16);
     }
 }
 
 hipError_t launch_retile(int64_t K, int64_t N, const uint32_t *qweight, const uint16_t *scales,
-                         const uint16_t *zeros, uint4 *wt, uint32_t *sz, hipStream_t stream) {
+                         const uint16_t *zeros, uint4 *wt, uint32_t *sz, bool per_channel,
+                         hipStream_t stream) {
     const int64_t slots = N * K / 32;
     const unsigned blocks = (unsigned)((slots + 255) / 256);
     hipLaunchKernelGGL(retile_kernel, dim3(blocks), dim3(256), 0, stream, K, N, qweight, scales, zeros,
-                       wt, sz);
+                       wt, sz, per_channel ? 1 : 0);
     return hipGetLastError();
 }
 

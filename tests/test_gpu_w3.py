@@ -101,3 +101,22 @@ def test_w3_one_hot_and_exact_cases():
         y32 = dmr.dmr_qlinear_forward(layer2, bf16_dev(x), out_dtype=torch.float32).cpu().numpy()
         y_ref, _ = orc.forward3(words2, s2, z2, G, x)
         assert np.array_equal(y32.astype(np.float64), y_ref), M
+
+
+# ------------------------------------------------------------------ per-channel symmetric W4 (g = K, z = 8)
+
+@pytest.mark.parametrize("K,N,M", [(1024, 1024, 1), (384, 48, 7), (4096, 4096, 1), (1920, 272, 33), (512, 256, 200)])
+def test_per_channel_symmetric_layer(K, N, M):
+    rng = np.random.default_rng(90 + K + M)
+    q = rng.integers(0, 16, size=(N, K), dtype=np.uint8)
+    s_row = synth.to_bf16_bits(np.abs(synth.weights_f32(91 + K, N, 1)) + np.float32(2e-3))       # [N][1]
+    z_row = orc.f64_to_bf16(np.full((N, 1), 8.0))
+    words = orc.pack(q)
+    layer = dmr.dmr_qlinear_create_per_channel(u32_dev(words), bf16_dev(s_row.reshape(N)))
+    assert layer.g == K
+    # the oracle takes any group size that divides K: one group per row, zero point 8
+    assert np.array_equal(bits_host(dmr.dmr_qlinear_dequantize(layer)), orc.dequantize(words, s_row, z_row, K))
+    x = synth.activations_bf16(92 + K, M, K)
+    y32 = dmr.dmr_qlinear_forward(layer, bf16_dev(x), out_dtype=torch.float32).cpu().numpy()
+    y_ref, _ = orc.forward(words, s_row, z_row, K, x, threads=THREADS)
+    assert rel_err(y32, y_ref) <= TOL
