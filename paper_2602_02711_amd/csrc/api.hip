@@ -17,6 +17,20 @@ namespace {
 
 constexpr int64_t kSkinnyMaxM = 64;
 
+// Which INT4 kernel serves M rows of a (K, N) layer (measured crossovers, 256 CUs).  The workspace
+// query and the forward call both go through this.
+enum class W4Path { Gemv, Stream, Skinny2, Mid, Gemm };
+W4Path w4_path(int64_t M, int64_t K, int64_t N) {
+    if (M == 1) return W4Path::Gemv;
+    if (M <= 16) return dmr::w4_stream_fits(M, K, N) ? W4Path::Stream : W4Path::Mid;
+    const int64_t tiles = N / dmr::kTileRows;
+    // wide layers already give the register-blocked streaming kernel 4 tiles per workgroup
+    if (M <= kSkinnyMaxM) return tiles >= 1024 ? W4Path::Skinny2 : W4Path::Mid;
+    // the 128 x 128 GEMM needs a few hundred workgroups to fill the chip
+    const int64_t gemm_wgs = ((M + 127) / 128) * ((N + 127) / 128);
+    return (M <= 128 || gemm_wgs < 400) ? W4Path::Mid : W4Path::Gemm;
+}
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 dmr_status_t check_shape(int64_t K, int64_t N, int32_t g) {
@@ -41,10 +55,12 @@ size_t dmr_qlinear_storage_bytes(int64_t K, int64_t N, int32_t g) {
 }
 
 size_t dmr_qlinear_workspace_bytes(int64_t M, int64_t K, int64_t N) {
-    (void)N;
-    if (M <= 0 || K <= 0 || K % dmr::kGroup != 0) return 0;
-    // only the 16 < M <= 64 INT4 path stages anything outside LDS: its re-ordered activations
-    return dmr::w4_skinny2_workspace_bytes(M, K);
+    if (M <= 0 || K <= 0 || K % dmr::kGroup != 0 || N <= 0 || N % dmr::kTileRows != 0) return 0;
+    switch (w4_path(M, K, N)) {
+        case W4Path::Mid: return dmr::w4_mid_workspace_bytes(M, K, N);    // fp32 partials when K is split
+        case W4Path::Skinny2: return dmr::w4_skinny2_workspace_bytes(M, K);   // re-ordered activations
+        default: return 0;
+    }
 }
 
 dmr_status_t dmr_qlinear_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32_t g,
@@ -206,15 +222,17 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
     const size_t need = dmr_qlinear_workspace_bytes(M, layer->K, layer->N);
     if (need > 0 && (!d_ws || ws_bytes < need)) return DMR_ERR_WORKSPACE;
     const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz};
-    if (M == 1) {
+    const W4Path path = w4_path(M, layer->K, layer->N);
+    if (path == W4Path::Gemv) {
         const hipError_t e = dmr::launch_w4_gemv(L, d_x, d_y, f32, s);
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: shape outside its range
     }
-    if (M >= 2 && M <= 16) {
+    if (path == W4Path::Stream) {
         const hipError_t e = dmr::launch_w4_stream(L, d_x, M, d_y, f32, s);
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: activations do not fit LDS
     }
-    if (M > 16 && M <= kSkinnyMaxM) return hip_status(dmr::launch_w4_skinny2(L, d_x, M, d_y, f32, d_ws, s));
+    if (path == W4Path::Mid) return hip_status(dmr::launch_w4_mid(L, d_x, M, d_y, f32, d_ws, s));
+    if (path == W4Path::Skinny2) return hip_status(dmr::launch_w4_skinny2(L, d_x, M, d_y, f32, d_ws, s));
     if (M <= kSkinnyMaxM) return hip_status(dmr::launch_w4_skinny(L, d_x, M, d_y, f32, s));
     // the INT4 GEMM keeps weights exact (integer codes in the MFMA, scale per group in fp32); only the
     // 128 x 128 kernel has room for its per-group accumulators

@@ -74,6 +74,22 @@ __device__ __forceinline__ float row16_sum(float v) {
     return row_ror_add<1>(v);
 }
 
+// One streaming-layout word (8 nibbles) -> four MFMA B-operand registers, register i = the bf16 pair
+// (128 + nibble i, 128 + nibble i + 4), i.e. ((w >> 4 i) & 0x000F000F) | 0x43004300, in 7 VALU
+// instructions: two masks split the nibbles into bytes and v_perm_b32 interleaves them with the
+// 0x43 exponent byte (selector bytes 4..7 pick bytes of the first source, 0..3 of the second).
+// Deliberately no inline assembly: the wait states an MFMA needs after a VALU write of its
+// operands are only inserted by the compiler for instructions it emitted itself.
+__device__ __forceinline__ void unpack_word(uint32_t w, uint32_t (&out)[4]) {
+    const uint32_t even = w & 0x0F0F0F0Fu;            // nibbles 0, 2, 4, 6 as bytes
+    const uint32_t odd = (w >> 4) & 0x0F0F0F0Fu;      // nibbles 1, 3, 5, 7
+    const uint32_t exp = 0x43434343u;
+    out[0] = __builtin_amdgcn_perm(even, exp, 0x00060004u);   // nibbles 0, 4
+    out[1] = __builtin_amdgcn_perm(odd, exp, 0x00060004u);    // nibbles 1, 5
+    out[2] = __builtin_amdgcn_perm(even, exp, 0x00070005u);   // nibbles 2, 6
+    out[3] = __builtin_amdgcn_perm(odd, exp, 0x00070005u);    // nibbles 3, 7
+}
+
 // Position p (0..7) of a streaming-layout word -> nibble index.
 __host__ __device__ __forceinline__ int nibble_of_position(int p) { return (p >> 1) + 4 * (p & 1); }
 
@@ -107,12 +123,18 @@ hipError_t launch_w4_gemv(const LayerView &L, const uint16_t *x, void *y, bool o
 hipError_t launch_bf16_gemv(const uint16_t *w, const uint16_t *x, int64_t K, int64_t N, void *y,
                             bool out_f32, hipStream_t stream);
 // 2 <= M <= 16 streaming kernel; hipErrorInvalidValue (nothing launched) when the activations do not fit LDS.
+bool w4_stream_fits(int64_t M, int64_t K, int64_t N);
 hipError_t launch_w4_stream(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
                             hipStream_t stream);
 // 16 < M <= 64: activation pre-pass into `ws` (w4_skinny2_workspace_bytes), then the streaming kernel.
 size_t w4_skinny2_workspace_bytes(int64_t M, int64_t K);
 hipError_t launch_w4_skinny2(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
                              void *ws, hipStream_t stream);
+// 16 < M up to a few hundred rows: weights straight into registers, activations through LDS, optional
+// split of K whose fp32 partials go to `ws` (w4_mid_workspace_bytes) and are added by a second kernel.
+size_t w4_mid_workspace_bytes(int64_t M, int64_t K, int64_t N);
+hipError_t launch_w4_mid(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
+                         hipStream_t stream);
 hipError_t launch_retile3(int64_t K, int64_t N, const uint32_t *qweight, const uint16_t *scales,
                           const uint16_t *zeros, uint32_t *wt, uint32_t *sz, hipStream_t stream);
 hipError_t launch_dequantize3(const LayerView3 &L, uint16_t *w_bf16, hipStream_t stream);

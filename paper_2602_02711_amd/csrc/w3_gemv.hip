@@ -6,8 +6,8 @@
 //
 // Streaming layout of a lane's three words (32 weights k = 32 c + i): operand register r = i / 2
 // (the pair i = 2r, 2r + 1, low and high half).  For r < 15 the two 3-bit codes sit in field r % 5
-// of word r / 5: bits [3f, 3f+3) of the low half and of the high half, so one shift and one
-// v_and_or_b32 (mask 0x00070007, or 0x43004300) give the bf16 pair (128 + q, 128 + q).  Each half
+// of word r / 5: bits [3f, 3f+3) of the low half and of the high half, so a shift, an and
+// (mask 0x00070007) and an or (0x43004300) give the bf16 pair (128 + q, 128 + q).  Each half
 // keeps one spare bit (15 and 31); the three low spare bits are code 30, the three high ones code
 // 31 (register 15).
 #include <cstdlib>
@@ -19,12 +19,10 @@ namespace dmr {
 namespace {
 
 
-// (a & mask) | c in one VALU instruction; mask rides the scalar operand slot.
-__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) {
-    uint32_t r;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(c));
-    return r;
-}
+// (a & mask) | c.  Plain C on purpose (an and and an or): inline assembly for the fused
+// v_and_or_b32 is not an option next to MFMAs, whose operand wait states after a VALU write the
+// compiler inserts only for instructions it emitted itself.
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) { return (a & mask) | c; }
 
 struct Item {
     uint32_t w0, w1, w2;
@@ -39,10 +37,9 @@ __device__ __forceinline__ uint32_t pair_reg(uint32_t w0, uint32_t w1, uint32_t 
         const uint32_t w = (R / 5 == 0) ? w0 : (R / 5 == 1 ? w1 : w2);
         return and_or(w >> (3 * (R % 5)), mask, magic);
     }
-    uint32_t v = (w0 >> 15) & 0x00010001u;
+    uint32_t v = and_or(w0 >> 15, 0x00010001u, magic);
     v = and_or(w1 >> 14, 0x00020002u, v);
-    v = and_or(w2 >> 13, 0x00040004u, v);
-    return v | magic;
+    return and_or(w2 >> 13, 0x00040004u, v);
 }
 
 template <int P, int XL>

@@ -7,7 +7,7 @@
 // block loads, so the HBM stream never drains between tiles.  With S > 1 the partial sums meet in
 // LDS once, at the end, and are added in slice order (deterministic, no float atomics).
 //
-// Per block: 3 shifts + 4 v_and_or_b32 per packed word turn nibbles into bf16 (128 + q) pairs,
+// Per block: 2 masks, 1 shift and 4 v_perm_b32 per packed word turn nibbles into bf16 (128 + q) pairs,
 // four 16x16x32 MFMAs contract them with x (row 0 of the A operand; the other 15 rows repeat it
 // and are ignored), and
 //     acc += s * (D - (128 + z) * X)
@@ -21,13 +21,6 @@ namespace dmr {
 
 namespace {
 
-
-// (a & mask) | c in one VALU instruction; mask rides the scalar operand slot.
-__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) {
-    uint32_t r;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(c));
-    return r;
-}
 
 struct Item {
     uint4 w;
@@ -103,7 +96,6 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
     __syncthreads();
 
     const uint4 *xs = smem + g0 * 16;
-    const uint32_t mask = 0x000F000Fu, magic = 0x43004300u;
     float acc = 0.f;
     int ct = 0, cg = 0;
     auto compute = [&](const Item &cur) {
@@ -117,10 +109,7 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             Frag b;
-            b.w[0] = and_or(words[t], mask, magic);
-            b.w[1] = and_or(words[t] >> 4, mask, magic);
-            b.w[2] = and_or(words[t] >> 8, mask, magic);
-            b.w[3] = and_or(words[t] >> 12, mask, magic);
+            unpack_word(words[t], b.w);
             d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t].v, b.v, d, 0, 0, 0);
         }
         const float sc = __uint_as_float(cur.szw << 16);

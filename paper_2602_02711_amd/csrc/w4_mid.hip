@@ -1,0 +1,305 @@
+// W4A16 for batches of 17 rows up to several hundred (a group of parallel rollouts decoding together,
+// or a short prefill): too many rows for the pure streaming kernels, too few for a tiled GEMM to fill
+// 256 CUs.
+//
+// The streaming layout already is MFMA B-operand order, so the weights never touch LDS: a wave
+// loads its 1 KiB blocks straight into registers (nontemporal, double buffered one group ahead),
+// unpacks them with the bf16 magic number and feeds v_mfma_f32_16x16x32_bf16.  Only the activations
+// go through LDS: the workgroup's BM x 128 slice of x for the current group, double buffered, rows
+// padded to 272 bytes so that the 16-byte A-operand reads of 8 consecutive lanes fall in distinct
+// banks.  A wave owns MTW row tiles x R weight tiles; every A fragment it reads from LDS feeds R MFMAs
+// and every unpacked weight register MTW MFMAs.  The group sums of x come from one more MFMA against
+// an all-ones operand, already in accumulator layout, and a group contributes
+//     acc += s (D - (128 + z) X)                                  (exact codes, fp32 scale)
+// as in the decode kernels, so this path has their accuracy.
+//
+// Small N x M leaves too few (row block, column block) pairs for the chip; then K is split over
+// blockIdx.z, each split writes an fp32 partial tile to the caller's workspace and a second kernel
+// adds the partials in ascending split order (deterministic, no atomics).
+#include <algorithm>
+#include <cstdlib>
+
+#include "common.hpp"
+
+namespace dmr {
+
+namespace {
+
+constexpr int ROW_BYTES = 272;   // one activation row of a group in LDS: 128 bf16 + 16 bytes of padding
+
+
+// out_mode: 0 = fp32 y, 1 = bf16 y, 2 = fp32 partial [split][M][N]
+template <int MTW, int WM, int NW, int R>
+__global__ __launch_bounds__(64 * WM * NW, (WM * NW == 4) ? 2 : 1) void w4_mid_kernel(
+    const uint4 *__restrict__ wt, const uint32_t *__restrict__ sz, const uint16_t *__restrict__ x,
+    void *__restrict__ y, int M, int64_t K, int64_t N, int groups, int tiles, int gps, int out_mode) {
+    constexpr int THREADS = 64 * WM * NW;
+    constexpr int BM = 16 * MTW * WM;
+    constexpr int ROWS_PER_PASS = THREADS / 16;
+    constexpr int XL = BM / ROWS_PER_PASS;          // 16-byte pieces of x per thread and group
+    static_assert(BM % ROWS_PER_PASS == 0, "activation rows must divide over the threads");
+    extern __shared__ __attribute__((aligned(16))) uint8_t xl[];   // [2][BM][ROW_BYTES]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = lane >> 4, j = lane & 15;
+    const int wm = wave % WM, wn = wave / WM;
+    const int m0 = (int)blockIdx.y * BM;
+    const int gA = (int)blockIdx.z * gps;
+    const int gB = min(groups, gA + gps);
+
+    const int tile0 = ((int)blockIdx.x * NW + wn) * R;
+    int64_t wbase[R];          // block index of (tile, group 0); ragged last column block re-reads the last tile
+#pragma unroll
+    for (int rt = 0; rt < R; ++rt) wbase[rt] = (int64_t)min(tile0 + rt, tiles - 1) * groups;
+
+    struct Slot {
+        uint4 w[R];
+        uint32_t s[R];
+    };
+    Slot ring[2];
+    auto fetch_w = [&](Slot &s, int g) {
+#pragma unroll
+        for (int rt = 0; rt < R; ++rt) {
+            const int64_t block = wbase[rt] + g;
+            s.w[rt] = load_stream(wt + block * 64 + lane);
+            s.s[rt] = sz[block * kTileRows + j];
+        }
+    };
+
+    // activations: thread -> (row, 16-byte piece) of the BM x 128 slice.  Rows beyond M repeat row
+    // M - 1: MFMA rows are independent and those outputs are never stored, so no zero fill (whose
+    // per-lane select would make the loads conditional) is needed.
+    uint4 xr[XL];
+    const int xrow = tid >> 4, xpiece = tid & 15;
+    auto fetch_x = [&](int g) {
+#pragma unroll
+        for (int p = 0; p < XL; ++p) {
+            const int m = m0 + p * ROWS_PER_PASS + xrow;
+            const int mc = min(m, M - 1);
+            xr[p] = *reinterpret_cast<const uint4 *>(x + (int64_t)mc * K + (int64_t)g * kGroup + xpiece * 8);
+        }
+    };
+    auto put_x = [&](int buf) {
+        uint8_t *dst = xl + buf * (BM * ROW_BYTES);
+#pragma unroll
+        for (int p = 0; p < XL; ++p)
+            *reinterpret_cast<uint4 *>(dst + (p * ROWS_PER_PASS + xrow) * ROW_BYTES + xpiece * 16) = xr[p];
+    };
+
+    f32x4 acc[R][MTW];
+#pragma unroll
+    for (int rt = 0; rt < R; ++rt)
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt) acc[rt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    Frag ones;
+    ones.w[0] = ones.w[1] = ones.w[2] = ones.w[3] = 0x3F803F80u;
+
+    auto compute = [&](const Slot &s, int buf, bool valid) {
+        const uint8_t *src = xl + buf * (BM * ROW_BYTES) + (wm * MTW * 16 + j) * ROW_BYTES + c * 64;
+        f32x4 d[R][MTW], xs[MTW];
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt) {
+            xs[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int rt = 0; rt < R; ++rt) d[rt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            Frag a[MTW];
+#pragma unroll
+            for (int mt = 0; mt < MTW; ++mt)
+                a[mt].u = *reinterpret_cast<const uint4 *>(src + mt * 16 * ROW_BYTES + t * 16);
+#pragma unroll
+            for (int mt = 0; mt < MTW; ++mt)
+                xs[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mt].v, ones.v, xs[mt], 0, 0, 0);
+#pragma unroll
+            for (int rt = 0; rt < R; ++rt) {
+                const uint32_t word = t == 0 ? s.w[rt].x : t == 1 ? s.w[rt].y : t == 2 ? s.w[rt].z : s.w[rt].w;
+                Frag b;
+                unpack_word(word, b.w);
+#pragma unroll
+                for (int mt = 0; mt < MTW; ++mt)
+                    d[rt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mt].v, b.v, d[rt][mt], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int rt = 0; rt < R; ++rt) {
+            // a slot past the end of this split's k range re-reads its last group with scale 0
+            const float sc = valid ? __uint_as_float(s.s[rt] << 16) : 0.f;
+            const float cz = __uint_as_float(s.s[rt] & 0xFFFF0000u);   // -(128 + z)
+#pragma unroll
+            for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    acc[rt][mt][q] = fmaf(sc, fmaf(cz, xs[mt][q], d[rt][mt][q]), acc[rt][mt][q]);
+        }
+    };
+
+    fetch_w(ring[0], gA);
+    fetch_w(ring[1], min(gA + 1, gB - 1));
+    fetch_x(gA);
+    put_x(0);
+    __syncthreads();
+    for (int g = gA; g < gB; g += 2) {
+        fetch_x(min(g + 1, gB - 1));
+        compute(ring[0], 0, true);
+        fetch_w(ring[0], min(g + 2, gB - 1));
+        put_x(1);
+        __syncthreads();
+        fetch_x(min(g + 2, gB - 1));
+        compute(ring[1], 1, g + 1 < gB);
+        fetch_w(ring[1], min(g + 3, gB - 1));
+        put_x(0);
+        __syncthreads();
+    }
+
+    const int64_t part = out_mode == 2 ? (int64_t)blockIdx.z * M * N : 0;
+#pragma unroll
+    for (int rt = 0; rt < R; ++rt) {
+        const int tile = tile0 + rt;
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int m = m0 + (wm * MTW + mt) * 16 + c * 4 + q;
+                if (m < M && tile < tiles) {
+                    const int64_t o = (int64_t)m * N + (int64_t)tile * kTileRows + j;
+                    if (out_mode == 1)
+                        reinterpret_cast<uint16_t *>(y)[o] = f32_to_bf16(acc[rt][mt][q]);
+                    else
+                        reinterpret_cast<float *>(y)[part + o] = acc[rt][mt][q];
+                }
+            }
+    }
+}
+
+// y = sum over splits of part[split], four outputs per thread, splits in ascending order.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ part, void *__restrict__ y,
+                                                            int64_t total, int splits, int out_f32) {
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i >= total) return;
+    f32x4 v = *reinterpret_cast<const f32x4 *>(part + i);
+    for (int s = 1; s < splits; ++s) {
+        const f32x4 u = *reinterpret_cast<const f32x4 *>(part + (int64_t)s * total + i);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] += u[k];
+    }
+    if (out_f32) {
+        *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(y) + i) = v;
+    } else {
+        uint2 o;
+        o.x = pack_bf16x2(v[0], v[1]);
+        o.y = pack_bf16x2(v[2], v[3]);
+        *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(y) + i) = o;
+    }
+}
+
+struct MidPlan {
+    int MTW, WM, NW, R, SK, gps;
+};
+
+int env_int(const char *name, int fallback) {
+    const char *v = std::getenv(name);
+    return v ? std::atoi(v) : fallback;
+}
+
+// Pure host arithmetic (the workspace query must agree with the launch): 256 CUs assumed.
+MidPlan plan_mid(int64_t M, int64_t K, int64_t N) {
+    MidPlan p;
+    const int groups = (int)(K / kGroup), tiles = (int)(N / kTileRows);
+    if (M <= 64) {
+        p.MTW = (int)((M + 15) / 16);
+        if (p.MTW < 2) p.MTW = 2;
+        p.WM = 1;
+        p.NW = 4;
+    } else {
+        const int64_t pad3 = (M + 95) / 96 * 96, pad4 = (M + 127) / 128 * 128;
+        p.MTW = pad3 < pad4 ? 3 : 4;
+        p.WM = 2;
+        p.NW = 2;
+    }
+    const int BM = 16 * p.MTW * p.WM;
+    const int64_t mblocks = (M + BM - 1) / BM;
+    // Measured rules (gfx950, 256 CUs): split K while that keeps >= 8 groups per split and fewer than
+    // 384 workgroups exist; two weight tiles per wave unless that leaves under 256 workgroups
+    // even at the deepest split.
+    auto split_for = [&](int64_t wgs) {
+        int sk = 1;
+        while (wgs * sk < 384 && groups % (sk * 2) == 0 && groups / (sk * 2) >= 8) sk *= 2;
+        return sk;
+    };
+    auto wgs_for = [&](int R) { return (int64_t)((tiles + p.NW * R - 1) / (p.NW * R)) * mblocks; };
+    p.R = wgs_for(2) * split_for(wgs_for(2)) >= 256 ? 2 : 1;
+    const int r_env = env_int("DMR_MID_R", 0);
+    if (r_env == 1 || r_env == 2) p.R = r_env;
+    p.SK = split_for(wgs_for(p.R));
+    const int sk_env = env_int("DMR_MID_SK", 0);
+    if (sk_env >= 1 && groups % sk_env == 0) p.SK = sk_env;
+    p.gps = groups / p.SK;
+    return p;
+}
+
+template <int MTW, int WM, int NW, int R>
+hipError_t launch_cfg(const LayerView &L, const uint16_t *x, int M, void *dst, int out_mode, const MidPlan &p,
+                      hipStream_t stream) {
+    constexpr int BM = 16 * MTW * WM;
+    constexpr size_t lds = 2ull * BM * ROW_BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_mid_kernel<MTW, WM, NW, R>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int groups = (int)(L.K / kGroup), tiles = (int)(L.N / kTileRows);
+    const dim3 grid((unsigned)((tiles + NW * R - 1) / (NW * R)), (unsigned)((M + BM - 1) / BM), (unsigned)p.SK);
+    hipLaunchKernelGGL((w4_mid_kernel<MTW, WM, NW, R>), grid, dim3(64 * WM * NW), lds, stream, L.wt, L.sz, x, dst, M,
+                       L.K, L.N, groups, tiles, p.gps, out_mode);
+    return hipGetLastError();
+}
+
+template <int MTW, int WM, int NW>
+hipError_t launch_r(const LayerView &L, const uint16_t *x, int M, void *dst, int out_mode, const MidPlan &p,
+                    hipStream_t stream) {
+    // R = 4 was measured too: never faster, and with 4 row tiles per wave it needs more than the 256
+    // registers that two waves per SIMD leave
+    return p.R == 2 ? launch_cfg<MTW, WM, NW, 2>(L, x, M, dst, out_mode, p, stream)
+                    : launch_cfg<MTW, WM, NW, 1>(L, x, M, dst, out_mode, p, stream);
+}
+
+}  // namespace
+
+size_t w4_mid_workspace_bytes(int64_t M, int64_t K, int64_t N) {
+    const MidPlan p = plan_mid(M, K, N);
+    return p.SK > 1 ? (size_t)p.SK * (size_t)M * (size_t)N * sizeof(float) : 0;
+}
+
+hipError_t launch_w4_mid(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
+                         hipStream_t stream) {
+    const MidPlan p = plan_mid(M, L.K, L.N);
+    const bool split = p.SK > 1;
+    void *dst = split ? ws : y;
+    const int out_mode = split ? 2 : (out_f32 ? 0 : 1);
+    const int iM = (int)M;
+    hipError_t e;
+    if (p.WM == 1) {
+        switch (p.MTW) {
+            case 2: e = launch_r<2, 1, 4>(L, x, iM, dst, out_mode, p, stream); break;
+            case 3: e = launch_r<3, 1, 4>(L, x, iM, dst, out_mode, p, stream); break;
+            default: e = launch_r<4, 1, 4>(L, x, iM, dst, out_mode, p, stream); break;
+        }
+    } else {
+        e = p.MTW == 3 ? launch_r<3, 2, 2>(L, x, iM, dst, out_mode, p, stream)
+                       : launch_r<4, 2, 2>(L, x, iM, dst, out_mode, p, stream);
+    }
+    if (e != hipSuccess || !split) return e;
+    const int64_t total = M * L.N;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, stream,
+                       static_cast<const float *>(ws), y, total, p.SK, out_f32 ? 1 : 0);
+    return hipGetLastError();
+}
+
+}  // namespace dmr

@@ -18,12 +18,6 @@ namespace dmr {
 
 namespace {
 
-__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) {
-    uint32_t r;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(c));
-    return r;
-}
-
 // ---- pre-pass --------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void xfrag_kernel(const uint16_t *__restrict__ x, uint4 *__restrict__ xf,
                                                     float *__restrict__ xg, int M, int64_t K, int groups,
@@ -82,7 +76,6 @@ __global__ __launch_bounds__(256) void w4_skinny2_kernel(const uint4 *__restrict
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[rt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const uint32_t mask = 0x000F000Fu, magic = 0x43004300u;
     for (int g = g0; g < g1; ++g) {
         uint4 w[R];
         uint32_t szw[R];
@@ -111,10 +104,7 @@ __global__ __launch_bounds__(256) void w4_skinny2_kernel(const uint4 *__restrict
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 Frag b;
-                b.w[0] = and_or(words[t], mask, magic);
-                b.w[1] = and_or(words[t] >> 4, mask, magic);
-                b.w[2] = and_or(words[t] >> 8, mask, magic);
-                b.w[3] = and_or(words[t] >> 12, mask, magic);
+                unpack_word(words[t], b.w);
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
                     d[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mt][t].v, b.v, d[mt], 0, 0, 0);

@@ -25,12 +25,6 @@ int env_int(const char *name, int fallback) {
 
 constexpr uint32_t kOnes = 0x3F803F80u;    // bf16 pair (1.0, 1.0)
 
-__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) {
-    uint32_t r;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(c));
-    return r;
-}
-
 struct Item {
     uint4 w;
     uint32_t szw;
@@ -86,7 +80,6 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
     const uint4 *xrow = smem + (j < M ? j : M - 1) * row_stride + c * 4;
     Frag ones;
     ones.u = make_uint4(kOnes, kOnes, kOnes, kOnes);
-    const uint32_t mask = 0x000F000Fu, magic = 0x43004300u;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     int cs = 0, cg = 0;   // consume pointer: (tile step, slot within step)
 
@@ -102,10 +95,7 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 Frag b;
-                b.w[0] = and_or(words[t], mask, magic);
-                b.w[1] = and_or(words[t] >> 4, mask, magic);
-                b.w[2] = and_or(words[t] >> 8, mask, magic);
-                b.w[3] = and_or(words[t] >> 12, mask, magic);
+                unpack_word(words[t], b.w);
                 d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t].v, b.v, d, 0, 0, 0);
                 xsum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t].v, ones.v, xsum, 0, 0, 0);
             }
@@ -181,6 +171,24 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
 }
 
 }  // namespace
+
+// Whether the M activation rows (plus the reduction buffer of the default launch shape on 256 CUs)
+// fit the 160 KB of LDS; pure host arithmetic, so that the caller can plan its workspace.
+bool w4_stream_fits(int64_t M, int64_t K, int64_t N) {
+    if (M < 2 || M > 16) return false;
+    const int groups = (int)(K / kGroup), tiles = (int)(N / kTileRows);
+    const size_t xbytes = (size_t)M * (groups * 16 + 1) * sizeof(uint4);
+    int nw = 16, S = 16;
+    if (tiles >= 4 * 256) {
+        nw = 8;
+        S = 2;
+    } else if (tiles > 256) {
+        nw = 8;
+        S = 4;
+    }
+    while (S > groups) S >>= 1;
+    return xbytes + (S > 1 ? (size_t)nw * 64 * sizeof(f32x4) : 0) <= 160 * 1024;
+}
 
 hipError_t launch_w4_stream(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
                             hipStream_t stream) {

@@ -35,10 +35,18 @@ def test_size_queries(lib):
     assert lib.dmr_qlinear_storage_bytes(1024, 1024, 64) == 0
     assert lib.dmr_qlinear_workspace_bytes(1, 4096, 4096) == 0
     assert lib.dmr_qlinear_workspace_bytes(16, 4096, 4096) == 0
-    # 16 < M <= 64: activations in MFMA operand order (4 KiB per group and row tile) + their group sums
-    assert lib.dmr_qlinear_workspace_bytes(64, 4096, 4096) == 32 * 4 * (4096 + 64)
-    assert lib.dmr_qlinear_workspace_bytes(17, 4096, 4096) == 32 * 2 * (4096 + 64)
-    assert lib.dmr_qlinear_workspace_bytes(65, 4096, 4096) == 0
+    # 16 < M <= 64 on a wide layer: activations in MFMA operand order (4 KiB per group and row tile)
+    # plus their group sums
+    assert lib.dmr_qlinear_workspace_bytes(64, 4096, 28672) == 32 * 4 * (4096 + 64)
+    assert lib.dmr_qlinear_workspace_bytes(17, 4096, 28672) == 32 * 2 * (4096 + 64)
+    # rollout batches on layers too small to fill the chip: fp32 partials of a 4-way (8-way) split of K
+    assert lib.dmr_qlinear_workspace_bytes(64, 4096, 4096) == 4 * 64 * 4096 * 4
+    assert lib.dmr_qlinear_workspace_bytes(17, 4096, 4096) == 4 * 17 * 4096 * 4
+    assert lib.dmr_qlinear_workspace_bytes(65, 4096, 4096) == 4 * 65 * 4096 * 4
+    assert lib.dmr_qlinear_workspace_bytes(8, 14336, 4096) == 8 * 8 * 4096 * 4    # rows exceed LDS
+    # enough column blocks: no split; large M: the tiled GEMM
+    assert lib.dmr_qlinear_workspace_bytes(128, 4096, 28672) == 0
+    assert lib.dmr_qlinear_workspace_bytes(600, 4096, 28672) == 0
 
 
 def test_status_strings(lib):

@@ -142,8 +142,8 @@ def test_power_of_two_scales_small_integer_activations_are_exact(M):
     assert np.array_equal(y32.astype(np.float64), y_ref)      # any summation order is exact here
 
 
-@pytest.mark.parametrize("M", [1, 64, 130])
-def test_zero_point_only_weights_give_zero(M):
+@pytest.mark.parametrize("N,M", [(64, 1), (64, 64), (64, 130), (1024, 6400)])
+def test_zero_point_only_weights_give_zero(N, M):
     # q == z everywhere, so w^ == 0 and y == 0.  With small-integer activations every partial sum
     # is exact and all paths must return exactly 0.  With Gaussian activations the tiled path
     # (per-weight dequantisation) is still exactly 0; the streaming path forms
@@ -151,7 +151,7 @@ def test_zero_point_only_weights_give_zero(M):
     # to stay four orders of magnitude below the size of an ordinary output (the 1e-2 bar is 100x
     # looser still).
     rng = np.random.default_rng(60)
-    K, N = 512, 64
+    K = 512
     zc = rng.integers(0, 16, size=(N, K // G))
     q = np.repeat(zc, G, axis=1).astype(np.uint8)
     s_f32 = np.abs(synth.weights_f32(61, N, K // G)) + np.float32(1e-3)
@@ -163,7 +163,7 @@ def test_zero_point_only_weights_give_zero(M):
     assert torch.count_nonzero(y_int).item() == 0
     x = synth.activations_bf16(62, M, K)
     y32 = dmr.dmr_qlinear_forward(layer, bf16_dev(x), out_dtype=torch.float32)
-    if M > 64:
+    if M > 128 and -(-M // 128) * -(-N // 128) >= 400:        # large enough for the tiled GEMM
         assert torch.count_nonzero(y32).item() == 0
     else:
         ordinary = float(s_f32.mean()) * 4.6 * np.sqrt(K)     # rms of x . w^ for codes spread over 0..15
@@ -209,6 +209,18 @@ def test_prefill_ragged_shapes(K, N, M):
     y32, y16 = forward_both(make_layer(words, s, z), x)
     y_ref, _ = orc.forward(words, s, z, G, x, threads=THREADS)
     check_forward(y32, y16, y_ref, f"prefill ragged K={K} N={N} M={M}")
+
+
+@pytest.mark.parametrize("K,N,M", [(1024, 1024, 65), (4096, 4096, 100), (512, 272, 130), (1792, 512, 96),
+                                   (1024, 4096, 200), (2048, 1040, 257), (4096, 6144, 384)])
+def test_forward_rollout_batch_sizes(K, N, M):
+    # 64 < M <= 512: row blocks of 96 / 128, ragged column blocks, K split over workgroups (also with an
+    # odd number of groups per split) and the partial-sum pass
+    _, words, s, z = quantized(7000 + K + N + M, N, K)
+    x = synth.activations_bf16(7001 + K + N + M, M, K)
+    y32, y16 = forward_both(make_layer(words, s, z), x)
+    y_ref, _ = orc.forward(words, s, z, G, x, threads=THREADS)
+    check_forward(y32, y16, y_ref, f"rollout batch ({K},{N}) M={M}")
 
 
 @pytest.mark.parametrize("idx,M", [(1, 512), (2, 2048), (3, 2048), (0, 8192)])
