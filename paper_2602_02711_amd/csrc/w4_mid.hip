@@ -1,13 +1,13 @@
 // W4A16 for batches of 17 rows up to several hundred (a group of parallel rollouts decoding together,
 // or a short prefill): too many rows for the pure streaming kernels, too few for a tiled GEMM to fill
-// 256 CUs.
+// 256 CUs.  Also serves 2..16 rows when K is so long that the rows do not fit LDS whole.
 //
 // The streaming layout already is MFMA B-operand order, so the weights never touch LDS: a wave
-// loads its 1 KiB blocks straight into registers (nontemporal, double buffered one group ahead),
+// loads its 1 KiB blocks straight into registers (nontemporal, requested four groups ahead),
 // unpacks them with the bf16 magic number and feeds v_mfma_f32_16x16x32_bf16.  Only the activations
-// go through LDS: the workgroup's BM x 128 slice of x for the current group, double buffered, rows
-// padded to 272 bytes so that the 16-byte A-operand reads of 8 consecutive lanes fall in distinct
-// banks.  A wave owns MTW row tiles x R weight tiles; every A fragment it reads from LDS feeds R MFMAs
+// go through LDS: the workgroup's BM x 128 slice of x for the current group, double buffered (and
+// requested three groups ahead into registers), rows padded to 272 bytes so that the 16-byte
+// A-operand reads of 8 consecutive lanes fall in distinct banks.  A wave owns MTW row tiles x R weight tiles; every A fragment it reads from LDS feeds R MFMAs
 // and every unpacked weight register MTW MFMAs.  The group sums of x come from one more MFMA against
 // an all-ones operand, already in accumulator layout, and a group contributes
 //     acc += s (D - (128 + z) X)                                  (exact codes, fp32 scale)
@@ -58,7 +58,7 @@ __global__ __launch_bounds__(64 * WM * NW, (WM * NW == 4) ? 2 : 1) void w4_mid_k
         uint4 w[R];
         uint32_t s[R];
     };
-    Slot ring[2];
+    Slot ring[4];
     auto fetch_w = [&](Slot &s, int g) {
 #pragma unroll
         for (int rt = 0; rt < R; ++rt) {
@@ -68,24 +68,27 @@ __global__ __launch_bounds__(64 * WM * NW, (WM * NW == 4) ? 2 : 1) void w4_mid_k
         }
     };
 
-    // activations: thread -> (row, 16-byte piece) of the BM x 128 slice.  Rows beyond M repeat row
-    // M - 1: MFMA rows are independent and those outputs are never stored, so no zero fill (whose
-    // per-lane select would make the loads conditional) is needed.
-    uint4 xr[XL];
+    // activations: thread -> (row, 16-byte piece) of the BM x 128 slice.  Rows beyond M wrap around to
+    // rows m mod M: MFMA rows are independent and those outputs are never stored, so no zero fill
+    // (whose per-lane select would make the loads conditional) is needed.
+    u32x4_t xr[2][XL];     // two groups in flight (a plain vector type: the array has to stay in registers)
     const int xrow = tid >> 4, xpiece = tid & 15;
-    auto fetch_x = [&](int g) {
+    const uint16_t *xsrc[XL];
 #pragma unroll
-        for (int p = 0; p < XL; ++p) {
-            const int m = m0 + p * ROWS_PER_PASS + xrow;
-            const int mc = min(m, M - 1);
-            xr[p] = *reinterpret_cast<const uint4 *>(x + (int64_t)mc * K + (int64_t)g * kGroup + xpiece * 8);
-        }
+    for (int p = 0; p < XL; ++p) {
+        const int m = m0 + p * ROWS_PER_PASS + xrow;
+        xsrc[p] = x + (int64_t)(m < M ? m : m % M) * K + xpiece * 8;
+    }
+    auto fetch_x = [&](int set, int g) {
+#pragma unroll
+        for (int p = 0; p < XL; ++p)
+            xr[set][p] = *reinterpret_cast<const u32x4_t *>(xsrc[p] + (int64_t)g * kGroup);
     };
-    auto put_x = [&](int buf) {
+    auto put_x = [&](int set, int buf) {
         uint8_t *dst = xl + buf * (BM * ROW_BYTES);
 #pragma unroll
         for (int p = 0; p < XL; ++p)
-            *reinterpret_cast<uint4 *>(dst + (p * ROWS_PER_PASS + xrow) * ROW_BYTES + xpiece * 16) = xr[p];
+            *reinterpret_cast<u32x4_t *>(dst + (p * ROWS_PER_PASS + xrow) * ROW_BYTES + xpiece * 16) = xr[set][p];
     };
 
     f32x4 acc[R][MTW];
@@ -138,22 +141,29 @@ __global__ __launch_bounds__(64 * WM * NW, (WM * NW == 4) ? 2 : 1) void w4_mid_k
         }
     };
 
-    fetch_w(ring[0], gA);
-    fetch_w(ring[1], min(gA + 1, gB - 1));
-    fetch_x(gA);
-    put_x(0);
+    // Software pipeline, one group of 128 k per phase: the weights of a phase were requested four
+    // phases earlier, its activations three phases earlier into registers and written to the other
+    // LDS buffer one phase earlier.  Phases come in fours (static register indices); a phase past the
+    // end of this split's k range re-reads the last group with scale 0, so that every wave passes the
+    // same barriers and every load is unconditional.  (Walking the groups in a different order per
+    // workgroup was measured and is slower: workgroups in step share the activations in cache.)
+    const int last = gB - 1;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) fetch_w(ring[u], min(gA + u, last));
+    fetch_x(0, gA);
+    put_x(0, 0);
+    fetch_x(1, min(gA + 1, last));
+    fetch_x(0, min(gA + 2, last));
     __syncthreads();
-    for (int g = gA; g < gB; g += 2) {
-        fetch_x(min(g + 1, gB - 1));
-        compute(ring[0], 0, true);
-        fetch_w(ring[0], min(g + 2, gB - 1));
-        put_x(1);
-        __syncthreads();
-        fetch_x(min(g + 2, gB - 1));
-        compute(ring[1], 1, g + 1 < gB);
-        fetch_w(ring[1], min(g + 3, gB - 1));
-        put_x(0);
-        __syncthreads();
+    for (int g = gA; g < gB; g += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            compute(ring[u], u & 1, g + u < gB);
+            fetch_w(ring[u], min(g + u + 4, last));
+            put_x((u + 1) & 1, (u + 1) & 1);                 // group g + u + 1
+            fetch_x((u + 1) & 1, min(g + u + 3, last));
+            __syncthreads();
+        }
     }
 
     const int64_t part = out_mode == 2 ? (int64_t)blockIdx.z * M * N : 0;
@@ -212,7 +222,6 @@ MidPlan plan_mid(int64_t M, int64_t K, int64_t N) {
     const int groups = (int)(K / kGroup), tiles = (int)(N / kTileRows);
     if (M <= 64) {
         p.MTW = (int)((M + 15) / 16);
-        if (p.MTW < 2) p.MTW = 2;
         p.WM = 1;
         p.NW = 4;
     } else {
@@ -287,6 +296,7 @@ hipError_t launch_w4_mid(const LayerView &L, const uint16_t *x, int64_t M, void 
     hipError_t e;
     if (p.WM == 1) {
         switch (p.MTW) {
+            case 1: e = launch_r<1, 1, 4>(L, x, iM, dst, out_mode, p, stream); break;
             case 2: e = launch_r<2, 1, 4>(L, x, iM, dst, out_mode, p, stream); break;
             case 3: e = launch_r<3, 1, 4>(L, x, iM, dst, out_mode, p, stream); break;
             default: e = launch_r<4, 1, 4>(L, x, iM, dst, out_mode, p, stream); break;
