@@ -59,10 +59,13 @@ typedef enum {
  * (dmr_qlinear_create's d_storage).  0 if the shape is not supported. */
 size_t dmr_qlinear_storage_bytes(int64_t K, int64_t N, int32_t g);
 
-/* Bytes of scratch dmr_qlinear_forward needs for this shape (d_ws); may be 0, and then d_ws may be
- * NULL.  Non-zero only for 16 < M <= 64, where the activations are re-ordered once per call.  The
- * bf16 forward never needs any. */
+/* Bytes of scratch dmr_qlinear_forward (resp. dmr_qlinear_bf16_forward) needs for this shape
+ * (d_ws); may be 0, and then d_ws may be NULL.  Non-zero for batches of rollouts (a few to a few
+ * hundred rows): either the activations re-ordered once per call, or fp32 partial sums when K is
+ * split over workgroups because M x N alone would leave most of the chip idle.  Contents are
+ * undefined after the call. */
 size_t dmr_qlinear_workspace_bytes(int64_t M, int64_t K, int64_t N);
+size_t dmr_qlinear_bf16_workspace_bytes(int64_t M, int64_t K, int64_t N);
 
 /*
  * Prepare one low-precision Linear layer (a layer of the W4A16 copy, Sec. 5.1 / App. E): re-tile
@@ -95,8 +98,8 @@ dmr_status_t dmr_qlinear_dequantize(const dmr_qlinear_t *layer, uint16_t *d_w_bf
  * A step routed to the low-precision copy (Sec. 3, Eq. 1 with r_t = low):
  *   y[m][n] = sum_k x[m][k] * (q[n][k] - z[n][k/g]) * s[n][k/g]
  * with the dequantisation fused into the product and fp32 accumulation.  d_x is bf16 [M][K];
- * d_y is [M][N] of the type `out` names.  M <= 64 takes the weight-streaming path (decode, a
- * group of parallel rollouts), larger M the tiled MFMA path (prefill of a long prompt, App. B).
+ * d_y is [M][N] of the type `out` names.  Small M takes the weight-streaming paths (decode, a
+ * group of parallel rollouts), large M the tiled MFMA path (prefill of a long prompt, App. B).
  */
 dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x, int64_t M,
                                  void *d_y, dmr_out_t out, void *d_ws, size_t ws_bytes,
@@ -105,7 +108,8 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
 /*
  * The same layer in the bf16 high-precision copy (Sec. 5.1; a step with r_t = high):
  *   y[m][n] = sum_k x[m][k] * W[n][k],  W bf16 [N][K], fp32 accumulation.
- * This is the denominator of the T_high / T_low ratio (Eq. 9).  Needs no handle.
+ * This is the denominator of the T_high / T_low ratio (Eq. 9).  Needs no handle; d_ws as
+ * dmr_qlinear_bf16_workspace_bytes says.
  */
 dmr_status_t dmr_qlinear_bf16_forward(const uint16_t *d_w, const uint16_t *d_x, int64_t M,
                                       int64_t K, int64_t N, void *d_y, dmr_out_t out, void *d_ws,

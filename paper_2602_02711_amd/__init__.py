@@ -7,14 +7,14 @@ the same names, and the seeded input generators.
 from .binding import (DMR_OUT_BF16, DMR_OUT_FP32, DmrError, Layer, dmr_qlinear_bf16_forward,
                       dmr_qlinear_create, dmr_qlinear_dequantize, dmr_qlinear_destroy,
                       dmr_qlinear_forward, dmr_qlinear_quantize, dmr_qlinear_storage_bytes,
-                      dmr_qlinear_workspace_bytes, dmr_probe_hbm_read, dmr_qlinear_w3_create,
+                      dmr_qlinear_workspace_bytes, dmr_qlinear_bf16_workspace_bytes, dmr_probe_hbm_read, dmr_qlinear_w3_create,
                       dmr_qlinear_quantize_w3, dmr_qlinear_w3_storage_bytes,
                       dmr_qlinear_w3_workspace_bytes, dmr_qlinear_create_per_channel)
 
 __all__ = [
     "DMR_OUT_BF16", "DMR_OUT_FP32", "DmrError", "Layer", "dmr_qlinear_bf16_forward",
     "dmr_qlinear_create", "dmr_qlinear_dequantize", "dmr_qlinear_destroy", "dmr_qlinear_forward",
-    "dmr_qlinear_quantize", "dmr_qlinear_storage_bytes", "dmr_qlinear_workspace_bytes",
+    "dmr_qlinear_quantize", "dmr_qlinear_storage_bytes", "dmr_qlinear_workspace_bytes", "dmr_qlinear_bf16_workspace_bytes",
     "dmr_probe_hbm_read", "dmr_qlinear_w3_create", "dmr_qlinear_quantize_w3",
     "dmr_qlinear_w3_storage_bytes", "dmr_qlinear_w3_workspace_bytes", "dmr_qlinear_create_per_channel",
 ]

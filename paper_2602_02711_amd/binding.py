@@ -20,7 +20,8 @@ DMR_ERR_NULL, DMR_ERR_SHAPE, DMR_ERR_ALIGN, DMR_ERR_WORKSPACE, DMR_ERR_UNSUPPORT
 DMR_OUT_BF16, DMR_OUT_FP32 = 0, 1
 
 EXPORTS = (
-    "dmr_qlinear_storage_bytes", "dmr_qlinear_workspace_bytes", "dmr_qlinear_create",
+    "dmr_qlinear_storage_bytes", "dmr_qlinear_workspace_bytes", "dmr_qlinear_bf16_workspace_bytes",
+    "dmr_qlinear_create",
     "dmr_qlinear_dequantize", "dmr_qlinear_forward", "dmr_qlinear_bf16_forward",
     "dmr_qlinear_quantize", "dmr_qlinear_destroy", "dmr_qlinear_shape", "dmr_status_string",
     "dmr_probe_hbm_read", "dmr_qlinear_w3_storage_bytes", "dmr_qlinear_w3_workspace_bytes",
@@ -51,6 +52,8 @@ def lib() -> ctypes.CDLL:
         L.dmr_qlinear_storage_bytes.argtypes = [i64, i64, i32]
         L.dmr_qlinear_workspace_bytes.restype = sz
         L.dmr_qlinear_workspace_bytes.argtypes = [i64, i64, i64]
+        L.dmr_qlinear_bf16_workspace_bytes.restype = sz
+        L.dmr_qlinear_bf16_workspace_bytes.argtypes = [i64, i64, i64]
         L.dmr_qlinear_create.restype = ctypes.c_int
         L.dmr_qlinear_create.argtypes = [ctypes.POINTER(vp), i64, i64, i32, vp, vp, vp, vp, sz, vp]
         L.dmr_qlinear_dequantize.restype = ctypes.c_int
@@ -138,6 +141,10 @@ def dmr_qlinear_workspace_bytes(M: int, K: int, N: int) -> int:
     return int(lib().dmr_qlinear_workspace_bytes(M, K, N))
 
 
+def dmr_qlinear_bf16_workspace_bytes(M: int, K: int, N: int) -> int:
+    return int(lib().dmr_qlinear_bf16_workspace_bytes(M, K, N))
+
+
 def dmr_qlinear_create(qweight: torch.Tensor, scales: torch.Tensor, zeros: torch.Tensor, g: int = 128,
                        storage: torch.Tensor | None = None, stream=None) -> Layer:
     pq = _dev(qweight, "qweight", _U32)
@@ -209,6 +216,10 @@ def dmr_qlinear_bf16_forward(w: torch.Tensor, x: torch.Tensor, out: torch.Tensor
     po = _dev(out, "out", (torch.bfloat16, torch.float32))
     if tuple(out.shape) != (M, N):
         raise ValueError("out must be [M][N]")
+    if workspace is None:
+        need = dmr_qlinear_bf16_workspace_bytes(M, K, N)
+        if need > 0:
+            workspace = torch.empty(need, dtype=torch.uint8, device=x.device)    # device memory only
     pws, wbytes = _workspace(workspace)
     _check(lib().dmr_qlinear_bf16_forward(pw_, px, M, K, N, po, _out_code(out.dtype), pws, wbytes,
                                           _stream(stream)), "dmr_qlinear_bf16_forward")

@@ -31,6 +31,17 @@ W4Path w4_path(int64_t M, int64_t K, int64_t N) {
     return (M <= 128 || gemm_wgs < 400) ? W4Path::Mid : W4Path::Gemm;
 }
 
+// The bf16 twin: GEMV, first-generation skinny kernel for 2..16 rows, then the same size classes.
+enum class Bf16Path { Gemv, Skinny, Mid, GemmBig, Gemm };
+Bf16Path bf16_path(int64_t M, int64_t N) {
+    if (M == 1) return Bf16Path::Gemv;
+    if (M <= 16) return Bf16Path::Skinny;
+    // measured crossover: the tiled kernels win once they have more than ~128 workgroups
+    const int64_t gemm_wgs = ((M + 127) / 128) * ((N + 127) / 128);
+    if (M <= 64 || gemm_wgs <= 128) return Bf16Path::Mid;
+    return dmr::gemm_big_applies(M, N) ? Bf16Path::GemmBig : Bf16Path::Gemm;
+}
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 dmr_status_t check_shape(int64_t K, int64_t N, int32_t g) {
@@ -61,6 +72,11 @@ size_t dmr_qlinear_workspace_bytes(int64_t M, int64_t K, int64_t N) {
         case W4Path::Skinny2: return dmr::w4_skinny2_workspace_bytes(M, K);   // re-ordered activations
         default: return 0;
     }
+}
+
+size_t dmr_qlinear_bf16_workspace_bytes(int64_t M, int64_t K, int64_t N) {
+    if (M <= 0 || K <= 0 || K % dmr::kGroup != 0 || N <= 0 || N % dmr::kTileRows != 0) return 0;
+    return bf16_path(M, N) == Bf16Path::Mid ? dmr::bf16_mid_workspace_bytes(M, K, N) : 0;
 }
 
 dmr_status_t dmr_qlinear_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32_t g,
@@ -136,7 +152,8 @@ size_t dmr_qlinear_w3_storage_bytes(int64_t K, int64_t N, int32_t g) {
 
 size_t dmr_qlinear_w3_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     if (M <= 1 || K <= 0 || N <= 0) return 0;
-    return (size_t)N * (size_t)K * 2;   // M > 1: the layer is dequantised to bf16 there first
+    // M > 1: the layer is dequantised to bf16 there first; the bf16 path's own scratch follows
+    return (size_t)N * (size_t)K * 2 + dmr_qlinear_bf16_workspace_bytes(M, K, N);
 }
 
 dmr_status_t dmr_qlinear_w3_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32_t g,
@@ -212,12 +229,13 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
             if (e != hipErrorInvalidValue) return hip_status(e);
         }
         // M > 1 (or a shape outside the GEMV's range): dequantise into the workspace, then the bf16 path
-        const size_t need3 = (size_t)layer->N * (size_t)layer->K * 2;
+        const size_t need3 = dmr_qlinear_w3_workspace_bytes(M, layer->K, layer->N);
         if (!d_ws || ws_bytes < need3) return DMR_ERR_WORKSPACE;
         const hipError_t e = dmr::launch_dequantize3(L3, static_cast<uint16_t *>(d_ws), s);
         if (e != hipSuccess) return DMR_ERR_HIP;
+        const size_t wbytes = (size_t)layer->N * (size_t)layer->K * 2;       // bf16 weights, then the twin's own scratch
         return dmr_qlinear_bf16_forward(static_cast<const uint16_t *>(d_ws), d_x, M, layer->K, layer->N, d_y, out,
-                                        nullptr, 0, stream);
+                                        static_cast<uint8_t *>(d_ws) + wbytes, need3 - wbytes, stream);
     }
     const size_t need = dmr_qlinear_workspace_bytes(M, layer->K, layer->N);
     if (need > 0 && (!d_ws || ws_bytes < need)) return DMR_ERR_WORKSPACE;
@@ -250,16 +268,22 @@ dmr_status_t dmr_qlinear_bf16_forward(const uint16_t *d_w, const uint16_t *d_x, 
     if (!d_w || !d_x || !d_y) return DMR_ERR_NULL;
     if (!aligned16(d_w) || !aligned16(d_x) || !aligned16(d_y) || (d_ws && !aligned16(d_ws)))
         return DMR_ERR_ALIGN;
-    (void)ws_bytes;   // the bf16 path needs no workspace
+    const size_t need = dmr_qlinear_bf16_workspace_bytes(M, K, N);
+    if (need > 0 && (!d_ws || ws_bytes < need)) return DMR_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool f32 = out == DMR_OUT_FP32;
-    if (M == 1) {
+    const Bf16Path path = bf16_path(M, N);
+    if (path == Bf16Path::Gemv) {
         const hipError_t e = dmr::launch_bf16_gemv(d_w, d_x, K, N, d_y, f32, s);
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: K outside its range
+        return hip_status(dmr::launch_bf16_skinny(d_w, d_x, M, K, N, d_y, f32, s));
     }
-    if (M <= kSkinnyMaxM) return hip_status(dmr::launch_bf16_skinny(d_w, d_x, M, K, N, d_y, f32, s));
-    if (dmr::gemm_big_applies(M, N)) return hip_status(dmr::launch_bf16_gemm_big(d_w, d_x, M, K, N, d_y, f32, s));
-    return hip_status(dmr::launch_bf16_gemm(d_w, d_x, M, K, N, d_y, f32, s));
+    switch (path) {
+        case Bf16Path::Skinny: return hip_status(dmr::launch_bf16_skinny(d_w, d_x, M, K, N, d_y, f32, s));
+        case Bf16Path::Mid: return hip_status(dmr::launch_bf16_mid(d_w, d_x, M, K, N, d_y, f32, d_ws, s));
+        case Bf16Path::GemmBig: return hip_status(dmr::launch_bf16_gemm_big(d_w, d_x, M, K, N, d_y, f32, s));
+        default: return hip_status(dmr::launch_bf16_gemm(d_w, d_x, M, K, N, d_y, f32, s));
+    }
 }
 
 dmr_status_t dmr_qlinear_quantize(int64_t K, int64_t N, int32_t g, const float *d_w, uint32_t *d_qweight,

@@ -135,6 +135,10 @@ hipError_t launch_w4_skinny2(const LayerView &L, const uint16_t *x, int64_t M, v
 size_t w4_mid_workspace_bytes(int64_t M, int64_t K, int64_t N);
 hipError_t launch_w4_mid(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
                          hipStream_t stream);
+// bf16 twin of launch_w4_mid.
+size_t bf16_mid_workspace_bytes(int64_t M, int64_t K, int64_t N);
+hipError_t launch_bf16_mid(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N, void *y,
+                           bool out_f32, void *ws, hipStream_t stream);
 hipError_t launch_retile3(int64_t K, int64_t N, const uint32_t *qweight, const uint16_t *scales,
                           const uint16_t *zeros, uint32_t *wt, uint32_t *sz, hipStream_t stream);
 hipError_t launch_dequantize3(const LayerView3 &L, uint16_t *w_bf16, hipStream_t stream);

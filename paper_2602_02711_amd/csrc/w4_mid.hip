@@ -17,9 +17,8 @@
 // blockIdx.z, each split writes an fp32 partial tile to the caller's workspace and a second kernel
 // adds the partials in ascending split order (deterministic, no atomics).
 #include <algorithm>
-#include <cstdlib>
 
-#include "common.hpp"
+#include "mid_plan.hpp"
 
 namespace dmr {
 
@@ -207,50 +206,6 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
     }
 }
 
-struct MidPlan {
-    int MTW, WM, NW, R, SK, gps;
-};
-
-int env_int(const char *name, int fallback) {
-    const char *v = std::getenv(name);
-    return v ? std::atoi(v) : fallback;
-}
-
-// Pure host arithmetic (the workspace query must agree with the launch): 256 CUs assumed.
-MidPlan plan_mid(int64_t M, int64_t K, int64_t N) {
-    MidPlan p;
-    const int groups = (int)(K / kGroup), tiles = (int)(N / kTileRows);
-    if (M <= 64) {
-        p.MTW = (int)((M + 15) / 16);
-        p.WM = 1;
-        p.NW = 4;
-    } else {
-        const int64_t pad3 = (M + 95) / 96 * 96, pad4 = (M + 127) / 128 * 128;
-        p.MTW = pad3 < pad4 ? 3 : 4;
-        p.WM = 2;
-        p.NW = 2;     // 8-wave workgroups (128 x 128 tiles) were measured too: no faster
-    }
-    const int BM = 16 * p.MTW * p.WM;
-    const int64_t mblocks = (M + BM - 1) / BM;
-    // Measured rules (gfx950, 256 CUs): split K while that keeps >= 8 groups per split and fewer than
-    // 384 workgroups exist; two weight tiles per wave unless that leaves under 256 workgroups
-    // even at the deepest split.
-    auto split_for = [&](int64_t wgs) {
-        int sk = 1;
-        while (wgs * sk < 384 && groups % (sk * 2) == 0 && groups / (sk * 2) >= 8) sk *= 2;
-        return sk;
-    };
-    auto wgs_for = [&](int R) { return (int64_t)((tiles + p.NW * R - 1) / (p.NW * R)) * mblocks; };
-    p.R = wgs_for(2) * split_for(wgs_for(2)) >= 256 ? 2 : 1;
-    const int r_env = env_int("DMR_MID_R", 0);
-    if (r_env == 1 || r_env == 2) p.R = r_env;
-    p.SK = split_for(wgs_for(p.R));
-    const int sk_env = env_int("DMR_MID_SK", 0);
-    if (sk_env >= 1 && groups % sk_env == 0) p.SK = sk_env;
-    p.gps = groups / p.SK;
-    return p;
-}
-
 template <int MTW, int WM, int NW, int R>
 hipError_t launch_cfg(const LayerView &L, const uint16_t *x, int M, void *dst, int out_mode, const MidPlan &p,
                       hipStream_t stream) {
@@ -281,6 +236,13 @@ hipError_t launch_r(const LayerView &L, const uint16_t *x, int M, void *dst, int
 
 }  // namespace
 
+hipError_t launch_splitk_reduce(const float *part, void *y, int64_t total, int splits, bool out_f32,
+                                hipStream_t stream) {
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, stream, part, y,
+                       total, splits, out_f32 ? 1 : 0);
+    return hipGetLastError();
+}
+
 size_t w4_mid_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     const MidPlan p = plan_mid(M, K, N);
     return p.SK > 1 ? (size_t)p.SK * (size_t)M * (size_t)N * sizeof(float) : 0;
@@ -306,10 +268,7 @@ hipError_t launch_w4_mid(const LayerView &L, const uint16_t *x, int64_t M, void 
                        : launch_r<4, 2, 2>(L, x, iM, dst, out_mode, p, stream);
     }
     if (e != hipSuccess || !split) return e;
-    const int64_t total = M * L.N;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, stream,
-                       static_cast<const float *>(ws), y, total, p.SK, out_f32 ? 1 : 0);
-    return hipGetLastError();
+    return launch_splitk_reduce(static_cast<const float *>(ws), y, M * L.N, p.SK, out_f32, stream);
 }
 
 }  // namespace dmr
