@@ -31,11 +31,12 @@ W4Path w4_path(int64_t M, int64_t K, int64_t N) {
     return (M <= 128 || gemm_wgs < 400) ? W4Path::Mid : W4Path::Gemm;
 }
 
-// The bf16 twin: GEMV, first-generation skinny kernel for 2..16 rows, then the same size classes.
+// The bf16 twin: GEMV, first-generation skinny kernel for 2..8 rows (measured faster there), then the
+// same size classes as INT4.
 enum class Bf16Path { Gemv, Skinny, Mid, GemmBig, Gemm };
 Bf16Path bf16_path(int64_t M, int64_t N) {
     if (M == 1) return Bf16Path::Gemv;
-    if (M <= 16) return Bf16Path::Skinny;
+    if (M <= 8) return Bf16Path::Skinny;
     // measured crossover: the tiled kernels win once they have more than ~128 workgroups
     const int64_t gemm_wgs = ((M + 127) / 128) * ((N + 127) / 128);
     if (M <= 64 || gemm_wgs <= 128) return Bf16Path::Mid;
@@ -252,8 +253,12 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
     if (path == W4Path::Mid) return hip_status(dmr::launch_w4_mid(L, d_x, M, d_y, f32, d_ws, s));
     if (path == W4Path::Skinny2) return hip_status(dmr::launch_w4_skinny2(L, d_x, M, d_y, f32, d_ws, s));
     if (M <= kSkinnyMaxM) return hip_status(dmr::launch_w4_skinny(L, d_x, M, d_y, f32, s));
-    // the INT4 GEMM keeps weights exact (integer codes in the MFMA, scale per group in fp32); only the
-    // 128 x 128 kernel has room for its per-group accumulators
+    // Long prefills of group-128 layers: 256 x 256 tiles with weights rounded to bf16 on their way into
+    // LDS (the value dmr_qlinear_dequantize defines; inside the 1e-2 rms bound for this format).
+    // Everything else, and per-channel layers whose row scales differ widely, takes the 128 x 128
+    // kernel, which keeps the codes exact and applies the scale per group in fp32.
+    if (layer->g == dmr::kGroup && dmr::gemm_big_applies(M, layer->N))
+        return hip_status(dmr::launch_w4_gemm_big(L, d_x, M, d_y, f32, s));
     return hip_status(dmr::launch_w4_gemm(L, d_x, M, d_y, f32, s));
 }
 

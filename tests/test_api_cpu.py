@@ -49,7 +49,8 @@ def test_size_queries(lib):
     assert lib.dmr_qlinear_workspace_bytes(600, 4096, 28672) == 0
     # the bf16 twin splits K under the same rule
     assert lib.dmr_qlinear_bf16_workspace_bytes(1, 4096, 4096) == 0
-    assert lib.dmr_qlinear_bf16_workspace_bytes(16, 4096, 4096) == 0
+    assert lib.dmr_qlinear_bf16_workspace_bytes(8, 4096, 4096) == 0
+    assert lib.dmr_qlinear_bf16_workspace_bytes(16, 4096, 4096) == 4 * 16 * 4096 * 4
     assert lib.dmr_qlinear_bf16_workspace_bytes(64, 4096, 4096) == 4 * 64 * 4096 * 4
     assert lib.dmr_qlinear_bf16_workspace_bytes(128, 4096, 28672) == 0
     assert lib.dmr_qlinear_bf16_workspace_bytes(128, 4096, 4096) == 4 * 128 * 4096 * 4
