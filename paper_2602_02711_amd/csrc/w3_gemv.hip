@@ -5,11 +5,12 @@
 // 64 lanes x 12 bytes = 768 bytes (0.40625 bytes per weight with scale and zero point).
 //
 // Streaming layout of a lane's three words (32 weights k = 32 c + i): operand register r = i / 2
-// (the pair i = 2r, 2r + 1, low and high half).  For r < 15 the two 3-bit codes sit in field r % 5
-// of word r / 5: bits [3f, 3f+3) of the low half and of the high half, so a shift, an and
-// (mask 0x00070007) and an or (0x43004300) give the bf16 pair (128 + q, 128 + q).  Each half
-// keeps one spare bit (15 and 31); the three low spare bits are code 30, the three high ones code
-// 31 (register 15).
+// (the pair i = 2r, 2r + 1, low and high half).  Every byte holds two codes in bits [0, 3) and
+// [3, 6): `w & 0x07070707` and `(w >> 3) & 0x07070707` each leave four codes as clean bytes, and
+// v_perm_b32 interleaves two of them with the 0x43 exponent byte into a bf16 pair (128 + q,
+// 128 + q): 7 VALU instructions for the 4 registers of a word.  The spare bits [6, 8) of the bytes
+// carry the last 8 codes (two low bits in words 0 and 1, the third bit in word 2): 14 more
+// instructions for registers 12..15, 35 per block in all.
 #include <cstdlib>
 
 #include "common.hpp"
@@ -19,27 +20,31 @@ namespace dmr {
 namespace {
 
 
-// (a & mask) | c.  Plain C on purpose (an and and an or): inline assembly for the fused
-// v_and_or_b32 is not an option next to MFMAs, whose operand wait states after a VALU write the
-// compiler inserts only for instructions it emitted itself.
-__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) { return (a & mask) | c; }
-
 struct Item {
     uint32_t w0, w1, w2;
     uint32_t szw;
 };
 
-// Operand register r (0..15) of a lane's three words.
-template <int R>
-__device__ __forceinline__ uint32_t pair_reg(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t mask,
-                                             uint32_t magic) {
-    if (R < 15) {
-        const uint32_t w = (R / 5 == 0) ? w0 : (R / 5 == 1 ? w1 : w2);
-        return and_or(w >> (3 * (R % 5)), mask, magic);
+// The 16 operand registers of a lane's three words (no inline assembly: the wait states an MFMA
+// needs after a VALU write of its operands are only inserted for compiler-emitted instructions).
+__device__ __forceinline__ void unpack3(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t (&r)[16]) {
+    const uint32_t m7 = 0x07070707u, exp = 0x43434343u;
+    const uint32_t sel_a = 0x00060004u, sel_b = 0x00070005u;     // bytes (0, 2) resp. (1, 3) of the codes
+    const uint32_t w[3] = {w0, w1, w2};
+#pragma unroll
+    for (int v = 0; v < 3; ++v) {
+        const uint32_t f0 = w[v] & m7, f1 = (w[v] >> 3) & m7;
+        r[4 * v + 0] = __builtin_amdgcn_perm(f0, exp, sel_a);
+        r[4 * v + 1] = __builtin_amdgcn_perm(f0, exp, sel_b);
+        r[4 * v + 2] = __builtin_amdgcn_perm(f1, exp, sel_a);
+        r[4 * v + 3] = __builtin_amdgcn_perm(f1, exp, sel_b);
     }
-    uint32_t v = and_or(w0 >> 15, 0x00010001u, magic);
-    v = and_or(w1 >> 14, 0x00020002u, v);
-    return and_or(w2 >> 13, 0x00040004u, v);
+    const uint32_t c0 = (((w2 >> 6) & 0x01010101u) << 2) | ((w0 >> 6) & 0x03030303u);
+    const uint32_t c1 = (((w2 >> 7) & 0x01010101u) << 2) | ((w1 >> 6) & 0x03030303u);
+    r[12] = __builtin_amdgcn_perm(c0, exp, sel_a);
+    r[13] = __builtin_amdgcn_perm(c0, exp, sel_b);
+    r[14] = __builtin_amdgcn_perm(c1, exp, sel_a);
+    r[15] = __builtin_amdgcn_perm(c1, exp, sel_b);
 }
 
 template <int P, int XL>
@@ -114,7 +119,6 @@ __global__ __launch_bounds__(1024) void w3_gemv_kernel(const uint32_t *__restric
     __syncthreads();
 
     const uint4 *xs = smem + g0 * 16;
-    const uint32_t mask = 0x00070007u, magic = 0x43004300u;
     float acc = 0.f;
     int ct = 0, cg = 0;
     auto compute = [&](const Item &cur) {
@@ -124,27 +128,15 @@ __global__ __launch_bounds__(1024) void w3_gemv_kernel(const uint32_t *__restric
 #pragma unroll
         for (int t = 0; t < 4; ++t) a[t].u = xp[t];
         f32x4 d = {0.f, 0.f, 0.f, 0.f};
-        Frag b;
-        b.w[0] = pair_reg<0>(cur.w0, cur.w1, cur.w2, mask, magic);
-        b.w[1] = pair_reg<1>(cur.w0, cur.w1, cur.w2, mask, magic);
-        b.w[2] = pair_reg<2>(cur.w0, cur.w1, cur.w2, mask, magic);
-        b.w[3] = pair_reg<3>(cur.w0, cur.w1, cur.w2, mask, magic);
-        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[0].v, b.v, d, 0, 0, 0);
-        b.w[0] = pair_reg<4>(cur.w0, cur.w1, cur.w2, mask, magic);
-        b.w[1] = pair_reg<5>(cur.w0, cur.w1, cur.w2, mask, magic);
-        b.w[2] = pair_reg<6>(cur.w0, cur.w1, cur.w2, mask, magic);
-        b.w[3] = pair_reg<7>(cur.w0, cur.w1, cur.w2, mask, magic);
-        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[1].v, b.v, d, 0, 0, 0);
-        b.w[0] = pair_reg<8>(cur.w0, cur.w1, cur.w2, mask, magic);
-        b.w[1] = pair_reg<9>(cur.w0, cur.w1, cur.w2, mask, magic);
-        b.w[2] = pair_reg<10>(cur.w0, cur.w1, cur.w2, mask, magic);
-        b.w[3] = pair_reg<11>(cur.w0, cur.w1, cur.w2, mask, magic);
-        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[2].v, b.v, d, 0, 0, 0);
-        b.w[0] = pair_reg<12>(cur.w0, cur.w1, cur.w2, mask, magic);
-        b.w[1] = pair_reg<13>(cur.w0, cur.w1, cur.w2, mask, magic);
-        b.w[2] = pair_reg<14>(cur.w0, cur.w1, cur.w2, mask, magic);
-        b.w[3] = pair_reg<15>(cur.w0, cur.w1, cur.w2, mask, magic);
-        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[3].v, b.v, d, 0, 0, 0);
+        uint32_t reg[16];
+        unpack3(cur.w0, cur.w1, cur.w2, reg);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            Frag b;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) b.w[i] = reg[4 * t + i];
+            d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t].v, b.v, d, 0, 0, 0);
+        }
         const float sc = __uint_as_float(cur.szw << 16);
         const float cz = __uint_as_float(cur.szw & 0xFFFF0000u);   // -(128 + z)
         acc = fmaf(sc, fmaf(cz, xg, d[0]), acc);
@@ -216,10 +208,11 @@ struct GemvPlan {
 GemvPlan plan_for(int groups, int tiles, int cus) {
     GemvPlan p;
     p.TW = 1;
-    p.S = tiles <= 2 * cus ? 16 : 8;
+    // measured on MI355X: the 768-byte blocks want shorter slices on wide layers than the 4-bit kernel
+    p.S = tiles <= 2 * cus ? 16 : 4;
     while (p.S > groups) p.S >>= 1;
     const int resident = cus * (16 / p.S);
-    p.grid = tiles < resident ? tiles : resident;
+    p.grid = tiles <= 2 * cus ? tiles : (tiles < resident ? tiles : resident);
     return p;
 }
 
@@ -279,7 +272,7 @@ hipError_t launch_w3_gemv(const LayerView3 &L, const uint16_t *x, void *y, bool 
         else DMR_GEMV3_LAUNCH(PP, 8);                                                                   \
         break;
     switch (P) {
-        DMR_GEMV3_CASE(1) DMR_GEMV3_CASE(2) DMR_GEMV3_CASE(3) DMR_GEMV3_CASE(4)
+        DMR_GEMV3_CASE(1) DMR_GEMV3_CASE(2) DMR_GEMV3_CASE(3) DMR_GEMV3_CASE(4) DMR_GEMV3_CASE(6) DMR_GEMV3_CASE(8)
         default: return hipErrorInvalidValue;
     }
 #undef DMR_GEMV3_CASE

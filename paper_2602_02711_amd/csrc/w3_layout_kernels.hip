@@ -3,8 +3,12 @@
 //
 // Canonical: 32 codes per three words, code j in bits [3j, 3j+3) of the 96-bit little-endian run.
 // Streaming: block (T, G) = 64 lanes x 3 words; lane l = 16 c + j owns row 16 T + j and the weights
-// k = 128 G + 32 c + i, i = 0..31.  Codes 2r and 2r+1 (r < 15) sit in field r % 5 of word r / 5, in
-// the low and the high 16-bit half; bit b of code 30 (31) is bit 15 (31) of word b.
+// k = 128 G + 32 c + i, i = 0..31, as 16 operand registers r = i / 2 (code 2r in the low half, 2r + 1
+// in the high half).  Every byte of the three words holds two codes, bits [0, 3) and [3, 6), so that
+// one mask isolates four codes as clean bytes: register r < 12 takes word r / 4, field (r / 2) % 2,
+// bytes (r % 2) and (r % 2) + 2.  The two spare bits of each byte carry the last eight codes:
+// registers 12, 13 (14, 15) have their low two bits in bits [6, 8) of the bytes of word 0 (word 1)
+// and their third bit in bit 6 (bit 7) of the same byte of word 2.
 #include "common.hpp"
 
 namespace dmr {
@@ -15,22 +19,29 @@ namespace {
 __device__ __forceinline__ void encode_lane(const uint32_t (&code)[32], uint32_t (&w)[3]) {
     w[0] = w[1] = w[2] = 0;
 #pragma unroll
-    for (int r = 0; r < 15; ++r) {
-        w[r / 5] |= code[2 * r] << (3 * (r % 5));
-        w[r / 5] |= code[2 * r + 1] << (16 + 3 * (r % 5));
+    for (int r = 0; r < 12; ++r) {
+        const int v = r / 4, f = (r / 2) % 2, p = r % 2;
+        w[v] |= code[2 * r] << (8 * p + 3 * f);
+        w[v] |= code[2 * r + 1] << (8 * (p + 2) + 3 * f);
     }
 #pragma unroll
-    for (int b = 0; b < 3; ++b) {
-        w[b] |= ((code[30] >> b) & 1u) << 15;
-        w[b] |= ((code[31] >> b) & 1u) << 31;
+    for (int e = 0; e < 8; ++e) {
+        const int cc = e / 4, idx = e % 4;
+        const int b = ((idx & 1) << 1) | (idx >> 1);       // codes of a register sit in bytes (0, 2) or (1, 3)
+        w[cc] |= (code[24 + e] & 3u) << (8 * b + 6);
+        w[2] |= (code[24 + e] >> 2) << (8 * b + 6 + cc);
     }
 }
 
 __device__ __forceinline__ uint32_t decode_lane(const uint32_t (&w)[3], int i) {
-    const int r = i >> 1, hi = i & 1;
-    if (r < 15) return (w[r / 5] >> (16 * hi + 3 * (r % 5))) & 7u;
-    const int sh = hi ? 31 : 15;
-    return ((w[0] >> sh) & 1u) | (((w[1] >> sh) & 1u) << 1) | (((w[2] >> sh) & 1u) << 2);
+    const int r = i >> 1, h = i & 1;
+    if (r < 12) {
+        const int v = r / 4, f = (r / 2) % 2, p = r % 2;
+        return (w[v] >> (8 * (p + 2 * h) + 3 * f)) & 7u;
+    }
+    const int e = i - 24, cc = e / 4, idx = e % 4;
+    const int b = ((idx & 1) << 1) | (idx >> 1);
+    return ((w[cc] >> (8 * b + 6)) & 3u) | (((w[2] >> (8 * b + 6 + cc)) & 1u) << 2);
 }
 
 }  // namespace

@@ -185,8 +185,11 @@ GemvPlan plan_for(int groups, int tiles, int cus) {
     p.TW = 1;
     p.S = tiles <= 2 * cus ? 16 : 8;
     while (p.S > groups) p.S >>= 1;
+    // Few tiles: one workgroup per tile (up to two 16-wave workgroups share a CU), which measured
+    // faster than handing some workgroups a second tile.  Many tiles: as many workgroups as stay
+    // resident, tiles round-robin.
     const int resident = cus * (16 / p.S);
-    p.grid = tiles < resident ? tiles : resident;
+    p.grid = tiles <= 2 * cus ? tiles : (tiles < resident ? tiles : resident);
     return p;
 }
 
