@@ -79,6 +79,10 @@ def _load():
         lib.oracle_dequantize_bits.argtypes = [i64, i64, i64, i32, vp, vp, vp, vp]
         lib.oracle_forward_bits.restype = i32
         lib.oracle_forward_bits.argtypes = [i64, i64, i64, i32, i64, vp, vp, vp, vp, vp, i32]
+        lib.oracle_rmsnorm.restype = i32
+        lib.oracle_rmsnorm.argtypes = [i64, i64, vp, vp, ctypes.c_double, vp]
+        lib.oracle_swiglu.restype = i32
+        lib.oracle_swiglu.argtypes = [i64, i64, vp, vp]
         lib.oracle_max_threads.restype = i32
         lib.oracle_max_threads.argtypes = []
         _lib = lib
@@ -293,3 +297,26 @@ def forward3(qweight, s, z, g: int, x_bits, threads: int = 1):
     used = _check(_load().oracle_forward_bits(K, N, g, 3, M, _p(qweight), _p(s), _p(z), _p(x_bits), _p(y),
                                               int(threads)), "oracle_forward_bits")
     return y, used
+
+
+def rmsnorm(x_bits, gamma_bits, eps: float) -> np.ndarray:
+    """bf16 [M][K], bf16 [K] -> bf16 [M][K]: x * gamma / sqrt(mean(x^2) + eps), one rounding at the end."""
+    x_bits = _arr(x_bits, np.uint16)
+    gamma_bits = _arr(gamma_bits, np.uint16)
+    M, K = x_bits.shape
+    if gamma_bits.shape != (K,):
+        raise ValueError("gamma must be [K]")
+    out = np.empty((M, K), dtype=np.uint16)
+    _check(_load().oracle_rmsnorm(M, K, _p(x_bits), _p(gamma_bits), float(eps), _p(out)), "oracle_rmsnorm")
+    return out
+
+
+def swiglu(in_bits) -> np.ndarray:
+    """bf16 [M][2I] (gate half, then up half) -> bf16 [M][I]: silu(gate) * up, one rounding at the end."""
+    in_bits = _arr(in_bits, np.uint16)
+    M, two_i = in_bits.shape
+    if two_i % 2:
+        raise ValueError("the last axis holds a gate half and an up half")
+    out = np.empty((M, two_i // 2), dtype=np.uint16)
+    _check(_load().oracle_swiglu(M, two_i // 2, _p(in_bits), _p(out)), "oracle_swiglu")
+    return out

@@ -26,13 +26,21 @@
  *   - forward gives  y[m][n] = sum_k x[m][k] * w^[n][k]   in fp64, k ascending
  *   - bf16 twin      y[m][n] = sum_k x[m][k] * W[n][k]    in fp64, k ascending
  *
+ *   - decoder glue between the Linear layers of one routed step (the models of Sec. 5.1 are
+ *     pre-norm decoders with RMSNorm and a SwiGLU MLP; the paper does not restate these
+ *     operations, so they are written out here in their textbook form, all arithmetic in fp64
+ *     with one rounding to bf16 at the end, because the next Linear takes bf16 activations):
+ *       rmsnorm  out[m][k] = RNE_bf16( x[m][k] * gamma[k] / sqrt(mean_k(x[m][k]^2) + eps) )
+ *       swiglu   out[m][i] = RNE_bf16( silu(in[m][i]) * in[m][I + i] ),  silu(a) = a / (1 + exp(-a))
+ *     (the fused gate+up projection writes the gate half first, then the up half)
+ *
  * Everything is row-major and contiguous.  bf16 values travel as uint16_t bit patterns.
  * All functions return 0 on success and a negative number on a bad argument.
  *
  * Parity status: every function here is pinned by the CPU tests (hand-worked 2x2 and 4x8
  * examples, pack/unpack bijection, zero-point-only and power-of-two-scale exact cases,
  * integer-matmul special case, closed-form quantiser error bound, an independent numpy
- * twin on tiny shapes).  oracle_forward on the large random configurations has no printed
+ * twin on tiny shapes; the glue by hand-worked vectors, closed forms and invariances).  oracle_forward on the large random configurations has no printed
  * value anywhere in the paper to compare with: beyond those pins it is "parity unpinned".
  */
 #include <math.h>
@@ -406,6 +414,41 @@ int oracle_bf16_forward_sampled(int64_t K, int64_t N, int64_t M, const uint16_t 
             acc += oracle_bf16_to_f64(x_bits[m * K + k]) * oracle_bf16_to_f64(w_bits[n * K + k]);
         out[i] = acc;
     }
+    return 0;
+}
+
+/* ---- decoder glue (see the header) ----------------------------------------------------- */
+
+int oracle_rmsnorm(int64_t M, int64_t K, const uint16_t *x_bits, const uint16_t *gamma_bits, double eps,
+                   uint16_t *out_bits)
+{
+    if (M < 0 || K <= 0 || !x_bits || !gamma_bits || !out_bits || !(eps >= 0.0)) return -1;
+    for (int64_t m = 0; m < M; ++m) {
+        double ss = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            const double v = oracle_bf16_to_f64(x_bits[m * K + k]);
+            ss += v * v;
+        }
+        const double denom = sqrt(ss / (double)K + eps);
+        for (int64_t k = 0; k < K; ++k) {
+            const double v = oracle_bf16_to_f64(x_bits[m * K + k]);
+            const double gma = oracle_bf16_to_f64(gamma_bits[k]);
+            /* an all-zero row with eps = 0 is 0 / 0: defined as 0 */
+            out_bits[m * K + k] = oracle_f64_to_bf16(denom > 0.0 ? v * gma / denom : 0.0);
+        }
+    }
+    return 0;
+}
+
+int oracle_swiglu(int64_t M, int64_t I, const uint16_t *in_bits, uint16_t *out_bits)
+{
+    if (M < 0 || I <= 0 || !in_bits || !out_bits) return -1;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t i = 0; i < I; ++i) {
+            const double a = oracle_bf16_to_f64(in_bits[m * 2 * I + i]);
+            const double b = oracle_bf16_to_f64(in_bits[m * 2 * I + I + i]);
+            out_bits[m * I + i] = oracle_f64_to_bf16(a / (1.0 + exp(-a)) * b);
+        }
     return 0;
 }
 

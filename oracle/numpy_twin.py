@@ -23,6 +23,17 @@ def f32_to_bf16_bits(values):
     return ((u + 0x7FFF + lsb) >> 16).astype(np.uint16)
 
 
+def f64_to_bf16_bits(values):
+    """RNE fp64 -> bf16 in one step (normal range): scale so that one bf16 ulp is 1, rint, scale back."""
+    v = np.asarray(values, dtype=np.float64)
+    out = np.zeros(v.shape, dtype=np.float64)
+    nz = v != 0
+    e = np.floor(np.log2(np.abs(v[nz])))
+    ulp = np.exp2(e - 7)
+    out[nz] = np.rint(v[nz] / ulp) * ulp          # both scalings are exact (powers of two)
+    return (out.astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+
+
 def unpack(qweight):
     qweight = np.asarray(qweight, dtype=np.uint32)
     shifts = (4 * np.arange(8, dtype=np.uint32))[None, None, :]
@@ -99,3 +110,18 @@ def dequantize_exact3(qweight, s_bits, z_bits, g):
 
 def forward3(qweight, s_bits, z_bits, g, x_bits):
     return np.einsum("mk,nk->mn", bf16_bits_to_f64(x_bits), dequantize_exact3(qweight, s_bits, z_bits, g))
+
+
+def rmsnorm(x_bits, gamma_bits, eps):
+    x = bf16_bits_to_f64(x_bits)
+    rms = np.sqrt((x * x).mean(axis=1, keepdims=True) + eps)
+    with np.errstate(invalid="ignore", divide="ignore"):
+        y = np.where(rms > 0, x * bf16_bits_to_f64(gamma_bits)[None, :] / rms, 0.0)
+    return f64_to_bf16_bits(y)
+
+
+def swiglu(in_bits):
+    v = bf16_bits_to_f64(in_bits)
+    half = v.shape[1] // 2
+    gate, up = v[:, :half], v[:, half:]
+    return f64_to_bf16_bits(gate / (1.0 + np.exp(-gate)) * up)

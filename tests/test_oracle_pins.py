@@ -426,3 +426,74 @@ def test_w3_quantizer_dequantize_forward():
     q4a, s4a, z4a = orc.quantize(w, g)
     q4b, s4b, z4b = orc.quantize_bits(w, g, 4)
     assert np.array_equal(q4a, q4b) and np.array_equal(s4a, s4b) and np.array_equal(z4a, z4b)
+
+
+# ------------------------------------------------------------------ decoder glue (RMSNorm, SwiGLU)
+
+def test_glue_handworked(golden):
+    gd = golden("handworked_glue.txt")
+    x = _h(gd["rmsnorm_x"]).astype(np.uint16)[None, :]
+    gamma = _h(gd["rmsnorm_gamma"]).astype(np.uint16)
+    assert np.array_equal(orc.rmsnorm(x, gamma, 0.0)[0], _h(gd["rmsnorm_out"]).astype(np.uint16))
+    gu = _h(gd["swiglu_in"]).astype(np.uint16)[None, :]
+    assert np.array_equal(orc.swiglu(gu)[0], _h(gd["swiglu_out"]).astype(np.uint16))
+
+
+def test_rmsnorm_closed_forms_and_invariances():
+    rng = np.random.default_rng(41)
+    K = 96
+    one = orc.f64_to_bf16(np.ones(K))
+    # a constant row has rms |c|: the result is sign(c) exactly
+    for c in (0.75, -3.0, 1e-3):
+        x = orc.f64_to_bf16(np.full((1, K), c))
+        assert np.array_equal(orc.bf16_to_f64(orc.rmsnorm(x, one, 0.0))[0], np.full(K, np.sign(c)))
+    x = synth.activations_bf16(42, 5, K)
+    gamma = orc.f64_to_bf16(rng.uniform(0.5, 2.0, K))
+    y = orc.rmsnorm(x, gamma, 0.0)
+    # scaling the row by a power of two changes nothing (eps = 0)
+    x4 = orc.f64_to_bf16(orc.bf16_to_f64(x) * 4.0)
+    assert np.array_equal(orc.rmsnorm(x4, gamma, 0.0), y)
+    # with gamma = 1 the output has unit mean square up to the bf16 rounding of each element
+    y1 = orc.bf16_to_f64(orc.rmsnorm(x, one, 0.0))
+    assert np.all(np.abs((y1 ** 2).mean(axis=1) - 1.0) < 2.0 ** -7)
+    # gamma multiplies element-wise: a one-hot gamma keeps exactly that element
+    hot = np.zeros(K)
+    hot[7] = 1.0
+    yh = orc.bf16_to_f64(orc.rmsnorm(x, orc.f64_to_bf16(hot), 0.0))
+    assert np.array_equal(yh[:, 7], y1[:, 7]) and np.count_nonzero(np.delete(yh, 7, axis=1)) == 0
+    # eps enters under the root: a zero row stays zero, and a huge eps shrinks the row by sqrt(eps)
+    assert np.count_nonzero(orc.rmsnorm(np.zeros((1, K), np.uint16), gamma, 1e-6)) == 0
+    assert np.count_nonzero(orc.rmsnorm(np.zeros((1, K), np.uint16), gamma, 0.0)) == 0
+    big = orc.bf16_to_f64(orc.rmsnorm(x, one, 2.0 ** 20))
+    ref = orc.bf16_to_f64(x) / np.sqrt((orc.bf16_to_f64(x) ** 2).mean(axis=1, keepdims=True) + 2.0 ** 20)
+    assert np.all(np.abs(big - ref) <= np.abs(ref) * 2.0 ** -8)
+    assert np.array_equal(twin.rmsnorm(x, gamma, 1e-5), orc.rmsnorm(x, gamma, 1e-5))
+    with pytest.raises(ValueError):
+        orc.rmsnorm(x, gamma[:-1], 0.0)
+
+
+def test_swiglu_closed_forms():
+    rng = np.random.default_rng(43)
+    I = 64
+    g = orc.bf16_to_f64(synth.activations_bf16(44, 3, I)) * 3.0
+    u = orc.bf16_to_f64(synth.activations_bf16(45, 3, I))
+    def run(gate, up):
+        return orc.bf16_to_f64(orc.swiglu(np.concatenate([orc.f64_to_bf16(gate), orc.f64_to_bf16(up)], axis=1)))
+    g, u = orc.bf16_to_f64(orc.f64_to_bf16(g)), orc.bf16_to_f64(orc.f64_to_bf16(u))
+    assert np.count_nonzero(run(np.zeros_like(g), u)) == 0          # silu(0) = 0
+    assert np.count_nonzero(run(g, np.zeros_like(u))) == 0
+    # silu(a) - silu(-a) = a: with up = 1 the two results differ by the gate, up to their roundings
+    p, n = run(g, np.ones_like(u)), run(-g, np.ones_like(u))
+    assert np.all(np.abs(p - n - g) <= (np.abs(p) + np.abs(n)) * 2.0 ** -8 + 1e-30)
+    # far in the tails silu is the identity resp. zero
+    assert np.array_equal(run(np.full((1, I), 32.0), u[:1]), u[:1] * 32.0)
+    assert np.all(np.abs(run(np.full((1, I), -40.0), u[:1])) < 1e-14)
+    # the up half scales linearly by powers of two
+    assert np.array_equal(run(g, u * 8.0), run(g, u) * 8.0)
+    # the halves are (gate | up), not interleaved and not swapped
+    packed = np.concatenate([orc.f64_to_bf16(g), orc.f64_to_bf16(u)], axis=1)
+    assert np.array_equal(twin.swiglu(packed), orc.swiglu(packed))
+    swapped = np.concatenate([orc.f64_to_bf16(u), orc.f64_to_bf16(g)], axis=1)
+    assert not np.array_equal(orc.swiglu(swapped), orc.swiglu(packed))
+    with pytest.raises(ValueError):
+        orc.swiglu(packed[:, :-1])
