@@ -116,6 +116,53 @@ dmr_status_t dmr_qlinear_bf16_forward(const uint16_t *d_w, const uint16_t *d_x, 
                                       size_t ws_bytes, void *stream);
 
 /*
+ * Decoder glue between the Linear layers of one routed step.  The models of Sec. 5.1 are pre-norm
+ * decoders with RMSNorm and a SwiGLU MLP; the paper does not restate these operations, they are
+ * taken in their textbook form, computed in fp32 with one rounding to bf16 at the end (the next
+ * Linear takes bf16 activations):
+ *   rmsnorm  out[m][k] = bf16( x[m][k] * gamma[k] / sqrt(mean_k(x[m][k]^2) + eps) )      (0 for a zero row)
+ *   swiglu   out[m][i] = bf16( silu(in[m][i]) * in[m][I + i] ),  silu(a) = a / (1 + exp(-a)),
+ *            in = [M][2 I], the gate half of the fused gate+up projection first, then the up half.
+ * K and I must be multiples of 8; all pointers device memory, 16-byte aligned.
+ */
+dmr_status_t dmr_glue_rmsnorm(const uint16_t *d_x, const uint16_t *d_gamma, float eps, int64_t M,
+                              int64_t K, uint16_t *d_out, void *stream);
+dmr_status_t dmr_glue_swiglu(const uint16_t *d_in, int64_t M, int64_t I, uint16_t *d_out, void *stream);
+
+/*
+ * A Linear of either copy (Eq. 1) with its surrounding glue fused in, so that a decode step is a
+ * chain of Linear launches only (App. B: decode cost is one pass over the weights per token, so
+ * every extra launch between them is pure overhead):
+ *   prologue  DMR_PRO_RMSNORM: the layer runs on rmsnorm(d_in, d_gamma, eps), d_in = [M][K]
+ *             DMR_PRO_SWIGLU:  the layer runs on swiglu(d_in), d_in = [M][2 K]
+ *             DMR_PRO_NONE:    d_in = [M][K] as in the plain forward
+ *   epilogue  d_residual (bf16 [M][N]) or NULL: y = acc + residual in fp32, rounded once to `out`.
+ * M = 1 fuses the prologue into the staging of the activation row and the residual into the
+ * output store of the weight-streaming kernel; larger M runs the glue kernels into d_ws and then
+ * the plain forward.  d_ws as the matching *_fused_workspace_bytes query says (never 0 with a
+ * prologue or a residual).
+ */
+typedef enum {
+    DMR_PRO_NONE = 0,
+    DMR_PRO_RMSNORM = 1,
+    DMR_PRO_SWIGLU = 2
+} dmr_prologue_t;
+
+size_t dmr_qlinear_fused_workspace_bytes(const dmr_qlinear_t *layer, int64_t M, dmr_prologue_t pro,
+                                         int32_t has_residual);
+size_t dmr_qlinear_bf16_fused_workspace_bytes(int64_t M, int64_t K, int64_t N, dmr_prologue_t pro,
+                                              int32_t has_residual);
+dmr_status_t dmr_qlinear_forward_fused(const dmr_qlinear_t *layer, dmr_prologue_t pro,
+                                       const uint16_t *d_in, const uint16_t *d_gamma, float eps,
+                                       const uint16_t *d_residual, int64_t M, void *d_y, dmr_out_t out,
+                                       void *d_ws, size_t ws_bytes, void *stream);
+dmr_status_t dmr_qlinear_bf16_forward_fused(const uint16_t *d_w, dmr_prologue_t pro,
+                                            const uint16_t *d_in, const uint16_t *d_gamma, float eps,
+                                            const uint16_t *d_residual, int64_t M, int64_t K, int64_t N,
+                                            void *d_y, dmr_out_t out, void *d_ws, size_t ws_bytes,
+                                            void *stream);
+
+/*
  * Offline step that produces the low-precision copy (App. E names AWQ/GPTQ; this is plain
  * asymmetric round-to-nearest, which yields the same format): fp32 weights [N][K] to canonical
  * qweight / scales / zeros.  Per (row, group): lo = min(w, 0), hi = max(w, 0),

@@ -26,7 +26,11 @@ EXPORTS = (
     "dmr_qlinear_quantize", "dmr_qlinear_destroy", "dmr_qlinear_shape", "dmr_status_string",
     "dmr_probe_hbm_read", "dmr_qlinear_w3_storage_bytes", "dmr_qlinear_w3_workspace_bytes",
     "dmr_qlinear_w3_create", "dmr_qlinear_quantize_w3", "dmr_qlinear_bits", "dmr_qlinear_create_per_channel",
+    "dmr_glue_rmsnorm", "dmr_glue_swiglu", "dmr_qlinear_fused_workspace_bytes",
+    "dmr_qlinear_bf16_fused_workspace_bytes", "dmr_qlinear_forward_fused", "dmr_qlinear_bf16_forward_fused",
 )
+
+DMR_PRO_NONE, DMR_PRO_RMSNORM, DMR_PRO_SWIGLU = 0, 1, 2
 
 
 class DmrError(RuntimeError):
@@ -82,6 +86,20 @@ def lib() -> ctypes.CDLL:
         L.dmr_qlinear_bits.argtypes = [vp]
         L.dmr_probe_hbm_read.restype = ctypes.c_int
         L.dmr_probe_hbm_read.argtypes = [vp, sz, vp, i32, vp]
+        f32 = ctypes.c_float
+        L.dmr_glue_rmsnorm.restype = ctypes.c_int
+        L.dmr_glue_rmsnorm.argtypes = [vp, vp, f32, i64, i64, vp, vp]
+        L.dmr_glue_swiglu.restype = ctypes.c_int
+        L.dmr_glue_swiglu.argtypes = [vp, i64, i64, vp, vp]
+        L.dmr_qlinear_fused_workspace_bytes.restype = sz
+        L.dmr_qlinear_fused_workspace_bytes.argtypes = [vp, i64, ctypes.c_int, i32]
+        L.dmr_qlinear_bf16_fused_workspace_bytes.restype = sz
+        L.dmr_qlinear_bf16_fused_workspace_bytes.argtypes = [i64, i64, i64, ctypes.c_int, i32]
+        L.dmr_qlinear_forward_fused.restype = ctypes.c_int
+        L.dmr_qlinear_forward_fused.argtypes = [vp, ctypes.c_int, vp, vp, f32, vp, i64, vp, ctypes.c_int, vp, sz, vp]
+        L.dmr_qlinear_bf16_forward_fused.restype = ctypes.c_int
+        L.dmr_qlinear_bf16_forward_fused.argtypes = [vp, ctypes.c_int, vp, vp, f32, vp, i64, i64, i64, vp,
+                                                     ctypes.c_int, vp, sz, vp]
         L.dmr_status_string.restype = ctypes.c_char_p
         L.dmr_status_string.argtypes = [ctypes.c_int]
         _lib = L
@@ -314,3 +332,91 @@ def dmr_qlinear_destroy(layer: Layer) -> None:
     handle, layer.handle = getattr(layer, "handle", None), None
     if handle and _lib is not None:
         _lib.dmr_qlinear_destroy(handle)
+
+
+# ---- decoder glue and fused forwards -------------------------------------------------------------
+
+def dmr_glue_rmsnorm(x: torch.Tensor, gamma: torch.Tensor, eps: float, out: torch.Tensor | None = None,
+                     stream=None) -> torch.Tensor:
+    px, pg = _dev(x, "x", _BF16), _dev(gamma, "gamma", _BF16)
+    M, K = x.shape
+    if tuple(gamma.shape) != (K,):
+        raise ValueError("gamma must be [K]")
+    if out is None:
+        out = torch.empty((M, K), dtype=torch.bfloat16, device=x.device)
+    po = _dev(out, "out", _BF16)
+    _check(lib().dmr_glue_rmsnorm(px, pg, float(eps), M, K, po, _stream(stream)), "dmr_glue_rmsnorm")
+    return out
+
+
+def dmr_glue_swiglu(gate_up: torch.Tensor, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    pi = _dev(gate_up, "gate_up", _BF16)
+    M, two_i = gate_up.shape
+    if two_i % 2:
+        raise ValueError("gate_up must be [M][2 I]")
+    if out is None:
+        out = torch.empty((M, two_i // 2), dtype=torch.bfloat16, device=gate_up.device)
+    po = _dev(out, "out", _BF16)
+    _check(lib().dmr_glue_swiglu(pi, M, two_i // 2, po, _stream(stream)), "dmr_glue_swiglu")
+    return out
+
+
+def _fused_args(pro, inp, gamma, residual, K, N):
+    pi = _dev(inp, "inp", _BF16)
+    want = 2 * K if pro == DMR_PRO_SWIGLU else K
+    if inp.dim() != 2 or inp.shape[1] != want:
+        raise ValueError(f"inp must be [M][{want}]")
+    M = inp.shape[0]
+    pg = None
+    if pro == DMR_PRO_RMSNORM:
+        pg = _dev(gamma, "gamma", _BF16)
+        if tuple(gamma.shape) != (K,):
+            raise ValueError("gamma must be [K]")
+    pr = None
+    if residual is not None:
+        pr = _dev(residual, "residual", _BF16)
+        if tuple(residual.shape) != (M, N):
+            raise ValueError("residual must be [M][N]")
+    return pi, pg, pr, M
+
+
+def dmr_qlinear_forward_fused(layer: Layer, pro: int, inp: torch.Tensor, gamma: torch.Tensor | None = None,
+                              eps: float = 0.0, residual: torch.Tensor | None = None,
+                              out: torch.Tensor | None = None, out_dtype=torch.bfloat16,
+                              workspace: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    pi, pg, pr, M = _fused_args(pro, inp, gamma, residual, layer.K, layer.N)
+    if out is None:
+        out = torch.empty((M, layer.N), dtype=out_dtype, device=inp.device)
+    po = _dev(out, "out", (torch.bfloat16, torch.float32))
+    if tuple(out.shape) != (M, layer.N):
+        raise ValueError("out must be [M][N]")
+    if workspace is None:
+        need = int(lib().dmr_qlinear_fused_workspace_bytes(layer.handle, M, pro, 1 if residual is not None else 0))
+        if need > 0:
+            workspace = torch.empty(need, dtype=torch.uint8, device=inp.device)    # device memory only
+    pw, wbytes = _workspace(workspace)
+    _check(lib().dmr_qlinear_forward_fused(layer.handle, pro, pi, pg, float(eps), pr, M, po, _out_code(out.dtype),
+                                           pw, wbytes, _stream(stream)), "dmr_qlinear_forward_fused")
+    return out
+
+
+def dmr_qlinear_bf16_forward_fused(w: torch.Tensor, pro: int, inp: torch.Tensor, gamma: torch.Tensor | None = None,
+                                   eps: float = 0.0, residual: torch.Tensor | None = None,
+                                   out: torch.Tensor | None = None, out_dtype=torch.bfloat16,
+                                   workspace: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    pw_ = _dev(w, "w", _BF16)
+    N, K = w.shape
+    pi, pg, pr, M = _fused_args(pro, inp, gamma, residual, K, N)
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=inp.device)
+    po = _dev(out, "out", (torch.bfloat16, torch.float32))
+    if tuple(out.shape) != (M, N):
+        raise ValueError("out must be [M][N]")
+    if workspace is None:
+        need = int(lib().dmr_qlinear_bf16_fused_workspace_bytes(M, K, N, pro, 1 if residual is not None else 0))
+        if need > 0:
+            workspace = torch.empty(need, dtype=torch.uint8, device=inp.device)    # device memory only
+    pws, wbytes = _workspace(workspace)
+    _check(lib().dmr_qlinear_bf16_forward_fused(pw_, pro, pi, pg, float(eps), pr, M, K, N, po, _out_code(out.dtype),
+                                                pws, wbytes, _stream(stream)), "dmr_qlinear_bf16_forward_fused")
+    return out

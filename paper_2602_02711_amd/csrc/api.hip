@@ -2,7 +2,7 @@
 // the choice of kernel by M.  No device memory is allocated here or anywhere in the library.
 #include <new>
 
-#include "common.hpp"
+#include "glue.hpp"
 
 struct dmr_qlinear {
     int64_t K, N;
@@ -41,6 +41,15 @@ Bf16Path bf16_path(int64_t M, int64_t N) {
     const int64_t gemm_wgs = ((M + 127) / 128) * ((N + 127) / 128);
     if (M <= 64 || gemm_wgs <= 128) return Bf16Path::Mid;
     return dmr::gemm_big_applies(M, N) ? Bf16Path::GemmBig : Bf16Path::Gemm;
+}
+
+size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
+
+// Workspace of a fused forward that falls back to glue kernel + plain forward: the glue output
+// (bf16 [M][K]), the fp32 result awaiting its residual ([M][N]), then the plain forward's own.
+size_t fused_extra_bytes(int64_t M, int64_t K, int64_t N, int pro, bool has_res) {
+    return (pro != DMR_PRO_NONE ? align256((size_t)M * (size_t)K * 2) : 0) +
+           (has_res ? align256((size_t)M * (size_t)N * 4) : 0);
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -289,6 +298,139 @@ dmr_status_t dmr_qlinear_bf16_forward(const uint16_t *d_w, const uint16_t *d_x, 
         case Bf16Path::GemmBig: return hip_status(dmr::launch_bf16_gemm_big(d_w, d_x, M, K, N, d_y, f32, s));
         default: return hip_status(dmr::launch_bf16_gemm(d_w, d_x, M, K, N, d_y, f32, s));
     }
+}
+
+dmr_status_t dmr_glue_rmsnorm(const uint16_t *d_x, const uint16_t *d_gamma, float eps, int64_t M, int64_t K,
+                              uint16_t *d_out, void *stream) {
+    if (M < 0 || M > (int64_t(1) << 22) || K <= 0 || K % 8 != 0 || K > (int64_t(1) << 31)) return DMR_ERR_SHAPE;
+    if (!(eps >= 0.f)) return DMR_ERR_UNSUPPORTED;
+    if (M == 0) return DMR_OK;
+    if (!d_x || !d_gamma || !d_out) return DMR_ERR_NULL;
+    if (!aligned16(d_x) || !aligned16(d_gamma) || !aligned16(d_out)) return DMR_ERR_ALIGN;
+    return hip_status(dmr::launch_rmsnorm(d_x, d_gamma, eps, M, K, d_out, static_cast<hipStream_t>(stream)));
+}
+
+dmr_status_t dmr_glue_swiglu(const uint16_t *d_in, int64_t M, int64_t I, uint16_t *d_out, void *stream) {
+    if (M < 0 || M > (int64_t(1) << 22) || I <= 0 || I % 8 != 0 || I > (int64_t(1) << 30)) return DMR_ERR_SHAPE;
+    if (M == 0) return DMR_OK;
+    if (!d_in || !d_out) return DMR_ERR_NULL;
+    if (!aligned16(d_in) || !aligned16(d_out)) return DMR_ERR_ALIGN;
+    return hip_status(dmr::launch_swiglu(d_in, M, I, d_out, static_cast<hipStream_t>(stream)));
+}
+
+size_t dmr_qlinear_fused_workspace_bytes(const dmr_qlinear_t *layer, int64_t M, dmr_prologue_t pro,
+                                         int32_t has_residual) {
+    if (!layer || M <= 0) return 0;
+    const size_t inner = layer->bits == 3 ? dmr_qlinear_w3_workspace_bytes(M, layer->K, layer->N)
+                                          : dmr_qlinear_workspace_bytes(M, layer->K, layer->N);
+    return fused_extra_bytes(M, layer->K, layer->N, pro, has_residual != 0) + inner;
+}
+
+size_t dmr_qlinear_bf16_fused_workspace_bytes(int64_t M, int64_t K, int64_t N, dmr_prologue_t pro,
+                                              int32_t has_residual) {
+    if (M <= 0 || K <= 0 || N <= 0) return 0;
+    return fused_extra_bytes(M, K, N, pro, has_residual != 0) + dmr_qlinear_bf16_workspace_bytes(M, K, N);
+}
+
+}  // extern "C"
+
+namespace {
+
+// Argument checks shared by the two fused forwards; DMR_OK means "go on".
+dmr_status_t check_fused(dmr_prologue_t pro, const uint16_t *d_in, const uint16_t *d_gamma, float eps,
+                         const uint16_t *d_residual, int64_t M, const void *d_y, dmr_out_t out, const void *d_ws) {
+    if (M < 0 || M > (int64_t(1) << 22)) return DMR_ERR_SHAPE;
+    if (out != DMR_OUT_BF16 && out != DMR_OUT_FP32) return DMR_ERR_UNSUPPORTED;
+    if (pro != DMR_PRO_NONE && pro != DMR_PRO_RMSNORM && pro != DMR_PRO_SWIGLU) return DMR_ERR_UNSUPPORTED;
+    if (pro == DMR_PRO_RMSNORM && !(eps >= 0.f)) return DMR_ERR_UNSUPPORTED;
+    if (M == 0) return DMR_OK;
+    if (!d_in || !d_y || (pro == DMR_PRO_RMSNORM && !d_gamma)) return DMR_ERR_NULL;
+    if (!aligned16(d_in) || !aligned16(d_y) || (d_gamma && !aligned16(d_gamma)) ||
+        (d_residual && !aligned16(d_residual)) || (d_ws && !aligned16(d_ws)))
+        return DMR_ERR_ALIGN;
+    return DMR_OK;
+}
+
+// The unfused composition: glue kernel into the workspace, plain forward (fp32 if a residual
+// follows), residual add.  `forward` runs the plain forward on (x, y, out type, inner workspace).
+template <typename Forward>
+dmr_status_t run_unfused(dmr_prologue_t pro, const uint16_t *d_in, const uint16_t *d_gamma, float eps,
+                         const uint16_t *d_residual, int64_t M, int64_t K, int64_t N, void *d_y, dmr_out_t out,
+                         void *d_ws, size_t ws_bytes, hipStream_t s, Forward forward) {
+    uint8_t *ws = static_cast<uint8_t *>(d_ws);
+    size_t used = 0;
+    const uint16_t *x = d_in;
+    if (pro != DMR_PRO_NONE) {
+        uint16_t *xg = reinterpret_cast<uint16_t *>(ws);
+        used += align256((size_t)M * (size_t)K * 2);
+        const hipError_t e = pro == DMR_PRO_RMSNORM ? dmr::launch_rmsnorm(d_in, d_gamma, eps, M, K, xg, s)
+                                                     : dmr::launch_swiglu(d_in, M, K, xg, s);
+        if (e != hipSuccess) return DMR_ERR_HIP;
+        x = xg;
+    }
+    if (!d_residual) return forward(x, d_y, out, ws + used, ws_bytes - used);
+    float *acc = reinterpret_cast<float *>(ws + used);
+    used += align256((size_t)M * (size_t)N * 4);
+    const dmr_status_t st = forward(x, acc, DMR_OUT_FP32, ws + used, ws_bytes - used);
+    if (st != DMR_OK) return st;
+    return hip_status(dmr::launch_add_residual(acc, d_residual, M * N, d_y, out == DMR_OUT_FP32, s));
+}
+
+}  // namespace
+
+extern "C" {
+
+dmr_status_t dmr_qlinear_forward_fused(const dmr_qlinear_t *layer, dmr_prologue_t pro, const uint16_t *d_in,
+                                       const uint16_t *d_gamma, float eps, const uint16_t *d_residual, int64_t M,
+                                       void *d_y, dmr_out_t out, void *d_ws, size_t ws_bytes, void *stream) {
+    if (!layer) return DMR_ERR_NULL;
+    const dmr_status_t chk = check_fused(pro, d_in, d_gamma, eps, d_residual, M, d_y, out, d_ws);
+    if (chk != DMR_OK || M == 0) return chk;
+    const size_t need = dmr_qlinear_fused_workspace_bytes(layer, M, pro, d_residual != nullptr);
+    if (need > 0 && (!d_ws || ws_bytes < need)) return DMR_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (M == 1 && layer->bits == 4) {
+        const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz};
+        dmr::Fusion f;
+        f.pro = (int)pro;
+        f.aux = d_gamma;
+        f.eps = eps;
+        f.res = d_residual;
+        const hipError_t e = dmr::launch_w4_gemv_fused(L, d_in, d_y, out == DMR_OUT_FP32, f, s);
+        if (e != hipErrorInvalidValue) return hip_status(e);   // else: shape outside the GEMV's range
+    }
+    return run_unfused(pro, d_in, d_gamma, eps, d_residual, M, layer->K, layer->N, d_y, out, d_ws, ws_bytes, s,
+                       [&](const uint16_t *x, void *y, dmr_out_t o, void *ws, size_t wsb) {
+                           return dmr_qlinear_forward(layer, x, M, y, o, ws, wsb, stream);
+                       });
+}
+
+dmr_status_t dmr_qlinear_bf16_forward_fused(const uint16_t *d_w, dmr_prologue_t pro, const uint16_t *d_in,
+                                            const uint16_t *d_gamma, float eps, const uint16_t *d_residual,
+                                            int64_t M, int64_t K, int64_t N, void *d_y, dmr_out_t out, void *d_ws,
+                                            size_t ws_bytes, void *stream) {
+    const dmr_status_t shape = check_shape(K, N, dmr::kGroup);
+    if (shape != DMR_OK) return shape;
+    const dmr_status_t chk = check_fused(pro, d_in, d_gamma, eps, d_residual, M, d_y, out, d_ws);
+    if (chk != DMR_OK || M == 0) return chk;
+    if (!d_w) return DMR_ERR_NULL;
+    if (!aligned16(d_w)) return DMR_ERR_ALIGN;
+    const size_t need = dmr_qlinear_bf16_fused_workspace_bytes(M, K, N, pro, d_residual != nullptr);
+    if (need > 0 && (!d_ws || ws_bytes < need)) return DMR_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (M == 1) {
+        dmr::Fusion f;
+        f.pro = (int)pro;
+        f.aux = d_gamma;
+        f.eps = eps;
+        f.res = d_residual;
+        const hipError_t e = dmr::launch_bf16_gemv_fused(d_w, d_in, K, N, d_y, out == DMR_OUT_FP32, f, s);
+        if (e != hipErrorInvalidValue) return hip_status(e);   // else: K outside its range, or RMSNorm over slices
+    }
+    return run_unfused(pro, d_in, d_gamma, eps, d_residual, M, K, N, d_y, out, d_ws, ws_bytes, s,
+                       [&](const uint16_t *x, void *y, dmr_out_t o, void *ws, size_t wsb) {
+                           return dmr_qlinear_bf16_forward(d_w, x, M, K, N, y, o, ws, wsb, stream);
+                       });
 }
 
 dmr_status_t dmr_qlinear_quantize(int64_t K, int64_t N, int32_t g, const float *d_w, uint32_t *d_qweight,

@@ -7,7 +7,7 @@
 // whole, once), 4 XC v_dot2_f32_bf16 per lane and a 6-step lane butterfly.  The loads of row r+1
 // are in flight while row r is reduced.  With S > 1 slices per row the partial sums of a
 // workgroup's 4 wavefronts meet in LDS and are added in slice order.
-#include "common.hpp"
+#include "glue.hpp"
 
 namespace dmr {
 
@@ -31,11 +31,15 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 constexpr int kWaves = 4;   // wavefronts per workgroup
 
-template <int XC>
+// PRO: glue fused into the load of the activation slice (glue.hpp).  RMSNorm needs the whole row in
+// one wave (S == 1); `res`, if not null, is a bf16 residual added to the result.
+template <int XC, int PRO>
 __global__ __launch_bounds__(kWaves * 64) void bf16_gemv_kernel(const uint16_t *__restrict__ w,
                                                                 const uint16_t *__restrict__ x,
                                                                 void *__restrict__ y, int64_t K, int64_t N,
-                                                                int S, int rpw, int out_f32) {
+                                                                int S, int rpw, int out_f32,
+                                                                const uint16_t *__restrict__ aux, float eps,
+                                                                const uint16_t *__restrict__ res) {
     extern __shared__ float red[];   // [kWaves][rpw]
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -56,7 +60,24 @@ __global__ __launch_bounds__(kWaves * 64) void bf16_gemv_kernel(const uint16_t *
         const bool ok = k < K;
         koff[cidx] = ok ? k : 0;
         xr[cidx] = ok ? *reinterpret_cast<const uint4 *>(x + k) : make_uint4(0, 0, 0, 0);
+        if (PRO == kProSwiGLU && ok) xr[cidx] = swiglu_piece(xr[cidx], *reinterpret_cast<const uint4 *>(x + K + k));
     }
+    if (PRO == kProRmsNorm) {
+        float ss = 0.f;
+#pragma unroll
+        for (int cidx = 0; cidx < XC; ++cidx) ss += sumsq_piece(xr[cidx]);     // zeros beyond K
+        const float scale = rms_scale(wave_sum(ss), 1.0f / (float)K, eps);
+#pragma unroll
+        for (int cidx = 0; cidx < XC; ++cidx)
+            xr[cidx] = rmsnorm_piece(xr[cidx], *reinterpret_cast<const uint4 *>(aux + koff[cidx]), scale);
+    }
+    auto store_out = [&](int64_t r, float v) {
+        if (res) v += __uint_as_float((uint32_t)res[r] << 16);
+        if (out_f32)
+            reinterpret_cast<float *>(y)[r] = v;
+        else
+            reinterpret_cast<uint16_t *>(y)[r] = f32_to_bf16(v);
+    };
 
     uint4 cur[XC], nxt[XC];
     auto load_row = [&](uint4 (&dst)[XC], int64_t r) {
@@ -76,13 +97,10 @@ __global__ __launch_bounds__(kWaves * 64) void bf16_gemv_kernel(const uint16_t *
         }
         const float sum = wave_sum(a0 + a1);
         if (lane == 0) {
-            if (S > 1) {
+            if (S > 1)
                 red[wave * rpw + i] = sum;
-            } else if (out_f32) {
-                reinterpret_cast<float *>(y)[r0 + i] = sum;
-            } else {
-                reinterpret_cast<uint16_t *>(y)[r0 + i] = f32_to_bf16(sum);
-            }
+            else
+                store_out(r0 + i, sum);
         }
     };
     if (rows > 0) {
@@ -105,10 +123,7 @@ __global__ __launch_bounds__(kWaves * 64) void bf16_gemv_kernel(const uint16_t *
         if (r < N) {
             float sum = 0.f;
             for (int q = 0; q < S; ++q) sum += red[(b * S + q) * rpw + i];
-            if (out_f32)
-                reinterpret_cast<float *>(y)[r] = sum;
-            else
-                reinterpret_cast<uint16_t *>(y)[r] = f32_to_bf16(sum);
+            store_out(r, sum);
         }
     }
 }
@@ -117,6 +132,11 @@ __global__ __launch_bounds__(kWaves * 64) void bf16_gemv_kernel(const uint16_t *
 
 hipError_t launch_bf16_gemv(const uint16_t *w, const uint16_t *x, int64_t K, int64_t N, void *y,
                             bool out_f32, hipStream_t stream) {
+    return launch_bf16_gemv_fused(w, x, K, N, y, out_f32, Fusion{}, stream);
+}
+
+hipError_t launch_bf16_gemv_fused(const uint16_t *w, const uint16_t *x, int64_t K, int64_t N, void *y, bool out_f32,
+                                  const Fusion &f, hipStream_t stream) {
     // slices per row: keep at most 8 chunks of 512 values of x in registers
     const int64_t chunks = (K + 511) / 512;
     int S = 1;
@@ -133,10 +153,15 @@ hipError_t launch_bf16_gemv(const uint16_t *w, const uint16_t *x, int64_t K, int
     const size_t lds = S > 1 ? (size_t)kWaves * rpw * sizeof(float) : 0;
     const int of = out_f32 ? 1 : 0;
     const int irpw = (int)rpw;
+    if (f.pro == kProRmsNorm && S != 1) return hipErrorInvalidValue;   // the row must sit in one wave
+#define DMR_BF16_GEMV_LAUNCH(X, PRO)                                                                   \
+    hipLaunchKernelGGL((bf16_gemv_kernel<X, PRO>), dim3(grid), dim3(kWaves * 64), lds, stream, w, x, y, K, N, \
+                       S, irpw, of, f.aux, f.eps, f.res)
 #define DMR_BF16_GEMV_CASE(X)                                                                          \
     case X:                                                                                            \
-        hipLaunchKernelGGL((bf16_gemv_kernel<X>), dim3(grid), dim3(kWaves * 64), lds, stream, w, x, y, K, N, \
-                           S, irpw, of);                                                               \
+        if (f.pro == kProRmsNorm) DMR_BF16_GEMV_LAUNCH(X, kProRmsNorm);                                 \
+        else if (f.pro == kProSwiGLU) DMR_BF16_GEMV_LAUNCH(X, kProSwiGLU);                              \
+        else DMR_BF16_GEMV_LAUNCH(X, kProNone);                                                         \
         break;
     switch (XC) {
         DMR_BF16_GEMV_CASE(1) DMR_BF16_GEMV_CASE(2) DMR_BF16_GEMV_CASE(3) DMR_BF16_GEMV_CASE(4)
@@ -144,6 +169,7 @@ hipError_t launch_bf16_gemv(const uint16_t *w, const uint16_t *x, int64_t K, int
         default: return hipErrorInvalidValue;
     }
 #undef DMR_BF16_GEMV_CASE
+#undef DMR_BF16_GEMV_LAUNCH
     return hipGetLastError();
 }
 

@@ -15,7 +15,7 @@
 // once per workgroup while x is staged and kept in LDS beside it.
 #include <cstdlib>
 
-#include "common.hpp"
+#include "glue.hpp"
 
 namespace dmr {
 
@@ -27,13 +27,18 @@ struct Item {
     uint32_t szw;
 };
 
-template <int P, int XL>
+// PRO selects glue fused into the activation staging (glue.hpp): the row is normalised (RMSNorm,
+// gamma in `aux`) or formed from a gate half and an up half (SwiGLU, x then holds 2 K values) in
+// registers on its way into LDS.  `res`, if not null, is a bf16 residual added to the result.
+template <int P, int XL, int PRO>
 __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__ wt,
                                                        const uint32_t *__restrict__ sz,
                                                        const uint16_t *__restrict__ x,
                                                        void *__restrict__ y, int groups, int tiles,
-                                                       int lgS, int lgTW, int nT_max, int out_f32) {
-    extern __shared__ uint4 smem[];          // x (16 uint4 per group), X[groups], red[nT_max][TW][S][16]
+                                                       int lgS, int lgTW, int nT_max, int out_f32,
+                                                       const uint16_t *__restrict__ aux, float eps,
+                                                       const uint16_t *__restrict__ res) {
+    extern __shared__ uint4 smem[];          // x (16 uint4 per group), X[groups], red[nT_max][TW][S][16], 16 floats
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform (SGPR)
     const int S = 1 << lgS, TW = 1 << lgTW;
@@ -49,11 +54,15 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
 
     // x -> registers now (oldest loads), -> LDS after the first weight loads have been issued
     uint4 xreg[XL];
+    uint4 xaux[PRO == kProNone ? 1 : XL];     // gamma pieces (RMSNorm) or up pieces (SwiGLU)
     const int x16 = groups * 16;
 #pragma unroll
     for (int u = 0; u < XL; ++u) {
         const int i = (int)threadIdx.x + u * (int)blockDim.x;
-        xreg[u] = reinterpret_cast<const uint4 *>(x)[i < x16 ? i : 0];
+        const int ic = i < x16 ? i : 0;
+        xreg[u] = reinterpret_cast<const uint4 *>(x)[ic];
+        if (PRO == kProRmsNorm) xaux[u] = reinterpret_cast<const uint4 *>(aux)[ic];
+        if (PRO == kProSwiGLU) xaux[u] = reinterpret_cast<const uint4 *>(x)[x16 + ic];
     }
 
     // Issue pointer (it, ig) walks (tile step, group in slice) and saturates at the last block,
@@ -79,6 +88,29 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
     }
     float *xsum_lds = reinterpret_cast<float *>(smem + x16);                 // X[group]
     float *red = xsum_lds + ((groups + 3) & ~3);
+    if (PRO == kProRmsNorm) {
+        // sum of squares of the whole row: lanes -> wave (DPP, two cross-row steps) -> 16 waves via LDS
+        float *part = red + (lgS > 0 ? (nT_max << (lgTW + lgS)) * 16 : 0);
+        float ss = 0.f;
+#pragma unroll
+        for (int u = 0; u < XL; ++u)
+            if ((int)threadIdx.x + u * (int)blockDim.x < x16) ss += sumsq_piece(xreg[u]);
+        ss = row16_sum(ss);
+        ss += __shfl_xor(ss, 16, 64);
+        ss += __shfl_xor(ss, 32, 64);
+        if (lane == 0) part[wave] = ss;
+        __syncthreads();
+        float total = 0.f;
+        const int nw = (int)blockDim.x >> 6;
+        for (int q = 0; q < nw; ++q) total += part[q];          // same order in every thread
+        const float scale = rms_scale(total, 1.0f / (float)(groups * kGroup), eps);
+#pragma unroll
+        for (int u = 0; u < XL; ++u) xreg[u] = rmsnorm_piece(xreg[u], xaux[u], scale);
+    }
+    if (PRO == kProSwiGLU) {
+#pragma unroll
+        for (int u = 0; u < XL; ++u) xreg[u] = swiglu_piece(xreg[u], xaux[u]);
+    }
 #pragma unroll
     for (int u = 0; u < XL; ++u) {
         const int i = (int)threadIdx.x + u * (int)blockDim.x;
@@ -95,6 +127,14 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
     }
     __syncthreads();
 
+    // output: the fp32 result, plus the residual if there is one, rounded once if bf16 is asked for
+    auto store_out = [&](int64_t n, float v) {
+        if (res) v += __uint_as_float((uint32_t)res[n] << 16);
+        if (out_f32)
+            reinterpret_cast<float *>(y)[n] = v;
+        else
+            reinterpret_cast<uint16_t *>(y)[n] = f32_to_bf16(v);
+    };
     const uint4 *xs = smem + g0 * 16;
     float acc = 0.f;
     int ct = 0, cg = 0;
@@ -120,11 +160,7 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
                 if (lgS > 0) {
                     red[((((ct << lgTW) + tw) << lgS) + s) * 16 + lane] = acc;
                 } else {
-                    const int64_t n = (int64_t)(t_first + ct * t_step) * kTileRows + lane;
-                    if (out_f32)
-                        reinterpret_cast<float *>(y)[n] = acc;
-                    else
-                        reinterpret_cast<uint16_t *>(y)[n] = f32_to_bf16(acc);
+                    store_out((int64_t)(t_first + ct * t_step) * kTileRows + lane, acc);
                 }
             }
             acc = 0.f;
@@ -158,13 +194,7 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
         float v = red[((slot << lgS) + q) * 16 + col];
         for (int m = S >> 1; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
         const int tile = ((int)blockIdx.x << lgTW) + (slot & (TW - 1)) + (slot >> lgTW) * t_step;
-        if (q == 0 && tile < tiles) {
-            const int64_t n = (int64_t)tile * kTileRows + col;
-            if (out_f32)
-                reinterpret_cast<float *>(y)[n] = v;
-            else
-                reinterpret_cast<uint16_t *>(y)[n] = f32_to_bf16(v);
-        }
+        if (q == 0 && tile < tiles) store_out((int64_t)tile * kTileRows + col, v);
     }
 }
 
@@ -197,6 +227,11 @@ GemvPlan plan_for(int groups, int tiles, int cus) {
 
 hipError_t launch_w4_gemv(const LayerView &L, const uint16_t *x, void *y, bool out_f32,
                           hipStream_t stream) {
+    return launch_w4_gemv_fused(L, x, y, out_f32, Fusion{}, stream);
+}
+
+hipError_t launch_w4_gemv_fused(const LayerView &L, const uint16_t *x, void *y, bool out_f32, const Fusion &f,
+                                hipStream_t stream) {
     const int groups = (int)(L.K / kGroup);
     const int tiles = (int)(L.N / kTileRows);
     static int cus = 0;   // compute units of the (single) device, asked once
@@ -228,7 +263,8 @@ hipError_t launch_w4_gemv(const LayerView &L, const uint16_t *x, void *y, bool o
     const int nT_max = (tiles + t_step - 1) / t_step;
     const int gw_max = (groups + plan.S - 1) / plan.S;
     const size_t lds = (size_t)groups * 16 * sizeof(uint4) + (size_t)((groups + 3) & ~3) * sizeof(float) +
-                       (plan.S > 1 ? (size_t)nT_max * nw * 16 * sizeof(float) : 0);
+                       (plan.S > 1 ? (size_t)nT_max * nw * 16 * sizeof(float) : 0) +
+                       (f.pro == kProRmsNorm ? 16 * sizeof(float) : 0);
     if (lds > 64 * 1024) return hipErrorInvalidValue;   // caller falls back to the general kernel
 
     // Ring depth: four blocks in flight per wave measured best (more costs registers, hence
@@ -238,9 +274,15 @@ hipError_t launch_w4_gemv(const LayerView &L, const uint16_t *x, void *y, bool o
     P = env_int("DMR_GEMV_P", P);
     const dim3 g(plan.grid), b(nw * 64);
     const int of = out_f32 ? 1 : 0;
+#define DMR_GEMV_LAUNCH_PRO(PP, XX, PRO)                                                               \
+    hipLaunchKernelGGL((w4_gemv_kernel<PP, XX, PRO>), g, b, lds, stream, L.wt, L.sz, x, y, groups, tiles, \
+                       lgS, lgTW, nT_max, of, f.aux, f.eps, f.res)
 #define DMR_GEMV_LAUNCH(PP, XX)                                                                        \
-    hipLaunchKernelGGL((w4_gemv_kernel<PP, XX>), g, b, lds, stream, L.wt, L.sz, x, y, groups, tiles, lgS, \
-                       lgTW, nT_max, of)
+    do {                                                                                               \
+        if (f.pro == kProRmsNorm) DMR_GEMV_LAUNCH_PRO(PP, XX, kProRmsNorm);                             \
+        else if (f.pro == kProSwiGLU) DMR_GEMV_LAUNCH_PRO(PP, XX, kProSwiGLU);                          \
+        else DMR_GEMV_LAUNCH_PRO(PP, XX, kProNone);                                                     \
+    } while (0)
 #define DMR_GEMV_CASE(PP)                                                                              \
     case PP:                                                                                           \
         if (xl_need <= 1) DMR_GEMV_LAUNCH(PP, 1);                                                      \
@@ -254,6 +296,7 @@ hipError_t launch_w4_gemv(const LayerView &L, const uint16_t *x, void *y, bool o
     }
 #undef DMR_GEMV_CASE
 #undef DMR_GEMV_LAUNCH
+#undef DMR_GEMV_LAUNCH_PRO
     return hipGetLastError();
 }
 
