@@ -192,6 +192,140 @@ def mixed_step(args, dmr, synth, torch, dev):
     print(json.dumps(result), flush=True)
 
 
+def chain_step(args, dmr, synth, torch, dev):
+    """One decode step (M = 1) of a 32-layer 7B-class decoder as a dependent chain of its Linear layers
+    with the glue between them: per layer RMSNorm -> qkv, attn_out + residual, RMSNorm -> gate_up,
+    SwiGLU -> down + residual.  Attention itself is not a Linear and is not modelled: the first 4096
+    columns of the qkv output stand in for its result, so that the shapes chain.  Timed four ways: the
+    glue fused into the Linear launches (4 launches per layer) or as kernels of its own (rmsnorm x 2,
+    swiglu, residual add x 2: 9 launches per layer), for the INT4 copy and for the bf16 copy."""
+    G, LAYERS, H, I = synth.GROUP, 32, 4096, 14336
+    gen = torch.Generator(device=dev)
+    t0 = time.time()
+    int4, bf16, gammas = [], [], []
+    for li in range(LAYERS):
+        l4, l16 = {}, {}
+        for si, (name, K, N) in enumerate(synth.LAYER_SHAPES):
+            gen.manual_seed(synth.seed_for(4, si, 0, layer=li))
+            w = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02
+            qw, s, z = dmr.dmr_qlinear_quantize(w, G)
+            l4[name] = dmr.dmr_qlinear_create(qw, s, z, G)
+            l16[name] = w.to(torch.bfloat16)
+            del w, qw, s, z
+        int4.append(l4)
+        bf16.append(l16)
+        gen.manual_seed(synth.seed_for(4, 5, 0, layer=li))
+        gammas.append((1.0 + 0.1 * torch.randn((2, H), generator=gen, device=dev)).to(torch.bfloat16))
+    gen.manual_seed(synth.seed_for(4, 0, 1))
+    h0 = torch.randn((1, H), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    bufs = {"qkv": torch.empty((1, 6144), dtype=torch.bfloat16, device=dev),
+            "gu": torch.empty((1, 2 * I), dtype=torch.bfloat16, device=dev),
+            "act": torch.empty((1, I), dtype=torch.bfloat16, device=dev),
+            "norm": torch.empty((1, H), dtype=torch.bfloat16, device=dev),
+            "h": [torch.empty((1, H), dtype=torch.bfloat16, device=dev) for _ in range(3)],
+            "ws": torch.empty(1 << 20, dtype=torch.uint8, device=dev)}
+    torch.cuda.synchronize()
+    log(f"[bench] 128 layers resident after {time.time() - t0:.1f}s")
+    stream = torch.cuda.Stream()
+    EPS = 1e-6
+    R, S, NONE = dmr.DMR_PRO_RMSNORM, dmr.DMR_PRO_SWIGLU, dmr.DMR_PRO_NONE
+
+    def step(low: bool, fused: bool, single_rounding: bool = False, layers: int = LAYERS):
+        # single_rounding (check only): the unfused composition with the residual added to the fp32
+        # result and rounded once, i.e. the arithmetic the fused epilogue performs
+        h = bufs["h"][0]
+        h.copy_(h0)
+        for li in range(layers):
+            g1, g2 = gammas[li][0], gammas[li][1]
+            h1, h2 = bufs["h"][1], bufs["h"][2]
+            L = int4[li] if low else bf16[li]
+
+            def lin(name, pro, inp, gamma, res, out):
+                if fused:
+                    if low:
+                        dmr.dmr_qlinear_forward_fused(L[name], pro, inp, gamma=gamma, eps=EPS, residual=res, out=out,
+                                                      workspace=bufs["ws"])
+                    else:
+                        dmr.dmr_qlinear_bf16_forward_fused(L[name], pro, inp, gamma=gamma, eps=EPS, residual=res,
+                                                           out=out, workspace=bufs["ws"])
+                    return
+                x = inp
+                if pro == R:
+                    x = dmr.dmr_glue_rmsnorm(inp, gamma, EPS, out=bufs["norm"])
+                if pro == S:
+                    x = dmr.dmr_glue_swiglu(inp, out=bufs["act"])
+                if single_rounding and res is not None:
+                    y32 = (dmr.dmr_qlinear_forward(L[name], x, out_dtype=torch.float32) if low else
+                           dmr.dmr_qlinear_bf16_forward(L[name], x, out_dtype=torch.float32))
+                    out.copy_((y32 + res.float()).to(torch.bfloat16))
+                    return
+                if low:
+                    dmr.dmr_qlinear_forward(L[name], x, out=out)
+                else:
+                    dmr.dmr_qlinear_bf16_forward(L[name], x, out=out)
+                if res is not None:
+                    out.add_(res)
+
+            lin("qkv", R, h, g1, None, bufs["qkv"])
+            lin("attn_out", NONE, bufs["qkv"][:, :H], None, h, h1)      # attention stand-in: the q slice
+            lin("gate_up", R, h1, g2, None, bufs["gu"])
+            lin("down", S, bufs["gu"], None, h1, h2)
+            bufs["h"][0], bufs["h"][2] = h2, h
+            h = h2
+        return h
+
+    def timed(low: bool, fused: bool):
+        with torch.cuda.stream(stream):
+            for _ in range(args.warmup):
+                step(low, fused)
+            stream.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                for _ in range(args.steps):
+                    step(low, fused)
+            for _ in range(2):
+                graph.replay()
+            stream.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            graph.replay()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / args.steps
+
+    with torch.cuda.stream(stream):
+        # consistency of the fused kernels with the unfused composition, over the first decoder layer
+        # (over all 32 the bf16 residual stream amplifies single-ulp differences: informational only)
+        ref1 = step(True, False, single_rounding=True, layers=1).float().clone()
+        got1 = step(True, True, layers=1).float().clone()
+        ref = step(True, False, single_rounding=True).float().clone()
+        got = step(True, True).float().clone()
+        stream.synchronize()
+    drift1 = float((ref1 - got1).abs().max() / ref1.pow(2).mean().sqrt())
+    drift = float((ref - got).abs().max() / ref.pow(2).mean().sqrt())
+    times = {(low, fused): timed(low, fused) for low in (True, False) for fused in (True, False)}
+    b4 = LAYERS * sum(int4_bytes(K, N, 1) for _, K, N in synth.LAYER_SHAPES)
+    t = times[(True, True)]
+    result = {
+        "metric": "dependent decode chain (Linear layers + fused glue) of the INT4 copy: us per step",
+        "value": round(t * 1e3, 1), "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(t, 5), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "32 layers x (rmsnorm->qkv, attn_out+residual, rmsnorm->gate_up, swiglu->down+residual), "
+                               "M=1, attention replaced by the q slice, hip-graph replay"},
+        "us_per_step": {"int4_fused": round(times[(True, True)] * 1e3, 1),
+                        "int4_unfused": round(times[(True, False)] * 1e3, 1),
+                        "bf16_fused": round(times[(False, True)] * 1e3, 1),
+                        "bf16_unfused": round(times[(False, False)] * 1e3, 1)},
+        "speedup_fused_vs_unfused_int4": round(times[(True, False)] / times[(True, True)], 3),
+        "speedup_int4_vs_bf16_fused": round(times[(False, True)] / times[(True, True)], 3),
+        "int4_GBps_fused": round(b4 / (t * 1e-3) / 1e9, 1),
+        "fused_vs_unfused_hidden_max_diff_over_rms": {"after_1_layer": round(drift1, 5),
+                                                      "after_32_layers": round(drift, 5)},
+    }
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -200,7 +334,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly from Python instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
-    ap.add_argument("--workload", choices=("decode_sweep", "full_step", "mixed_step"), default="decode_sweep",
+    ap.add_argument("--workload", choices=("decode_sweep", "full_step", "mixed_step", "chain_step"), default="decode_sweep",
                     help="decode_sweep (default, the headline metric) or full_step: all 129 Linear layers of "
                          "a 32-layer 7B-class decoder per step")
     ap.add_argument("--m", type=int, default=1, help="rows of activations for --workload full_step")
@@ -223,6 +357,8 @@ def main():
         return full_step(args, dmr, synth, torch, dev)
     if args.workload == "mixed_step":
         return mixed_step(args, dmr, synth, torch, dev)
+    if args.workload == "chain_step":
+        return chain_step(args, dmr, synth, torch, dev)
     G = synth.GROUP
     M = 1
 

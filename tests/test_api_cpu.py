@@ -109,6 +109,36 @@ def test_forward_and_friends_reject_bad_arguments(lib):
     assert qz(1024, 8, 128, FAKE, FAKE, FAKE, FAKE, None) == binding.DMR_ERR_SHAPE
 
 
+def test_glue_and_fused_forwards_reject_bad_arguments(lib):
+    rn, sw = lib.dmr_glue_rmsnorm, lib.dmr_glue_swiglu
+    assert rn(FAKE, FAKE, 1e-6, 1, 1001, FAKE, None) == binding.DMR_ERR_SHAPE          # K not a multiple of 8
+    assert rn(FAKE, FAKE, 1e-6, -1, 1024, FAKE, None) == binding.DMR_ERR_SHAPE
+    assert rn(FAKE, FAKE, -1.0, 1, 1024, FAKE, None) == binding.DMR_ERR_UNSUPPORTED
+    assert rn(FAKE, FAKE, 1e-6, 0, 1024, FAKE, None) == binding.DMR_OK
+    assert rn(FAKE, None, 1e-6, 1, 1024, FAKE, None) == binding.DMR_ERR_NULL
+    assert rn(FAKE + 8, FAKE, 1e-6, 1, 1024, FAKE, None) == binding.DMR_ERR_ALIGN
+    assert sw(FAKE, 1, 12, FAKE, None) == binding.DMR_ERR_SHAPE
+    assert sw(None, 1, 16, FAKE, None) == binding.DMR_ERR_NULL
+    assert sw(FAKE, 1, 16, FAKE + 2, None) == binding.DMR_ERR_ALIGN
+    ff = lib.dmr_qlinear_forward_fused
+    assert ff(None, 1, FAKE, FAKE, 1e-6, None, 1, FAKE, 0, FAKE, 1 << 30, None) == binding.DMR_ERR_NULL
+    bf = lib.dmr_qlinear_bf16_forward_fused
+    ok_ws = (FAKE, 1 << 30)
+    assert bf(FAKE, 1, FAKE, FAKE, 1e-6, None, 1, 1000, 1024, FAKE, 0, *ok_ws, None) == binding.DMR_ERR_SHAPE
+    assert bf(FAKE, 3, FAKE, FAKE, 1e-6, None, 1, 1024, 1024, FAKE, 0, *ok_ws, None) == binding.DMR_ERR_UNSUPPORTED
+    assert bf(FAKE, 1, FAKE, None, 1e-6, None, 1, 1024, 1024, FAKE, 0, *ok_ws, None) == binding.DMR_ERR_NULL   # gamma
+    assert bf(FAKE, 2, FAKE, None, 0.0, FAKE + 4, 1, 1024, 1024, FAKE, 0, *ok_ws, None) == binding.DMR_ERR_ALIGN
+    assert bf(FAKE, 1, FAKE, FAKE, 1e-6, None, 0, 1024, 1024, FAKE, 0, None, 0, None) == binding.DMR_OK
+    # a prologue or a residual needs the workspace the query names
+    q = lib.dmr_qlinear_bf16_fused_workspace_bytes
+    assert q(1, 4096, 4096, 0, 0) == 0
+    assert q(1, 4096, 4096, 1, 0) == 8192 and q(1, 4096, 4096, 0, 1) == 16384
+    assert q(5, 4096, 4096, 2, 1) == 5 * 4096 * 2 + 5 * 4096 * 4 + lib.dmr_qlinear_bf16_workspace_bytes(5, 4096, 4096)
+    assert bf(FAKE, 1, FAKE, FAKE, 1e-6, None, 1, 4096, 4096, FAKE, 0, None, 0, None) == binding.DMR_ERR_WORKSPACE
+    assert bf(FAKE, 1, FAKE, FAKE, 1e-6, None, 1, 4096, 4096, FAKE, 0, FAKE, 100, None) == binding.DMR_ERR_WORKSPACE
+    assert lib.dmr_qlinear_fused_workspace_bytes(None, 1, 1, 0) == 0
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(TypeError):
