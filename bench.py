@@ -326,6 +326,80 @@ def chain_step(args, dmr, synth, torch, dev):
     print(json.dumps(result), flush=True)
 
 
+def layer_sweep(args, dmr, synth, torch, dev):
+    """Per-layer times of both copies at the row counts in --ms (rollout batches, prefill) on the four
+    decoder shapes: hip-graph replay, weights rotating over >= 1 GiB of resident copies per shape, the
+    workspace allocated once outside the timed region."""
+    G = synth.GROUP
+    Ms = [int(v) for v in args.ms.split(",")]
+    which = args.shapes.split(",") if args.shapes else [n for n, _, _ in synth.SWEEP_SHAPES]
+    stream = torch.cuda.Stream()
+
+    def timeit(fn, iters):
+        with torch.cuda.stream(stream):
+            for i in range(3):
+                fn(i)
+            stream.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                for i in range(iters):
+                    fn(3 + i)
+            for _ in range(2):
+                graph.replay()
+            stream.synchronize()
+            best = float("inf")
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                graph.replay()
+                e1.record(stream)
+                torch.cuda.synchronize()
+                best = min(best, e0.elapsed_time(e1) * 1e3 / iters)
+        return best
+
+    rows = []
+    for si, (name, K, N) in enumerate(synth.SWEEP_SHAPES):
+        if name not in which:
+            continue
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(synth.seed_for(2, si, 0))
+        w = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02
+        qw, s, z = dmr.dmr_qlinear_quantize(w, G)
+        n4 = -(-(1 << 30) // int4_bytes(K, N))
+        n16 = -(-(1 << 30) // bf16_bytes(K, N))
+        layers = [dmr.dmr_qlinear_create(qw, s, z, G) for _ in range(n4)]
+        wbs = [w.to(torch.bfloat16).clone() for _ in range(n16)]
+        del w, qw, s, z
+        for M in Ms:
+            gen.manual_seed(synth.seed_for(2, si, 1) + M)
+            x = torch.randn((M, K), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+            y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+            ws4 = torch.empty(max(dmr.dmr_qlinear_workspace_bytes(M, K, N), 16), dtype=torch.uint8, device=dev)
+            ws16 = torch.empty(max(dmr.dmr_qlinear_bf16_workspace_bytes(M, K, N), 16), dtype=torch.uint8, device=dev)
+            iters = 100 if M <= 64 else (20 if M <= 1024 else 5)
+            t4 = timeit(lambda i: dmr.dmr_qlinear_forward(layers[i % n4], x, out=y, workspace=ws4), iters)
+            t16 = timeit(lambda i: dmr.dmr_qlinear_bf16_forward(wbs[i % n16], x, out=y, workspace=ws16), iters)
+            flops = 2.0 * M * K * N
+            rows.append({"shape": name, "K": K, "N": N, "M": M, "int4_us": round(t4, 2), "bf16_us": round(t16, 2),
+                         "speedup": round(t16 / t4, 3),
+                         "int4_GBps": round(int4_bytes(K, N, M) / t4 / 1e3, 1),
+                         "bf16_GBps": round(bf16_bytes(K, N, M) / t16 / 1e3, 1),
+                         "int4_TFLOPs": round(flops / t4 / 1e6, 1), "bf16_TFLOPs": round(flops / t16 / 1e6, 1)})
+            log(f"[bench] {name:9s} M={M:5d} int4 {t4:9.2f} us  bf16 {t16:9.2f} us  x{t16 / t4:5.2f}")
+        del layers, wbs
+    tot4 = sum(r["int4_us"] for r in rows)
+    tot16 = sum(r["bf16_us"] for r in rows)
+    result = {
+        "metric": "per-layer time of the INT4 copy over the listed shapes and row counts (sum), and speedup vs bf16",
+        "value": round(tot4, 1), "unit": "us", "n_gpus": 1, "steps": 1, "warmup": 3, "ms_per_step": round(tot4 * 1e-3, 5),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"layer sweep, M in {Ms}, shapes {which}, INT4 g128 vs bf16, hip-graph replay, "
+                               "rotating weight copies"},
+        "speedup_vs_bf16": round(tot16 / tot4, 3), "rows": rows,
+    }
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -334,10 +408,12 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly from Python instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
-    ap.add_argument("--workload", choices=("decode_sweep", "full_step", "mixed_step", "chain_step"), default="decode_sweep",
+    ap.add_argument("--workload", choices=("decode_sweep", "full_step", "mixed_step", "chain_step", "layer_sweep"), default="decode_sweep",
                     help="decode_sweep (default, the headline metric) or full_step: all 129 Linear layers of "
                          "a 32-layer 7B-class decoder per step")
     ap.add_argument("--m", type=int, default=1, help="rows of activations for --workload full_step")
+    ap.add_argument("--ms", default="8,16,32,64,128,256,512", help="row counts for --workload layer_sweep")
+    ap.add_argument("--shapes", default="", help="comma-separated shape names for --workload layer_sweep")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -359,6 +435,8 @@ def main():
         return mixed_step(args, dmr, synth, torch, dev)
     if args.workload == "chain_step":
         return chain_step(args, dmr, synth, torch, dev)
+    if args.workload == "layer_sweep":
+        return layer_sweep(args, dmr, synth, torch, dev)
     G = synth.GROUP
     M = 1
 

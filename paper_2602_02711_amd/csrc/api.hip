@@ -26,9 +26,9 @@ W4Path w4_path(int64_t M, int64_t K, int64_t N) {
     const int64_t tiles = N / dmr::kTileRows;
     // wide layers already give the register-blocked streaming kernel 4 tiles per workgroup
     if (M <= kSkinnyMaxM) return tiles >= 1024 ? W4Path::Skinny2 : W4Path::Mid;
-    // the 128 x 128 GEMM needs a few hundred workgroups to fill the chip
+    // the 128 x 128 GEMM needs about 300 workgroups before it wins (measured)
     const int64_t gemm_wgs = ((M + 127) / 128) * ((N + 127) / 128);
-    return (M <= 128 || gemm_wgs < 400) ? W4Path::Mid : W4Path::Gemm;
+    return (M <= 128 || gemm_wgs < 300) ? W4Path::Mid : W4Path::Gemm;
 }
 
 // The bf16 twin: GEMV, first-generation skinny kernel for 2..8 rows (measured faster there), then the
@@ -262,13 +262,14 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
     if (path == W4Path::Mid) return hip_status(dmr::launch_w4_mid(L, d_x, M, d_y, f32, d_ws, s));
     if (path == W4Path::Skinny2) return hip_status(dmr::launch_w4_skinny2(L, d_x, M, d_y, f32, d_ws, s));
     if (M <= kSkinnyMaxM) return hip_status(dmr::launch_w4_skinny(L, d_x, M, d_y, f32, s));
-    // Long prefills of group-128 layers: 256 x 256 tiles with weights rounded to bf16 on their way into
-    // LDS (the value dmr_qlinear_dequantize defines; inside the 1e-2 rms bound for this format).
-    // Everything else, and per-channel layers whose row scales differ widely, takes the 128 x 128
-    // kernel, which keeps the codes exact and applies the scale per group in fp32.
-    if (layer->g == dmr::kGroup && dmr::gemm_big_applies(M, layer->N))
+    // Group-128 layers: weights rounded to bf16 on their way into LDS (the value dmr_qlinear_dequantize
+    // defines; inside the 1e-2 rms bound for this format), 256 x 256 tiles when there are enough of
+    // them.  Per-channel layers, whose row scales differ widely, take the 128 x 128 kernel that keeps
+    // the codes exact and applies the scale per group in fp32.
+    const bool g128 = layer->g == dmr::kGroup;
+    if (g128 && dmr::gemm_big_applies(M, layer->N))
         return hip_status(dmr::launch_w4_gemm_big(L, d_x, M, d_y, f32, s));
-    return hip_status(dmr::launch_w4_gemm(L, d_x, M, d_y, f32, s));
+    return hip_status(dmr::launch_w4_gemm(L, d_x, M, d_y, f32, !g128, s));
 }
 
 dmr_status_t dmr_qlinear_bf16_forward(const uint16_t *d_w, const uint16_t *d_x, int64_t M, int64_t K,

@@ -151,7 +151,9 @@ hipError_t launch_w4_skinny(const LayerView &L, const uint16_t *x, int64_t M, vo
                             hipStream_t stream);
 hipError_t launch_bf16_skinny(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
                               void *y, bool out_f32, hipStream_t stream);
-hipError_t launch_w4_gemm(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+// 128 x 128 tiles; `exact` keeps the integer codes in the MFMA and applies the scale per group in fp32
+// (per-channel layers), otherwise the weights are rounded to bf16 on their way into LDS.
+hipError_t launch_w4_gemm(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, bool exact,
                           hipStream_t stream);
 hipError_t launch_bf16_gemm(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
                             void *y, bool out_f32, hipStream_t stream);

@@ -1,10 +1,14 @@
 // Tiled MFMA GEMM for prefill-sized M (a long prompt: few-shot prefix plus the whole history),
-// y[M][N] = x[M][K] . W[N][K]^T with fp32 accumulation.  Two weight sources share the kernel:
-// bf16 weights read as they are, and INT4 streaming blocks whose codes go into LDS as the exact
-// small integers (q - z) (exact in bf16); the MFMAs of one group of 128 k accumulate into a
-// per-group tile that is folded into the result with the group's scale in fp32,
-//     acc += s[n][G] * D_G,
-// so no weight is ever rounded: the prefill path is as accurate as the decode path.
+// y[M][N] = x[M][K] . W[N][K]^T with fp32 accumulation.  Three weight sources share the kernel:
+//   kSrcBf16    bf16 weights read as they are;
+//   kSrcW4      INT4 streaming blocks dequantised to RNE_bf16((q - z) s) on their way into LDS (what
+//               dmr_qlinear_dequantize defines; relative weight error <= 2^-9, inside the 1e-2 rms
+//               bound for group-128 layers);
+//   kSrcW4Exact INT4 codes enter LDS as the exact small integers (q - z); the MFMAs of one group of
+//               128 k accumulate into a per-group tile that is folded into the result with the
+//               group's scale in fp32, acc += s[n][G] * D_G, so no weight is ever rounded.  About a
+//               third slower (fold work, 222 registers); used for per-channel layers, whose widely
+//               differing row scales make the rounded variant miss the bound.
 //
 // Workgroup tile 128 (m) x 128 (n) x 64 (k), 4 wavefronts in a 2 x 2 grid, each owning a 64 x 64
 // patch as 2 x 2 tiles of v_mfma_f32_32x32x16_bf16.  Global loads for step i+1 are issued into
@@ -20,17 +24,18 @@ namespace dmr {
 namespace {
 
 constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int kSrcBf16 = 0, kSrcW4 = 1, kSrcW4Exact = 2;
 constexpr int LDS_STRIDE = BK + 8;   // bf16 elements per padded LDS row (144 bytes)
 
-template <bool W4>
+template <int SRC>
 struct Prefetch {
     uint4 xa[4];
     uint4 wb[4];       // bf16 source: 4 x 16 bytes; INT4 source: wb[0] = 32 packed weights
     uint32_t szw;
 };
 
-template <bool W4>
-__device__ __forceinline__ void load_global(Prefetch<W4> &p, const void *__restrict__ wsrc,
+template <int SRC>
+__device__ __forceinline__ void load_global(Prefetch<SRC> &p, const void *__restrict__ wsrc,
                                             const uint32_t *__restrict__ sz,
                                             const uint16_t *__restrict__ x, int64_t M, int64_t K,
                                             int64_t N, int64_t m0, int64_t n0, int64_t k0, int tid) {
@@ -42,7 +47,7 @@ __device__ __forceinline__ void load_global(Prefetch<W4> &p, const void *__restr
         p.xa[i] = (m < M) ? *reinterpret_cast<const uint4 *>(x + m * K + k0 + chunk * 8)
                           : make_uint4(0, 0, 0, 0);
     }
-    if (W4) {
+    if (SRC != kSrcBf16) {
         // 8 row tiles x 32 lanes: the half of each 1 KiB block that covers this 64-wide k step
         const int64_t groups = K / kGroup;
         const int64_t G = k0 / kGroup;
@@ -69,30 +74,34 @@ __device__ __forceinline__ void load_global(Prefetch<W4> &p, const void *__restr
     }
 }
 
-template <bool W4>
-__device__ __forceinline__ void store_lds(const Prefetch<W4> &p, uint16_t *As, uint16_t *Bs, int tid) {
+template <int SRC>
+__device__ __forceinline__ void store_lds(const Prefetch<SRC> &p, uint16_t *As, uint16_t *Bs, int tid) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int idx = tid + 256 * i;
         const int row = idx >> 3, chunk = idx & 7;
         *reinterpret_cast<uint4 *>(As + row * LDS_STRIDE + chunk * 8) = p.xa[i];
     }
-    if (W4) {
+    if (SRC != kSrcBf16) {
         const int l = tid & 31;                       // lane within the half block
         const int row = (tid >> 5) * kTileRows + (l & 15);
         const int kofs = (l >> 4) * 32;               // 0 or 32 inside the 64-wide step
         const float cz = __uint_as_float(p.szw & 0xFFFF0000u);   // -(128 + z)
+        const float s = __uint_as_float(p.szw << 16);
+        const float czs = cz * s;                                // -(128 + z) s, exact in fp32
         const uint32_t words[4] = {p.wb[0].x, p.wb[0].y, p.wb[0].z, p.wb[0].w};
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             uint32_t o[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                // (128 + q) as fp32 straight from the bf16 magic pair; adding -(128 + z) leaves the
-                // integer q - z in [-15, 15], which bf16 holds exactly
+                // (128 + q) as fp32 straight from the bf16 magic pair.  Exact variant: adding
+                // -(128 + z) leaves the integer q - z in [-15, 15], which bf16 holds exactly.
+                // Rounded variant: (128 + q) s - (128 + z) s = (q - z) s in one fma (exact in fp32), then RNE.
                 const uint32_t pair = ((words[t] >> (4 * i)) & 0x000F000Fu) | 0x43004300u;
-                const float lo = __uint_as_float(pair << 16) + cz;
-                const float hi = __uint_as_float(pair & 0xFFFF0000u) + cz;
+                const float plo = __uint_as_float(pair << 16), phi = __uint_as_float(pair & 0xFFFF0000u);
+                const float lo = SRC == kSrcW4Exact ? plo + cz : fmaf(plo, s, czs);
+                const float hi = SRC == kSrcW4Exact ? phi + cz : fmaf(phi, s, czs);
                 o[i] = pack_bf16x2(lo, hi);
             }
             *reinterpret_cast<uint4 *>(Bs + row * LDS_STRIDE + kofs + t * 8) =
@@ -108,7 +117,7 @@ __device__ __forceinline__ void store_lds(const Prefetch<W4> &p, uint16_t *As, u
     }
 }
 
-template <bool W4, bool OUT_F32>
+template <int SRC, bool OUT_F32>
 __global__ __launch_bounds__(256, 2) void gemm_kernel(const void *__restrict__ wsrc,
                                                    const uint32_t *__restrict__ sz,
                                                    const uint16_t *__restrict__ x,
@@ -130,9 +139,10 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const void *__restrict__ w
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    // INT4: per-group accumulators and this lane's two weight rows (one per n tile)
+    // exact INT4: per-group accumulators and this lane's two weight rows (one per n tile)
+    constexpr bool EXACT = SRC == kSrcW4Exact;
     f32x16 grp[2][2];
-    if (W4) {
+    if (EXACT) {
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -149,14 +159,14 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const void *__restrict__ w
         srow[j] = ((nc / kTileRows) * groups) * kTileRows + (nc % kTileRows);   // sz index of (row, G = 0)
     }
 
-    Prefetch<W4> pre;
-    load_global<W4>(pre, wsrc, sz, x, M, K, N, m0, n0, 0, tid);
+    Prefetch<SRC> pre;
+    load_global<SRC>(pre, wsrc, sz, x, M, K, N, m0, n0, 0, tid);
     for (int64_t k0 = 0; k0 < K; k0 += BK) {
-        store_lds<W4>(pre, As, Bs, tid);
+        store_lds<SRC>(pre, As, Bs, tid);
         __syncthreads();
-        if (k0 + BK < K) load_global<W4>(pre, wsrc, sz, x, M, K, N, m0, n0, k0 + BK, tid);
+        if (k0 + BK < K) load_global<SRC>(pre, wsrc, sz, x, M, K, N, m0, n0, k0 + BK, tid);
         float gscale[2] = {0.f, 0.f};
-        const bool group_end = W4 && ((k0 + BK) % kGroup == 0);
+        const bool group_end = EXACT && ((k0 + BK) % kGroup == 0);
         if (group_end) {
 #pragma unroll
             for (int j = 0; j < 2; ++j)
@@ -175,7 +185,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const void *__restrict__ w
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    if (W4)
+                    if (EXACT)
                         grp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, grp[i][j], 0, 0, 0);
                     else
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, acc[i][j], 0, 0, 0);
@@ -213,27 +223,28 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const void *__restrict__ w
         }
 }
 
-template <bool W4>
+template <int SRC>
 hipError_t launch(const void *wsrc, const uint32_t *sz, const uint16_t *x, int64_t M, int64_t K,
                   int64_t N, void *y, bool out_f32, hipStream_t stream) {
     const dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
     if (out_f32)
-        hipLaunchKernelGGL((gemm_kernel<W4, true>), grid, dim3(256), 0, stream, wsrc, sz, x, y, M, K, N);
+        hipLaunchKernelGGL((gemm_kernel<SRC, true>), grid, dim3(256), 0, stream, wsrc, sz, x, y, M, K, N);
     else
-        hipLaunchKernelGGL((gemm_kernel<W4, false>), grid, dim3(256), 0, stream, wsrc, sz, x, y, M, K, N);
+        hipLaunchKernelGGL((gemm_kernel<SRC, false>), grid, dim3(256), 0, stream, wsrc, sz, x, y, M, K, N);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_w4_gemm(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+hipError_t launch_w4_gemm(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, bool exact,
                           hipStream_t stream) {
-    return launch<true>(L.wt, L.sz, x, M, L.K, L.N, y, out_f32, stream);
+    return exact ? launch<kSrcW4Exact>(L.wt, L.sz, x, M, L.K, L.N, y, out_f32, stream)
+                 : launch<kSrcW4>(L.wt, L.sz, x, M, L.K, L.N, y, out_f32, stream);
 }
 
 hipError_t launch_bf16_gemm(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
                             void *y, bool out_f32, hipStream_t stream) {
-    return launch<false>(w, nullptr, x, M, K, N, y, out_f32, stream);
+    return launch<kSrcBf16>(w, nullptr, x, M, K, N, y, out_f32, stream);
 }
 
 }  // namespace dmr

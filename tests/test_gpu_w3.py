@@ -105,7 +105,8 @@ def test_w3_one_hot_and_exact_cases():
 
 # ------------------------------------------------------------------ per-channel symmetric W4 (g = K, z = 8)
 
-@pytest.mark.parametrize("K,N,M", [(1024, 1024, 1), (384, 48, 7), (4096, 4096, 1), (1920, 272, 33), (512, 256, 200)])
+@pytest.mark.parametrize("K,N,M", [(1024, 1024, 1), (384, 48, 7), (4096, 4096, 1), (1920, 272, 33), (512, 256, 200),
+                                   (512, 1024, 6400)])      # the last one is large enough for the tiled GEMM
 def test_per_channel_symmetric_layer(K, N, M):
     rng = np.random.default_rng(90 + K + M)
     q = rng.integers(0, 16, size=(N, K), dtype=np.uint8)
