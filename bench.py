@@ -199,7 +199,7 @@ def chain_step(args, dmr, synth, torch, dev):
     columns of the qkv output stand in for its result, so that the shapes chain.  Timed four ways: the
     glue fused into the Linear launches (4 launches per layer) or as kernels of its own (rmsnorm x 2,
     swiglu, residual add x 2: 9 launches per layer), for the INT4 copy and for the bf16 copy."""
-    G, LAYERS, H, I = synth.GROUP, 32, 4096, 14336
+    G, LAYERS, H, I, M = synth.GROUP, 32, 4096, 14336, args.m
     gen = torch.Generator(device=dev)
     t0 = time.time()
     int4, bf16, gammas = [], [], []
@@ -217,13 +217,14 @@ def chain_step(args, dmr, synth, torch, dev):
         gen.manual_seed(synth.seed_for(4, 5, 0, layer=li))
         gammas.append((1.0 + 0.1 * torch.randn((2, H), generator=gen, device=dev)).to(torch.bfloat16))
     gen.manual_seed(synth.seed_for(4, 0, 1))
-    h0 = torch.randn((1, H), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
-    bufs = {"qkv": torch.empty((1, 6144), dtype=torch.bfloat16, device=dev),
-            "gu": torch.empty((1, 2 * I), dtype=torch.bfloat16, device=dev),
-            "act": torch.empty((1, I), dtype=torch.bfloat16, device=dev),
-            "norm": torch.empty((1, H), dtype=torch.bfloat16, device=dev),
-            "h": [torch.empty((1, H), dtype=torch.bfloat16, device=dev) for _ in range(3)],
-            "ws": torch.empty(1 << 20, dtype=torch.uint8, device=dev)}
+    h0 = torch.randn((M, H), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    bufs = {"qkv": torch.empty((M, 6144), dtype=torch.bfloat16, device=dev),
+            "q": torch.empty((M, H), dtype=torch.bfloat16, device=dev),
+            "gu": torch.empty((M, 2 * I), dtype=torch.bfloat16, device=dev),
+            "act": torch.empty((M, I), dtype=torch.bfloat16, device=dev),
+            "norm": torch.empty((M, H), dtype=torch.bfloat16, device=dev),
+            "h": [torch.empty((M, H), dtype=torch.bfloat16, device=dev) for _ in range(3)],
+            "ws": torch.empty(64 << 20, dtype=torch.uint8, device=dev)}
     torch.cuda.synchronize()
     log(f"[bench] 128 layers resident after {time.time() - t0:.1f}s")
     stream = torch.cuda.Stream()
@@ -267,7 +268,12 @@ def chain_step(args, dmr, synth, torch, dev):
                     out.add_(res)
 
             lin("qkv", R, h, g1, None, bufs["qkv"])
-            lin("attn_out", NONE, bufs["qkv"][:, :H], None, h, h1)      # attention stand-in: the q slice
+            if M == 1:
+                attn = bufs["qkv"][:, :H]                 # attention stand-in: the q slice (a view at M = 1)
+            else:
+                attn = bufs["q"]
+                attn.copy_(bufs["qkv"][:, :H])            # one strided copy per layer, in all four variants
+            lin("attn_out", NONE, attn, None, h, h1)
             lin("gate_up", R, h1, g2, None, bufs["gu"])
             lin("down", S, bufs["gu"], None, h1, h2)
             bufs["h"][0], bufs["h"][2] = h2, h
@@ -304,15 +310,15 @@ def chain_step(args, dmr, synth, torch, dev):
     drift1 = float((ref1 - got1).abs().max() / ref1.pow(2).mean().sqrt())
     drift = float((ref - got).abs().max() / ref.pow(2).mean().sqrt())
     times = {(low, fused): timed(low, fused) for low in (True, False) for fused in (True, False)}
-    b4 = LAYERS * sum(int4_bytes(K, N, 1) for _, K, N in synth.LAYER_SHAPES)
+    b4 = LAYERS * sum(int4_bytes(K, N, M) for _, K, N in synth.LAYER_SHAPES)
     t = times[(True, True)]
     result = {
         "metric": "dependent decode chain (Linear layers + fused glue) of the INT4 copy: us per step",
         "value": round(t * 1e3, 1), "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(t, 5), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "32 layers x (rmsnorm->qkv, attn_out+residual, rmsnorm->gate_up, swiglu->down+residual), "
-                               "M=1, attention replaced by the q slice, hip-graph replay"},
+        "config": {"workload": f"32 layers x (rmsnorm->qkv, attn_out+residual, rmsnorm->gate_up, swiglu->down+residual), "
+                               f"M={M}, attention replaced by the q slice, hip-graph replay"},
         "us_per_step": {"int4_fused": round(times[(True, True)] * 1e3, 1),
                         "int4_unfused": round(times[(True, False)] * 1e3, 1),
                         "bf16_fused": round(times[(False, True)] * 1e3, 1),
@@ -411,7 +417,7 @@ def main():
     ap.add_argument("--workload", choices=("decode_sweep", "full_step", "mixed_step", "chain_step", "layer_sweep"), default="decode_sweep",
                     help="decode_sweep (default, the headline metric) or full_step: all 129 Linear layers of "
                          "a 32-layer 7B-class decoder per step")
-    ap.add_argument("--m", type=int, default=1, help="rows of activations for --workload full_step")
+    ap.add_argument("--m", type=int, default=1, help="rows of activations for --workload full_step / chain_step")
     ap.add_argument("--ms", default="8,16,32,64,128,256,512", help="row counts for --workload layer_sweep")
     ap.add_argument("--shapes", default="", help="comma-separated shape names for --workload layer_sweep")
     args = ap.parse_args()

@@ -137,9 +137,10 @@ dmr_status_t dmr_glue_swiglu(const uint16_t *d_in, int64_t M, int64_t I, uint16_
  *             DMR_PRO_SWIGLU:  the layer runs on swiglu(d_in), d_in = [M][2 K]
  *             DMR_PRO_NONE:    d_in = [M][K] as in the plain forward
  *   epilogue  d_residual (bf16 [M][N]) or NULL: y = acc + residual in fp32, rounded once to `out`.
- * M = 1 fuses the prologue into the staging of the activation row and the residual into the
- * output store of the weight-streaming kernel; larger M runs the glue kernels into d_ws and then
- * the plain forward.  d_ws as the matching *_fused_workspace_bytes query says (never 0 with a
+ * M = 1 (both copies) fuses the prologue into the staging of the activation row and the residual
+ * into the output store of the weight-streaming kernel; 2 <= M <= 16 of the INT4 copy fuses the
+ * residual only (a prologue would be recomputed by every workgroup); anything else runs the glue
+ * kernels into d_ws and then the plain forward.  d_ws as the matching *_fused_workspace_bytes query says (never 0 with a
  * prologue or a residual).
  */
 typedef enum {

@@ -400,6 +400,28 @@ dmr_status_t dmr_qlinear_forward_fused(const dmr_qlinear_t *layer, dmr_prologue_
         const hipError_t e = dmr::launch_w4_gemv_fused(L, d_in, d_y, out == DMR_OUT_FP32, f, s);
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: shape outside the GEMV's range
     }
+    if (M >= 2 && M <= 16 && layer->bits == 4 && dmr::w4_stream_fits(M, layer->K, layer->N)) {
+        const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz};
+        dmr::Fusion f;
+        f.pro = (int)pro;
+        f.aux = d_gamma;
+        f.eps = eps;
+        f.res = d_residual;
+        const uint16_t *x = d_in;
+        // In this kernel every workgroup would recompute the prologue for all M rows, which measured
+        // slower than one launch of the stand-alone kernel: the prologue runs on its own, the residual
+        // stays fused.
+        if (pro != DMR_PRO_NONE) {
+            uint16_t *xg = static_cast<uint16_t *>(d_ws);
+            const hipError_t eg = pro == DMR_PRO_RMSNORM ? dmr::launch_rmsnorm(d_in, d_gamma, eps, M, layer->K, xg, s)
+                                                          : dmr::launch_swiglu(d_in, M, layer->K, xg, s);
+            if (eg != hipSuccess) return DMR_ERR_HIP;
+            x = xg;
+            f.pro = dmr::kProNone;
+        }
+        const hipError_t e = dmr::launch_w4_stream_fused(L, x, M, d_y, out == DMR_OUT_FP32, f, s);
+        if (e != hipErrorInvalidValue) return hip_status(e);
+    }
     return run_unfused(pro, d_in, d_gamma, eps, d_residual, M, layer->K, layer->N, d_y, out, d_ws, ws_bytes, s,
                        [&](const uint16_t *x, void *y, dmr_out_t o, void *ws, size_t wsb) {
                            return dmr_qlinear_forward(layer, x, M, y, o, ws, wsb, stream);

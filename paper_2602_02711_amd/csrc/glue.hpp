@@ -73,9 +73,12 @@ hipError_t launch_swiglu(const uint16_t *in, int64_t M, int64_t I, uint16_t *out
 hipError_t launch_add_residual(const float *acc, const uint16_t *res, int64_t count, void *out, bool out_f32,
                                hipStream_t stream);
 
-// M == 1 forwards with fused glue; hipErrorInvalidValue (nothing launched) for what they do not take.
+// Weight-streaming forwards with fused glue; hipErrorInvalidValue (nothing launched) for what they do not take.
 hipError_t launch_w4_gemv_fused(const LayerView &L, const uint16_t *x, void *y, bool out_f32, const Fusion &f,
                                 hipStream_t stream);
+// 2 <= M <= 16 with the rows whole in LDS.
+hipError_t launch_w4_stream_fused(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+                                  const Fusion &f, hipStream_t stream);
 hipError_t launch_bf16_gemv_fused(const uint16_t *w, const uint16_t *x, int64_t K, int64_t N, void *y, bool out_f32,
                                   const Fusion &f, hipStream_t stream);
 

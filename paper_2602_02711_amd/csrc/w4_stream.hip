@@ -10,9 +10,12 @@
 //     two barriers.  Every wave executes the same nT_max * GW_max item slots and therefore the same
 //     number of barriers whatever its share of the work: slots beyond a wave's work re-read its last
 //     block from cache and skip the arithmetic.
+// Of the decoder glue (glue.hpp) only the residual add is fused here (at the store).  A prologue
+// would be recomputed for all M rows by every workgroup, which measured slower than one launch of the
+// stand-alone RMSNorm / SwiGLU kernel from two rows on.
 #include <cstdlib>
 
-#include "common.hpp"
+#include "glue.hpp"
 
 namespace dmr {
 
@@ -36,7 +39,8 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
                                                          const uint16_t *__restrict__ x,
                                                          void *__restrict__ y, int M, int64_t N,
                                                          int groups, int tiles, int lgS, int lgTW,
-                                                         int nT_max, int gw_max, int out_f32) {
+                                                         int nT_max, int gw_max, int out_f32,
+                                                         const uint16_t *__restrict__ res) {
     extern __shared__ uint4 smem[];   // x rows [M][groups * 16 + 1] uint4, then red[TW][S][64] float4
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -75,6 +79,13 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
         for (int i = threadIdx.x; i < x16; i += blockDim.x)
             smem[r * row_stride + i] = reinterpret_cast<const uint4 *>(x)[(int64_t)r * x16 + i];
     __syncthreads();
+    auto store_out = [&](int64_t o, float v) {
+        if (res) v += __uint_as_float((uint32_t)res[o] << 16);
+        if (out_f32)
+            reinterpret_cast<float *>(y)[o] = v;
+        else
+            reinterpret_cast<uint16_t *>(y)[o] = f32_to_bf16(v);
+    };
 
     float *red = reinterpret_cast<float *>(smem + M * row_stride);
     const uint4 *xrow = smem + (j < M ? j : M - 1) * row_stride + c * 4;
@@ -112,13 +123,7 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int row = (lane >> 4) * 4 + r;
-                        if (row < M) {
-                            const int64_t o = (int64_t)row * N + (int64_t)tile * kTileRows + (lane & 15);
-                            if (out_f32)
-                                reinterpret_cast<float *>(y)[o] = acc[r];
-                            else
-                                reinterpret_cast<uint16_t *>(y)[o] = f32_to_bf16(acc[r]);
-                        }
+                        if (row < M) store_out((int64_t)row * N + (int64_t)tile * kTileRows + (lane & 15), acc[r]);
                     }
                 }
             } else {
@@ -138,13 +143,7 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
                             const int row = (lane >> 4) * 4 + r;
-                            if (row < M) {
-                                const int64_t o = (int64_t)row * N + (int64_t)t2 * kTileRows + (lane & 15);
-                                if (out_f32)
-                                    reinterpret_cast<float *>(y)[o] = v[r];
-                                else
-                                    reinterpret_cast<uint16_t *>(y)[o] = f32_to_bf16(v[r]);
-                            }
+                            if (row < M) store_out((int64_t)row * N + (int64_t)t2 * kTileRows + (lane & 15), v[r]);
                         }
                     }
                 }
@@ -192,7 +191,12 @@ bool w4_stream_fits(int64_t M, int64_t K, int64_t N) {
 
 hipError_t launch_w4_stream(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
                             hipStream_t stream) {
-    if (M < 2 || M > 16) return hipErrorInvalidValue;
+    return launch_w4_stream_fused(L, x, M, y, out_f32, Fusion{}, stream);
+}
+
+hipError_t launch_w4_stream_fused(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+                                  const Fusion &f, hipStream_t stream) {
+    if (M < 2 || M > 16 || f.pro != kProNone) return hipErrorInvalidValue;
     const int groups = (int)(L.K / kGroup);
     const int tiles = (int)(L.N / kTileRows);
     static int cus = 0;
@@ -274,7 +278,7 @@ hipError_t launch_w4_stream(const LayerView &L, const uint16_t *x, int64_t M, vo
             attr_set[PP] = true;                                                                        \
         }                                                                                               \
         hipLaunchKernelGGL((w4_stream_kernel<PP>), dim3(grid), dim3(nw * 64), lds, stream, L.wt, L.sz, x, y, \
-                           iM, L.N, groups, tiles, lgS, lgTW, nT_max, gw_max, of);                      \
+                           iM, L.N, groups, tiles, lgS, lgTW, nT_max, gw_max, of, f.res);                     \
     } break;
     switch (P) {
         DMR_STREAM_CASE(1) DMR_STREAM_CASE(2) DMR_STREAM_CASE(3) DMR_STREAM_CASE(4)

@@ -74,11 +74,11 @@ CASES = [(dmr.DMR_PRO_RMSNORM, 4096, 6144, False), (dmr.DMR_PRO_RMSNORM, 4096, 4
          (dmr.DMR_PRO_NONE, 4096, 4096, True), (dmr.DMR_PRO_RMSNORM, 1024, 1024, True)]
 
 
-@pytest.mark.parametrize("M", [1, 5, 40])
+@pytest.mark.parametrize("M", [1, 5, 16, 40])
 @pytest.mark.parametrize("pro,K,N,with_res", CASES)
 def test_fused_forward_int4(pro, K, N, with_res, M):
-    if M > 1 and K * N > 4096 * 6144:
-        pytest.skip("oracle cost: the large shapes are checked at M = 1")
+    if M > 5 and K * N > 4096 * 6144:
+        pytest.skip("oracle cost: the large shapes are checked at M <= 5")
     _, words, s, z = quantized(8200 + K + N, N, K)
     layer = dmr.dmr_qlinear_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
     width = 2 * K if pro == dmr.DMR_PRO_SWIGLU else K
@@ -98,17 +98,18 @@ def test_fused_forward_int4(pro, K, N, with_res, M):
     assert np.array_equal(y16, orc.f32_to_bf16(y32))          # bf16 output = one rounding of the same fp32 value
 
 
+@pytest.mark.parametrize("M", [1, 8])
 @pytest.mark.parametrize("pro,K,N,with_res", CASES)
-def test_fused_gemv_matches_unfused_composition(pro, K, N, with_res):
-    # M = 1: the fused kernel against glue kernel + plain forward + residual of the same library.  The sum
+def test_fused_kernels_match_unfused_composition(pro, K, N, with_res, M):
+    # The fused streaming kernels against glue kernel + plain forward + residual of the same library.  The sum
     # of squares is reduced in a different order, so a normalised activation may differ by one bf16 ulp;
     # the outputs must agree far below the parity tolerance.
     _, words, s, z = quantized(8300 + K + N, N, K)
     layer = dmr.dmr_qlinear_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
     width = 2 * K if pro == dmr.DMR_PRO_SWIGLU else K
-    inp = bf16_dev(synth.activations_bf16(8301 + K, 1, width))
+    inp = bf16_dev(synth.activations_bf16(8301 + K, M, width))
     gm = bf16_dev(gamma_bits(8302 + K, K))
-    res = bf16_dev(synth.activations_bf16(8303 + N, 1, N)) if with_res else None
+    res = bf16_dev(synth.activations_bf16(8303 + N, M, N)) if with_res else None
     fused = dmr.dmr_qlinear_forward_fused(layer, pro, inp, gamma=gm, eps=EPS, residual=res, out_dtype=torch.float32)
     x = inp
     if pro == dmr.DMR_PRO_RMSNORM:
