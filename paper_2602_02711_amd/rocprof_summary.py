@@ -30,7 +30,9 @@ def _one(directory, pattern):
 
 
 def short(name: str) -> str:
-    name = name.replace("void dmr::(anonymous namespace)::", "").replace("dmr::", "")
+    if name.startswith("void "):
+        name = name[5:]
+    name = name.replace("dmr::(anonymous namespace)::", "").replace("dmr::", "")
     return name.split("(")[0]
 
 
@@ -74,18 +76,20 @@ def main():
     ap.add_argument("--write-dir")
     ap.add_argument("--command", required=True, help="the full profiled command, for the record")
     ap.add_argument("--kernel", default="w4_gemv_kernel", help="substring naming the dominant kernel")
+    ap.add_argument("--title", default="decode GEMV sweep (bench.py)", help="what was profiled, for the heading")
     ap.add_argument("--out-md", required=True)
     ap.add_argument("--out-json")
     args = ap.parse_args()
 
     stats = trace_stats(args.trace_dir)
-    lines = ["# rocprofv3 summary: decode GEMV sweep (bench.py), MI355X", "",
+    lines = [f"# rocprofv3 summary: {args.title}, MI355X", "",
              "Commands (each its own run, from /tmp with TMPDIR=/tmp):", "", "```", args.command, "```", "",
              "## Kernel durations (--kernel-trace), microseconds", "",
              "| kernel | grid | wg | calls | mean | min | max |", "|---|---|---|---|---|---|---|"]
     dom_calls = dom_total = 0.0
     for (name, grid, wg), (n, mean, lo, hi) in sorted(stats.items(), key=lambda kv: -kv[1][0] * kv[1][1]):
-        if "gemv" in name or "skinny" in name or "gemm_kernel" in name:
+        if any(tag in name for tag in ("gemv", "skinny", "gemm", "mid_kernel", "stream", "splitk", "rmsnorm",
+                                       "swiglu", "residual", "xfrag")):
             lines.append(f"| {name} | {grid} | {wg} | {n} | {mean:.2f} | {lo:.2f} | {hi:.2f} |")
         if args.kernel in name:
             dom_calls += n
