@@ -71,7 +71,11 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
     int it = 0, ig = 0, issued = 0;
     Item ring[P];
     auto issue = [&](Item &dst) {
-        const int64_t block = (int64_t)(t_first + it * t_step) * groups + (g0 + ig);
+        // a wave without work (its first tile lies beyond the matrix) loads the last tile instead, so
+        // that the loads stay unconditional: a branch around them would make the compiler wait for
+        // all of them (vmcnt(0)) where only the activations are needed
+        const int tile = min(t_first + it * t_step, tiles - 1);
+        const int64_t block = (int64_t)tile * groups + (g0 + ig);
         dst.w = load_stream(wt + block * 64 + lane);
         dst.szw = load_stream(sz + block * kTileRows + j);
         if (issued + 1 < items) {
@@ -82,10 +86,8 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
             }
         }
     };
-    if (items > 0) {
 #pragma unroll
-        for (int p = 0; p < P; ++p) issue(ring[p]);
-    }
+    for (int p = 0; p < P; ++p) issue(ring[p]);
     float *xsum_lds = reinterpret_cast<float *>(smem + x16);                 // X[group]
     float *red = xsum_lds + ((groups + 3) & ~3);
     if (PRO == kProRmsNorm) {
