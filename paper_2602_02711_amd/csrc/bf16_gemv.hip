@@ -66,7 +66,7 @@ __global__ __launch_bounds__(kWaves * 64) void bf16_gemv_kernel(const uint16_t *
         float ss = 0.f;
 #pragma unroll
         for (int cidx = 0; cidx < XC; ++cidx) ss += sumsq_piece(xr[cidx]);     // zeros beyond K
-        const float scale = rms_scale(wave_sum(ss), 1.0f / (float)K, eps);
+        const float scale = rms_scale(wave64_sum(ss), 1.0f / (float)K, eps);
 #pragma unroll
         for (int cidx = 0; cidx < XC; ++cidx)
             xr[cidx] = rmsnorm_piece(xr[cidx], *reinterpret_cast<const uint4 *>(aux + koff[cidx]), scale);

@@ -2,9 +2,12 @@
 // and gate+up projections, SwiGLU before the down projection, the residual add after the attention
 // output and down projections).  The stand-alone kernels and the fused M == 1 prologues both call
 // these helpers, so that an element is computed the same way wherever it is computed:
-//   rmsnorm  RNE_bf16((x * scale) * gamma),  scale = 1 / sqrt(sum(x^2) / K + eps)   (0 for an all-zero row)
-//   swiglu   RNE_bf16((gate / (1 + exp(-gate))) * up)
-// in fp32.  A piece is 8 consecutive bf16 values (one 16-byte access).
+//   rmsnorm  RNE_bf16((x * scale) * gamma),  scale = rsq(sum(x^2) / K + eps)         (0 for an all-zero row)
+//   swiglu   RNE_bf16((gate * rcp(1 + exp(-gate))) * up)
+// in fp32, with the hardware's reciprocal, reciprocal square root and exp2 (about 1 ulp of fp32 each:
+// the result is rounded to bf16, 16 bits coarser, right after, and on the small decode layers the
+// prologue sits on the critical path, where the correctly rounded sequences cost about 1 us).
+// A piece is 8 consecutive bf16 values (one 16-byte access).
 #pragma once
 #include "common.hpp"
 
@@ -36,7 +39,17 @@ __device__ __forceinline__ float sumsq_piece(const uint4 &x) {
 
 __device__ __forceinline__ float rms_scale(float sumsq, float inv_k, float eps) {
     const float v = fmaf(sumsq, inv_k, eps);
-    return v > 0.f ? 1.0f / sqrtf(v) : 0.f;
+    return v > 0.f ? __builtin_amdgcn_rsqf(v) : 0.f;
+}
+
+// Sum over the 64 lanes of a wave, the same value in every lane: DPP row sums, then the four row sums
+// through scalar registers (no LDS round trip).
+__device__ __forceinline__ float wave64_sum(float v) {
+    v = row16_sum(v);
+    const int b = __float_as_int(v);
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(b, 0)), r1 = __int_as_float(__builtin_amdgcn_readlane(b, 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(b, 32)), r3 = __int_as_float(__builtin_amdgcn_readlane(b, 48));
+    return (r0 + r1) + (r2 + r3);
 }
 
 __device__ __forceinline__ uint4 rmsnorm_piece(const uint4 &x, const uint4 &gamma, float scale) {
@@ -51,7 +64,7 @@ __device__ __forceinline__ uint4 rmsnorm_piece(const uint4 &x, const uint4 &gamm
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
 
-__device__ __forceinline__ float silu(float a) { return a / (1.0f + expf(-a)); }
+__device__ __forceinline__ float silu(float a) { return a * __builtin_amdgcn_rcpf(1.0f + __expf(-a)); }
 
 __device__ __forceinline__ uint4 swiglu_piece(const uint4 &gate, const uint4 &up) {
     const uint32_t g[4] = {gate.x, gate.y, gate.z, gate.w}, u[4] = {up.x, up.y, up.z, up.w};

@@ -18,9 +18,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint16_t *__restrict
     const int pieces = (int)(K / 8);
     float ss = 0.f;
     for (int i = threadIdx.x; i < pieces; i += 256) ss += sumsq_piece(src[i]);
-    ss = row16_sum(ss);
-    ss += __shfl_xor(ss, 16, 64);
-    ss += __shfl_xor(ss, 32, 64);
+    ss = wave64_sum(ss);
     if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
     __syncthreads();
     const float scale = rms_scale((part[0] + part[1]) + (part[2] + part[3]), 1.0f / (float)K, eps);

@@ -97,14 +97,12 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
 #pragma unroll
         for (int u = 0; u < XL; ++u)
             if ((int)threadIdx.x + u * (int)blockDim.x < x16) ss += sumsq_piece(xreg[u]);
-        ss = row16_sum(ss);
-        ss += __shfl_xor(ss, 16, 64);
-        ss += __shfl_xor(ss, 32, 64);
+        ss = wave64_sum(ss);
         if (lane == 0) part[wave] = ss;
         __syncthreads();
-        float total = 0.f;
+        // every wave adds the (at most 16) wave sums in the same DPP tree
         const int nw = (int)blockDim.x >> 6;
-        for (int q = 0; q < nw; ++q) total += part[q];          // same order in every thread
+        const float total = row16_sum(j < nw ? part[j] : 0.f);
         const float scale = rms_scale(total, 1.0f / (float)(groups * kGroup), eps);
 #pragma unroll
         for (int u = 0; u < XL; ++u) xreg[u] = rmsnorm_piece(xreg[u], xaux[u], scale);
