@@ -33,6 +33,26 @@ struct Item {
     uint32_t szw;
 };
 
+// Copy `total` 16-byte pieces of x into LDS, piece p to slot p + p / x16 (rows padded by one piece; the
+// division by multiplication with ceil(2^32 / x16)), B loads in flight per thread.  (Plain vector
+// type for the staging registers: an array of HIP's uint4 struct ends up in scratch memory.)
+template <int B>
+__device__ __forceinline__ void stage_rows(const uint16_t *__restrict__ x, uint4 *smem, int total,
+                                           uint32_t x16_magic) {
+    const int T = (int)blockDim.x;
+    for (int base = (int)threadIdx.x; base < total; base += B * T) {
+        u32x4_t v[B];
+#pragma unroll
+        for (int u = 0; u < B; ++u)
+            v[u] = reinterpret_cast<const u32x4_t *>(x)[min(base + u * T, total - 1)];
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+            const int p = base + u * T;
+            if (p < total) reinterpret_cast<u32x4_t *>(smem)[p + (int)__umulhi((uint32_t)p, x16_magic)] = v[u];
+        }
+    }
+}
+
 template <int P>
 __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict__ wt,
                                                          const uint32_t *__restrict__ sz,
@@ -40,7 +60,7 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
                                                          void *__restrict__ y, int M, int64_t N,
                                                          int groups, int tiles, int lgS, int lgTW,
                                                          int nT_max, int gw_max, int out_f32,
-                                                         const uint16_t *__restrict__ res) {
+                                                         const uint16_t *__restrict__ res, uint32_t x16_magic) {
     extern __shared__ uint4 smem[];   // x rows [M][groups * 16 + 1] uint4, then red[TW][S][64] float4
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -74,10 +94,17 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
 #pragma unroll
     for (int p = 0; p < P; ++p) issue(ring[p]);
 
-    // stage the M activation rows
-    for (int r = 0; r < M; ++r)
-        for (int i = threadIdx.x; i < x16; i += blockDim.x)
-            smem[r * row_stride + i] = reinterpret_cast<const uint4 *>(x)[(int64_t)r * x16 + i];
+    // Stage the M activation rows: x is one contiguous run of M * x16 pieces; piece p of row
+    // r = p / x16 (by multiplication with ceil(2^32 / x16), exact in this range) lands at p + r because
+    // rows are padded by one piece.  Up to eight loads are issued before the first store, so that a
+    // thread pays the memory latency once per batch and not once per piece.
+    {
+        const int total = M * x16;
+        if (total <= 2 * (int)blockDim.x)
+            stage_rows<2>(x, smem, total, x16_magic);      // a few rows: no point in six padding loads
+        else
+            stage_rows<8>(x, smem, total, x16_magic);
+    }
     __syncthreads();
     auto store_out = [&](int64_t o, float v) {
         if (res) v += __uint_as_float((uint32_t)res[o] << 16);
@@ -268,6 +295,7 @@ hipError_t launch_w4_stream_fused(const LayerView &L, const uint16_t *x, int64_t
     if (P > slots) P = slots;
     const int of = out_f32 ? 1 : 0;
     const int iM = (int)M;
+    const uint32_t x16_magic = (uint32_t)(((uint64_t(1) << 32) + (uint64_t)groups * 16 - 1) / ((uint64_t)groups * 16));
     static bool attr_set[9] = {false, false, false, false, false, false, false, false, false};
 #define DMR_STREAM_CASE(PP)                                                                             \
     case PP: {                                                                                          \
@@ -278,7 +306,7 @@ hipError_t launch_w4_stream_fused(const LayerView &L, const uint16_t *x, int64_t
             attr_set[PP] = true;                                                                        \
         }                                                                                               \
         hipLaunchKernelGGL((w4_stream_kernel<PP>), dim3(grid), dim3(nw * 64), lds, stream, L.wt, L.sz, x, y, \
-                           iM, L.N, groups, tiles, lgS, lgTW, nT_max, gw_max, of, f.res);                     \
+                           iM, L.N, groups, tiles, lgS, lgTW, nT_max, gw_max, of, f.res, x16_magic);          \
     } break;
     switch (P) {
         DMR_STREAM_CASE(1) DMR_STREAM_CASE(2) DMR_STREAM_CASE(3) DMR_STREAM_CASE(4)
