@@ -3,6 +3,7 @@
 #include <new>
 
 #include "glue.hpp"
+#include "panel_plan.hpp"
 
 struct dmr_qlinear {
     int64_t K, N;
@@ -19,10 +20,14 @@ constexpr int64_t kSkinnyMaxM = 64;
 
 // Which INT4 kernel serves M rows of a (K, N) layer (measured crossovers, 256 CUs).  The workspace
 // query and the forward call both go through this.
-enum class W4Path { Gemv, Stream, Skinny2, Mid, Gemm };
+enum class W4Path { Gemv, Stream, Panel, Skinny2, Mid, Gemm };
 W4Path w4_path(int64_t M, int64_t K, int64_t N) {
     if (M == 1) return W4Path::Gemv;
-    if (M <= 16) return dmr::w4_stream_fits(M, K, N) ? W4Path::Stream : W4Path::Mid;
+    if (M <= 16) {
+        if (dmr::w4_stream_fits(M, K, N)) return W4Path::Stream;
+        // long rows: k-sliced panels of x in LDS (measured 10-15 % ahead of the rollout-batch kernel)
+        return dmr::w4_panel_applies(M, K, N) ? W4Path::Panel : W4Path::Mid;
+    }
     const int64_t tiles = N / dmr::kTileRows;
     // wide layers already give the register-blocked streaming kernel 4 tiles per workgroup
     if (M <= kSkinnyMaxM) return tiles >= 1024 ? W4Path::Skinny2 : W4Path::Mid;
@@ -79,6 +84,7 @@ size_t dmr_qlinear_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     if (M <= 0 || K <= 0 || K % dmr::kGroup != 0 || N <= 0 || N % dmr::kTileRows != 0) return 0;
     switch (w4_path(M, K, N)) {
         case W4Path::Mid: return dmr::w4_mid_workspace_bytes(M, K, N);    // fp32 partials when K is split
+        case W4Path::Panel: return dmr::w4_panel_workspace_bytes(M, K, N);    // likewise
         case W4Path::Skinny2: return dmr::w4_skinny2_workspace_bytes(M, K);   // re-ordered activations
         default: return 0;
     }
@@ -259,6 +265,7 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
         const hipError_t e = dmr::launch_w4_stream(L, d_x, M, d_y, f32, s);
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: activations do not fit LDS
     }
+    if (path == W4Path::Panel) return hip_status(dmr::launch_w4_panel(L, d_x, M, d_y, f32, d_ws, s));
     if (path == W4Path::Mid) return hip_status(dmr::launch_w4_mid(L, d_x, M, d_y, f32, d_ws, s));
     if (path == W4Path::Skinny2) return hip_status(dmr::launch_w4_skinny2(L, d_x, M, d_y, f32, d_ws, s));
     if (M <= kSkinnyMaxM) return hip_status(dmr::launch_w4_skinny(L, d_x, M, d_y, f32, s));

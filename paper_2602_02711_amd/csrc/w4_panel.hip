@@ -1,0 +1,269 @@
+// W4A16 panel kernel for 2 <= M <= 16 rows of a layer whose activations do not fit LDS as a whole
+// (K = 14336 from five rows on).
+//
+// A workgroup owns TW * R weight tiles (16 rows each) and one slice of gq groups along k.  It stages
+// the M x (128 gq) panel of x in LDS once (rows padded by 16 bytes, as in the M <= 16 streaming
+// kernel), then its WAVES = S * TW wavefronts stream their weight blocks straight from HBM into
+// registers (ring of four outstanding items, an item = the R blocks of one group) with no barrier in
+// the loop: wave (s, tw) walks sub-slice s of the k slice for tiles (blockIdx.x * TW + tw) * R + r.
+// Differences from the kernels around it:
+//   - the group sums of x (the zero-point term needs sum_k x over each group) are formed once per
+//     workgroup, by one pass of MFMAs against all-ones right after the staging, and kept in LDS as a
+//     table [group][row tile][4 row quads] of fp32x4; the main loop spends its MFMAs on weights only;
+//   - an activation fragment read from LDS feeds R weight tiles (half the LDS traffic at R = 2);
+//   - K may be split over blockIdx.y, fp32 partials [split][M][N] added by the shared reduction kernel
+//     in ascending order; the S sub-slices inside a workgroup are added through LDS (the panel's
+//     memory, reused after a barrier) in ascending order as well.  Results do not depend on timing.
+#include "panel_plan.hpp"
+
+namespace dmr {
+
+namespace {
+
+constexpr uint32_t kOnes = 0x3F803F80u;    // bf16 pair (1.0, 1.0)
+
+template <int R>
+struct PanelItem {
+    u32x4_t w[R];
+    uint32_t szw[R];
+};
+
+// Copy the M x x16 pieces (16 bytes each) of the k slice starting at column k0 of x[M][K] into LDS,
+// piece (row, col) to slot row * (x16 + 1) + col; B loads in flight per thread.
+template <int B>
+__device__ __forceinline__ void stage_panel(const uint16_t *__restrict__ x, uint4 *smem, int M, int64_t K,
+                                            int64_t k0, int x16, uint32_t x16_magic) {
+    const int T = (int)blockDim.x;
+    const int total = M * x16;
+    for (int base = (int)threadIdx.x; base < total; base += B * T) {
+        u32x4_t v[B];
+        int slot[B];
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+            const int p = min(base + u * T, total - 1);
+            const int row = (int)__umulhi((uint32_t)p, x16_magic);
+            const int col = p - row * x16;
+            slot[u] = p + row;
+            v[u] = *reinterpret_cast<const u32x4_t *>(x + (int64_t)row * K + k0 + col * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < B; ++u)
+            if (base + u * T < total) reinterpret_cast<u32x4_t *>(smem)[slot[u]] = v[u];
+    }
+}
+
+// out_mode: 0 = fp32 y, 1 = bf16 y, 2 = fp32 partial [split][M][N]
+template <int MT, int R, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void w4_panel_kernel(const uint4 *__restrict__ wt,
+                                                              const uint32_t *__restrict__ sz,
+                                                              const uint16_t *__restrict__ x,
+                                                              void *__restrict__ y, int M, int64_t K, int64_t N,
+                                                              int groups, int tiles, int gq, int lgS,
+                                                              int out_mode, uint32_t x16_magic) {
+    extern __shared__ uint4 smem[];   // panel [M][gq * 16 + 1] uint4, then xs [gq][MT][4] f32x4
+    constexpr int P = 4;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int S = 1 << lgS, TW = WAVES >> lgS;
+    const int s = wave & (S - 1), tw = wave >> lgS;
+    const int c = lane >> 4, j = lane & 15;
+    const int ga = (int)blockIdx.y * gq;                           // first group of this k slice
+    const int gl0 = (gq * s) >> lgS;                               // this wave's sub-slice, slice-local
+    const int GW = ((gq * (s + 1)) >> lgS) - gl0;                  // >= 1 (S <= gq)
+    const int tile0 = ((int)blockIdx.x * TW + tw) * R;
+    const int x16 = gq * 16, row_stride = x16 + 1;
+
+    // weight stream: unconditional, clamped loads (a tile past the end re-reads the last tile, an item
+    // past the sub-slice its last group)
+    PanelItem<R> ring[P];
+    auto issue = [&](PanelItem<R> &dst, int i) {
+        const int g = ga + gl0 + (i < GW ? i : GW - 1);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int tile = min(tile0 + r, tiles - 1);
+            const int64_t block = (int64_t)tile * groups + g;
+            dst.w[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(wt + block * 64 + lane));
+            dst.szw[r] = load_stream(sz + block * kTileRows + j);
+        }
+    };
+#pragma unroll
+    for (int p = 0; p < P; ++p) issue(ring[p], p);
+
+    {
+        const int total = M * x16;
+        if (total <= 2 * (int)blockDim.x)
+            stage_panel<2>(x, smem, M, K, (int64_t)ga * kGroup, x16, x16_magic);
+        else
+            stage_panel<8>(x, smem, M, K, (int64_t)ga * kGroup, x16, x16_magic);
+    }
+    __syncthreads();
+
+    // group sums of x: unit u = (group, row tile) -> D = A . ones, every column of D the row sums
+    f32x4 *xs = reinterpret_cast<f32x4 *>(smem + M * row_stride);
+    {
+        Frag ones;
+        ones.u = make_uint4(kOnes, kOnes, kOnes, kOnes);
+        for (int u = wave; u < gq * MT; u += WAVES) {
+            const int gl = u / MT, mt = u - gl * MT;
+            const int row = min(mt * 16 + j, M - 1);
+            const uint4 *xp = smem + row * row_stride + gl * 16 + c * 4;
+            f32x4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                Frag a;
+                a.u = xp[t];
+                d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, ones.v, d, 0, 0, 0);
+            }
+            if (j == 0) xs[u * 4 + c] = d;
+        }
+    }
+    __syncthreads();
+
+    const uint4 *xrow[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) xrow[mt] = smem + min(mt * 16 + j, M - 1) * row_stride + c * 4;
+
+    f32x4 acc[R][MT];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[r][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto consume = [&](const PanelItem<R> &cur, int i) {
+        const int gl = gl0 + i;
+        f32x4 d[R][MT];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) d[r][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            Frag a[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) a[mt].u = xrow[mt][gl * 16 + t];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                Frag b;
+                unpack_word(cur.w[r][t], b.w);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    d[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mt].v, b.v, d[r][mt], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const f32x4 xsum = xs[(gl * MT + mt) * 4 + c];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const float sc = __uint_as_float(cur.szw[r] << 16);
+                const float cz = __uint_as_float(cur.szw[r] & 0xFFFF0000u);   // -(128 + z)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[r][mt][q] = fmaf(sc, fmaf(cz, xsum[q], d[r][mt][q]), acc[r][mt][q]);
+            }
+        }
+    };
+
+    int base = 0;
+    for (; base + P <= GW; base += P) {
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const PanelItem<R> cur = ring[p];
+            issue(ring[p], base + p + P);
+            consume(cur, base + p);
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < P - 1; ++p)
+        if (base + p < GW) consume(ring[p], base + p);
+
+    const int64_t part = out_mode == 2 ? (int64_t)blockIdx.y * M * N : 0;
+    auto store_tile = [&](int tile, int mt, const f32x4 &v) {
+        if (tile >= tiles) return;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int row = mt * 16 + c * 4 + q;
+            if (row < M) {
+                const int64_t o = (int64_t)row * N + (int64_t)tile * kTileRows + j;
+                if (out_mode == 1)
+                    reinterpret_cast<uint16_t *>(y)[o] = f32_to_bf16(v[q]);
+                else
+                    reinterpret_cast<float *>(y)[part + o] = v[q];
+            }
+        }
+    };
+
+    if (lgS == 0) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) store_tile(tile0 + r, mt, acc[r][mt]);
+        return;
+    }
+    // cross-slice sum: red[tw][r][mt][s][64] f32x4 in the panel's memory
+    __syncthreads();   // every wave has finished reading the panel and the sums
+    f32x4 *red = reinterpret_cast<f32x4 *>(smem);
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) red[((((tw * R + r) * MT + mt) << lgS) + s) * 64 + lane] = acc[r][mt];
+    __syncthreads();
+    for (int u = wave; u < TW * R * MT; u += WAVES) {
+        const f32x4 *src = red + ((u << lgS) * 64 + lane);
+        f32x4 v = src[0];
+        for (int q = 1; q < S; ++q) {
+            const f32x4 w2 = src[q * 64];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += w2[e];
+        }
+        const int mt = u % MT, tr = u / MT;                 // tr = tw * R + r
+        store_tile((int)blockIdx.x * TW * R + tr, mt, v);
+    }
+}
+
+template <int MT, int R, int WAVES>
+hipError_t launch_cfg(const LayerView &L, const uint16_t *x, int M, void *dst, int out_mode, const PanelPlan &p,
+                      hipStream_t stream) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_panel_kernel<MT, R, WAVES>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int groups = (int)(L.K / kGroup), tiles = (int)(L.N / kTileRows);
+    const int TW = WAVES / p.S;
+    int lgS = 0;
+    while ((1 << lgS) < p.S) ++lgS;
+    const uint32_t x16_magic = (uint32_t)(((uint64_t(1) << 32) + (uint64_t)p.gq * 16 - 1) / ((uint64_t)p.gq * 16));
+    const dim3 grid((unsigned)((tiles + TW * R - 1) / (TW * R)), (unsigned)p.SK);
+    hipLaunchKernelGGL((w4_panel_kernel<MT, R, WAVES>), grid, dim3(64 * WAVES), p.lds, stream, L.wt, L.sz, x, dst, M,
+                       L.K, L.N, groups, tiles, p.gq, lgS, out_mode, x16_magic);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+size_t w4_panel_workspace_bytes(int64_t M, int64_t K, int64_t N) {
+    const PanelPlan p = plan_panel(M, K, N);
+    return (p.ok && p.SK > 1) ? (size_t)p.SK * (size_t)M * (size_t)N * sizeof(float) : 0;
+}
+
+bool w4_panel_applies(int64_t M, int64_t K, int64_t N) { return plan_panel(M, K, N).ok; }
+
+hipError_t launch_w4_panel(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
+                           hipStream_t stream) {
+    const PanelPlan p = plan_panel(M, L.K, L.N);
+    if (!p.ok) return hipErrorInvalidValue;
+    const bool split = p.SK > 1;
+    if (split && !ws) return hipErrorInvalidValue;
+    void *dst = split ? ws : y;
+    const int out_mode = split ? 2 : (out_f32 ? 0 : 1);
+    // the planner only produces one tile per wave in 16-wave workgroups; the kernel itself is written
+    // for MT row tiles x R weight tiles per wave (MT * R <= 2 fits the 128 registers of 16 waves)
+    if (p.MT != 1 || p.R != 1 || p.WAVES != 16) return hipErrorInvalidValue;
+    const hipError_t e = launch_cfg<1, 1, 16>(L, x, (int)M, dst, out_mode, p, stream);
+    if (e != hipSuccess || !split) return e;
+    return launch_splitk_reduce(static_cast<const float *>(ws), y, M * L.N, p.SK, out_f32, stream);
+}
+
+}  // namespace dmr

@@ -43,7 +43,7 @@ def test_size_queries(lib):
     assert lib.dmr_qlinear_workspace_bytes(64, 4096, 4096) == 4 * 64 * 4096 * 4
     assert lib.dmr_qlinear_workspace_bytes(17, 4096, 4096) == 4 * 17 * 4096 * 4
     assert lib.dmr_qlinear_workspace_bytes(65, 4096, 4096) == 4 * 65 * 4096 * 4
-    assert lib.dmr_qlinear_workspace_bytes(8, 14336, 4096) == 8 * 8 * 4096 * 4    # rows exceed LDS
+    assert lib.dmr_qlinear_workspace_bytes(8, 14336, 4096) == 4 * 8 * 4096 * 4    # rows exceed LDS: four k slices
     # enough column blocks: no split; large M: the tiled GEMM
     assert lib.dmr_qlinear_workspace_bytes(128, 4096, 28672) == 0
     assert lib.dmr_qlinear_workspace_bytes(600, 4096, 28672) == 0

@@ -93,7 +93,8 @@ def test_forward_small_shape_all_skinny_m(M):
 
 @pytest.mark.parametrize("K,N,M", [(128, 16, 1), (384, 48, 7), (1920, 272, 20), (640, 16, 64), (256, 4112, 3),
                                    (1920, 272, 7), (128, 16, 16), (4096, 4112, 16), (14336, 528, 4),
-                                   (14336, 528, 5), (1920, 8208, 2)])
+                                   (14336, 528, 5), (1920, 8208, 2), (14336, 528, 16), (14336, 272, 9),
+                                   (7168, 1040, 13), (14464, 64, 16)])
 def test_forward_ragged_shapes(K, N, M):
     _, words, s, z = quantized(3000 + K + N, N, K)
     x = synth.activations_bf16(3001 + K + N, M, K)
