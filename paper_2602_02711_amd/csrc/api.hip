@@ -4,6 +4,7 @@
 
 #include "glue.hpp"
 #include "panel_plan.hpp"
+#include "wide_plan.hpp"
 
 struct dmr_qlinear {
     int64_t K, N;
@@ -20,7 +21,7 @@ constexpr int64_t kSkinnyMaxM = 64;
 
 // Which INT4 kernel serves M rows of a (K, N) layer (measured crossovers, 256 CUs).  The workspace
 // query and the forward call both go through this.
-enum class W4Path { Gemv, Stream, Panel, Skinny2, Mid, Gemm };
+enum class W4Path { Gemv, Stream, Panel, Wide, Skinny2, Mid, Gemm };
 W4Path w4_path(int64_t M, int64_t K, int64_t N) {
     if (M == 1) return W4Path::Gemv;
     if (M <= 16) {
@@ -28,6 +29,7 @@ W4Path w4_path(int64_t M, int64_t K, int64_t N) {
         // long rows: k-sliced panels of x in LDS (measured 10-15 % ahead of the rollout-batch kernel)
         return dmr::w4_panel_applies(M, K, N) ? W4Path::Panel : W4Path::Mid;
     }
+    if (M <= kSkinnyMaxM && dmr::w4_wide_applies(M, K, N)) return W4Path::Wide;
     const int64_t tiles = N / dmr::kTileRows;
     // wide layers already give the register-blocked streaming kernel 4 tiles per workgroup
     if (M <= kSkinnyMaxM) return tiles >= 1024 ? W4Path::Skinny2 : W4Path::Mid;
@@ -266,6 +268,7 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: activations do not fit LDS
     }
     if (path == W4Path::Panel) return hip_status(dmr::launch_w4_panel(L, d_x, M, d_y, f32, d_ws, s));
+    if (path == W4Path::Wide) return hip_status(dmr::launch_w4_wide(L, d_x, M, d_y, f32, s));
     if (path == W4Path::Mid) return hip_status(dmr::launch_w4_mid(L, d_x, M, d_y, f32, d_ws, s));
     if (path == W4Path::Skinny2) return hip_status(dmr::launch_w4_skinny2(L, d_x, M, d_y, f32, d_ws, s));
     if (M <= kSkinnyMaxM) return hip_status(dmr::launch_w4_skinny(L, d_x, M, d_y, f32, s));

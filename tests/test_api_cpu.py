@@ -35,10 +35,11 @@ def test_size_queries(lib):
     assert lib.dmr_qlinear_storage_bytes(1024, 1024, 64) == 0
     assert lib.dmr_qlinear_workspace_bytes(1, 4096, 4096) == 0
     assert lib.dmr_qlinear_workspace_bytes(16, 4096, 4096) == 0
-    # 16 < M <= 64 on a wide layer: activations in MFMA operand order (4 KiB per group and row tile)
-    # plus their group sums
-    assert lib.dmr_qlinear_workspace_bytes(64, 4096, 28672) == 32 * 4 * (4096 + 64)
-    assert lib.dmr_qlinear_workspace_bytes(17, 4096, 28672) == 32 * 2 * (4096 + 64)
+    # 16 < M <= 64 on a wide layer: activation panels in LDS, no workspace; when the group count is not a
+    # multiple of four: activations in MFMA operand order (4 KiB per group and row tile) plus their group sums
+    assert lib.dmr_qlinear_workspace_bytes(64, 4096, 28672) == 0
+    assert lib.dmr_qlinear_workspace_bytes(17, 4096, 28672) == 0
+    assert lib.dmr_qlinear_workspace_bytes(64, 4224, 28672) == 33 * 4 * (4096 + 64)
     # rollout batches on layers too small to fill the chip: fp32 partials of a 4-way (8-way) split of K
     assert lib.dmr_qlinear_workspace_bytes(64, 4096, 4096) == 4 * 64 * 4096 * 4
     assert lib.dmr_qlinear_workspace_bytes(17, 4096, 4096) == 4 * 17 * 4096 * 4

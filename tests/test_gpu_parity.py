@@ -224,6 +224,19 @@ def test_forward_rollout_batch_sizes(K, N, M):
     check_forward(y32, y16, y_ref, f"rollout batch ({K},{N}) M={M}")
 
 
+@pytest.mark.parametrize("K,N,M", [(512, 16400, 17), (1536, 16400, 33), (1024, 16512, 48), (1536, 16528, 64),
+                                   (2560, 16384, 20), (640, 16400, 40)])
+def test_forward_wide_layers_small_batches(K, N, M):
+    # 17 <= M <= 64 on layers of >= 1024 weight tiles: chunked activation panels in LDS (one chunk, an odd
+    # and an even number of chunks), 2..4 row tiles with a ragged last one, a ragged last column block; five
+    # groups (not a multiple of the chunk): the pre-pass kernel that re-orders the activations in memory
+    _, words, s, z = quantized(7500 + K + N + M, N, K)
+    x = synth.activations_bf16(7501 + K + N + M, M, K)
+    y32, y16 = forward_both(make_layer(words, s, z), x)
+    y_ref, _ = orc.forward(words, s, z, G, x, threads=THREADS)
+    check_forward(y32, y16, y_ref, f"wide layer ({K},{N}) M={M}")
+
+
 @pytest.mark.parametrize("idx,M", [(1, 512), (2, 2048), (3, 2048), (0, 8192)])
 def test_prefill_sampled_outputs_at_full_size(idx, M):
     name, K, N = synth.SWEEP_SHAPES[idx]
