@@ -38,11 +38,14 @@ W4Path w4_path(int64_t M, int64_t K, int64_t N) {
     return (M <= 128 || gemm_wgs < 300) ? W4Path::Mid : W4Path::Gemm;
 }
 
-// The bf16 twin: GEMV, first-generation skinny kernel for 2..8 rows (measured faster there), then the
-// same size classes as INT4.
-enum class Bf16Path { Gemv, Skinny, Mid, GemmBig, Gemm };
-Bf16Path bf16_path(int64_t M, int64_t N) {
+// The bf16 twin: GEMV, the direct-from-L2 skinny kernel for 2..8 rows (measured faster there than the
+// LDS-staged kernels), then the same size classes as INT4.
+enum class Bf16Path { Gemv, Stream, Skinny, Mid, GemmBig, Gemm };
+Bf16Path bf16_path(int64_t M, int64_t K, int64_t N) {
     if (M == 1) return Bf16Path::Gemv;
+    // the streaming kernel wins (by ~12 %) only for 9..16 rows of the widest layers; below that the
+    // direct-from-L2 kernel, elsewhere the rollout-batch kernel measured faster
+    if (M > 8 && M <= 16 && N / dmr::kTileRows >= 1024 && dmr::bf16_stream_fits(M, K, N)) return Bf16Path::Stream;
     if (M <= 8) return Bf16Path::Skinny;
     // measured crossover: the tiled kernels win once they have more than ~128 workgroups
     const int64_t gemm_wgs = ((M + 127) / 128) * ((N + 127) / 128);
@@ -94,7 +97,7 @@ size_t dmr_qlinear_workspace_bytes(int64_t M, int64_t K, int64_t N) {
 
 size_t dmr_qlinear_bf16_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     if (M <= 0 || K <= 0 || K % dmr::kGroup != 0 || N <= 0 || N % dmr::kTileRows != 0) return 0;
-    return bf16_path(M, N) == Bf16Path::Mid ? dmr::bf16_mid_workspace_bytes(M, K, N) : 0;
+    return bf16_path(M, K, N) == Bf16Path::Mid ? dmr::bf16_mid_workspace_bytes(M, K, N) : 0;
 }
 
 dmr_status_t dmr_qlinear_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32_t g,
@@ -297,13 +300,14 @@ dmr_status_t dmr_qlinear_bf16_forward(const uint16_t *d_w, const uint16_t *d_x, 
     if (need > 0 && (!d_ws || ws_bytes < need)) return DMR_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool f32 = out == DMR_OUT_FP32;
-    const Bf16Path path = bf16_path(M, N);
+    const Bf16Path path = bf16_path(M, K, N);
     if (path == Bf16Path::Gemv) {
         const hipError_t e = dmr::launch_bf16_gemv(d_w, d_x, K, N, d_y, f32, s);
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: K outside its range
         return hip_status(dmr::launch_bf16_skinny(d_w, d_x, M, K, N, d_y, f32, s));
     }
     switch (path) {
+        case Bf16Path::Stream: return hip_status(dmr::launch_bf16_stream(d_w, d_x, M, K, N, d_y, f32, nullptr, s));
         case Bf16Path::Skinny: return hip_status(dmr::launch_bf16_skinny(d_w, d_x, M, K, N, d_y, f32, s));
         case Bf16Path::Mid: return hip_status(dmr::launch_bf16_mid(d_w, d_x, M, K, N, d_y, f32, d_ws, s));
         case Bf16Path::GemmBig: return hip_status(dmr::launch_bf16_gemm_big(d_w, d_x, M, K, N, d_y, f32, s));
@@ -459,6 +463,19 @@ dmr_status_t dmr_qlinear_bf16_forward_fused(const uint16_t *d_w, dmr_prologue_t 
         f.res = d_residual;
         const hipError_t e = dmr::launch_bf16_gemv_fused(d_w, d_in, K, N, d_y, out == DMR_OUT_FP32, f, s);
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: K outside its range, or RMSNorm over slices
+    }
+    if (bf16_path(M, K, N) == Bf16Path::Stream) {
+        // as in the INT4 kernel of this size class: stand-alone prologue, residual fused at the store
+        const uint16_t *x = d_in;
+        if (pro != DMR_PRO_NONE) {
+            uint16_t *xg = static_cast<uint16_t *>(d_ws);
+            const hipError_t eg = pro == DMR_PRO_RMSNORM ? dmr::launch_rmsnorm(d_in, d_gamma, eps, M, K, xg, s)
+                                                          : dmr::launch_swiglu(d_in, M, K, xg, s);
+            if (eg != hipSuccess) return DMR_ERR_HIP;
+            x = xg;
+        }
+        const hipError_t e = dmr::launch_bf16_stream(d_w, x, M, K, N, d_y, out == DMR_OUT_FP32, d_residual, s);
+        if (e != hipErrorInvalidValue) return hip_status(e);
     }
     return run_unfused(pro, d_in, d_gamma, eps, d_residual, M, K, N, d_y, out, d_ws, ws_bytes, s,
                        [&](const uint16_t *x, void *y, dmr_out_t o, void *ws, size_t wsb) {

@@ -126,6 +126,10 @@ hipError_t launch_bf16_gemv(const uint16_t *w, const uint16_t *x, int64_t K, int
 bool w4_stream_fits(int64_t M, int64_t K, int64_t N);
 hipError_t launch_w4_stream(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
                             hipStream_t stream);
+// bf16 twin of the streaming kernel (optional residual added at the store).
+bool bf16_stream_fits(int64_t M, int64_t K, int64_t N);
+hipError_t launch_bf16_stream(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N, void *y,
+                              bool out_f32, const uint16_t *res, hipStream_t stream);
 // 16 < M <= 64: activation pre-pass into `ws` (w4_skinny2_workspace_bytes), then the streaming kernel.
 size_t w4_skinny2_workspace_bytes(int64_t M, int64_t K);
 hipError_t launch_w4_skinny2(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,

@@ -71,7 +71,8 @@ def oracle_chain(pro, inp, gm, forward):
 
 CASES = [(dmr.DMR_PRO_RMSNORM, 4096, 6144, False), (dmr.DMR_PRO_RMSNORM, 4096, 4096, True),
          (dmr.DMR_PRO_SWIGLU, 14336, 4096, True), (dmr.DMR_PRO_SWIGLU, 1024, 272, False),
-         (dmr.DMR_PRO_NONE, 4096, 4096, True), (dmr.DMR_PRO_RMSNORM, 1024, 1024, True)]
+         (dmr.DMR_PRO_NONE, 4096, 4096, True), (dmr.DMR_PRO_RMSNORM, 1024, 1024, True),
+         (dmr.DMR_PRO_RMSNORM, 512, 16400, True)]       # wide layer: the bf16 streaming kernel at M = 12
 
 
 @pytest.mark.parametrize("M", [1, 5, 16, 40])

@@ -265,7 +265,9 @@ def bf16_both(w_bits, x_bits):
                                    (4096, 4096, 1), (14336, 4096, 8), (4096, 6144, 64),
                                    (256, 144, 65), (1024, 400, 300), (4096, 4096, 512),
                                    (1024, 1024, 17), (1024, 1024, 100), (512, 272, 130), (1792, 512, 96),
-                                   (4096, 4096, 200), (2048, 1040, 257)])
+                                   (4096, 4096, 200), (2048, 1040, 257), (1920, 272, 2), (384, 48, 5),
+                                   (4096, 4112, 16), (4096, 28672, 4), (4096, 6144, 9), (128, 16, 16),
+                                   (1024, 16400, 12), (4096, 28672, 16), (256, 16384, 9)])
 def test_bf16_forward(K, N, M):
     w = synth.to_bf16_bits(synth.weights_f32(6000 + K + N, N, K))
     x = synth.activations_bf16(6001 + K + M, M, K)
