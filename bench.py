@@ -25,6 +25,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 CACHE_DEFEAT_BYTES = 1 << 30
+MS_DEFAULT = "8,16,32,64,128,256,512"
 
 
 def int4_bytes(K, N, M=1):
@@ -406,6 +407,75 @@ def layer_sweep(args, dmr, synth, torch, dev):
     print(json.dumps(result), flush=True)
 
 
+def w3_sweep(args, dmr, synth, torch, dev):
+    """The W3A16 (group 128) variant next to W4A16 on the four decoder shapes at the row counts in --ms
+    (default 1): hip-graph replay, weights rotating over >= 1 GiB of resident copies per shape.  Reports
+    the measured W4 / W3 time ratio (the paper projects 1.15 for a native 3-bit kernel, App. A)."""
+    G = synth.GROUP
+    Ms = [int(v) for v in args.ms.split(",")] if args.ms != MS_DEFAULT else [1]
+    stream = torch.cuda.Stream()
+
+    def timeit(fn, iters):
+        with torch.cuda.stream(stream):
+            for i in range(3):
+                fn(i)
+            stream.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                for i in range(iters):
+                    fn(3 + i)
+            for _ in range(2):
+                graph.replay()
+            stream.synchronize()
+            best = float("inf")
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                graph.replay()
+                e1.record(stream)
+                torch.cuda.synchronize()
+                best = min(best, e0.elapsed_time(e1) * 1e3 / iters)
+        return best
+
+    def w3_bytes(K, N, M):
+        return N * K * 3 // 8 + N * (K // G) * 4 + M * K * 2 + M * N * 2
+
+    rows = []
+    for si, (name, K, N) in enumerate(synth.SWEEP_SHAPES):
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(synth.seed_for(2, si, 0))
+        w = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02
+        q4 = dmr.dmr_qlinear_quantize(w, G)
+        q3 = dmr.dmr_qlinear_quantize_w3(w, G)
+        n = -(-(1 << 30) // w3_bytes(K, N, 1))
+        l4 = [dmr.dmr_qlinear_create(*q4, G) for _ in range(n)]
+        l3 = [dmr.dmr_qlinear_w3_create(*q3, G) for _ in range(n)]
+        del w, q4, q3
+        for M in Ms:
+            gen.manual_seed(synth.seed_for(2, si, 1) + M)
+            x = torch.randn((M, K), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+            y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+            ws4 = torch.empty(max(dmr.dmr_qlinear_workspace_bytes(M, K, N), 16), dtype=torch.uint8, device=dev)
+            ws3 = torch.empty(max(dmr.dmr_qlinear_w3_workspace_bytes(M, K, N), 16), dtype=torch.uint8, device=dev)
+            t4 = timeit(lambda i: dmr.dmr_qlinear_forward(l4[i % n], x, out=y, workspace=ws4), 100)
+            t3 = timeit(lambda i: dmr.dmr_qlinear_forward(l3[i % n], x, out=y, workspace=ws3), 100)
+            rows.append({"shape": name, "K": K, "N": N, "M": M, "w4_us": round(t4, 2), "w3_us": round(t3, 2),
+                         "w4_over_w3": round(t4 / t3, 3), "w3_GBps": round(w3_bytes(K, N, M) / t3 / 1e3, 1),
+                         "w4_GBps": round(int4_bytes(K, N, M) / t4 / 1e3, 1)})
+            log(f"[bench] {name:9s} M={M:3d} W4 {t4:7.2f} us  W3 {t3:7.2f} us  W4/W3 {t4 / t3:5.3f}")
+        del l4, l3
+    tot4 = sum(r["w4_us"] for r in rows)
+    tot3 = sum(r["w3_us"] for r in rows)
+    result = {
+        "metric": "per-layer time of the W3A16 copy over the four decoder shapes (sum), and W4A16 / W3A16 time ratio",
+        "value": round(tot3, 2), "unit": "us", "n_gpus": 1, "steps": 1, "warmup": 3, "ms_per_step": round(tot3 * 1e-3, 5),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"W3A16 g128 vs W4A16 g128 sweep, M in {Ms}, hip-graph replay, rotating weight copies"},
+        "w4_over_w3": round(tot4 / tot3, 3), "paper_projection_w4_over_w3": 1.15, "rows": rows,
+    }
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -414,11 +484,11 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly from Python instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
-    ap.add_argument("--workload", choices=("decode_sweep", "full_step", "mixed_step", "chain_step", "layer_sweep"), default="decode_sweep",
+    ap.add_argument("--workload", choices=("decode_sweep", "full_step", "mixed_step", "chain_step", "layer_sweep", "w3_sweep"), default="decode_sweep",
                     help="decode_sweep (default, the headline metric) or full_step: all 129 Linear layers of "
                          "a 32-layer 7B-class decoder per step")
     ap.add_argument("--m", type=int, default=1, help="rows of activations for --workload full_step / chain_step")
-    ap.add_argument("--ms", default="8,16,32,64,128,256,512", help="row counts for --workload layer_sweep")
+    ap.add_argument("--ms", default=MS_DEFAULT, help="row counts for --workload layer_sweep / w3_sweep (there the default is 1)")
     ap.add_argument("--shapes", default="", help="comma-separated shape names for --workload layer_sweep")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -443,6 +513,8 @@ def main():
         return chain_step(args, dmr, synth, torch, dev)
     if args.workload == "layer_sweep":
         return layer_sweep(args, dmr, synth, torch, dev)
+    if args.workload == "w3_sweep":
+        return w3_sweep(args, dmr, synth, torch, dev)
     G = synth.GROUP
     M = 1
 

@@ -173,7 +173,9 @@ size_t dmr_qlinear_w3_storage_bytes(int64_t K, int64_t N, int32_t g) {
 
 size_t dmr_qlinear_w3_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     if (M <= 1 || K <= 0 || N <= 0) return 0;
-    // M > 1: the layer is dequantised to bf16 there first; the bf16 path's own scratch follows
+    if (M <= 16 && dmr::w4_stream_fits(M, K, N)) return 0;      // native streaming kernel
+    if (M <= 16 && dmr::w4_panel_applies(M, K, N)) return dmr::w4_panel_workspace_bytes(M, K, N);   // k-sliced panels
+    // otherwise the layer is dequantised to bf16 there first; the bf16 path's own scratch follows
     return (size_t)N * (size_t)K * 2 + dmr_qlinear_bf16_workspace_bytes(M, K, N);
 }
 
@@ -249,7 +251,17 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
             const hipError_t e = dmr::launch_w3_gemv(L3, d_x, d_y, f32, s);
             if (e != hipErrorInvalidValue) return hip_status(e);
         }
-        // M > 1 (or a shape outside the GEMV's range): dequantise into the workspace, then the bf16 path
+        if (M >= 2 && M <= 16 && dmr::w4_stream_fits(M, layer->K, layer->N)) {
+            const hipError_t e = dmr::launch_w3_stream(L3, d_x, M, d_y, f32, s);
+            if (e != hipErrorInvalidValue) return hip_status(e);
+        }
+        if (M >= 2 && M <= 16 && dmr::w4_panel_applies(M, layer->K, layer->N)) {
+            if (ws_bytes < dmr::w4_panel_workspace_bytes(M, layer->K, layer->N)) return DMR_ERR_WORKSPACE;
+            const hipError_t e = dmr::launch_w3_panel(L3, d_x, M, d_y, f32, d_ws, s);
+            if (e != hipErrorInvalidValue) return hip_status(e);
+        }
+        // larger M (or a shape outside the streaming kernels' range): dequantise into the workspace, then
+        // the bf16 path
         const size_t need3 = dmr_qlinear_w3_workspace_bytes(M, layer->K, layer->N);
         if (!d_ws || ws_bytes < need3) return DMR_ERR_WORKSPACE;
         const hipError_t e = dmr::launch_dequantize3(L3, static_cast<uint16_t *>(d_ws), s);

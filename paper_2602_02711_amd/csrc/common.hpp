@@ -148,6 +148,9 @@ hipError_t launch_retile3(int64_t K, int64_t N, const uint32_t *qweight, const u
 hipError_t launch_dequantize3(const LayerView3 &L, uint16_t *w_bf16, hipStream_t stream);
 hipError_t launch_quantize3(int64_t K, int64_t N, const float *w, uint32_t *qweight, uint16_t *scales,
                             uint16_t *zeros, hipStream_t stream);
+// 2 <= M <= 16 on a 3-bit layer; hipErrorInvalidValue (nothing launched) when the activations do not fit LDS.
+hipError_t launch_w3_stream(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+                            hipStream_t stream);
 hipError_t launch_w3_gemv(const LayerView3 &L, const uint16_t *x, void *y, bool out_f32, hipStream_t stream);
 hipError_t launch_hbm_read_probe(const void *buf, size_t bytes, uint32_t *sink, int blocks,
                                  hipStream_t stream);

@@ -72,6 +72,8 @@ inline PanelPlan plan_panel(int64_t M, int64_t K, int64_t N) {
 
 size_t w4_panel_workspace_bytes(int64_t M, int64_t K, int64_t N);
 bool w4_panel_applies(int64_t M, int64_t K, int64_t N);
+hipError_t launch_w3_panel(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
+                           hipStream_t stream);
 hipError_t launch_w4_panel(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
                            hipStream_t stream);
 

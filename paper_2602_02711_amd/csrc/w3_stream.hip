@@ -1,0 +1,263 @@
+// W3A16 (group 128) streaming kernel for 2 <= M <= 16: the 4-bit streaming kernel of this size class
+// (S k slices x TW tiles of wavefronts per workgroup, all M activation rows staged in LDS with rows
+// padded by 16 bytes, a register ring of P outstanding block loads per wave, 16x16x32 MFMAs, group-wise
+// zero point and scale, the cross-slice sum at every tile step through one reused LDS buffer) on the
+// 3-bit streaming layout: a block is 64 lanes x 3 words, unpacked to the 16 operand registers of the
+// four MFMAs as in the M == 1 kernel (w3_unpack.hpp).  No glue fusion: 3-bit layers take the unfused
+// composition.
+#include <cstdlib>
+
+#include "w3_unpack.hpp"
+
+namespace dmr {
+
+namespace {
+
+int env_int(const char *name, int fallback) {
+    const char *v = std::getenv(name);
+    return (v && *v) ? std::atoi(v) : fallback;
+}
+
+constexpr uint32_t kOnes = 0x3F803F80u;    // bf16 pair (1.0, 1.0)
+
+struct Item {
+    uint32_t w0, w1, w2;
+    uint32_t szw;
+};
+
+// Copy `total` 16-byte pieces of x into LDS, piece p to slot p + p / x16 (rows padded by one piece; the
+// division by multiplication with ceil(2^32 / x16)), B loads in flight per thread.  (Plain vector
+// type for the staging registers: an array of HIP's uint4 struct ends up in scratch memory.)
+template <int B>
+__device__ __forceinline__ void stage_rows(const uint16_t *__restrict__ x, uint4 *smem, int total,
+                                           uint32_t x16_magic) {
+    const int T = (int)blockDim.x;
+    for (int base = (int)threadIdx.x; base < total; base += B * T) {
+        u32x4_t v[B];
+#pragma unroll
+        for (int u = 0; u < B; ++u)
+            v[u] = reinterpret_cast<const u32x4_t *>(x)[min(base + u * T, total - 1)];
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+            const int p = base + u * T;
+            if (p < total) reinterpret_cast<u32x4_t *>(smem)[p + (int)__umulhi((uint32_t)p, x16_magic)] = v[u];
+        }
+    }
+}
+
+template <int P>
+__global__ __launch_bounds__(1024) void w3_stream_kernel(const uint32_t *__restrict__ wt,
+                                                         const uint32_t *__restrict__ sz,
+                                                         const uint16_t *__restrict__ x,
+                                                         void *__restrict__ y, int M, int64_t N,
+                                                         int groups, int tiles, int lgS, int lgTW,
+                                                         int nT_max, int gw_max, int out_f32, uint32_t x16_magic) {
+    extern __shared__ uint4 smem[];   // x rows [M][groups * 16 + 1] uint4, then red[TW][S][64] float4
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int S = 1 << lgS, TW = 1 << lgTW;
+    const int s = wave & (S - 1), tw = wave >> lgS;
+    const int c = lane >> 4, j = lane & 15;
+    const int g0 = (groups * s) >> lgS;
+    const int GW = ((groups * (s + 1)) >> lgS) - g0;          // 0 <= GW <= gw_max
+    const int t_first = ((int)blockIdx.x << lgTW) + tw;
+    const int t_step = (int)gridDim.x << lgTW;
+    const int slots = nT_max * gw_max;                          // the same for every wave
+    const int x16 = groups * 16, row_stride = x16 + 1;
+
+    // Slot (step, gi) -> block to load, clamped into this wave's valid range (or to the matrix's last
+    // tile if it owns none): every load is unconditional and in bounds.
+    int is = 0, ig = 0;   // issue pointer
+    Item ring[P];
+    auto issue = [&](Item &dst) {
+        int tile = t_first + is * t_step;
+        tile = tile < tiles ? tile : tiles - 1;
+        int g = g0 + (ig < GW ? ig : GW - 1);
+        g = g < 0 ? 0 : (g < groups ? g : groups - 1);
+        const int64_t block = (int64_t)tile * groups + g;
+        const uint32_t *pw = wt + (block * 64 + lane) * 3;
+        dst.w0 = load_stream(pw);
+        dst.w1 = load_stream(pw + 1);
+        dst.w2 = load_stream(pw + 2);
+        dst.szw = load_stream(sz + block * kTileRows + j);
+        if (++ig == gw_max) {
+            ig = 0;
+            if (is + 1 < nT_max) ++is;      // saturate at the last step
+        }
+    };
+#pragma unroll
+    for (int p = 0; p < P; ++p) issue(ring[p]);
+
+    // Stage the M activation rows: x is one contiguous run of M * x16 pieces; piece p of row
+    // r = p / x16 (by multiplication with ceil(2^32 / x16), exact in this range) lands at p + r because
+    // rows are padded by one piece.  Up to eight loads are issued before the first store, so that a
+    // thread pays the memory latency once per batch and not once per piece.
+    {
+        const int total = M * x16;
+        if (total <= 2 * (int)blockDim.x)
+            stage_rows<2>(x, smem, total, x16_magic);      // a few rows: no point in six padding loads
+        else
+            stage_rows<8>(x, smem, total, x16_magic);
+    }
+    __syncthreads();
+    auto store_out = [&](int64_t o, float v) {
+        if (out_f32)
+            reinterpret_cast<float *>(y)[o] = v;
+        else
+            reinterpret_cast<uint16_t *>(y)[o] = f32_to_bf16(v);
+    };
+
+    float *red = reinterpret_cast<float *>(smem + M * row_stride);
+    const uint4 *xrow = smem + (j < M ? j : M - 1) * row_stride + c * 4;
+    Frag ones;
+    ones.u = make_uint4(kOnes, kOnes, kOnes, kOnes);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    int cs = 0, cg = 0;   // consume pointer: (tile step, slot within step)
+
+    auto consume = [&](const Item &cur) {
+        const int tile = t_first + cs * t_step;
+        if (cg < GW && tile < tiles) {
+            const uint4 *xp = xrow + (g0 + cg) * 16;
+            Frag a[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) a[t].u = xp[t];
+            uint32_t r16[16];
+            unpack3(cur.w0, cur.w1, cur.w2, r16);
+            f32x4 d = {0.f, 0.f, 0.f, 0.f}, xsum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                Frag b;
+                b.u = make_uint4(r16[4 * t], r16[4 * t + 1], r16[4 * t + 2], r16[4 * t + 3]);
+                d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t].v, b.v, d, 0, 0, 0);
+                xsum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t].v, ones.v, xsum, 0, 0, 0);
+            }
+            const float sc = __uint_as_float(cur.szw << 16);
+            const float cz = __uint_as_float(cur.szw & 0xFFFF0000u);   // -(128 + z)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[r] = fmaf(sc, fmaf(cz, xsum[r], d[r]), acc[r]);
+        }
+        if (++cg == gw_max) {
+            // tile step finished: every wave arrives here exactly once per step
+            if (lgS == 0) {
+                // one slice: the wave owns the whole k range, its tile goes straight to memory
+                if (tile < tiles) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int row = (lane >> 4) * 4 + r;
+                        if (row < M) store_out((int64_t)row * N + (int64_t)tile * kTileRows + (lane & 15), acc[r]);
+                    }
+                }
+            } else {
+                reinterpret_cast<f32x4 *>(red)[((tw << lgS) + s) * 64 + lane] = acc;
+                __syncthreads();
+                // wave w2 < TW adds the S partial tiles of tile lane w2 in slice order
+                if (wave < TW) {
+                    const f32x4 *part = reinterpret_cast<const f32x4 *>(red) + ((wave << lgS) * 64 + lane);
+                    f32x4 v = part[0];
+                    for (int q = 1; q < S; ++q) {
+                        const f32x4 u = part[q * 64];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[r] += u[r];
+                    }
+                    const int t2 = ((int)blockIdx.x << lgTW) + wave + cs * t_step;
+                    if (t2 < tiles) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const int row = (lane >> 4) * 4 + r;
+                            if (row < M) store_out((int64_t)row * N + (int64_t)t2 * kTileRows + (lane & 15), v[r]);
+                        }
+                    }
+                }
+                __syncthreads();
+            }
+            acc = f32x4{0.f, 0.f, 0.f, 0.f};
+            cg = 0;
+            ++cs;
+        }
+    };
+
+    int base = 0;
+    for (; base + P < slots; base += P) {
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const Item cur = ring[p];
+            issue(ring[p]);
+            consume(cur);
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+        if (base + p < slots) consume(ring[p]);
+}
+
+}  // namespace
+
+hipError_t launch_w3_stream(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+                            hipStream_t stream) {
+    // same LDS footprint and launch shapes as the 4-bit kernel
+    if (!w4_stream_fits(M, L.K, L.N)) return hipErrorInvalidValue;
+    const int groups = (int)(L.K / kGroup);
+    const int tiles = (int)(L.N / kTileRows);
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            cus = v;
+        else
+            cus = 256;
+    }
+    const size_t xbytes = (size_t)M * (groups * 16 + 1) * sizeof(uint4);
+    int nw = 16, S = 16;
+    if (tiles >= 4 * cus) {
+        nw = 8;
+        S = 2;
+    } else if (tiles > cus) {
+        nw = 8;
+        S = 4;
+    }
+    nw = env_int("DMR_W3STREAM_NW", nw);      // sweep overrides (unset in production)
+    S = env_int("DMR_W3STREAM_S", S);
+    if (nw < 1 || nw > 16 || S < 1 || S > nw || (nw & (nw - 1)) || (S & (S - 1))) return hipErrorInvalidValue;
+    while (S > groups) S >>= 1;
+    const int TW = nw / S;
+    const size_t lds = xbytes + (S > 1 ? (size_t)nw * 64 * sizeof(f32x4) : 0);
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
+    int per_cu = (int)((160 * 1024) / lds);
+    if (per_cu > 16 / nw) per_cu = 16 / nw;
+    const int wgs = (tiles + TW - 1) / TW;
+    const int grid = wgs < per_cu * cus ? wgs : per_cu * cus;
+    int lgS = 0, lgTW = 0;
+    while ((1 << lgS) < S) ++lgS;
+    while ((1 << lgTW) < TW) ++lgTW;
+    const int t_step = grid * TW;
+    const int nT_max = (tiles + t_step - 1) / t_step;
+    const int gw_max = (groups + S - 1) / S;
+    const int slots = nT_max * gw_max;
+    int P = env_int("DMR_W3STREAM_P", 4);
+    if (P > slots) P = slots;
+    const int of = out_f32 ? 1 : 0;
+    const int iM = (int)M;
+    const uint32_t x16_magic = (uint32_t)(((uint64_t(1) << 32) + (uint64_t)groups * 16 - 1) / ((uint64_t)groups * 16));
+    static bool attr_set[7] = {false, false, false, false, false, false, false};
+#define DMR_W3STREAM_CASE(PP)                                                                            \
+    case PP: {                                                                                           \
+        if (!attr_set[PP]) {                                                                             \
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&w3_stream_kernel<PP>), \
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); \
+            if (e != hipSuccess) return e;                                                               \
+            attr_set[PP] = true;                                                                         \
+        }                                                                                                \
+        hipLaunchKernelGGL((w3_stream_kernel<PP>), dim3(grid), dim3(nw * 64), lds, stream, L.wt, L.sz, x, y, iM, \
+                           L.N, groups, tiles, lgS, lgTW, nT_max, gw_max, of, x16_magic);                \
+    } break;
+    switch (P) {
+        DMR_W3STREAM_CASE(1) DMR_W3STREAM_CASE(2) DMR_W3STREAM_CASE(3) DMR_W3STREAM_CASE(4)
+        DMR_W3STREAM_CASE(5) DMR_W3STREAM_CASE(6)
+        default: return hipErrorInvalidValue;
+    }
+#undef DMR_W3STREAM_CASE
+    return hipGetLastError();
+}
+
+}  // namespace dmr

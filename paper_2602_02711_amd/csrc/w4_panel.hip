@@ -1,4 +1,4 @@
-// W4A16 panel kernel for 2 <= M <= 16 rows of a layer whose activations do not fit LDS as a whole
+// W4A16 / W3A16 panel kernel for 2 <= M <= 16 rows of a layer whose activations do not fit LDS as a whole
 // (K = 14336 from five rows on).
 //
 // A workgroup owns TW * R weight tiles (16 rows each) and one slice of gq groups along k.  It stages
@@ -15,6 +15,7 @@
 //     in ascending order; the S sub-slices inside a workgroup are added through LDS (the panel's
 //     memory, reused after a barrier) in ascending order as well.  Results do not depend on timing.
 #include "panel_plan.hpp"
+#include "w3_unpack.hpp"
 
 namespace dmr {
 
@@ -22,9 +23,10 @@ namespace {
 
 constexpr uint32_t kOnes = 0x3F803F80u;    // bf16 pair (1.0, 1.0)
 
-template <int R>
+// BITS = 4: one 16-byte word group per lane and block; BITS = 3: three words (the 3-bit streaming layout)
+template <int R, int BITS>
 struct PanelItem {
-    u32x4_t w[R];
+    u32x4_t w[R];          // BITS == 3: .x .y .z hold the three words
     uint32_t szw[R];
 };
 
@@ -53,8 +55,8 @@ __device__ __forceinline__ void stage_panel(const uint16_t *__restrict__ x, uint
 }
 
 // out_mode: 0 = fp32 y, 1 = bf16 y, 2 = fp32 partial [split][M][N]
-template <int MT, int R, int WAVES>
-__global__ __launch_bounds__(64 * WAVES) void w4_panel_kernel(const uint4 *__restrict__ wt,
+template <int MT, int R, int WAVES, int BITS>
+__global__ __launch_bounds__(64 * WAVES) void w4_panel_kernel(const void *__restrict__ wt,
                                                               const uint32_t *__restrict__ sz,
                                                               const uint16_t *__restrict__ x,
                                                               void *__restrict__ y, int M, int64_t K, int64_t N,
@@ -75,14 +77,21 @@ __global__ __launch_bounds__(64 * WAVES) void w4_panel_kernel(const uint4 *__res
 
     // weight stream: unconditional, clamped loads (a tile past the end re-reads the last tile, an item
     // past the sub-slice its last group)
-    PanelItem<R> ring[P];
-    auto issue = [&](PanelItem<R> &dst, int i) {
+    PanelItem<R, BITS> ring[P];
+    auto issue = [&](PanelItem<R, BITS> &dst, int i) {
         const int g = ga + gl0 + (i < GW ? i : GW - 1);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int tile = min(tile0 + r, tiles - 1);
             const int64_t block = (int64_t)tile * groups + g;
-            dst.w[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(wt + block * 64 + lane));
+            if constexpr (BITS == 4) {
+                dst.w[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(wt) + block * 64 + lane);
+            } else {
+                const uint32_t *pw = reinterpret_cast<const uint32_t *>(wt) + (block * 64 + lane) * 3;
+                dst.w[r].x = load_stream(pw);
+                dst.w[r].y = load_stream(pw + 1);
+                dst.w[r].z = load_stream(pw + 2);
+            }
             dst.szw[r] = load_stream(sz + block * kTileRows + j);
         }
     };
@@ -129,13 +138,18 @@ __global__ __launch_bounds__(64 * WAVES) void w4_panel_kernel(const uint4 *__res
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[r][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    auto consume = [&](const PanelItem<R> &cur, int i) {
+    auto consume = [&](const PanelItem<R, BITS> &cur, int i) {
         const int gl = gl0 + i;
         f32x4 d[R][MT];
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) d[r][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        uint32_t r16[R][16];
+        if constexpr (BITS == 3) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) unpack3(cur.w[r].x, cur.w[r].y, cur.w[r].z, r16[r]);
+        }
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             Frag a[MT];
@@ -144,7 +158,10 @@ __global__ __launch_bounds__(64 * WAVES) void w4_panel_kernel(const uint4 *__res
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 Frag b;
-                unpack_word(cur.w[r][t], b.w);
+                if constexpr (BITS == 4)
+                    unpack_word(cur.w[r][t], b.w);
+                else
+                    b.u = make_uint4(r16[r][4 * t], r16[r][4 * t + 1], r16[r][4 * t + 2], r16[r][4 * t + 3]);
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
                     d[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mt].v, b.v, d[r][mt], 0, 0, 0);
@@ -167,7 +184,7 @@ __global__ __launch_bounds__(64 * WAVES) void w4_panel_kernel(const uint4 *__res
     for (; base + P <= GW; base += P) {
 #pragma unroll
         for (int p = 0; p < P; ++p) {
-            const PanelItem<R> cur = ring[p];
+            const PanelItem<R, BITS> cur = ring[p];
             issue(ring[p], base + p + P);
             consume(cur, base + p);
         }
@@ -220,24 +237,24 @@ __global__ __launch_bounds__(64 * WAVES) void w4_panel_kernel(const uint4 *__res
     }
 }
 
-template <int MT, int R, int WAVES>
-hipError_t launch_cfg(const LayerView &L, const uint16_t *x, int M, void *dst, int out_mode, const PanelPlan &p,
-                      hipStream_t stream) {
+template <int MT, int R, int WAVES, int BITS>
+hipError_t launch_cfg(int64_t K, int64_t N, const void *wt, const uint32_t *sz, const uint16_t *x, int M, void *dst,
+                      int out_mode, const PanelPlan &p, hipStream_t stream) {
     static bool attr_set = false;
     if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_panel_kernel<MT, R, WAVES>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_panel_kernel<MT, R, WAVES, BITS>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int groups = (int)(L.K / kGroup), tiles = (int)(L.N / kTileRows);
+    const int groups = (int)(K / kGroup), tiles = (int)(N / kTileRows);
     const int TW = WAVES / p.S;
     int lgS = 0;
     while ((1 << lgS) < p.S) ++lgS;
     const uint32_t x16_magic = (uint32_t)(((uint64_t(1) << 32) + (uint64_t)p.gq * 16 - 1) / ((uint64_t)p.gq * 16));
     const dim3 grid((unsigned)((tiles + TW * R - 1) / (TW * R)), (unsigned)p.SK);
-    hipLaunchKernelGGL((w4_panel_kernel<MT, R, WAVES>), grid, dim3(64 * WAVES), p.lds, stream, L.wt, L.sz, x, dst, M,
-                       L.K, L.N, groups, tiles, p.gq, lgS, out_mode, x16_magic);
+    hipLaunchKernelGGL((w4_panel_kernel<MT, R, WAVES, BITS>), grid, dim3(64 * WAVES), p.lds, stream, wt, sz, x, dst, M,
+                       K, N, groups, tiles, p.gq, lgS, out_mode, x16_magic);
     return hipGetLastError();
 }
 
@@ -250,9 +267,11 @@ size_t w4_panel_workspace_bytes(int64_t M, int64_t K, int64_t N) {
 
 bool w4_panel_applies(int64_t M, int64_t K, int64_t N) { return plan_panel(M, K, N).ok; }
 
-hipError_t launch_w4_panel(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
-                           hipStream_t stream) {
-    const PanelPlan p = plan_panel(M, L.K, L.N);
+namespace {
+
+hipError_t launch_panel(int bits, int64_t K, int64_t N, const void *wt, const uint32_t *sz, const uint16_t *x,
+                        int64_t M, void *y, bool out_f32, void *ws, hipStream_t stream) {
+    const PanelPlan p = plan_panel(M, K, N);
     if (!p.ok) return hipErrorInvalidValue;
     const bool split = p.SK > 1;
     if (split && !ws) return hipErrorInvalidValue;
@@ -261,9 +280,22 @@ hipError_t launch_w4_panel(const LayerView &L, const uint16_t *x, int64_t M, voi
     // the planner only produces one tile per wave in 16-wave workgroups; the kernel itself is written
     // for MT row tiles x R weight tiles per wave (MT * R <= 2 fits the 128 registers of 16 waves)
     if (p.MT != 1 || p.R != 1 || p.WAVES != 16) return hipErrorInvalidValue;
-    const hipError_t e = launch_cfg<1, 1, 16>(L, x, (int)M, dst, out_mode, p, stream);
+    const hipError_t e = bits == 3 ? launch_cfg<1, 1, 16, 3>(K, N, wt, sz, x, (int)M, dst, out_mode, p, stream)
+                                   : launch_cfg<1, 1, 16, 4>(K, N, wt, sz, x, (int)M, dst, out_mode, p, stream);
     if (e != hipSuccess || !split) return e;
-    return launch_splitk_reduce(static_cast<const float *>(ws), y, M * L.N, p.SK, out_f32, stream);
+    return launch_splitk_reduce(static_cast<const float *>(ws), y, M * N, p.SK, out_f32, stream);
+}
+
+}  // namespace
+
+hipError_t launch_w4_panel(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
+                           hipStream_t stream) {
+    return launch_panel(4, L.K, L.N, L.wt, L.sz, x, M, y, out_f32, ws, stream);
+}
+
+hipError_t launch_w3_panel(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
+                           hipStream_t stream) {
+    return launch_panel(3, L.K, L.N, L.wt, L.sz, x, M, y, out_f32, ws, stream);
 }
 
 }  // namespace dmr

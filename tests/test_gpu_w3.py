@@ -59,7 +59,8 @@ def test_w3_device_quantiser_matches_oracle_bit_for_bit(K, N):
 
 @pytest.mark.parametrize("K,N,M", [(1024, 1024, 1), (128, 16, 1), (384, 48, 1), (1920, 272, 1), (4096, 28672, 1),
                                    (14336, 4096, 1), (4096, 6144, 1), (1024, 1024, 5), (384, 48, 64),
-                                   (1024, 400, 300)])
+                                   (1024, 400, 300), (384, 48, 2), (1920, 272, 7), (4096, 4112, 16), (4096, 28672, 8),
+                                   (256, 4112, 3), (14336, 528, 4), (14336, 528, 12)])
 def test_w3_forward(K, N, M):
     _, words, s, z = quantized3(7200 + K + N, N, K)
     x = synth.activations_bf16(7201 + K + M, M, K)
