@@ -267,8 +267,9 @@ hipError_t launch_w4_gemv_fused(const LayerView &L, const uint16_t *x, void *y, 
                        (f.pro == kProRmsNorm ? 16 * sizeof(float) : 0);
     if (lds > 64 * 1024) return hipErrorInvalidValue;   // caller falls back to the general kernel
 
-    // Ring depth: four blocks in flight per wave measured best (more costs registers, hence
-    // resident waves); shorter streams take their whole length.
+    // Ring depth: four blocks in flight per wave measured best (six to eight measured 10-25 % slower on
+    // the long-K layer even where a wave's whole stream is seven blocks); shorter streams take their
+    // whole length.
     const int items_max = nT_max * gw_max;
     int P = items_max < 4 ? items_max : 4;
     P = env_int("DMR_GEMV_P", P);
