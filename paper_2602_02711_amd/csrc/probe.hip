@@ -12,12 +12,12 @@ __global__ __launch_bounds__(256) void hbm_read_probe_kernel(const uint4 *__rest
     for (; i + 7 * stride < n16; i += 8 * stride) {
         uint4 v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = buf[i + u * stride];
+        for (int u = 0; u < 8; ++u) v[u] = load_stream(buf + i + u * stride);   // nontemporal, as the weights are read
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
     for (; i < n16; i += stride) {
-        const uint4 v = buf[i];
+        const uint4 v = load_stream(buf + i);
         acc ^= v.x ^ v.y ^ v.z ^ v.w;
     }
     // one store per thread keeps the loads alive without adding measurable traffic
