@@ -155,13 +155,10 @@ hipError_t launch_cfg(const uint16_t *w, const uint16_t *x, int M, int64_t K, in
                       const MidPlan &p, hipStream_t stream) {
     constexpr int BM = 16 * MTW * WM;
     constexpr size_t lds = 2ull * BM * ROW_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&bf16_mid_kernel<MTW, WM, NW, R>),
+    // once per process and kernel instantiation (thread-safe static initialisation)
+    static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(&bf16_mid_kernel<MTW, WM, NW, R>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (attr_status != hipSuccess) return attr_status;
     const int groups = (int)(K / kGroup), tiles = (int)(N / kTileRows);
     const dim3 grid((unsigned)((tiles + NW * R - 1) / (NW * R)), (unsigned)((M + BM - 1) / BM), (unsigned)p.SK);
     hipLaunchKernelGGL((bf16_mid_kernel<MTW, WM, NW, R>), grid, dim3(64 * WM * NW), lds, stream, w, x, dst, M, K, N,

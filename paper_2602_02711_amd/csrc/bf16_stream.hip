@@ -16,11 +16,6 @@ namespace dmr {
 
 namespace {
 
-int env_int(const char *name, int fallback) {
-    const char *v = std::getenv(name);
-    return (v && *v) ? std::atoi(v) : fallback;
-}
-
 struct Item {
     u32x4_t w[4];
 };
@@ -195,15 +190,7 @@ hipError_t launch_bf16_stream(const uint16_t *w, const uint16_t *x, int64_t M, i
     if (!bf16_stream_fits(M, K, N)) return hipErrorInvalidValue;
     const int groups = (int)(K / kGroup);
     const int tiles = (int)(N / kTileRows);
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            cus = v;
-        else
-            cus = 256;
-    }
+    const int cus = compute_units();
     // Measured on MI355X (sweep over waves, k slices and ring depth at M = 4 and 16 on the four decoder
     // shapes): unlike the INT4 kernel, whose blocks are contiguous, the row-major weights want all 16
     // waves of a workgroup along k on the same 16 rows (whole rows stream at a time) and only two items
@@ -235,15 +222,11 @@ hipError_t launch_bf16_stream(const uint16_t *w, const uint16_t *x, int64_t M, i
     const int of = out_f32 ? 1 : 0;
     const int iM = (int)M;
     const uint32_t x16_magic = (uint32_t)(((uint64_t(1) << 32) + (uint64_t)groups * 16 - 1) / ((uint64_t)groups * 16));
-    static bool attr_set[4] = {false, false, false, false};
 #define DMR_BSTREAM_CASE(PP)                                                                              \
     case PP: {                                                                                            \
-        if (!attr_set[PP]) {                                                                              \
-            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&bf16_stream_kernel<PP>), \
+        static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(&bf16_stream_kernel<PP>), \
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); \
-            if (e != hipSuccess) return e;                                                                \
-            attr_set[PP] = true;                                                                          \
-        }                                                                                                 \
+        if (attr_status != hipSuccess) return attr_status; \
         hipLaunchKernelGGL((bf16_stream_kernel<PP>), dim3(grid), dim3(nw * 64), lds, stream, w, x, y, iM, K, N, \
                            groups, tiles, lgS, lgTW, nT_max, gw_max, of, res, x16_magic);                 \
     } break;

@@ -20,6 +20,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <cstdlib>
+
 #include "../../include/dmr_qlinear.h"
 
 namespace dmr {
@@ -92,6 +94,27 @@ __device__ __forceinline__ void unpack_word(uint32_t w, uint32_t (&out)[4]) {
 
 // Position p (0..7) of a streaming-layout word -> nibble index.
 __host__ __device__ __forceinline__ int nibble_of_position(int p) { return (p >> 1) + 4 * (p & 1); }
+
+// Launch-shape overrides for tuning sweeps: read only when DMR_TUNING is set in the environment (one
+// lookup per process), so that production launches never touch the environment.
+inline int env_int(const char *name, int fallback) {
+    static const bool tuning = std::getenv("DMR_TUNING") != nullptr;
+    if (!tuning) return fallback;
+    const char *v = std::getenv(name);
+    return (v && *v) ? std::atoi(v) : fallback;
+}
+
+// Compute units of the current device (asked once per process; 256 if the query fails).
+inline int compute_units() {
+    static const int cus = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            return v;
+        return 256;
+    }();
+    return cus;
+}
 
 struct LayerView {
     int64_t K, N;

@@ -201,13 +201,10 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const void *__restrict__ 
 template <bool W4, bool OUT_F32>
 hipError_t launch_one(const void *wsrc, const uint32_t *sz, const uint16_t *x, int64_t M, int64_t K,
                       int64_t N, void *y, hipStream_t stream) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_big_kernel<W4, OUT_F32>),
+    // once per process and kernel instantiation (thread-safe static initialisation)
+    static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_big_kernel<W4, OUT_F32>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (attr_status != hipSuccess) return attr_status;
     // Workgroups go to the 8 XCDs round-robin by linear index and each XCD has its own L2.  When the
     // tile grid divides evenly, the index is decoded so that the 32 workgroups an XCD runs at a time
     // form a compact 4 x 8 patch of tiles (12 operand panels instead of ~17) and the 8 patches of a

@@ -12,11 +12,6 @@ struct MidPlan {
     int MTW, WM, NW, R, SK, gps;
 };
 
-inline int env_int(const char *name, int fallback) {
-    const char *v = std::getenv(name);
-    return v ? std::atoi(v) : fallback;
-}
-
 // Pure host arithmetic (the workspace query must agree with the launch): 256 CUs assumed.
 inline MidPlan plan_mid(int64_t M, int64_t K, int64_t N) {
     MidPlan p;

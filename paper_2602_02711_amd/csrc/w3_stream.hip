@@ -13,11 +13,6 @@ namespace dmr {
 
 namespace {
 
-int env_int(const char *name, int fallback) {
-    const char *v = std::getenv(name);
-    return (v && *v) ? std::atoi(v) : fallback;
-}
-
 constexpr uint32_t kOnes = 0x3F803F80u;    // bf16 pair (1.0, 1.0)
 
 struct Item {
@@ -198,15 +193,7 @@ hipError_t launch_w3_stream(const LayerView3 &L, const uint16_t *x, int64_t M, v
     if (!w4_stream_fits(M, L.K, L.N)) return hipErrorInvalidValue;
     const int groups = (int)(L.K / kGroup);
     const int tiles = (int)(L.N / kTileRows);
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            cus = v;
-        else
-            cus = 256;
-    }
+    const int cus = compute_units();
     const size_t xbytes = (size_t)M * (groups * 16 + 1) * sizeof(uint4);
     int nw = 16, S = 16;
     if (tiles >= 4 * cus) {
@@ -239,15 +226,11 @@ hipError_t launch_w3_stream(const LayerView3 &L, const uint16_t *x, int64_t M, v
     const int of = out_f32 ? 1 : 0;
     const int iM = (int)M;
     const uint32_t x16_magic = (uint32_t)(((uint64_t(1) << 32) + (uint64_t)groups * 16 - 1) / ((uint64_t)groups * 16));
-    static bool attr_set[7] = {false, false, false, false, false, false, false};
 #define DMR_W3STREAM_CASE(PP)                                                                            \
     case PP: {                                                                                           \
-        if (!attr_set[PP]) {                                                                             \
-            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&w3_stream_kernel<PP>), \
+        static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(&w3_stream_kernel<PP>), \
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); \
-            if (e != hipSuccess) return e;                                                               \
-            attr_set[PP] = true;                                                                         \
-        }                                                                                                \
+        if (attr_status != hipSuccess) return attr_status; \
         hipLaunchKernelGGL((w3_stream_kernel<PP>), dim3(grid), dim3(nw * 64), lds, stream, L.wt, L.sz, x, y, iM, \
                            L.N, groups, tiles, lgS, lgTW, nT_max, gw_max, of, x16_magic);                \
     } break;

@@ -198,11 +198,6 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
     }
 }
 
-int env_int(const char *name, int fallback) {
-    const char *v = std::getenv(name);
-    return (v && *v) ? std::atoi(v) : fallback;
-}
-
 struct GemvPlan {
     int S, TW, grid;
 };
@@ -234,15 +229,7 @@ hipError_t launch_w4_gemv_fused(const LayerView &L, const uint16_t *x, void *y, 
                                 hipStream_t stream) {
     const int groups = (int)(L.K / kGroup);
     const int tiles = (int)(L.N / kTileRows);
-    static int cus = 0;   // compute units of the (single) device, asked once
-    if (cus == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            cus = v;
-        else
-            cus = 256;
-    }
+    const int cus = compute_units();
     GemvPlan plan = plan_for(groups, tiles, cus);
     // sweep overrides (unset in production)
     plan.S = env_int("DMR_GEMV_S", plan.S);

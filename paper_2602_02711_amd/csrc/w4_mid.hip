@@ -211,13 +211,10 @@ hipError_t launch_cfg(const LayerView &L, const uint16_t *x, int M, void *dst, i
                       hipStream_t stream) {
     constexpr int BM = 16 * MTW * WM;
     constexpr size_t lds = 2ull * BM * ROW_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_mid_kernel<MTW, WM, NW, R>),
+    // once per process and kernel instantiation (thread-safe static initialisation)
+    static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_mid_kernel<MTW, WM, NW, R>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (attr_status != hipSuccess) return attr_status;
     const int groups = (int)(L.K / kGroup), tiles = (int)(L.N / kTileRows);
     const dim3 grid((unsigned)((tiles + NW * R - 1) / (NW * R)), (unsigned)((M + BM - 1) / BM), (unsigned)p.SK);
     hipLaunchKernelGGL((w4_mid_kernel<MTW, WM, NW, R>), grid, dim3(64 * WM * NW), lds, stream, L.wt, L.sz, x, dst, M,

@@ -240,13 +240,10 @@ __global__ __launch_bounds__(64 * WAVES) void w4_panel_kernel(const void *__rest
 template <int MT, int R, int WAVES, int BITS>
 hipError_t launch_cfg(int64_t K, int64_t N, const void *wt, const uint32_t *sz, const uint16_t *x, int M, void *dst,
                       int out_mode, const PanelPlan &p, hipStream_t stream) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_panel_kernel<MT, R, WAVES, BITS>),
+    // once per process and kernel instantiation (thread-safe static initialisation)
+    static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_panel_kernel<MT, R, WAVES, BITS>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (attr_status != hipSuccess) return attr_status;
     const int groups = (int)(K / kGroup), tiles = (int)(N / kTileRows);
     const int TW = WAVES / p.S;
     int lgS = 0;

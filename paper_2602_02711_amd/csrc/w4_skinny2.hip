@@ -158,13 +158,10 @@ hipError_t launch_main(const LayerView &L, const uint4 *xf, const float *xg, int
     int S = 4;
     while (S > groups) S >>= 1;
     const size_t lds = (size_t)S * R * MT * 64 * sizeof(f32x4);
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_skinny2_kernel<MT, R>),
+    // once per process and kernel instantiation (thread-safe static initialisation)
+    static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_skinny2_kernel<MT, R>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (attr_status != hipSuccess) return attr_status;
     const unsigned grid = (unsigned)((tiles + R - 1) / R);
     hipLaunchKernelGGL((w4_skinny2_kernel<MT, R>), dim3(grid), dim3(S * 64), lds, stream, L.wt, L.sz, xf, xg, y,
                        M, L.N, groups, tiles, out_f32 ? 1 : 0);

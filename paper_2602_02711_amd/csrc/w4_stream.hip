@@ -21,11 +21,6 @@ namespace dmr {
 
 namespace {
 
-int env_int(const char *name, int fallback) {
-    const char *v = std::getenv(name);
-    return (v && *v) ? std::atoi(v) : fallback;
-}
-
 constexpr uint32_t kOnes = 0x3F803F80u;    // bf16 pair (1.0, 1.0)
 
 struct Item {
@@ -226,15 +221,7 @@ hipError_t launch_w4_stream_fused(const LayerView &L, const uint16_t *x, int64_t
     if (M < 2 || M > 16 || f.pro != kProNone) return hipErrorInvalidValue;
     const int groups = (int)(L.K / kGroup);
     const int tiles = (int)(L.N / kTileRows);
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            cus = v;
-        else
-            cus = 256;
-    }
+    const int cus = compute_units();
     // Choose (waves per workgroup, k slices S, tile lanes TW = waves / S).  The activations' LDS
     // footprint limits how many workgroups a CU holds.
     const size_t xbytes = (size_t)M * (groups * 16 + 1) * sizeof(uint4);
@@ -296,15 +283,11 @@ hipError_t launch_w4_stream_fused(const LayerView &L, const uint16_t *x, int64_t
     const int of = out_f32 ? 1 : 0;
     const int iM = (int)M;
     const uint32_t x16_magic = (uint32_t)(((uint64_t(1) << 32) + (uint64_t)groups * 16 - 1) / ((uint64_t)groups * 16));
-    static bool attr_set[9] = {false, false, false, false, false, false, false, false, false};
 #define DMR_STREAM_CASE(PP)                                                                             \
     case PP: {                                                                                          \
-        if (!attr_set[PP]) {                                                                            \
-            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_stream_kernel<PP>), \
+        static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_stream_kernel<PP>), \
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); \
-            if (e != hipSuccess) return e;                                                              \
-            attr_set[PP] = true;                                                                        \
-        }                                                                                               \
+        if (attr_status != hipSuccess) return attr_status; \
         hipLaunchKernelGGL((w4_stream_kernel<PP>), dim3(grid), dim3(nw * 64), lds, stream, L.wt, L.sz, x, y, \
                            iM, L.N, groups, tiles, lgS, lgTW, nT_max, gw_max, of, f.res, x16_magic);          \
     } break;

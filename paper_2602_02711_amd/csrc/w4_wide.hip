@@ -218,13 +218,10 @@ __global__ __launch_bounds__(512) void w4_wide_kernel(const uint4 *__restrict__ 
 
 template <int MT, int R, int S, int CG>
 hipError_t launch_cfg(const LayerView &L, const uint16_t *x, int M, void *y, bool out_f32, hipStream_t stream) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_wide_kernel<MT, R, S, CG>),
+    // once per process and kernel instantiation (thread-safe static initialisation)
+    static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_wide_kernel<MT, R, S, CG>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (attr_status != hipSuccess) return attr_status;
     const int groups = (int)(L.K / kGroup), tiles = (int)(L.N / kTileRows);
     constexpr int TW = 8 / S;
     static_assert(TW * R == kWideTilesPerWg && CG == kWideChunk, "the planner assumes this shape");
