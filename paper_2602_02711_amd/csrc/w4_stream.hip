@@ -48,7 +48,7 @@ __device__ __forceinline__ void stage_rows(const uint16_t *__restrict__ x, uint4
     }
 }
 
-template <int P>
+template <int P, bool XS>
 __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict__ wt,
                                                          const uint32_t *__restrict__ sz,
                                                          const uint16_t *__restrict__ x,
@@ -56,7 +56,7 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
                                                          int groups, int tiles, int lgS, int lgTW,
                                                          int nT_max, int gw_max, int out_f32,
                                                          const uint16_t *__restrict__ res, uint32_t x16_magic) {
-    extern __shared__ uint4 smem[];   // x rows [M][groups * 16 + 1] uint4, then red[TW][S][64] float4
+    extern __shared__ uint4 smem[];   // x rows [M][groups * 16 + 1] uint4, xs[groups][4] float4, red[TW][S][64] float4
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int S = 1 << lgS, TW = 1 << lgTW;
@@ -101,6 +101,25 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
             stage_rows<8>(x, smem, total, x16_magic);
     }
     __syncthreads();
+    // XS: the group sums of x (every column of A . ones holds the row sums) are formed once per workgroup
+    // into a table instead of by four more MFMAs per block; pays when a wave streams many blocks
+    f32x4 *xs = reinterpret_cast<f32x4 *>(smem + M * row_stride);
+    if constexpr (XS) {
+        Frag ones1;
+        ones1.u = make_uint4(kOnes, kOnes, kOnes, kOnes);
+        const uint4 *xr = smem + (j < M ? j : M - 1) * row_stride + c * 4;
+        for (int u = wave; u < groups; u += (int)(blockDim.x >> 6)) {
+            f32x4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                Frag a;
+                a.u = xr[u * 16 + t];
+                d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, ones1.v, d, 0, 0, 0);
+            }
+            if (j == 0) xs[u * 4 + c] = d;
+        }
+        __syncthreads();
+    }
     auto store_out = [&](int64_t o, float v) {
         if (res) v += __uint_as_float((uint32_t)res[o] << 16);
         if (out_f32)
@@ -109,7 +128,7 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
             reinterpret_cast<uint16_t *>(y)[o] = f32_to_bf16(v);
     };
 
-    float *red = reinterpret_cast<float *>(smem + M * row_stride);
+    float *red = reinterpret_cast<float *>(smem + M * row_stride + groups * 4);
     const uint4 *xrow = smem + (j < M ? j : M - 1) * row_stride + c * 4;
     Frag ones;
     ones.u = make_uint4(kOnes, kOnes, kOnes, kOnes);
@@ -130,8 +149,9 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
                 Frag b;
                 unpack_word(words[t], b.w);
                 d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t].v, b.v, d, 0, 0, 0);
-                xsum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t].v, ones.v, xsum, 0, 0, 0);
+                if constexpr (!XS) xsum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t].v, ones.v, xsum, 0, 0, 0);
             }
+            if constexpr (XS) xsum = xs[(g0 + cg) * 4 + c];
             const float sc = __uint_as_float(cur.szw << 16);
             const float cz = __uint_as_float(cur.szw & 0xFFFF0000u);   // -(128 + z)
 #pragma unroll
@@ -198,7 +218,7 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
 bool w4_stream_fits(int64_t M, int64_t K, int64_t N) {
     if (M < 2 || M > 16) return false;
     const int groups = (int)(K / kGroup), tiles = (int)(N / kTileRows);
-    const size_t xbytes = (size_t)M * (groups * 16 + 1) * sizeof(uint4);
+    const size_t xbytes = (size_t)M * (groups * 16 + 1) * sizeof(uint4) + (size_t)groups * 4 * sizeof(f32x4);
     int nw = 16, S = 16;
     if (tiles >= 4 * 256) {
         nw = 8;
@@ -224,7 +244,7 @@ hipError_t launch_w4_stream_fused(const LayerView &L, const uint16_t *x, int64_t
     const int cus = compute_units();
     // Choose (waves per workgroup, k slices S, tile lanes TW = waves / S).  The activations' LDS
     // footprint limits how many workgroups a CU holds.
-    const size_t xbytes = (size_t)M * (groups * 16 + 1) * sizeof(uint4);
+    const size_t xbytes = (size_t)M * (groups * 16 + 1) * sizeof(uint4) + (size_t)groups * 4 * sizeof(f32x4);
     // Measured on MI355X (sweep over waves per workgroup, S, ring depth at M = 2..16): few, long k
     // slices win once there are several tiles per CU; one tile per CU wants all 16 slices.
     int best_nw, best_S;
@@ -285,12 +305,25 @@ hipError_t launch_w4_stream_fused(const LayerView &L, const uint16_t *x, int64_t
     const uint32_t x16_magic = (uint32_t)(((uint64_t(1) << 32) + (uint64_t)groups * 16 - 1) / ((uint64_t)groups * 16));
 #define DMR_STREAM_CASE(PP)                                                                             \
     case PP: {                                                                                          \
-        static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_stream_kernel<PP>), \
+        static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_stream_kernel<PP, false>), \
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); \
         if (attr_status != hipSuccess) return attr_status; \
-        hipLaunchKernelGGL((w4_stream_kernel<PP>), dim3(grid), dim3(nw * 64), lds, stream, L.wt, L.sz, x, y, \
+        hipLaunchKernelGGL((w4_stream_kernel<PP, false>), dim3(grid), dim3(nw * 64), lds, stream, L.wt, L.sz, x, y, \
                            iM, L.N, groups, tiles, lgS, lgTW, nT_max, gw_max, of, f.res, x16_magic);          \
     } break;
+    // Group sums from a table when a wave streams at least sixteen blocks and the table costs it at most
+    // a quarter as many MFMA passes as it saves (the widest layers: 0.3-0.9 us of 17 on gate+up; on the
+    // 6144-row layer, eight blocks per wave, it measured 0.3 us slower).
+    const int units = (groups + nw - 1) / nw;
+    const bool xs_table = env_int("DMR_STREAM_XS", (P == 4 && slots >= 16 && 4 * units <= slots) ? 1 : 0) == 1 && P == 4;
+    if (xs_table) {
+        static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_stream_kernel<4, true>),
+                                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (attr_status != hipSuccess) return attr_status;
+        hipLaunchKernelGGL((w4_stream_kernel<4, true>), dim3(grid), dim3(nw * 64), lds, stream, L.wt, L.sz, x, y, iM, L.N,
+                           groups, tiles, lgS, lgTW, nT_max, gw_max, of, f.res, x16_magic);
+        return hipGetLastError();
+    }
     switch (P) {
         DMR_STREAM_CASE(1) DMR_STREAM_CASE(2) DMR_STREAM_CASE(3) DMR_STREAM_CASE(4)
         DMR_STREAM_CASE(5) DMR_STREAM_CASE(6) DMR_STREAM_CASE(7) DMR_STREAM_CASE(8)
