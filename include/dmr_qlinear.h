@@ -138,8 +138,9 @@ dmr_status_t dmr_glue_swiglu(const uint16_t *d_in, int64_t M, int64_t I, uint16_
  *             DMR_PRO_NONE:    d_in = [M][K] as in the plain forward
  *   epilogue  d_residual (bf16 [M][N]) or NULL: y = acc + residual in fp32, rounded once to `out`.
  * M = 1 (both copies) fuses the prologue into the staging of the activation row and the residual
- * into the output store of the weight-streaming kernel; 2 <= M <= 16 of the INT4 copy fuses the
- * residual only (a prologue would be recomputed by every workgroup); anything else runs the glue
+ * into the output store of the weight-streaming kernel; 2 <= M <= 16 fuses the residual only, where
+ * the streaming kernel of that size class serves the shape (a prologue would be recomputed by every
+ * workgroup, so it runs as a kernel of its own into d_ws); anything else runs the glue
  * kernels into d_ws and then the plain forward.  d_ws as the matching *_fused_workspace_bytes query says (never 0 with a
  * prologue or a residual).
  */
@@ -179,9 +180,10 @@ dmr_status_t dmr_qlinear_quantize(int64_t K, int64_t N, int32_t g, const float *
  * which it could only run fake-quantised and whose cost it projected as T_W4 / 1.15 (App. A).  Format:
  * codes 0..7, 32 per three words along k (code j in bits [3j, 3j+3) of the 96-bit little-endian run),
  * qweight3 uint32 [N][3K/32]; scales and zeros as for 4 bits, zero points 0..7.  The handle these
- * calls return is used with dmr_qlinear_dequantize / _forward / _destroy like a 4-bit one.  M = 1
- * runs a native weight-streaming kernel; M > 1 dequantises the layer into d_ws
- * (dmr_qlinear_w3_workspace_bytes) and takes the bf16 path.
+ * calls return is used with dmr_qlinear_dequantize / _forward / _destroy like a 4-bit one.  M <= 16
+ * runs native weight-streaming kernels (d_ws only for fp32 partial sums when K is long and split);
+ * larger M dequantises the layer into d_ws and takes the bf16 path.  d_ws as
+ * dmr_qlinear_w3_workspace_bytes says.
  */
 size_t dmr_qlinear_w3_storage_bytes(int64_t K, int64_t N, int32_t g);
 size_t dmr_qlinear_w3_workspace_bytes(int64_t M, int64_t K, int64_t N);
