@@ -292,10 +292,8 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
     // them.  Per-channel layers, whose row scales differ widely, take the 128 x 128 kernel that keeps
     // the codes exact and applies the scale per group in fp32.
     const bool g128 = layer->g == dmr::kGroup;
-    if (g128 && dmr::gemm_big_applies(M, layer->N)) {
-        if (dmr::env_int("DMR_GEMM_DMA", 0) == 1) return hip_status(dmr::launch_w4_gemm_dma(L, d_x, M, d_y, f32, s));
+    if (g128 && dmr::gemm_big_applies(M, layer->N))
         return hip_status(dmr::launch_w4_gemm_big(L, d_x, M, d_y, f32, s));
-    }
     return hip_status(dmr::launch_w4_gemm(L, d_x, M, d_y, f32, !g128, s));
 }
 
@@ -324,9 +322,7 @@ dmr_status_t dmr_qlinear_bf16_forward(const uint16_t *d_w, const uint16_t *d_x, 
         case Bf16Path::Stream: return hip_status(dmr::launch_bf16_stream(d_w, d_x, M, K, N, d_y, f32, nullptr, s));
         case Bf16Path::Skinny: return hip_status(dmr::launch_bf16_skinny(d_w, d_x, M, K, N, d_y, f32, s));
         case Bf16Path::Mid: return hip_status(dmr::launch_bf16_mid(d_w, d_x, M, K, N, d_y, f32, d_ws, s));
-        case Bf16Path::GemmBig:
-            if (dmr::env_int("DMR_GEMM_DMA", 0) == 1) return hip_status(dmr::launch_bf16_gemm_dma(d_w, d_x, M, K, N, d_y, f32, s));
-            return hip_status(dmr::launch_bf16_gemm_big(d_w, d_x, M, K, N, d_y, f32, s));
+        case Bf16Path::GemmBig: return hip_status(dmr::launch_bf16_gemm_big(d_w, d_x, M, K, N, d_y, f32, s));
         default: return hip_status(dmr::launch_bf16_gemm(d_w, d_x, M, K, N, d_y, f32, s));
     }
 }

@@ -187,17 +187,12 @@ hipError_t launch_w4_gemm(const LayerView &L, const uint16_t *x, int64_t M, void
                           hipStream_t stream);
 hipError_t launch_bf16_gemm(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
                             void *y, bool out_f32, hipStream_t stream);
-// 256 x 256 tiling for problems large enough to fill the chip with it.
+// 256 x 256 tiling (direct-to-LDS operand loads, four-stage pipeline) for problems large enough to fill the
+// chip with it.
 bool gemm_big_applies(int64_t M, int64_t N);
 hipError_t launch_w4_gemm_big(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
                               hipStream_t stream);
 hipError_t launch_bf16_gemm_big(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
-                                void *y, bool out_f32, hipStream_t stream);
-
-// 256 x 256 tiling with direct-to-LDS operand loads and a four-stage pipeline (K >= 128).
-hipError_t launch_w4_gemm_dma(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
-                              hipStream_t stream);
-hipError_t launch_bf16_gemm_dma(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
                                 void *y, bool out_f32, hipStream_t stream);
 
 }  // namespace dmr

@@ -1,123 +1,129 @@
-// Large-tile MFMA GEMM for long prefills: y[M][N] = x[M][K] . W[N][K]^T, fp32 accumulation.
+// Large-tile MFMA GEMM with direct-to-LDS operand loads: y[M][N] = x[M][K] . W[N][K]^T, fp32 accumulation.
 //
-// The 128 x 128 kernel is bound by LDS reads (1 KiB of operand fragments per 32x32x16 MFMA).  Here
-// a workgroup of 4 wavefronts owns a 256 x 256 tile and every wave a 128 x 128 patch (4 x 4 MFMA
-// tiles, 256 accumulator registers): 8 fragments feed 16 MFMAs, half the LDS bytes per MFMA.  LDS is
-// double buffered (2 x 72 KiB of 160), one barrier per 64-wide k step; the global loads of step
-// i + 1 are issued before the MFMAs of step i and written to the other buffer after them.
-// INT4 tiles are dequantised to RNE_bf16((q - z) s) on the way into LDS.
+// The 128 x 128 kernel is bound by LDS reads (1 KiB of operand fragments per 32x32x16 MFMA).  Here a
+// workgroup of 4 wavefronts owns a 256 x 256 tile and every wave a 128 x 128 patch (4 x 4 MFMA tiles, 256
+// accumulator registers): 8 fragments feed 16 MFMAs, half the LDS bytes per MFMA.  The bf16 operands travel global memory -> LDS without
+// passing through registers (`global_load_lds_dwordx4`: every lane names its own 16 global bytes, the
+// wave's 64 x 16 bytes land contiguously at a wave-uniform LDS address).  With no staging registers the
+// loads can run three to four k steps ahead: four LDS stages of 32 k (4 x 32 KiB), one barrier per step,
+// and the wait before it only covers the loads issued three steps earlier.  (A first version staged the
+// operands through registers: one step of prefetch was all the registers allowed, ~40 % of the time went
+// into waiting for it, and it measured 6-20 % slower on bf16 weights, 0-8 % on INT4.)
+//
+// LDS layout of a stage: operand rows of 32 bf16 = 64 bytes = four 16-byte chunks, unpadded (a load
+// instruction fills 16 consecutive rows), chunk c of row r stored at position c ^ ((r >> 2) & 3): the
+// 16 lanes of a quarter wave that read the same chunk of 16 consecutive rows then touch 16 different
+// 16-byte bank groups.  The swizzle is applied on the global side (lane l of a load instruction owns
+// LDS slot l, i.e. row l / 4, position l % 4, and fetches chunk (l % 4) ^ ((row >> 2) & 3) of that row).
+// Rows beyond M or N are clamped to the last row (their products are never stored).
+//
+// INT4 layers: the packed codes and scale / zero words of a k step (16 + 4 bytes per thread) are fetched
+// direct-to-LDS as well, into a small ring, one step further ahead; the lane that fetched them reads them
+// back a step before they are needed, dequantises to RNE_bf16((q - z) s) and writes its 64-byte row slice of
+// the weight tile.  No load in the loop targets a register, so no register wait ever drains the pipeline.
 #include "common.hpp"
 
 namespace dmr {
 
 namespace {
 
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int LDS_STRIDE = BK + 8;                       // bf16 elements per padded row (144 bytes)
-constexpr int TILE_ELEMS = BM * LDS_STRIDE;              // one operand, one buffer
-constexpr size_t LDS_BYTES = 4ull * TILE_ELEMS * sizeof(uint16_t);   // A and B, two buffers each
+constexpr int BM = 256, BN = 256, BK = 32, NS = 4;
+constexpr int ROW_BYTES = BK * 2;                         // 64
+constexpr int OPERAND_BYTES = BM * ROW_BYTES;             // 16 KiB per operand and stage
+constexpr int STAGE_BYTES = 2 * OPERAND_BYTES;            // A then B
+constexpr int NR = NS + 1;                                // ring of packed INT4 slices (requested one step further ahead)
+constexpr int RAW_W_BYTES = 4096, RAW_SZ_BYTES = 1024;    // per slot: 256 lanes x 16 bytes of codes, x 4 bytes of scale / zero
+constexpr int RAW_BYTES = RAW_W_BYTES + RAW_SZ_BYTES;
+constexpr size_t LDS_BYTES_BF16 = (size_t)NS * STAGE_BYTES;                      // 128 KiB
+constexpr size_t LDS_BYTES_W4 = LDS_BYTES_BF16 + (size_t)NR * RAW_BYTES + 1024;  // + 25 KiB of ring + 1 KiB of slack
 
-template <bool W4>
-struct Prefetch {
-    uint4 xa[8];
-    uint4 wb[W4 ? 2 : 8];
-    uint32_t szw[2];
-};
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void global_void;
 
-template <bool W4>
-__device__ __forceinline__ void load_global(Prefetch<W4> &p, const void *__restrict__ wsrc,
-                                            const uint32_t *__restrict__ sz,
-                                            const uint16_t *__restrict__ x, int64_t M, int64_t K,
-                                            int64_t N, int64_t m0, int64_t n0, int64_t k0, int tid) {
+// s_waitcnt vmcnt(N) (gfx9 encoding: vmcnt in bits [3:0] and [15:14], expcnt [6:4], lgkmcnt [11:8])
+// Also waits for this wave's LDS accesses (lgkmcnt = 0): the barrier that follows is a bare s_barrier.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (0 << 8));
+}
+
+// Workgroup barrier without the release / acquire fences of __syncthreads(): those would make the
+// compiler wait for every direct-to-LDS load in flight (they are LDS writes), i.e. for the whole
+// prefetch.  What must have landed is waited for explicitly (wait_vmcnt) before this is called; the
+// signal fences keep the compiler from moving memory accesses across the barrier.
+__device__ __forceinline__ void bare_barrier() {
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    __builtin_amdgcn_s_barrier();
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+}
+
+__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 2) & 3); }
+
+// INT4: one thread turns its 32 codes of a k step (16 bytes of the streaming layout plus the scale / zero word,
+// both fetched into `raw` by this same lane) into bf16 RNE((q - z) s) and writes the 64-byte row slice
+// of the weight tile.  Restrict pointers for the same reason as in mfma_step.
+__device__ __forceinline__ void dequant_row(const uint8_t *__restrict__ raw_w, const uint8_t *__restrict__ raw_sz,
+                                            uint8_t *__restrict__ Bs, int tid) {
+    const int lane = tid & 63, wave = tid >> 6;
+    const u32x4_t w = *reinterpret_cast<const u32x4_t *>(raw_w + wave * 1024 + lane * 16);
+    const uint32_t szw = *reinterpret_cast<const uint32_t *>(raw_sz + wave * 256 + lane * 4);
+    const int row = tid;                                       // tile tid / 16, row tid % 16 of it
+    const float s = __uint_as_float(szw << 16);
+    const float czs = __uint_as_float(szw & 0xFFFF0000u) * s;   // -(128 + z) s, exact
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int idx = tid + 256 * i;
-        const int row = idx >> 3, chunk = idx & 7;
-        const int64_t m = m0 + row;
-        p.xa[i] = (m < M) ? *reinterpret_cast<const uint4 *>(x + m * K + k0 + chunk * 8)
-                          : make_uint4(0, 0, 0, 0);
-    }
-    if (W4) {
-        const int64_t groups = K / kGroup;
-        const int64_t G = k0 / kGroup;
-        const int half = (int)((k0 % kGroup) / 64);
+    for (int t = 0; t < 4; ++t) {
+        uint32_t o[4];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int slot = tid + 256 * i;
-            const int64_t T = n0 / kTileRows + (slot >> 5);
-            const int l = half * 32 + (slot & 31);
-            if (T * kTileRows < N) {
-                p.wb[i] = reinterpret_cast<const uint4 *>(wsrc)[(T * groups + G) * 64 + l];
-                p.szw[i] = sz[(T * groups + G) * kTileRows + (l & 15)];
-            } else {
-                p.wb[i] = make_uint4(0, 0, 0, 0);
-                p.szw[i] = 0xC3000000u;   // s = 0, -(128 + z) = -128: contributes zeros
-            }
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t pair = ((w[t] >> (4 * q)) & 0x000F000Fu) | 0x43004300u;
+            const float lo = fmaf(__uint_as_float(pair << 16), s, czs);
+            const float hi = fmaf(__uint_as_float(pair & 0xFFFF0000u), s, czs);
+            o[q] = pack_bf16x2(lo, hi);
         }
-    } else {
-        const uint16_t *w = reinterpret_cast<const uint16_t *>(wsrc);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int idx = tid + 256 * i;
-            const int row = idx >> 3, chunk = idx & 7;
-            const int64_t n = n0 + row;
-            p.wb[i] = (n < N) ? *reinterpret_cast<const uint4 *>(w + n * K + k0 + chunk * 8)
-                              : make_uint4(0, 0, 0, 0);
-        }
+        const u32x4_t v = {o[0], o[1], o[2], o[3]};
+        *reinterpret_cast<u32x4_t *>(Bs + row * ROW_BYTES + swz(row, t) * 16) = v;
     }
 }
 
-template <bool W4>
-__device__ __forceinline__ void store_lds(const Prefetch<W4> &p, uint16_t *As, uint16_t *Bs, int tid) {
+// Operand fragments of one 16-wide k sub-step (ks = 0, 1) of an LDS stage.  The stage pointer is
+// `__restrict__` on purpose: after inlining, the LDS reads carry alias scopes, which is what lets the
+// compiler's wait-count pass tell them apart from the direct-to-LDS loads in flight into the other stages
+// (without scopes it waits for every outstanding load before the first LDS read, which would serialise
+// the pipeline; the wait for the stage that is read here is the explicit one in the kernel).
+__device__ __forceinline__ void load_frags_ab(const uint8_t *__restrict__ As, const uint8_t *__restrict__ Bs, int ks,
+                                              Frag (&a)[4], Frag (&b)[4], int lane, int wm, int wn) {
+    const int chunk = ks * 2 + (lane >> 5);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int idx = tid + 256 * i;
-        const int row = idx >> 3, chunk = idx & 7;
-        *reinterpret_cast<uint4 *>(As + row * LDS_STRIDE + chunk * 8) = p.xa[i];
+    for (int i = 0; i < 4; ++i) {
+        const int ra = wm * 128 + i * 32 + (lane & 31);
+        const int rb = wn * 128 + i * 32 + (lane & 31);
+        a[i].u = *reinterpret_cast<const uint4 *>(As + ra * ROW_BYTES + swz(ra, chunk) * 16);
+        b[i].u = *reinterpret_cast<const uint4 *>(Bs + rb * ROW_BYTES + swz(rb, chunk) * 16);
     }
-    if (W4) {
+}
+
+__device__ __forceinline__ void load_frags(const uint8_t *stage, int ks, Frag (&a)[4], Frag (&b)[4], int lane, int wm,
+                                           int wn) {
+    load_frags_ab(stage, stage + OPERAND_BYTES, ks, a, b, lane, wm, wn);
+}
+
+__device__ __forceinline__ void mfma_16(const Frag (&a)[4], const Frag (&b)[4], f32x16 (&acc)[4][4]) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int slot = tid + 256 * i;
-            const int l = slot & 31;
-            const int row = (slot >> 5) * kTileRows + (l & 15);
-            const int kofs = (l >> 4) * 32;
-            const float s = __uint_as_float(p.szw[i] << 16);
-            const float czs = __uint_as_float(p.szw[i] & 0xFFFF0000u) * s;   // -(128 + z) s, exact
-            const uint32_t words[4] = {p.wb[i].x, p.wb[i].y, p.wb[i].z, p.wb[i].w};
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                uint32_t o[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const uint32_t pair = ((words[t] >> (4 * q)) & 0x000F000Fu) | 0x43004300u;
-                    const float lo = fmaf(__uint_as_float(pair << 16), s, czs);
-                    const float hi = fmaf(__uint_as_float(pair & 0xFFFF0000u), s, czs);
-                    o[q] = pack_bf16x2(lo, hi);
-                }
-                *reinterpret_cast<uint4 *>(Bs + row * LDS_STRIDE + kofs + t * 8) =
-                    make_uint4(o[0], o[1], o[2], o[3]);
-            }
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int idx = tid + 256 * i;
-            const int row = idx >> 3, chunk = idx & 7;
-            *reinterpret_cast<uint4 *>(Bs + row * LDS_STRIDE + chunk * 8) = p.wb[i];
-        }
-    }
+        for (int j = 0; j < 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, acc[i][j], 0, 0, 0);
 }
 
 template <bool W4, bool OUT_F32>
-__global__ __launch_bounds__(256) void gemm_big_kernel(const void *__restrict__ wsrc,
-                                                       const uint32_t *__restrict__ sz,
-                                                       const uint16_t *__restrict__ x,
-                                                       void *__restrict__ y, int64_t M, int64_t K,
-                                                       int64_t N, int nbn, int lg_xm) {
-    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // As[2], Bs[2]
+__global__ __launch_bounds__(256) void gemm_big_kernel(const void *__restrict__ wsrc, const uint32_t *__restrict__ sz,
+                                                       const uint16_t *__restrict__ x, void *__restrict__ y,
+                                                       int64_t M, int64_t K, int64_t N, int nbn, int lg_xm) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];   // NS stages of {A, B}
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     int tm, tn;
     if (lg_xm < 0) {            // plain order: column blocks fastest
@@ -134,6 +140,73 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const void *__restrict__ 
     }
     const int64_t n0 = (int64_t)tn * BN;
     const int64_t m0 = (int64_t)tm * BM;
+    const int steps = (int)(K / BK);
+
+    // ---- direct-to-LDS loads: wave w fills rows [64 w, 64 w + 64) of an operand, 16 rows per instruction
+    const uint16_t *ga[4];
+    const uint16_t *gb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = wave * 64 + i * 16 + (lane >> 2);
+        const int chunk = swz(row, lane & 3);
+        const int64_t m = m0 + row < M ? m0 + row : M - 1;
+        ga[i] = x + m * K + chunk * 8;
+        if constexpr (!W4) {
+            const int64_t n = n0 + row < N ? n0 + row : N - 1;
+            gb[i] = reinterpret_cast<const uint16_t *>(wsrc) + n * K + chunk * 8;
+        }
+    }
+    // (the loads of a step past the end of k are issued all the same, clamped to the last step and into a
+    // stage nobody reads again: every iteration then issues the same instructions, which keeps the wait
+    // counts constant and the issue in one basic block with the LDS reads that follow).  The per-lane
+    // pointers are advanced in place, so that the address registers of the loads in flight are never
+    // reused for anything else.
+    int dma_step = 0;            // the step the pointers stand at
+    auto issue_dma = [&](int step) {
+        uint8_t *stage = lds + (step % NS) * STAGE_BYTES;
+        const int target = step < steps ? step : steps - 1;
+        const int adv = (target - dma_step) * BK;
+        dma_step = target;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            ga[i] += adv;
+            __builtin_amdgcn_global_load_lds((global_void *)ga[i], (lds_void *)(stage + (wave * 64 + i * 16) * ROW_BYTES),
+                                             16, 0, 0);
+        }
+        if constexpr (!W4) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                gb[i] += adv;
+                __builtin_amdgcn_global_load_lds((global_void *)gb[i],
+                                                 (lds_void *)(stage + OPERAND_BYTES + (wave * 64 + i * 16) * ROW_BYTES),
+                                                 16, 0, 0);
+            }
+        }
+    };
+
+    // ---- INT4 weight slices: thread -> (tile tid / 16, row j = tid % 16); the 32 weights of a k step are the
+    // 16 bytes of lane 16 c + j of the tile's block, c = (k0 % 128) / 32.  Every lane fetches its own
+    // 16 + 4 bytes into the raw ring (direct to LDS as well) and reads them back itself one step later.
+    uint8_t *raw = lds + LDS_BYTES_BF16;
+    const int wt_j = tid & 15;
+    const int64_t groups = K / kGroup;
+    int64_t wT = n0 / kTileRows + (tid >> 4);
+    const int64_t tiles_n = N / kTileRows;
+    if (wT >= tiles_n) wT = tiles_n - 1;
+    auto issue_raw = [&](int step) {
+        const int64_t k0 = (int64_t)(step < steps ? step : steps - 1) * BK;
+        const int64_t block = wT * groups + k0 / kGroup;
+        const int c = (int)((k0 % kGroup) / 32);
+        uint8_t *slot = raw + (step % NR) * RAW_BYTES;
+        __builtin_amdgcn_global_load_lds((global_void *)(reinterpret_cast<const u32x4_t *>(wsrc) + block * 64 + c * 16 + wt_j),
+                                         (lds_void *)(slot + wave * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((global_void *)(sz + block * kTileRows + wt_j),
+                                         (lds_void *)(slot + RAW_W_BYTES + wave * 256), 4, 0, 0);
+    };
+    auto dequant = [&](int step) {
+        const uint8_t *slot = raw + (step % NR) * RAW_BYTES;
+        dequant_row(slot, slot + RAW_W_BYTES, lds + (step % NS) * STAGE_BYTES + OPERAND_BYTES, tid);
+    };
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -143,42 +216,68 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const void *__restrict__ 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    Prefetch<W4> pre;
-    load_global<W4>(pre, wsrc, sz, x, M, K, N, m0, n0, 0, tid);
-    store_lds<W4>(pre, lds, lds + 2 * TILE_ELEMS, tid);
-    __syncthreads();
-    const int steps = (int)(K / BK);
-    for (int kt = 0; kt < steps; ++kt) {
-        const int cur = kt & 1;
-        const uint16_t *As = lds + cur * TILE_ELEMS;
-        const uint16_t *Bs = lds + (2 + cur) * TILE_ELEMS;
-        if (kt + 1 < steps) load_global<W4>(pre, wsrc, sz, x, M, K, N, m0, n0, (int64_t)(kt + 1) * BK, tid);
-        // fragments of k sub-step ks + 1 are requested before the MFMAs of sub-step ks
-        Frag a[2][4], b[2][4];
-        auto load_frags = [&](int set, int ks) {
-            const int kk = ks * 16 + (lane >> 5) * 8;
+    // Pipeline.  A k step has two 16-wide sub-steps; the fragments of a sub-step are read from LDS while the
+    // MFMAs of the sub-step before run, and the one barrier per step sits in the middle of the step:
+    //     read (kt, 1) | MFMA (kt, 0) | wait: loads of step kt + 1 landed, own LDS accesses done | barrier |
+    //     issue the loads of step kt + 4 into stage kt % 4 (free: everyone's reads of it are complete) |
+    //     read (kt + 1, 0) | MFMA (kt, 1)
+    // Load instructions of a wave in issue order: iteration j issues D(j + 4) (bf16: 8 instructions; INT4:
+    // A(j + 4), 4, then the raw slice R(j + 5), 2, one step further ahead because it is dequantised a step
+    // before it is multiplied).  vmcnt retires in order, so everything up to D(kt + 1) resp. R(kt + 2) has
+    // landed when at most the instructions of the two following iterations are outstanding.  The prologue
+    // issues in the same order.
+    Frag fa[2][4], fb[2][4];
+    if constexpr (W4) {
+        issue_raw(0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                a[set][i].u = *reinterpret_cast<const uint4 *>(As + (wm * 128 + i * 32 + (lane & 31)) * LDS_STRIDE + kk);
-                b[set][i].u = *reinterpret_cast<const uint4 *>(Bs + (wn * 128 + i * 32 + (lane & 31)) * LDS_STRIDE + kk);
-            }
-        };
-        load_frags(0, 0);
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            if (ks + 1 < BK / 16) load_frags((ks + 1) & 1, ks + 1);
-            __builtin_amdgcn_sched_barrier(0);   // keep the next fragments' reads ahead of these MFMAs
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i].v, b[ks & 1][j].v, acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+        for (int j = 0; j < 4; ++j) {
+            issue_dma(j);
+            issue_raw(j + 1);
         }
-        if (kt + 1 < steps)
-            store_lds<W4>(pre, lds + (cur ^ 1) * TILE_ELEMS, lds + (2 + (cur ^ 1)) * TILE_ELEMS, tid);
-        __syncthreads();
+        wait_vmcnt<24>();      // R(0) has landed (read back by the lane that fetched it: no barrier needed)
+        dequant(0);
+        wait_vmcnt<18>();      // ... A(0) and R(1) too
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) issue_dma(j);
+        wait_vmcnt<24>();
     }
+    bare_barrier();
+    load_frags(lds, 0, fa[0], fb[0], lane, wm, wn);
+
+    for (int kt = 0; kt < steps; ++kt) {
+        const uint8_t *cur = lds + (kt % NS) * STAGE_BYTES;
+        const bool more = kt + 1 < steps;                  // uniform over the workgroup
+        load_frags(cur, 1, fa[1], fb[1], lane, wm, wn);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (W4) {
+            // The raw slice of step kt + 1 landed before the previous barrier.  Unconditional (after the last
+            // step it rewrites a stage nobody reads) so that it shares a scheduling region with the MFMAs
+            // below and its ~130 VALU instructions go into their shadow: one MFMA, then eight VALU.
+            dequant(kt + 1);
+            mfma_16(fa[0], fb[0], acc);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);     // nine VALU
+            }
+        } else {
+            mfma_16(fa[0], fb[0], acc);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) {
+            wait_vmcnt<2 * (W4 ? 6 : 8)>();
+            bare_barrier();
+            load_frags(lds + ((kt + 1) % NS) * STAGE_BYTES, 0, fa[0], fb[0], lane, wm, wn);
+            __builtin_amdgcn_sched_barrier(0);
+            issue_dma(kt + 4);
+            if constexpr (W4) issue_raw(kt + 5);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_16(fa[1], fb[1], acc);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    wait_vmcnt<0>();           // the clamped loads of the last iterations are still in flight
 
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -199,11 +298,11 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const void *__restrict__ 
 }
 
 template <bool W4, bool OUT_F32>
-hipError_t launch_one(const void *wsrc, const uint32_t *sz, const uint16_t *x, int64_t M, int64_t K,
-                      int64_t N, void *y, hipStream_t stream) {
-    // once per process and kernel instantiation (thread-safe static initialisation)
+hipError_t launch_one(const void *wsrc, const uint32_t *sz, const uint16_t *x, int64_t M, int64_t K, int64_t N,
+                      void *y, hipStream_t stream) {
+    if (K / BK < 4) return hipErrorInvalidValue;
     static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_big_kernel<W4, OUT_F32>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
+                                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)(W4 ? LDS_BYTES_W4 : LDS_BYTES_BF16));
     if (attr_status != hipSuccess) return attr_status;
     // Workgroups go to the 8 XCDs round-robin by linear index and each XCD has its own L2.  When the
     // tile grid divides evenly, the index is decoded so that the 32 workgroups an XCD runs at a time
@@ -214,8 +313,8 @@ hipError_t launch_one(const void *wsrc, const uint32_t *sz, const uint16_t *x, i
     const int nbm = (int)((M + BM - 1) / BM), nbn = (int)((N + BN - 1) / BN);
     int lg_xm = 2;
     while (lg_xm >= 0 && (nbm % (4 << lg_xm) != 0 || nbn % (8 * (8 >> lg_xm)) != 0)) --lg_xm;
-    hipLaunchKernelGGL((gemm_big_kernel<W4, OUT_F32>), dim3((unsigned)(nbm * nbn)), dim3(256), LDS_BYTES, stream,
-                       wsrc, sz, x, y, M, K, N, nbn, lg_xm);
+    hipLaunchKernelGGL((gemm_big_kernel<W4, OUT_F32>), dim3((unsigned)(nbm * nbn)), dim3(256), W4 ? LDS_BYTES_W4 : LDS_BYTES_BF16, stream, wsrc,
+                       sz, x, y, M, K, N, nbn, lg_xm);
     return hipGetLastError();
 }
 
@@ -233,8 +332,8 @@ hipError_t launch_w4_gemm_big(const LayerView &L, const uint16_t *x, int64_t M, 
                    : launch_one<true, false>(L.wt, L.sz, x, M, L.K, L.N, y, stream);
 }
 
-hipError_t launch_bf16_gemm_big(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
-                                void *y, bool out_f32, hipStream_t stream) {
+hipError_t launch_bf16_gemm_big(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N, void *y,
+                                bool out_f32, hipStream_t stream) {
     return out_f32 ? launch_one<false, true>(w, nullptr, x, M, K, N, y, stream)
                    : launch_one<false, false>(w, nullptr, x, M, K, N, y, stream);
 }
