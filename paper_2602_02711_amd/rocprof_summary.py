@@ -4,6 +4,7 @@ Inputs are the files rocprofv3 writes with ``--output-format csv``:
   * ``--kernel-trace --stats``  ->  ``*_kernel_stats.csv`` and ``*_kernel_trace.csv``
   * ``--pmc FETCH_SIZE``        ->  ``*_counter_collection.csv``   (its own run)
   * ``--pmc WRITE_SIZE``        ->  ``*_counter_collection.csv``   (its own run)
+  * optionally one more ``--pmc`` run (``--pmc-dir``) whose counters are tabulated as they are
 
 FETCH_SIZE / WRITE_SIZE do not read in KiB on this chip, so both are scaled by what they read for
 a streaming kernel whose traffic is known exactly: the quantiser that bench.py runs once per
@@ -74,6 +75,7 @@ def main():
     ap.add_argument("--trace-dir", required=True)
     ap.add_argument("--fetch-dir")
     ap.add_argument("--write-dir")
+    ap.add_argument("--pmc-dir", help="a further --pmc run whose counters are tabulated as they are")
     ap.add_argument("--command", required=True, help="the full profiled command, for the record")
     ap.add_argument("--kernel", default="w4_gemv_kernel", help="substring naming the dominant kernel")
     ap.add_argument("--title", default="decode GEMV sweep (bench.py)", help="what was profiled, for the heading")
@@ -125,6 +127,24 @@ def main():
                         "traffic": (tot_f + tot_w) / tot_n, "scale_fetch": sf, "scale_write": sw})
             lines += ["", f"`{args.kernel}`: {tot_f / tot_n / 1e6:.3f} MB fetched + {tot_w / tot_n / 1e6:.4f} MB "
                           f"written per launch on average (algorithmic: 29.002 MB per launch over the four shapes).", ""]
+    if args.pmc_dir:
+        # any other counters of one --pmc run: mean per launch of every counter, per kernel of interest
+        table = collections.defaultdict(lambda: collections.defaultdict(list))
+        with open(_one(args.pmc_dir, "*_counter_collection.csv")) as fh:
+            for r in csv.DictReader(fh):
+                key = (short(r["Kernel_Name"]), int(r["Grid_Size"]), int(r["Workgroup_Size"]))
+                table[key][r["Counter_Name"]].append(float(r["Counter_Value"]))
+        names = sorted({c for cs in table.values() for c in cs})
+        lines += ["## Counters (--pmc " + " ".join(names) + "), mean per launch", "",
+                  "| kernel | grid | wg | launches | " + " | ".join(names) + " |", "|---|---|---|---|" + "---|" * len(names)]
+        for key, cs in sorted(table.items()):
+            name, grid, wg = key
+            if args.kernel not in name:
+                continue
+            n = max(len(v) for v in cs.values())
+            cells = [f"{sum(cs[c]) / len(cs[c]):.4g}" if c in cs else "" for c in names]
+            lines.append(f"| {name} | {grid} | {wg} | {n} | " + " | ".join(cells) + " |")
+        lines.append("")
     with open(args.out_md, "w") as fh:
         fh.write("\n".join(lines) + "\n")
     if args.out_json:
