@@ -320,10 +320,11 @@ hipError_t launch_one(const void *wsrc, const uint32_t *sz, const uint16_t *x, i
 
 }  // namespace
 
-// True when the 256 x 256 tiling gives every CU at least ~1.5 workgroups.
+// True when the 256 x 256 tiling gives every CU at least ~1.5 workgroups, or one round that fills at
+// least ~80 % of the 256 CUs (one workgroup is resident per CU).
 bool gemm_big_applies(int64_t M, int64_t N) {
     const int64_t wgs = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-    return wgs >= 384;
+    return wgs >= 384 || (wgs >= 208 && wgs <= 256);
 }
 
 hipError_t launch_w4_gemm_big(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,

@@ -237,7 +237,7 @@ def test_forward_wide_layers_small_batches(K, N, M):
     check_forward(y32, y16, y_ref, f"wide layer ({K},{N}) M={M}")
 
 
-@pytest.mark.parametrize("idx,M", [(1, 512), (2, 2048), (3, 2048), (0, 8192)])
+@pytest.mark.parametrize("idx,M", [(1, 512), (2, 2048), (3, 2048), (0, 8192), (2, 512), (2, 450)])
 def test_prefill_sampled_outputs_at_full_size(idx, M):
     name, K, N = synth.SWEEP_SHAPES[idx]
     _, words, s, z = quantized(synth.seed_for(3, idx, 0), N, K)
