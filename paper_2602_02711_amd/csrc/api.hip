@@ -323,7 +323,14 @@ dmr_status_t dmr_qlinear_bf16_forward(const uint16_t *d_w, const uint16_t *d_x, 
         case Bf16Path::Skinny: return hip_status(dmr::launch_bf16_skinny(d_w, d_x, M, K, N, d_y, f32, s));
         case Bf16Path::Mid: return hip_status(dmr::launch_bf16_mid(d_w, d_x, M, K, N, d_y, f32, d_ws, s));
         case Bf16Path::GemmBig: return hip_status(dmr::launch_bf16_gemm_big(d_w, d_x, M, K, N, d_y, f32, s));
-        default: return hip_status(dmr::launch_bf16_gemm(d_w, d_x, M, K, N, d_y, f32, s));
+        default: {
+            // 128 x 128 tiles: the direct-to-LDS kernel while its pipeline has room to pay (K >= 1024) and the
+            // grid is at most ~3 workgroups per CU (measured: 25-30 % ahead at 256 workgroups, level at 512,
+            // 8 % ahead at 768, 6 % behind at 1056)
+            const int64_t wgs = ((M + 127) / 128) * ((N + 127) / 128);
+            if (K >= 1024 && wgs <= 800) return hip_status(dmr::launch_bf16_gemm_dma128(d_w, d_x, M, K, N, d_y, f32, s));
+            return hip_status(dmr::launch_bf16_gemm(d_w, d_x, M, K, N, d_y, f32, s));
+        }
     }
 }
 

@@ -194,5 +194,7 @@ hipError_t launch_w4_gemm_big(const LayerView &L, const uint16_t *x, int64_t M, 
                               hipStream_t stream);
 hipError_t launch_bf16_gemm_big(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
                                 void *y, bool out_f32, hipStream_t stream);
+hipError_t launch_bf16_gemm_dma128(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
+                                   void *y, bool out_f32, hipStream_t stream);
 
 }  // namespace dmr
