@@ -27,6 +27,13 @@ def quantized(seed: int, N: int, K: int, g: int = synth.GROUP):
     return w, orc.pack(q), s, z
 
 
+def quantized3(seed: int, N: int, K: int, g: int = synth.GROUP):
+    """The 3-bit variant: seeded fp32 weights quantised by the ORACLE: (w, words3, s_bits, z_bits)."""
+    w = synth.weights_f32(seed, N, K)
+    q, s, z = orc.quantize_bits(w, g, 3)
+    return w, orc.pack3(q), s, z
+
+
 def half_ulp_bf16(values: np.ndarray) -> np.ndarray:
     a = np.abs(values)
     e = np.floor(np.log2(np.maximum(a, 2.0 ** -126)))

@@ -7,18 +7,12 @@ import paper_2602_02711_amd as dmr
 from oracle import cpu_oracle as orc
 from paper_2602_02711_amd import synth
 
-from gpu_util import bf16_dev, bits_host, half_ulp_bf16, rel_err, u32_dev
+from gpu_util import bf16_dev, bits_host, half_ulp_bf16, rel_err, u32_dev, quantized3
 
 pytestmark = pytest.mark.gpu
 G = synth.GROUP
 TOL = 1e-2
 THREADS = 16
-
-
-def quantized3(seed, N, K):
-    w = synth.weights_f32(seed, N, K)
-    q, s, z = orc.quantize_bits(w, G, 3)
-    return w, orc.pack3(q), s, z
 
 
 def make_layer3(words, s, z):
