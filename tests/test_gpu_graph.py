@@ -14,7 +14,8 @@ G = synth.GROUP
 
 
 @pytest.mark.parametrize("K,N,M", [(4096, 4096, 1), (4096, 4096, 8), (1024, 1024, 40), (4096, 4096, 128),
-                                   (4096, 28672, 48), (512, 1024, 6400)])
+                                   (4096, 28672, 48), (512, 1024, 6400), (4096, 28672, 16), (14336, 4096, 8),
+                                   (1024, 6400, 4000), (2048, 4096, 1024)])
 def test_graph_replays_match_eager(K, N, M):
     _, words, s, z = quantized(9000 + K + N, N, K)
     layer = dmr.dmr_qlinear_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
