@@ -287,6 +287,20 @@ def test_bf16_forward_small_integers_exact():
         assert np.array_equal(y32.astype(np.float64), y_ref), M
 
 
+@pytest.mark.parametrize("M", [1, 8, 40, 300])
+def test_int4_vocabulary_sized_layer_sampled(M):
+    # the largest N of the model (8016 weight tiles): every kernel class at a grid far beyond the decoder layers'
+    name, K, N = synth.LM_HEAD
+    _, words, s, z = quantized(synth.seed_for(4, 5, 0), N, K)
+    x = synth.activations_bf16(synth.seed_for(4, 5, 1) + M, M, K)
+    y32 = dmr.dmr_qlinear_forward(make_layer(words, s, z), bf16_dev(x), out_dtype=torch.float32).cpu().numpy()
+    ms, ns = sample_pairs(M, N, 77 + M)
+    y_ref = orc.forward_sampled(words, s, z, G, x, ms, ns)
+    err = float(np.max(np.abs(y32[ms, ns].astype(np.float64) - y_ref)) / np.sqrt(np.mean(y_ref ** 2)))
+    print(f"int4 {name}-sized layer M={M}: sampled max err {err:.3e} rms over {len(ms)} outputs")
+    assert err <= TOL
+
+
 def test_bf16_lm_head_shape_sampled():
     name, K, N = synth.LM_HEAD
     w = synth.to_bf16_bits(synth.weights_f32(synth.seed_for(4, 4, 0), N, K))
