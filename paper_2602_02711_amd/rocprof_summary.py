@@ -90,8 +90,8 @@ def main():
              "| kernel | grid | wg | calls | mean | min | max |", "|---|---|---|---|---|---|---|"]
     dom_calls = dom_total = 0.0
     for (name, grid, wg), (n, mean, lo, hi) in sorted(stats.items(), key=lambda kv: -kv[1][0] * kv[1][1]):
-        if any(tag in name for tag in ("gemv", "skinny", "gemm", "mid_kernel", "stream", "splitk", "rmsnorm",
-                                       "swiglu", "residual", "xfrag")):
+        if any(tag in name for tag in ("gemv", "skinny", "gemm", "mid_kernel", "stream", "panel", "wide", "splitk",
+                                       "rmsnorm", "swiglu", "residual", "xfrag")):
             lines.append(f"| {name} | {grid} | {wg} | {n} | {mean:.2f} | {lo:.2f} | {hi:.2f} |")
         if args.kernel in name:
             dom_calls += n
