@@ -23,11 +23,9 @@ __device__ __forceinline__ float dot8(const uint4 &w, const uint4 &x, float acc)
     return acc;
 }
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-    return v;
-}
+// Sum over the 64 lanes, the same value in every lane: DPP row sums, then the four row sums through
+// scalar registers (no LDS round trips, unlike a shuffle butterfly).
+__device__ __forceinline__ float wave_sum(float v) { return wave64_sum(v); }
 
 constexpr int kWaves = 4;   // wavefronts per workgroup
 

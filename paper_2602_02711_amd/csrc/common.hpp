@@ -69,6 +69,11 @@ template <int N>
 __device__ __forceinline__ float row_ror_add(float v) {
     return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xF, 0xF, false));
 }
+// v as seen through a DPP control word (quad_perm, row_mirror, ...), all lanes and banks enabled.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
 __device__ __forceinline__ float row16_sum(float v) {
     v = row_ror_add<8>(v);
     v = row_ror_add<4>(v);

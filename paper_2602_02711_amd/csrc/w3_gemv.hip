@@ -155,13 +155,16 @@ __global__ __launch_bounds__(1024) void w3_gemv_kernel(const uint32_t *__restric
     if (lgS == 0) return;
 
     // Cross-slice sum: thread e = (slot, column, slice) with the slice index fastest, so the S
-    // partials of one output sit in S adjacent lanes and fold in a fixed xor tree.
+    // partials of one output sit in S adjacent lanes and fold by DPP adds in a fixed order.
     __syncthreads();
     const int total = (nT_max << (lgTW + lgS)) * 16;
     for (int e = threadIdx.x; e < total; e += blockDim.x) {
         const int q = e & (S - 1), col = (e >> lgS) & 15, slot = e >> (lgS + 4);
         float v = red[((slot << lgS) + q) * 16 + col];
-        for (int m = S >> 1; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+        if (S >= 2) v += dpp_move<0xB1>(v);       // quad_perm [1, 0, 3, 2]
+        if (S >= 4) v += dpp_move<0x4E>(v);       // quad_perm [2, 3, 0, 1]
+        if (S >= 8) v += dpp_move<0x141>(v);      // row_half_mirror
+        if (S >= 16) v += dpp_move<0x140>(v);     // row_mirror
         const int tile = ((int)blockIdx.x << lgTW) + (slot & (TW - 1)) + (slot >> lgTW) * t_step;
         if (q == 0 && tile < tiles) {
             const int64_t n = (int64_t)tile * kTileRows + col;
