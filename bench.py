@@ -300,47 +300,6 @@ def chain_step(args, dmr, synth, torch, dev):
             torch.cuda.synchronize()
             return e0.elapsed_time(e1) / args.steps
 
-    # The same chain as ONE resident grid (M = 1 only): the stages of the fused variant, on the same buffers.
-    chain = None
-    if M == 1:
-        hb = list(bufs["h"])
-        stages = []
-        for li in range(LAYERS):
-            h, h1, h2 = hb
-            g1, g2 = gammas[li][0], gammas[li][1]
-            L = int4[li]
-            stages += [dict(layer=L["qkv"], pro=R, inp=h, gamma=g1, eps=EPS, out=bufs["qkv"]),
-                       dict(layer=L["attn_out"], pro=NONE, inp=bufs["qkv"][:, :H], residual=h, out=h1),
-                       dict(layer=L["gate_up"], pro=R, inp=h1, gamma=g2, eps=EPS, out=bufs["gu"]),
-                       dict(layer=L["down"], pro=S, inp=bufs["gu"], residual=h1, out=h2)]
-            hb = [h2, h1, h]
-        chain = dmr.dmr_chain_create(stages)
-        chain_out = hb[0]
-
-    def step_persistent():
-        bufs["h"][0].copy_(h0)
-        dmr.dmr_chain_forward(chain)
-        return chain_out
-
-    def timed_persistent():
-        with torch.cuda.stream(stream):
-            for _ in range(args.warmup):
-                step_persistent()
-            stream.synchronize()
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=stream):
-                for _ in range(args.steps):
-                    step_persistent()
-            for _ in range(2):
-                graph.replay()
-            stream.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            graph.replay()
-            e1.record(stream)
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / args.steps
-
     with torch.cuda.stream(stream):
         # consistency of the fused kernels with the unfused composition, over the first decoder layer
         # (over all 32 the bf16 residual stream amplifies single-ulp differences: informational only)
@@ -352,19 +311,6 @@ def chain_step(args, dmr, synth, torch, dev):
     drift1 = float((ref1 - got1).abs().max() / ref1.pow(2).mean().sqrt())
     drift = float((ref - got).abs().max() / ref.pow(2).mean().sqrt())
     times = {(low, fused): timed(low, fused) for low in (True, False) for fused in (True, False)}
-    persistent = None
-    if chain is not None:
-        with torch.cuda.stream(stream):
-            fused_final = step(True, True).float().clone()
-            pers_final = step_persistent().float().clone()
-            stream.synchronize()
-        t_p = timed_persistent()
-        persistent = {"us_per_step": round(t_p * 1e3, 1),
-                      "speedup_vs_fused_launches": round(times[(True, True)] / t_p, 3),
-                      "int4_GBps": round(LAYERS * sum(int4_bytes(K, N, M) for _, K, N in synth.LAYER_SHAPES) / (t_p * 1e-3) / 1e9, 1),
-                      "timed_out": bool(dmr.dmr_chain_timed_out(chain)),
-                      "vs_fused_launches_hidden_max_diff_over_rms":
-                          round(float((fused_final - pers_final).abs().max() / fused_final.pow(2).mean().sqrt()), 5)}
     b4 = LAYERS * sum(int4_bytes(K, N, M) for _, K, N in synth.LAYER_SHAPES)
     t = times[(True, True)]
     result = {
@@ -381,7 +327,6 @@ def chain_step(args, dmr, synth, torch, dev):
         "speedup_fused_vs_unfused_int4": round(times[(True, False)] / times[(True, True)], 3),
         "speedup_int4_vs_bf16_fused": round(times[(False, True)] / times[(True, True)], 3),
         "int4_GBps_fused": round(b4 / (t * 1e-3) / 1e9, 1),
-        "persistent_grid": persistent,
         "fused_vs_unfused_hidden_max_diff_over_rms": {"after_1_layer": round(drift1, 5),
                                                       "after_32_layers": round(drift, 5)},
     }

@@ -165,52 +165,6 @@ dmr_status_t dmr_qlinear_bf16_forward_fused(const uint16_t *d_w, dmr_prologue_t 
                                             void *stream);
 
 /*
- * A whole decode step of the low-precision copy as one launch (App. B: at M = 1 the cost of a step is
- * one pass over the weights; with one launch per Linear the memory system runs empty at every launch
- * boundary, which at these layer sizes is a third of the step).  A chain is a list of stages, each
- * exactly one dmr_qlinear_forward_fused call at M = 1 (4-bit layer, prologue, optional residual),
- * executed in order by a single grid that stays resident: stage i + 1 may read what any earlier stage
- * wrote (its d_in or d_residual), a grid-wide barrier separates the stages, and the weights of the next
- * stage are already streaming while the barrier completes.  Results are those of the per-stage calls up
- * to the order of the fp32 additions over k.
- *
- *   d_state   device memory of dmr_chain_state_bytes(n_stages) bytes, 16-byte aligned, owned by the caller
- *             and private to this chain until it is destroyed (stage table and barrier counter).
- *   stages    host array, copied; the device pointers in it are used by every later dmr_chain_forward,
- *             so the step's activation buffers are fixed when the chain is built.  Within one stage
- *             d_y must not overlap d_in or d_residual.  Layers: 4 bits, 2048 <= K <= 16384.
- *   create    synchronous (one small host-to-device copy); DMR_ERR_UNSUPPORTED for a layer outside the
- *             range above or when the grid cannot be made resident.
- *   forward   enqueues two kernels on `stream` (counter reset, chain); capturable in a HIP graph.  The
- *             grid occupies every CU until it ends: run nothing else on the device beside it.  Two
- *             forwards of one chain must not overlap.
- *   barrier   the wait at a barrier is bounded (about 2^18 polls); if a workgroup ever gives up, all
- *             later barriers open at once, the launch ends normally with meaningless outputs, and the
- *             sticky flag dmr_chain_timed_out reads (after synchronising `stream`) is 1.
- *             dmr_chain_set_spin_limit changes the bound (0 = give up at the first unsuccessful poll;
- *             meant for testing the time-out path).
- */
-#define DMR_CHAIN_MAX_STAGES 512
-typedef struct dmr_chain dmr_chain_t; /* opaque, lives in host memory */
-typedef struct {
-    const dmr_qlinear_t *layer;
-    dmr_prologue_t pro;
-    const uint16_t *d_in;       /* bf16 [K], or [2 K] with DMR_PRO_SWIGLU */
-    const uint16_t *d_gamma;    /* bf16 [K] with DMR_PRO_RMSNORM, else ignored */
-    float eps;
-    const uint16_t *d_residual; /* bf16 [N] or NULL */
-    void *d_y;                  /* [N] of the type `out` names */
-    dmr_out_t out;
-} dmr_chain_stage_t;
-size_t dmr_chain_state_bytes(int32_t n_stages);
-dmr_status_t dmr_chain_create(dmr_chain_t **out, const dmr_chain_stage_t *stages, int32_t n_stages,
-                              void *d_state, size_t state_bytes);
-dmr_status_t dmr_chain_forward(const dmr_chain_t *chain, void *stream);
-dmr_status_t dmr_chain_timed_out(const dmr_chain_t *chain, void *stream, int32_t *timed_out);
-dmr_status_t dmr_chain_set_spin_limit(dmr_chain_t *chain, int32_t polls);
-void dmr_chain_destroy(dmr_chain_t *chain);
-
-/*
  * Offline step that produces the low-precision copy (App. E names AWQ/GPTQ; this is plain
  * asymmetric round-to-nearest, which yields the same format): fp32 weights [N][K] to canonical
  * qweight / scales / zeros.  Per (row, group): lo = min(w, 0), hi = max(w, 0),

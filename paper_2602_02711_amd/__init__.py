@@ -4,8 +4,7 @@ The product is ``libdmr_qlinear.so`` (hand-written gfx950 kernels behind the C A
 ``include/dmr_qlinear.h``); this package holds its sources, its build step, a thin binding with
 the same names, and the seeded input generators.
 """
-from .binding import (Chain, dmr_chain_create, dmr_chain_forward, dmr_chain_set_spin_limit,
-                      dmr_chain_state_bytes, dmr_chain_timed_out, DMR_OUT_BF16, DMR_OUT_FP32, DMR_PRO_NONE, DMR_PRO_RMSNORM, DMR_PRO_SWIGLU, DmrError, Layer,
+from .binding import (DMR_OUT_BF16, DMR_OUT_FP32, DMR_PRO_NONE, DMR_PRO_RMSNORM, DMR_PRO_SWIGLU, DmrError, Layer,
                       dmr_glue_rmsnorm, dmr_glue_swiglu, dmr_probe_hbm_read, dmr_qlinear_bf16_forward,
                       dmr_qlinear_bf16_forward_fused, dmr_qlinear_bf16_workspace_bytes, dmr_qlinear_create,
                       dmr_qlinear_create_per_channel, dmr_qlinear_dequantize, dmr_qlinear_destroy,
@@ -21,6 +20,5 @@ __all__ = [
     "dmr_qlinear_create_per_channel", "dmr_qlinear_dequantize", "dmr_qlinear_destroy", "dmr_qlinear_forward",
     "dmr_qlinear_forward_fused", "dmr_qlinear_quantize", "dmr_qlinear_quantize_w3", "dmr_qlinear_storage_bytes",
     "dmr_qlinear_w3_create", "dmr_qlinear_w3_storage_bytes", "dmr_qlinear_w3_workspace_bytes",
-    "dmr_qlinear_workspace_bytes", "Chain", "dmr_chain_create", "dmr_chain_forward", "dmr_chain_set_spin_limit",
-    "dmr_chain_state_bytes", "dmr_chain_timed_out",
+    "dmr_qlinear_workspace_bytes",
 ]

@@ -28,18 +28,9 @@ EXPORTS = (
     "dmr_qlinear_w3_create", "dmr_qlinear_quantize_w3", "dmr_qlinear_bits", "dmr_qlinear_create_per_channel",
     "dmr_glue_rmsnorm", "dmr_glue_swiglu", "dmr_qlinear_fused_workspace_bytes",
     "dmr_qlinear_bf16_fused_workspace_bytes", "dmr_qlinear_forward_fused", "dmr_qlinear_bf16_forward_fused",
-    "dmr_chain_state_bytes", "dmr_chain_create", "dmr_chain_forward", "dmr_chain_timed_out",
-    "dmr_chain_set_spin_limit", "dmr_chain_destroy",
 )
 
 DMR_PRO_NONE, DMR_PRO_RMSNORM, DMR_PRO_SWIGLU = 0, 1, 2
-
-
-class _ChainStage(ctypes.Structure):
-    """dmr_chain_stage_t."""
-    _fields_ = [("layer", ctypes.c_void_p), ("pro", ctypes.c_int), ("d_in", ctypes.c_void_p),
-                ("d_gamma", ctypes.c_void_p), ("eps", ctypes.c_float), ("d_residual", ctypes.c_void_p),
-                ("d_y", ctypes.c_void_p), ("out", ctypes.c_int)]
 
 
 class DmrError(RuntimeError):
@@ -111,14 +102,6 @@ def lib() -> ctypes.CDLL:
                                                      ctypes.c_int, vp, sz, vp]
         L.dmr_status_string.restype = ctypes.c_char_p
         L.dmr_status_string.argtypes = [ctypes.c_int]
-        L.dmr_chain_state_bytes.restype = sz
-        L.dmr_chain_state_bytes.argtypes = [i32]
-        L.dmr_chain_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(_ChainStage), i32, vp, sz]
-        L.dmr_chain_forward.argtypes = [vp, vp]
-        L.dmr_chain_timed_out.argtypes = [vp, vp, ctypes.POINTER(i32)]
-        L.dmr_chain_set_spin_limit.argtypes = [vp, i32]
-        L.dmr_chain_destroy.restype = None
-        L.dmr_chain_destroy.argtypes = [vp]
         _lib = L
     return _lib
 
@@ -437,62 +420,3 @@ def dmr_qlinear_bf16_forward_fused(w: torch.Tensor, pro: int, inp: torch.Tensor,
     _check(lib().dmr_qlinear_bf16_forward_fused(pw_, pro, pi, pg, float(eps), pr, M, K, N, po, _out_code(out.dtype),
                                                 pws, wbytes, _stream(stream)), "dmr_qlinear_bf16_forward_fused")
     return out
-
-
-class Chain:
-    """Host handle of a persistent decode chain; keeps the tensors its stages point to alive."""
-
-    def __init__(self, handle: int, state: torch.Tensor, keep):
-        self.handle, self.state, self._keep = handle, state, keep
-
-    def __del__(self):
-        if getattr(self, "handle", None):
-            lib().dmr_chain_destroy(self.handle)
-            self.handle = None
-
-
-def dmr_chain_state_bytes(n_stages: int) -> int:
-    return int(lib().dmr_chain_state_bytes(n_stages))
-
-
-def dmr_chain_create(stages) -> Chain:
-    """``stages``: sequence of dicts with keys layer, pro, inp, out and optionally gamma, eps, residual
-    (the arguments of ``dmr_qlinear_forward_fused`` at M = 1, with fixed buffers)."""
-    n = len(stages)
-    arr = (_ChainStage * max(n, 1))()
-    keep = []
-    for i, st in enumerate(stages):
-        layer, out = st["layer"], st["out"]
-        gamma, res = st.get("gamma"), st.get("residual")
-        arr[i].layer = layer.handle
-        arr[i].pro = int(st.get("pro", DMR_PRO_NONE))
-        arr[i].d_in = _dev(st["inp"], "inp", _BF16)
-        arr[i].d_gamma = _dev(gamma, "gamma", _BF16) if gamma is not None else None
-        arr[i].eps = float(st.get("eps", 0.0))
-        arr[i].d_residual = _dev(res, "residual", _BF16) if res is not None else None
-        arr[i].d_y = _dev(out, "out", (torch.bfloat16, torch.float32))
-        arr[i].out = _out_code(out.dtype)
-        width = 2 * layer.K if arr[i].pro == DMR_PRO_SWIGLU else layer.K
-        if st["inp"].numel() != width or out.numel() != layer.N or (res is not None and res.numel() != layer.N) \
-                or (gamma is not None and gamma.numel() != layer.K):
-            raise ValueError(f"stage {i}: buffer sizes do not match the layer ({layer.K}, {layer.N})")
-        keep.append((layer, st["inp"], gamma, res, out))
-    nbytes = dmr_chain_state_bytes(n)
-    state = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=stages[0]["out"].device if n else "cuda")
-    handle = ctypes.c_void_p()
-    _check(lib().dmr_chain_create(ctypes.byref(handle), arr, n, state.data_ptr(), nbytes), "dmr_chain_create")
-    return Chain(handle.value, state, keep)
-
-
-def dmr_chain_forward(chain: Chain, stream=None) -> None:
-    _check(lib().dmr_chain_forward(chain.handle, _stream(stream)), "dmr_chain_forward")
-
-
-def dmr_chain_timed_out(chain: Chain, stream=None) -> bool:
-    flag = ctypes.c_int32(0)
-    _check(lib().dmr_chain_timed_out(chain.handle, _stream(stream), ctypes.byref(flag)), "dmr_chain_timed_out")
-    return bool(flag.value)
-
-
-def dmr_chain_set_spin_limit(chain: Chain, polls: int) -> None:
-    _check(lib().dmr_chain_set_spin_limit(chain.handle, polls), "dmr_chain_set_spin_limit")

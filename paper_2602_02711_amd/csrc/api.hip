@@ -1,8 +1,5 @@
 // C ABI of dmr_qlinear.h: argument checks (all before the first HIP call), the host handle, and
 // the choice of kernel by M.  No device memory is allocated here or anywhere in the library.
-#include <vector>
-
-#include "chain.hpp"
 #include <new>
 
 #include "glue.hpp"
@@ -16,10 +13,6 @@ struct dmr_qlinear {
     const uint4 *wt;        // 4-bit streaming blocks
     const uint32_t *wt3;    // 3-bit streaming blocks
     const uint32_t *sz;
-};
-
-struct dmr_chain {
-    dmr::ChainLaunch launch;
 };
 
 namespace {
@@ -527,86 +520,6 @@ dmr_status_t dmr_probe_hbm_read(const void *d_buf, size_t bytes, uint32_t *d_sin
     if (!aligned16(d_buf) || !aligned16(d_sink)) return DMR_ERR_ALIGN;
     return hip_status(dmr::launch_hbm_read_probe(d_buf, bytes, d_sink, blocks, static_cast<hipStream_t>(stream)));
 }
-
-size_t dmr_chain_state_bytes(int32_t n_stages) {
-    if (n_stages < 1 || n_stages > DMR_CHAIN_MAX_STAGES) return 0;
-    return dmr::kChainControlBytes + (size_t)n_stages * sizeof(dmr::ChainStage);
-}
-
-dmr_status_t dmr_chain_create(dmr_chain_t **out, const dmr_chain_stage_t *stages, int32_t n_stages, void *d_state,
-                              size_t state_bytes) {
-    if (!out || !stages || !d_state) return DMR_ERR_NULL;
-    *out = nullptr;
-    if (n_stages < 1 || n_stages > DMR_CHAIN_MAX_STAGES) return DMR_ERR_SHAPE;
-    if (!aligned16(d_state)) return DMR_ERR_ALIGN;
-    if (state_bytes < dmr_chain_state_bytes(n_stages)) return DMR_ERR_WORKSPACE;
-    std::vector<dmr::ChainStage> table((size_t)n_stages);
-    int g_max = 0, tiles_max = 0;
-    for (int32_t i = 0; i < n_stages; ++i) {
-        const dmr_chain_stage_t &st = stages[i];
-        if (!st.layer) return DMR_ERR_NULL;
-        const dmr_status_t chk = check_fused(st.pro, st.d_in, st.d_gamma, st.eps, st.d_residual, 1, st.d_y, st.out, nullptr);
-        if (chk != DMR_OK) return chk;
-        const int64_t groups = st.layer->K / dmr::kGroup, tiles = st.layer->N / dmr::kTileRows;
-        if (st.layer->bits != 4 || groups < dmr::kChainMinGroups || groups > dmr::kChainMaxGroups ||
-            tiles > (int64_t(1) << 20))
-            return DMR_ERR_UNSUPPORTED;
-        dmr::ChainStage &t = table[(size_t)i];
-        t.wt = st.layer->wt;
-        t.sz = st.layer->sz;
-        t.in = st.d_in;
-        t.aux = st.d_gamma;
-        t.res = st.d_residual;
-        t.out = st.d_y;
-        t.groups = (int32_t)groups;
-        t.tiles = (int32_t)tiles;
-        t.flags = (int32_t)st.pro | (st.out == DMR_OUT_FP32 ? 0x100 : 0);
-        t.eps = st.eps;
-        g_max = groups > g_max ? (int)groups : g_max;
-        tiles_max = tiles > tiles_max ? (int)tiles : tiles_max;
-    }
-    dmr::ChainLaunch c{};
-    c.ctl = static_cast<uint32_t *>(d_state);
-    c.tab = reinterpret_cast<const dmr::ChainStage *>(static_cast<const uint8_t *>(d_state) + dmr::kChainControlBytes);
-    c.n_stages = n_stages;
-    c.x16_cap = g_max * 16;
-    c.g_cap = (g_max + 3) & ~3;
-    c.spin_limit = 1 << 18;
-    // one workgroup per CU; the tiles of a stage go round-robin over them
-    c.grid = dmr::compute_units() < dmr::kChainMaxGrid ? dmr::compute_units() : dmr::kChainMaxGrid;
-    c.nt_cap = (tiles_max + c.grid - 1) / c.grid;
-    if (c.grid > dmr::chain_resident_grid(dmr::chain_lds_bytes(c))) return DMR_ERR_UNSUPPORTED;
-    if (hipMemset(d_state, 0, dmr::kChainControlBytes) != hipSuccess ||
-        hipMemcpy(const_cast<dmr::ChainStage *>(c.tab), table.data(), table.size() * sizeof(dmr::ChainStage),
-                  hipMemcpyHostToDevice) != hipSuccess)
-        return DMR_ERR_HIP;
-    *out = new dmr_chain{c};
-    return DMR_OK;
-}
-
-dmr_status_t dmr_chain_forward(const dmr_chain_t *chain, void *stream) {
-    if (!chain) return DMR_ERR_NULL;
-    return hip_status(dmr::launch_w4_chain(chain->launch, static_cast<hipStream_t>(stream)));
-}
-
-dmr_status_t dmr_chain_timed_out(const dmr_chain_t *chain, void *stream, int32_t *timed_out) {
-    if (!chain || !timed_out) return DMR_ERR_NULL;
-    uint32_t flag = 0;
-    if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess ||
-        hipMemcpy(&flag, chain->launch.ctl + dmr::kChainTimeoutWord, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess)
-        return DMR_ERR_HIP;
-    *timed_out = flag != 0;
-    return DMR_OK;
-}
-
-dmr_status_t dmr_chain_set_spin_limit(dmr_chain_t *chain, int32_t polls) {
-    if (!chain) return DMR_ERR_NULL;
-    if (polls < 0) return DMR_ERR_SHAPE;
-    chain->launch.spin_limit = polls;
-    return DMR_OK;
-}
-
-void dmr_chain_destroy(dmr_chain_t *chain) { delete chain; }
 
 void dmr_qlinear_destroy(dmr_qlinear_t *layer) { delete layer; }
 
