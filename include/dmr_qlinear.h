@@ -180,10 +180,10 @@ dmr_status_t dmr_qlinear_quantize(int64_t K, int64_t N, int32_t g, const float *
  * which it could only run fake-quantised and whose cost it projected as T_W4 / 1.15 (App. A).  Format:
  * codes 0..7, 32 per three words along k (code j in bits [3j, 3j+3) of the 96-bit little-endian run),
  * qweight3 uint32 [N][3K/32]; scales and zeros as for 4 bits, zero points 0..7.  The handle these
- * calls return is used with dmr_qlinear_dequantize / _forward / _destroy like a 4-bit one.  M <= 16
- * runs native weight-streaming kernels (d_ws only for fp32 partial sums when K is long and split);
- * larger M dequantises the layer into d_ws and takes the bf16 path.  d_ws as
- * dmr_qlinear_w3_workspace_bytes says.
+ * calls return is used with dmr_qlinear_dequantize / _forward / _destroy like a 4-bit one.  Decode and
+ * rollout batches (M up to 128, more on narrow layers) run native kernels that unpack the 3-bit codes in
+ * registers (d_ws only for fp32 partial sums where K is split); prefill-sized M dequantises the layer
+ * into d_ws and takes the bf16 path.  d_ws as dmr_qlinear_w3_workspace_bytes says.
  */
 size_t dmr_qlinear_w3_storage_bytes(int64_t K, int64_t N, int32_t g);
 size_t dmr_qlinear_w3_workspace_bytes(int64_t M, int64_t K, int64_t N);

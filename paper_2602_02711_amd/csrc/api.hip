@@ -38,6 +38,14 @@ W4Path w4_path(int64_t M, int64_t K, int64_t N) {
     return (M <= 128 || gemm_wgs < 300) ? W4Path::Mid : W4Path::Gemm;
 }
 
+// 3-bit layers: the rollout-batch kernel serves every row count that the 4-bit dispatch does not hand to a tiled
+// GEMM (there the layer is dequantised to bf16 first), and 2..16 rows that fit neither streaming kernel.
+bool w3_uses_mid(int64_t M, int64_t K, int64_t N) {
+    if (M < 2) return false;
+    const int64_t gemm_wgs = ((M + 127) / 128) * ((N + 127) / 128);
+    return M <= 128 || gemm_wgs < 300;
+}
+
 // The bf16 twin: GEMV, the direct-from-L2 skinny kernel for 2..8 rows (measured faster there than the
 // LDS-staged kernels), then the same size classes as INT4.
 enum class Bf16Path { Gemv, Stream, Skinny, Mid, GemmBig, Gemm };
@@ -175,6 +183,7 @@ size_t dmr_qlinear_w3_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     if (M <= 1 || K <= 0 || N <= 0) return 0;
     if (M <= 16 && dmr::w4_stream_fits(M, K, N)) return 0;      // native streaming kernel
     if (M <= 16 && dmr::w4_panel_applies(M, K, N)) return dmr::w4_panel_workspace_bytes(M, K, N);   // k-sliced panels
+    if (w3_uses_mid(M, K, N)) return dmr::w4_mid_workspace_bytes(M, K, N);                          // rollout batches
     // otherwise the layer is dequantised to bf16 there first; the bf16 path's own scratch follows
     return (size_t)N * (size_t)K * 2 + dmr_qlinear_bf16_workspace_bytes(M, K, N);
 }
@@ -260,8 +269,11 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
             const hipError_t e = dmr::launch_w3_panel(L3, d_x, M, d_y, f32, d_ws, s);
             if (e != hipErrorInvalidValue) return hip_status(e);
         }
-        // larger M (or a shape outside the streaming kernels' range): dequantise into the workspace, then
-        // the bf16 path
+        if (w3_uses_mid(M, layer->K, layer->N)) {
+            if (ws_bytes < dmr::w4_mid_workspace_bytes(M, layer->K, layer->N)) return DMR_ERR_WORKSPACE;
+            return hip_status(dmr::launch_w3_mid(L3, d_x, M, d_y, f32, d_ws, s));
+        }
+        // prefill-sized M: dequantise into the workspace, then the bf16 path
         const size_t need3 = dmr_qlinear_w3_workspace_bytes(M, layer->K, layer->N);
         if (!d_ws || ws_bytes < need3) return DMR_ERR_WORKSPACE;
         const hipError_t e = dmr::launch_dequantize3(L3, static_cast<uint16_t *>(d_ws), s);

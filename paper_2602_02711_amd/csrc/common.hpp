@@ -167,6 +167,9 @@ hipError_t launch_w4_skinny2(const LayerView &L, const uint16_t *x, int64_t M, v
 size_t w4_mid_workspace_bytes(int64_t M, int64_t K, int64_t N);
 hipError_t launch_w4_mid(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
                          hipStream_t stream);
+// The same kernel on a 3-bit layer (same plan and workspace as launch_w4_mid).
+hipError_t launch_w3_mid(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
+                         hipStream_t stream);
 // bf16 twin of launch_w4_mid.
 size_t bf16_mid_workspace_bytes(int64_t M, int64_t K, int64_t N);
 hipError_t launch_bf16_mid(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N, void *y,

@@ -16,9 +16,12 @@
 // Small N x M leaves too few (row block, column block) pairs for the chip; then K is split over
 // blockIdx.z, each split writes an fp32 partial tile to the caller's workspace and a second kernel
 // adds the partials in ascending split order (deterministic, no atomics).
+//
+// BITS = 3 runs the same kernel on the 3-bit streaming layout (768-byte blocks, three words per lane).
 #include <algorithm>
 
 #include "mid_plan.hpp"
+#include "w3_unpack.hpp"
 
 namespace dmr {
 
@@ -28,9 +31,9 @@ constexpr int ROW_BYTES = 272;   // one activation row of a group in LDS: 128 bf
 
 
 // out_mode: 0 = fp32 y, 1 = bf16 y, 2 = fp32 partial [split][M][N]
-template <int MTW, int WM, int NW, int R>
+template <int MTW, int WM, int NW, int R, int BITS>
 __global__ __launch_bounds__(64 * WM * NW, (WM * NW == 4) ? 2 : 1) void w4_mid_kernel(
-    const uint4 *__restrict__ wt, const uint32_t *__restrict__ sz, const uint16_t *__restrict__ x,
+    const void *__restrict__ wt, const uint32_t *__restrict__ sz, const uint16_t *__restrict__ x,
     void *__restrict__ y, int M, int64_t K, int64_t N, int groups, int tiles, int gps, int out_mode) {
     constexpr int THREADS = 64 * WM * NW;
     constexpr int BM = 16 * MTW * WM;
@@ -54,7 +57,7 @@ __global__ __launch_bounds__(64 * WM * NW, (WM * NW == 4) ? 2 : 1) void w4_mid_k
     for (int rt = 0; rt < R; ++rt) wbase[rt] = (int64_t)min(tile0 + rt, tiles - 1) * groups;
 
     struct Slot {
-        uint4 w[R];
+        uint4 w[R];            // BITS == 3: .x .y .z hold the lane's three words
         uint32_t s[R];
     };
     Slot ring[4];
@@ -62,7 +65,14 @@ __global__ __launch_bounds__(64 * WM * NW, (WM * NW == 4) ? 2 : 1) void w4_mid_k
 #pragma unroll
         for (int rt = 0; rt < R; ++rt) {
             const int64_t block = wbase[rt] + g;
-            s.w[rt] = load_stream(wt + block * 64 + lane);
+            if constexpr (BITS == 4) {
+                s.w[rt] = load_stream(static_cast<const uint4 *>(wt) + block * 64 + lane);
+            } else {
+                const uint32_t *pw = static_cast<const uint32_t *>(wt) + (block * 64 + lane) * 3;
+                s.w[rt].x = load_stream(pw);
+                s.w[rt].y = load_stream(pw + 1);
+                s.w[rt].z = load_stream(pw + 2);
+            }
             s.s[rt] = sz[block * kTileRows + j];
         }
     };
@@ -119,9 +129,16 @@ __global__ __launch_bounds__(64 * WM * NW, (WM * NW == 4) ? 2 : 1) void w4_mid_k
                 xs[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mt].v, ones.v, xs[mt], 0, 0, 0);
 #pragma unroll
             for (int rt = 0; rt < R; ++rt) {
-                const uint32_t word = t == 0 ? s.w[rt].x : t == 1 ? s.w[rt].y : t == 2 ? s.w[rt].z : s.w[rt].w;
                 Frag b;
-                unpack_word(word, b.w);
+                if constexpr (BITS == 4) {
+                    const uint32_t word = t == 0 ? s.w[rt].x : t == 1 ? s.w[rt].y : t == 2 ? s.w[rt].z : s.w[rt].w;
+                    unpack_word(word, b.w);
+                } else {
+                    if (t == 0) unpack3_step<0>(s.w[rt].x, s.w[rt].y, s.w[rt].z, b.w);
+                    if (t == 1) unpack3_step<1>(s.w[rt].x, s.w[rt].y, s.w[rt].z, b.w);
+                    if (t == 2) unpack3_step<2>(s.w[rt].x, s.w[rt].y, s.w[rt].z, b.w);
+                    if (t == 3) unpack3_step<3>(s.w[rt].x, s.w[rt].y, s.w[rt].z, b.w);
+                }
 #pragma unroll
                 for (int mt = 0; mt < MTW; ++mt)
                     d[rt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mt].v, b.v, d[rt][mt], 0, 0, 0);
@@ -206,29 +223,55 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
     }
 }
 
-template <int MTW, int WM, int NW, int R>
-hipError_t launch_cfg(const LayerView &L, const uint16_t *x, int M, void *dst, int out_mode, const MidPlan &p,
-                      hipStream_t stream) {
+template <int MTW, int WM, int NW, int R, int BITS>
+hipError_t launch_cfg(const void *wt, const uint32_t *sz, int64_t K, int64_t N, const uint16_t *x, int M, void *dst,
+                      int out_mode, const MidPlan &p, hipStream_t stream) {
     constexpr int BM = 16 * MTW * WM;
     constexpr size_t lds = 2ull * BM * ROW_BYTES;
     // once per process and kernel instantiation (thread-safe static initialisation)
-    static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_mid_kernel<MTW, WM, NW, R>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static const hipError_t attr_status = hipFuncSetAttribute(
+        reinterpret_cast<const void *>(&w4_mid_kernel<MTW, WM, NW, R, BITS>), hipFuncAttributeMaxDynamicSharedMemorySize,
+        (int)lds);
     if (attr_status != hipSuccess) return attr_status;
-    const int groups = (int)(L.K / kGroup), tiles = (int)(L.N / kTileRows);
+    const int groups = (int)(K / kGroup), tiles = (int)(N / kTileRows);
     const dim3 grid((unsigned)((tiles + NW * R - 1) / (NW * R)), (unsigned)((M + BM - 1) / BM), (unsigned)p.SK);
-    hipLaunchKernelGGL((w4_mid_kernel<MTW, WM, NW, R>), grid, dim3(64 * WM * NW), lds, stream, L.wt, L.sz, x, dst, M,
-                       L.K, L.N, groups, tiles, p.gps, out_mode);
+    hipLaunchKernelGGL((w4_mid_kernel<MTW, WM, NW, R, BITS>), grid, dim3(64 * WM * NW), lds, stream, wt, sz, x, dst, M,
+                       K, N, groups, tiles, p.gps, out_mode);
     return hipGetLastError();
 }
 
-template <int MTW, int WM, int NW>
-hipError_t launch_r(const LayerView &L, const uint16_t *x, int M, void *dst, int out_mode, const MidPlan &p,
-                    hipStream_t stream) {
+template <int MTW, int WM, int NW, int BITS>
+hipError_t launch_r(const void *wt, const uint32_t *sz, int64_t K, int64_t N, const uint16_t *x, int M, void *dst,
+                    int out_mode, const MidPlan &p, hipStream_t stream) {
     // R = 4 was measured too: never faster, and with 4 row tiles per wave it needs more than the 256
     // registers that two waves per SIMD leave
-    return p.R == 2 ? launch_cfg<MTW, WM, NW, 2>(L, x, M, dst, out_mode, p, stream)
-                    : launch_cfg<MTW, WM, NW, 1>(L, x, M, dst, out_mode, p, stream);
+    return p.R == 2 ? launch_cfg<MTW, WM, NW, 2, BITS>(wt, sz, K, N, x, M, dst, out_mode, p, stream)
+                    : launch_cfg<MTW, WM, NW, 1, BITS>(wt, sz, K, N, x, M, dst, out_mode, p, stream);
+}
+
+template <int BITS>
+hipError_t launch_mid(const void *wt, const uint32_t *sz, int64_t K, int64_t N, const uint16_t *x, int64_t M, void *y,
+                      bool out_f32, void *ws, hipStream_t stream) {
+    const MidPlan p = plan_mid(M, K, N);
+    const bool split = p.SK > 1;
+    if (split && !ws) return hipErrorInvalidValue;
+    void *dst = split ? ws : y;
+    const int out_mode = split ? 2 : (out_f32 ? 0 : 1);
+    const int iM = (int)M;
+    hipError_t e;
+    if (p.WM == 1) {
+        switch (p.MTW) {
+            case 1: e = launch_r<1, 1, 4, BITS>(wt, sz, K, N, x, iM, dst, out_mode, p, stream); break;
+            case 2: e = launch_r<2, 1, 4, BITS>(wt, sz, K, N, x, iM, dst, out_mode, p, stream); break;
+            case 3: e = launch_r<3, 1, 4, BITS>(wt, sz, K, N, x, iM, dst, out_mode, p, stream); break;
+            default: e = launch_r<4, 1, 4, BITS>(wt, sz, K, N, x, iM, dst, out_mode, p, stream); break;
+        }
+    } else {
+        e = p.MTW == 3 ? launch_r<3, 2, 2, BITS>(wt, sz, K, N, x, iM, dst, out_mode, p, stream)
+                       : launch_r<4, 2, 2, BITS>(wt, sz, K, N, x, iM, dst, out_mode, p, stream);
+    }
+    if (e != hipSuccess || !split) return e;
+    return launch_splitk_reduce(static_cast<const float *>(ws), y, M * N, p.SK, out_f32, stream);
 }
 
 }  // namespace
@@ -247,25 +290,12 @@ size_t w4_mid_workspace_bytes(int64_t M, int64_t K, int64_t N) {
 
 hipError_t launch_w4_mid(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
                          hipStream_t stream) {
-    const MidPlan p = plan_mid(M, L.K, L.N);
-    const bool split = p.SK > 1;
-    void *dst = split ? ws : y;
-    const int out_mode = split ? 2 : (out_f32 ? 0 : 1);
-    const int iM = (int)M;
-    hipError_t e;
-    if (p.WM == 1) {
-        switch (p.MTW) {
-            case 1: e = launch_r<1, 1, 4>(L, x, iM, dst, out_mode, p, stream); break;
-            case 2: e = launch_r<2, 1, 4>(L, x, iM, dst, out_mode, p, stream); break;
-            case 3: e = launch_r<3, 1, 4>(L, x, iM, dst, out_mode, p, stream); break;
-            default: e = launch_r<4, 1, 4>(L, x, iM, dst, out_mode, p, stream); break;
-        }
-    } else {
-        e = p.MTW == 3 ? launch_r<3, 2, 2>(L, x, iM, dst, out_mode, p, stream)
-                       : launch_r<4, 2, 2>(L, x, iM, dst, out_mode, p, stream);
-    }
-    if (e != hipSuccess || !split) return e;
-    return launch_splitk_reduce(static_cast<const float *>(ws), y, M * L.N, p.SK, out_f32, stream);
+    return launch_mid<4>(L.wt, L.sz, L.K, L.N, x, M, y, out_f32, ws, stream);
+}
+
+hipError_t launch_w3_mid(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
+                         hipStream_t stream) {
+    return launch_mid<3>(L.wt, L.sz, L.K, L.N, x, M, y, out_f32, ws, stream);
 }
 
 }  // namespace dmr

@@ -54,7 +54,11 @@ def test_w3_device_quantiser_matches_oracle_bit_for_bit(K, N):
 @pytest.mark.parametrize("K,N,M", [(1024, 1024, 1), (128, 16, 1), (384, 48, 1), (1920, 272, 1), (4096, 28672, 1),
                                    (14336, 4096, 1), (4096, 6144, 1), (1024, 1024, 5), (384, 48, 64),
                                    (1024, 400, 300), (384, 48, 2), (1920, 272, 7), (4096, 4112, 16), (4096, 28672, 8),
-                                   (256, 4112, 3), (14336, 528, 4), (14336, 528, 12)])
+                                   (256, 4112, 3), (14336, 528, 4), (14336, 528, 12),
+                                   # rollout batches beyond 16 rows: the register-unpack kernel with and without a split of K,
+                                   # one and two weight tiles per wave, 1..4 row tiles, 8-wave workgroups above 64 rows
+                                   (4096, 4096, 64), (14336, 4096, 40), (4096, 28672, 20), (2048, 1040, 128),
+                                   (512, 4096, 200), (1024, 2064, 130), (640, 80, 17), (4096, 6144, 33)])
 def test_w3_forward(K, N, M):
     _, words, s, z = quantized3(7200 + K + N, N, K)
     x = synth.activations_bf16(7201 + K + M, M, K)
