@@ -183,6 +183,7 @@ size_t dmr_qlinear_w3_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     if (M <= 1 || K <= 0 || N <= 0) return 0;
     if (M <= 16 && dmr::w4_stream_fits(M, K, N)) return 0;      // native streaming kernel
     if (M <= 16 && dmr::w4_panel_applies(M, K, N)) return dmr::w4_panel_workspace_bytes(M, K, N);   // k-sliced panels
+    if (M > 16 && M <= kSkinnyMaxM && dmr::w4_wide_applies(M, K, N)) return 0;                      // wide layers
     if (w3_uses_mid(M, K, N)) return dmr::w4_mid_workspace_bytes(M, K, N);                          // rollout batches
     // otherwise the layer is dequantised to bf16 there first; the bf16 path's own scratch follows
     return (size_t)N * (size_t)K * 2 + dmr_qlinear_bf16_workspace_bytes(M, K, N);
@@ -269,6 +270,8 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
             const hipError_t e = dmr::launch_w3_panel(L3, d_x, M, d_y, f32, d_ws, s);
             if (e != hipErrorInvalidValue) return hip_status(e);
         }
+        if (M > 16 && M <= kSkinnyMaxM && dmr::w4_wide_applies(M, layer->K, layer->N))
+            return hip_status(dmr::launch_w3_wide(L3, d_x, M, d_y, f32, s));
         if (w3_uses_mid(M, layer->K, layer->N)) {
             if (ws_bytes < dmr::w4_mid_workspace_bytes(M, layer->K, layer->N)) return DMR_ERR_WORKSPACE;
             return hip_status(dmr::launch_w3_mid(L3, d_x, M, d_y, f32, d_ws, s));

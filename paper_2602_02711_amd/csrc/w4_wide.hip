@@ -13,6 +13,8 @@
 // tiles.  The S partial tiles of a workgroup meet in LDS at the end (the panels' memory) and are added
 // in ascending order.  Splitting K over workgroups was measured and never paid on layers this wide
 // (the fp32 partials cost as much as the weights).  Rows of the last row tile beyond M are staged as copies of row M - 1 and never stored.
+// BITS = 3 runs the same kernel on the 3-bit streaming layout (768-byte blocks, three words per lane).
+#include "w3_unpack.hpp"
 #include "wide_plan.hpp"
 
 namespace dmr {
@@ -23,14 +25,14 @@ constexpr uint32_t kOnes = 0x3F803F80u;    // bf16 pair (1.0, 1.0)
 
 template <int R>
 struct WideItem {
-    u32x4_t w[R];
+    u32x4_t w[R];          // 3-bit layout: .x .y .z hold the lane's three words
     uint32_t szw[R];
 };
 
 constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v / 2); }
 
-template <int MT, int R, int S, int CG>
-__global__ __launch_bounds__(512) void w4_wide_kernel(const uint4 *__restrict__ wt, const uint32_t *__restrict__ sz,
+template <int MT, int R, int S, int CG, int BITS>
+__global__ __launch_bounds__(512) void w4_wide_kernel(const void *__restrict__ wt, const uint32_t *__restrict__ sz,
                                                       const uint16_t *__restrict__ x, void *__restrict__ y, int M,
                                                       int64_t K, int64_t N, int groups, int tiles, int out_f32) {
     constexpr int WAVES = 8, THREADS = 512, TW = WAVES / S, GWc = CG / S, P = GWc;
@@ -61,7 +63,14 @@ __global__ __launch_bounds__(512) void w4_wide_kernel(const uint4 *__restrict__ 
         for (int r = 0; r < R; ++r) {
             const int tile = min(tile0 + r, tiles - 1);
             const int64_t block = (int64_t)tile * groups + g;
-            dst.w[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(wt + block * 64 + lane));
+            if constexpr (BITS == 4) {
+                dst.w[r] = __builtin_nontemporal_load(static_cast<const u32x4_t *>(wt) + block * 64 + lane);
+            } else {
+                const uint32_t *pw = static_cast<const uint32_t *>(wt) + (block * 64 + lane) * 3;
+                dst.w[r].x = load_stream(pw);
+                dst.w[r].y = load_stream(pw + 1);
+                dst.w[r].z = load_stream(pw + 2);
+            }
             dst.szw[r] = load_stream(sz + block * kTileRows + j);
         }
     };
@@ -126,7 +135,14 @@ __global__ __launch_bounds__(512) void w4_wide_kernel(const uint4 *__restrict__ 
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 Frag b;
-                unpack_word(cur.w[r][t], b.w);
+                if constexpr (BITS == 4) {
+                    unpack_word(cur.w[r][t], b.w);
+                } else {
+                    if (t == 0) unpack3_step<0>(cur.w[r].x, cur.w[r].y, cur.w[r].z, b.w);
+                    if (t == 1) unpack3_step<1>(cur.w[r].x, cur.w[r].y, cur.w[r].z, b.w);
+                    if (t == 2) unpack3_step<2>(cur.w[r].x, cur.w[r].y, cur.w[r].z, b.w);
+                    if (t == 3) unpack3_step<3>(cur.w[r].x, cur.w[r].y, cur.w[r].z, b.w);
+                }
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
                     d[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mt].v, b.v, d[r][mt], 0, 0, 0);
@@ -216,19 +232,35 @@ __global__ __launch_bounds__(512) void w4_wide_kernel(const uint4 *__restrict__ 
     }
 }
 
-template <int MT, int R, int S, int CG>
-hipError_t launch_cfg(const LayerView &L, const uint16_t *x, int M, void *y, bool out_f32, hipStream_t stream) {
+template <int MT, int R, int S, int CG, int BITS>
+hipError_t launch_cfg(const void *wt, const uint32_t *sz, int64_t K, int64_t N, const uint16_t *x, int M, void *y,
+                      bool out_f32, hipStream_t stream) {
     // once per process and kernel instantiation (thread-safe static initialisation)
-    static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_wide_kernel<MT, R, S, CG>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    static const hipError_t attr_status = hipFuncSetAttribute(
+        reinterpret_cast<const void *>(&w4_wide_kernel<MT, R, S, CG, BITS>), hipFuncAttributeMaxDynamicSharedMemorySize,
+        160 * 1024);
     if (attr_status != hipSuccess) return attr_status;
-    const int groups = (int)(L.K / kGroup), tiles = (int)(L.N / kTileRows);
+    const int groups = (int)(K / kGroup), tiles = (int)(N / kTileRows);
     constexpr int TW = 8 / S;
     static_assert(TW * R == kWideTilesPerWg && CG == kWideChunk, "the planner assumes this shape");
     const unsigned grid = (unsigned)((tiles + TW * R - 1) / (TW * R));
-    hipLaunchKernelGGL((w4_wide_kernel<MT, R, S, CG>), dim3(grid), dim3(512), wide_lds_bytes(MT, R, S, CG), stream,
-                       L.wt, L.sz, x, y, M, L.K, L.N, groups, tiles, out_f32 ? 1 : 0);
+    hipLaunchKernelGGL((w4_wide_kernel<MT, R, S, CG, BITS>), dim3(grid), dim3(512), wide_lds_bytes(MT, R, S, CG), stream,
+                       wt, sz, x, y, M, K, N, groups, tiles, out_f32 ? 1 : 0);
     return hipGetLastError();
+}
+
+template <int BITS>
+hipError_t launch_wide(const void *wt, const uint32_t *sz, int64_t K, int64_t N, const uint16_t *x, int64_t M, void *y,
+                       bool out_f32, hipStream_t stream) {
+    const WidePlan p = plan_wide(M, K, N);
+    if (!p.ok) return hipErrorInvalidValue;
+    const int iM = (int)M;
+    switch (p.MT) {
+        case 2: return launch_cfg<2, 2, 2, 4, BITS>(wt, sz, K, N, x, iM, y, out_f32, stream);
+        case 3: return launch_cfg<3, 2, 2, 4, BITS>(wt, sz, K, N, x, iM, y, out_f32, stream);
+        case 4: return launch_cfg<4, 2, 2, 4, BITS>(wt, sz, K, N, x, iM, y, out_f32, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace
@@ -237,15 +269,12 @@ bool w4_wide_applies(int64_t M, int64_t K, int64_t N) { return plan_wide(M, K, N
 
 hipError_t launch_w4_wide(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
                           hipStream_t stream) {
-    const WidePlan p = plan_wide(M, L.K, L.N);
-    if (!p.ok) return hipErrorInvalidValue;
-    const int iM = (int)M;
-    switch (p.MT) {
-        case 2: return launch_cfg<2, 2, 2, 4>(L, x, iM, y, out_f32, stream);
-        case 3: return launch_cfg<3, 2, 2, 4>(L, x, iM, y, out_f32, stream);
-        case 4: return launch_cfg<4, 2, 2, 4>(L, x, iM, y, out_f32, stream);
-        default: return hipErrorInvalidValue;
-    }
+    return launch_wide<4>(L.wt, L.sz, L.K, L.N, x, M, y, out_f32, stream);
+}
+
+hipError_t launch_w3_wide(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+                          hipStream_t stream) {
+    return launch_wide<3>(L.wt, L.sz, L.K, L.N, x, M, y, out_f32, stream);
 }
 
 }  // namespace dmr

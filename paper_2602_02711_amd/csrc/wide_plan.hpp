@@ -34,5 +34,8 @@ inline WidePlan plan_wide(int64_t M, int64_t K, int64_t N) {
 bool w4_wide_applies(int64_t M, int64_t K, int64_t N);
 hipError_t launch_w4_wide(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
                           hipStream_t stream);
+// The same kernel on a 3-bit layer.
+hipError_t launch_w3_wide(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+                          hipStream_t stream);
 
 }  // namespace dmr

@@ -58,7 +58,9 @@ def test_w3_device_quantiser_matches_oracle_bit_for_bit(K, N):
                                    # rollout batches beyond 16 rows: the register-unpack kernel with and without a split of K,
                                    # one and two weight tiles per wave, 1..4 row tiles, 8-wave workgroups above 64 rows
                                    (4096, 4096, 64), (14336, 4096, 40), (4096, 28672, 20), (2048, 1040, 128),
-                                   (512, 4096, 200), (1024, 2064, 130), (640, 80, 17), (4096, 6144, 33)])
+                                   (512, 4096, 200), (1024, 2064, 130), (640, 80, 17), (4096, 6144, 33),
+                                   # wide layers at 17..64 rows: the wide-layer kernel (2, 3 and 4 row tiles, ragged last workgroup)
+                                   (512, 16400, 24), (512, 16448, 40), (1024, 16384, 64)])
 def test_w3_forward(K, N, M):
     _, words, s, z = quantized3(7200 + K + N, N, K)
     x = synth.activations_bf16(7201 + K + M, M, K)
