@@ -112,9 +112,9 @@ __global__ __launch_bounds__(64 * WM * NW, 2) void bf16_mid_kernel(const uint16_
     // loads and no barrier inside), so every wave passes the same barriers and every load is
     // unconditional.
     const int last = gB - 1;
+    fetch_x(0, gA);          // ahead of the weights: a wave's loads return in order, and this one is needed first
     fetch_w(ring[0], gA);
     fetch_w(ring[1], min(gA + 1, last));
-    fetch_x(0, gA);
     put_x(0, 0);
     fetch_x(1, min(gA + 1, last));
     fetch_x(0, min(gA + 2, last));

@@ -25,9 +25,9 @@ struct Item {
 // type for the staging registers: an array of HIP's uint4 struct ends up in scratch memory.)
 template <int B>
 __device__ __forceinline__ void stage_rows(const uint16_t *__restrict__ x, uint4 *smem, int total,
-                                           uint32_t x16_magic) {
+                                           uint32_t x16_magic, int first) {
     const int T = (int)blockDim.x;
-    for (int base = (int)threadIdx.x; base < total; base += B * T) {
+    for (int base = first + (int)threadIdx.x; base < total; base += B * T) {
         u32x4_t v[B];
 #pragma unroll
         for (int u = 0; u < B; ++u)
@@ -62,6 +62,16 @@ __global__ __launch_bounds__(1024) void bf16_stream_kernel(const uint16_t *__res
 
     // Slot (step, gi) -> block to load, clamped into this wave's valid range (or to the matrix's last
     // tile if it owns none): every load is unconditional and in bounds.
+    // The first pieces of the activation rows are requested before the weight ring: memory operations of a
+    // wave return in order, so behind the ring they would arrive only after its HBM latency.
+    constexpr int B0 = 8;
+    const int total = M * x16, T = (int)blockDim.x;
+    u32x4_t x0[B0];
+#pragma unroll
+    for (int u = 0; u < B0; ++u)
+        if (u * T < total)            // uniform
+            x0[u] = reinterpret_cast<const u32x4_t *>(x)[min((int)threadIdx.x + u * T, total - 1)];
+
     int is = 0, ig = 0;   // issue pointer
     Item ring[P];
     auto issue = [&](Item &dst) {
@@ -83,15 +93,15 @@ __global__ __launch_bounds__(1024) void bf16_stream_kernel(const uint16_t *__res
 
     // Stage the M activation rows: x is one contiguous run of M * x16 pieces; piece p of row
     // r = p / x16 (by multiplication with ceil(2^32 / x16), exact in this range) lands at p + r because
-    // rows are padded by one piece.  Up to eight loads are issued before the first store, so that a
-    // thread pays the memory latency once per batch and not once per piece.
-    {
-        const int total = M * x16;
-        if (total <= 2 * (int)blockDim.x)
-            stage_rows<2>(x, smem, total, x16_magic);      // a few rows: no point in six padding loads
-        else
-            stage_rows<8>(x, smem, total, x16_magic);
+    // rows are padded by one piece.  The first eight pieces per thread are in registers already; the rest
+    // follows in batches of eight loads before the first store, so that a thread pays the memory latency
+    // once per batch and not once per piece.
+#pragma unroll
+    for (int u = 0; u < B0; ++u) {
+        const int p = (int)threadIdx.x + u * T;
+        if (p < total) reinterpret_cast<u32x4_t *>(smem)[p + (int)__umulhi((uint32_t)p, x16_magic)] = x0[u];
     }
+    if (total > B0 * T) stage_rows<8>(x, smem, total, x16_magic, B0 * T);
     __syncthreads();
     auto store_out = [&](int64_t o, float v) {
         if (res) v += __uint_as_float((uint32_t)res[o] << 16);

@@ -164,9 +164,9 @@ __global__ __launch_bounds__(64 * WM * NW, (WM * NW == 4) ? 2 : 1) void w4_mid_k
     // same barriers and every load is unconditional.  (Walking the groups in a different order per
     // workgroup was measured and is slower: workgroups in step share the activations in cache.)
     const int last = gB - 1;
+    fetch_x(0, gA);          // ahead of the weights: a wave's loads return in order, and this one is needed first
 #pragma unroll
     for (int u = 0; u < 4; ++u) fetch_w(ring[u], min(gA + u, last));
-    fetch_x(0, gA);
     put_x(0, 0);
     fetch_x(1, min(gA + 1, last));
     fetch_x(0, min(gA + 2, last));

@@ -34,10 +34,10 @@ struct PanelItem {
 // piece (row, col) to slot row * (x16 + 1) + col; B loads in flight per thread.
 template <int B>
 __device__ __forceinline__ void stage_panel(const uint16_t *__restrict__ x, uint4 *smem, int M, int64_t K,
-                                            int64_t k0, int x16, uint32_t x16_magic) {
+                                            int64_t k0, int x16, uint32_t x16_magic, int first) {
     const int T = (int)blockDim.x;
     const int total = M * x16;
-    for (int base = (int)threadIdx.x; base < total; base += B * T) {
+    for (int base = first + (int)threadIdx.x; base < total; base += B * T) {
         u32x4_t v[B];
         int slot[B];
 #pragma unroll
@@ -75,6 +75,23 @@ __global__ __launch_bounds__(64 * WAVES) void w4_panel_kernel(const void *__rest
     const int tile0 = ((int)blockIdx.x * TW + tw) * R;
     const int x16 = gq * 16, row_stride = x16 + 1;
 
+    // The first pieces of the activation panel are requested before the weight ring: memory operations of a
+    // wave return in order, so behind the ring they would arrive only after its HBM latency.
+    constexpr int B0 = 8;
+    const int total = M * x16, T = (int)blockDim.x;
+    u32x4_t x0[B0];
+    int slot0[B0];
+#pragma unroll
+    for (int u = 0; u < B0; ++u) {
+        slot0[u] = 0;
+        if (u * T < total) {          // uniform
+            const int p = min((int)threadIdx.x + u * T, total - 1);
+            const int row = (int)__umulhi((uint32_t)p, x16_magic);
+            slot0[u] = p + row;
+            x0[u] = *reinterpret_cast<const u32x4_t *>(x + (int64_t)row * K + (int64_t)ga * kGroup + (p - row * x16) * 8);
+        }
+    }
+
     // weight stream: unconditional, clamped loads (a tile past the end re-reads the last tile, an item
     // past the sub-slice its last group)
     PanelItem<R, BITS> ring[P];
@@ -98,13 +115,10 @@ __global__ __launch_bounds__(64 * WAVES) void w4_panel_kernel(const void *__rest
 #pragma unroll
     for (int p = 0; p < P; ++p) issue(ring[p], p);
 
-    {
-        const int total = M * x16;
-        if (total <= 2 * (int)blockDim.x)
-            stage_panel<2>(x, smem, M, K, (int64_t)ga * kGroup, x16, x16_magic);
-        else
-            stage_panel<8>(x, smem, M, K, (int64_t)ga * kGroup, x16, x16_magic);
-    }
+#pragma unroll
+    for (int u = 0; u < B0; ++u)
+        if ((int)threadIdx.x + u * T < total) reinterpret_cast<u32x4_t *>(smem)[slot0[u]] = x0[u];
+    if (total > B0 * T) stage_panel<8>(x, smem, M, K, (int64_t)ga * kGroup, x16, x16_magic, B0 * T);
     __syncthreads();
 
     // group sums of x: unit u = (group, row tile) -> D = A . ones, every column of D the row sums

@@ -74,8 +74,6 @@ __global__ __launch_bounds__(512) void w4_wide_kernel(const void *__restrict__ w
             dst.szw[r] = load_stream(sz + block * kTileRows + j);
         }
     };
-#pragma unroll
-    for (int p = 0; p < P; ++p) issue(ring[p], p);
 
     // panel staging: piece p = u * THREADS + tid -> (row p >> LGC, column piece p & (16 CG - 1))
     u32x4_t xr[XL];
@@ -181,7 +179,9 @@ __global__ __launch_bounds__(512) void w4_wide_kernel(const void *__restrict__ w
         }
     };
 
-    fetch_x(0);
+    fetch_x(0);              // ahead of the weights: a wave's loads return in order, and the panel is needed first
+#pragma unroll
+    for (int p = 0; p < P; ++p) issue(ring[p], p);
     put_x(0);
     __syncthreads();
     sums(0);
