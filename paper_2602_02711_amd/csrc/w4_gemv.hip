@@ -65,6 +65,19 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
         if (PRO == kProSwiGLU) xaux[u] = reinterpret_cast<const uint4 *>(x)[x16 + ic];
     }
 
+    // The residual of the outputs this thread will store at the very end (first pass of the cross-slice sum) is
+    // requested now and parked in LDS beside x: fetched after the reduction it would add a cache round trip to
+    // the tail of the kernel.
+    constexpr bool kEarlyRes = XL <= 4;      // the widest staging variant has no register to spare
+    float res_first = 0.f;
+    if (kEarlyRes && res && lgS > 0) {
+        const int e = (int)threadIdx.x;
+        const int q = e & (S - 1), col = (e >> lgS) & 15, slot = e >> (lgS + 4);
+        const int tile = ((int)blockIdx.x << lgTW) + (slot & (TW - 1)) + (slot >> lgTW) * t_step;
+        if (q == 0 && e < (nT_max << (lgTW + lgS)) * 16 && tile < tiles)
+            res_first = __uint_as_float((uint32_t)res[(int64_t)tile * kTileRows + col] << 16);
+    }
+
     // Issue pointer (it, ig) walks (tile step, group in slice) and saturates at the last block,
     // so every issue is unconditional (the waitcnt bookkeeping stays exact); a wave whose item
     // count is not a multiple of P re-reads its last block up to P - 1 times from cache.
@@ -90,6 +103,7 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
     for (int p = 0; p < P; ++p) issue(ring[p]);
     float *xsum_lds = reinterpret_cast<float *>(smem + x16);                 // X[group]
     float *red = xsum_lds + ((groups + 3) & ~3);
+    float *res_lds = red + (lgS > 0 ? (nT_max << (lgTW + lgS)) * 16 : 0) + 16;   // one word per thread
     if (PRO == kProRmsNorm) {
         // sum of squares of the whole row: lanes -> wave (DPP, two cross-row steps) -> 16 waves via LDS
         float *part = red + (lgS > 0 ? (nT_max << (lgTW + lgS)) * 16 : 0);
@@ -125,6 +139,7 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
             if ((i & 15) == 0) xsum_lds[i >> 4] = part;
         }
     }
+    if (kEarlyRes && res) res_lds[threadIdx.x] = res_first;
     __syncthreads();
 
     // output: the fp32 result, plus the residual if there is one, rounded once if bf16 is asked for
@@ -199,7 +214,18 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
         if (S >= 8) v += dpp_move<0x141>(v);      // row_half_mirror
         if (S >= 16) v += dpp_move<0x140>(v);     // row_mirror
         const int tile = ((int)blockIdx.x << lgTW) + (slot & (TW - 1)) + (slot >> lgTW) * t_step;
-        if (q == 0 && tile < tiles) store_out((int64_t)tile * kTileRows + col, v);
+        if (q == 0 && tile < tiles) {
+            const int64_t n = (int64_t)tile * kTileRows + col;
+            if (kEarlyRes && e == (int)threadIdx.x) {   // first pass: the residual waits in LDS
+                const float r = res ? v + res_lds[threadIdx.x] : v;
+                if (out_f32)
+                    reinterpret_cast<float *>(y)[n] = r;
+                else
+                    reinterpret_cast<uint16_t *>(y)[n] = f32_to_bf16(r);
+            } else {
+                store_out(n, v);
+            }
+        }
     }
 }
 
@@ -255,8 +281,8 @@ hipError_t launch_w4_gemv_fused(const LayerView &L, const uint16_t *x, void *y, 
     const int nT_max = (tiles + t_step - 1) / t_step;
     const int gw_max = (groups + plan.S - 1) / plan.S;
     const size_t lds = (size_t)groups * 16 * sizeof(uint4) + (size_t)((groups + 3) & ~3) * sizeof(float) +
-                       (plan.S > 1 ? (size_t)nT_max * nw * 16 * sizeof(float) : 0) +
-                       (f.pro == kProRmsNorm ? 16 * sizeof(float) : 0);
+                       (plan.S > 1 ? (size_t)nT_max * nw * 16 * sizeof(float) : 0) + 16 * sizeof(float) +
+                       (f.res ? (size_t)nw * 64 * sizeof(float) : 0);
     if (lds > 64 * 1024) return hipErrorInvalidValue;   // caller falls back to the general kernel
 
     // Ring depth: four blocks in flight per wave measured best (six to eight measured 10-25 % slower on
