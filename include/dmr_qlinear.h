@@ -208,6 +208,22 @@ int32_t dmr_qlinear_bits(const dmr_qlinear_t *layer);
 dmr_status_t dmr_probe_hbm_read(const void *d_buf, size_t bytes, uint32_t *d_sink, int32_t blocks,
                                 void *stream);
 
+/*
+ * Diagnostic, not part of a routed step: the name of the kernel class that serves M rows of a (K, N) layer
+ * held in `format` ("w4_gemv", "w4_stream", "w4_panel", "w4_wide", "w4_skinny2", "w4_mid",
+ * "w4_gemm128_exact", the "w3_*" and "bf16_*" counterparts, "w3_dequant" for a 3-bit layer
+ * that is dequantised and handed to the bf16 path; "none" for an unsupported shape).  Pure host arithmetic,
+ * the same the forward calls use; a decode row too long for the M = 1 kernels' LDS budget is served by a
+ * fallback of the same name class.  Lets a test or a profile state which kernel it covers.
+ */
+typedef enum {
+    DMR_FMT_W4_G128 = 0,        /* dmr_qlinear_create */
+    DMR_FMT_W4_PER_CHANNEL = 1, /* dmr_qlinear_create_per_channel */
+    DMR_FMT_W3_G128 = 2,        /* dmr_qlinear_w3_create */
+    DMR_FMT_BF16 = 3            /* dmr_qlinear_bf16_forward */
+} dmr_format_t;
+const char *dmr_qlinear_kernel_path(dmr_format_t format, int64_t M, int64_t K, int64_t N);
+
 /* Release the host handle (NULL is allowed).  Device memory is the caller's and is untouched. */
 void dmr_qlinear_destroy(dmr_qlinear_t *layer);
 

@@ -28,9 +28,11 @@ EXPORTS = (
     "dmr_qlinear_w3_create", "dmr_qlinear_quantize_w3", "dmr_qlinear_bits", "dmr_qlinear_create_per_channel",
     "dmr_glue_rmsnorm", "dmr_glue_swiglu", "dmr_qlinear_fused_workspace_bytes",
     "dmr_qlinear_bf16_fused_workspace_bytes", "dmr_qlinear_forward_fused", "dmr_qlinear_bf16_forward_fused",
+    "dmr_qlinear_kernel_path",
 )
 
 DMR_PRO_NONE, DMR_PRO_RMSNORM, DMR_PRO_SWIGLU = 0, 1, 2
+DMR_FMT_W4_G128, DMR_FMT_W4_PER_CHANNEL, DMR_FMT_W3_G128, DMR_FMT_BF16 = 0, 1, 2, 3
 
 
 class DmrError(RuntimeError):
@@ -102,6 +104,8 @@ def lib() -> ctypes.CDLL:
                                                      ctypes.c_int, vp, sz, vp]
         L.dmr_status_string.restype = ctypes.c_char_p
         L.dmr_status_string.argtypes = [ctypes.c_int]
+        L.dmr_qlinear_kernel_path.restype = ctypes.c_char_p
+        L.dmr_qlinear_kernel_path.argtypes = [ctypes.c_int, i64, i64, i64]
         _lib = L
     return _lib
 
@@ -326,6 +330,10 @@ def dmr_probe_hbm_read(buf: torch.Tensor, sink: torch.Tensor, blocks: int, strea
     if sink.numel() < blocks * 256:
         raise ValueError("sink needs blocks * 256 words")
     _check(lib().dmr_probe_hbm_read(pb, buf.numel(), ps, blocks, _stream(stream)), "dmr_probe_hbm_read")
+
+
+def dmr_qlinear_kernel_path(fmt: int, M: int, K: int, N: int) -> str:
+    return lib().dmr_qlinear_kernel_path(fmt, M, K, N).decode()
 
 
 def dmr_qlinear_destroy(layer: Layer) -> None:

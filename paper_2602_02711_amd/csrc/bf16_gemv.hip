@@ -128,6 +128,13 @@ __global__ __launch_bounds__(kWaves * 64) void bf16_gemv_kernel(const uint16_t *
 
 }  // namespace
 
+// Whether the bf16 decode kernel takes rows of K values (at most eight 512-value chunks of x per wave after
+// slicing a row over the waves of a workgroup); longer rows go to the direct-from-L2 kernel.
+bool bf16_gemv_fits(int64_t K) {
+    const int64_t chunks = (K + 511) / 512;
+    return (chunks + kWaves - 1) / kWaves <= 8;
+}
+
 hipError_t launch_bf16_gemv(const uint16_t *w, const uint16_t *x, int64_t K, int64_t N, void *y,
                             bool out_f32, hipStream_t stream) {
     return launch_bf16_gemv_fused(w, x, K, N, y, out_f32, Fusion{}, stream);

@@ -109,17 +109,11 @@ inline int env_int(const char *name, int fallback) {
     return (v && *v) ? std::atoi(v) : fallback;
 }
 
-// Compute units of the current device (asked once per process; 256 if the query fails).
-inline int compute_units() {
-    static const int cus = [] {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            return v;
-        return 256;
-    }();
-    return cus;
-}
+// Compute units the launch shapes are planned for: a whole MI355X.  A constant, not a device query, so that
+// the host-side planners behind the workspace queries and the launchers always agree with each other (on a
+// partition with fewer CUs the shapes stay correct, only less well balanced).
+constexpr int kCus = 256;
+inline constexpr int compute_units() { return kCus; }
 
 struct LayerView {
     int64_t K, N;
@@ -145,9 +139,11 @@ hipError_t launch_dequantize(const LayerView &L, uint16_t *w_bf16, hipStream_t s
 hipError_t launch_quantize(int64_t K, int64_t N, const float *w, uint32_t *qweight,
                            uint16_t *scales, uint16_t *zeros, hipStream_t stream);
 // M == 1 decode kernel; returns hipErrorInvalidValue (nothing launched) for shapes it does not take.
+bool w4_gemv_fits(int64_t K, int64_t N, bool with_residual);
 hipError_t launch_w4_gemv(const LayerView &L, const uint16_t *x, void *y, bool out_f32,
                           hipStream_t stream);
 // M == 1 bf16 kernel; hipErrorInvalidValue (nothing launched) for K beyond its range.
+bool bf16_gemv_fits(int64_t K);
 hipError_t launch_bf16_gemv(const uint16_t *w, const uint16_t *x, int64_t K, int64_t N, void *y,
                             bool out_f32, hipStream_t stream);
 // 2 <= M <= 16 streaming kernel; hipErrorInvalidValue (nothing launched) when the activations do not fit LDS.
@@ -182,6 +178,7 @@ hipError_t launch_quantize3(int64_t K, int64_t N, const float *w, uint32_t *qwei
 // 2 <= M <= 16 on a 3-bit layer; hipErrorInvalidValue (nothing launched) when the activations do not fit LDS.
 hipError_t launch_w3_stream(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
                             hipStream_t stream);
+bool w3_gemv_fits(int64_t K, int64_t N);
 hipError_t launch_w3_gemv(const LayerView3 &L, const uint16_t *x, void *y, bool out_f32, hipStream_t stream);
 hipError_t launch_hbm_read_probe(const void *buf, size_t bytes, uint32_t *sink, int blocks,
                                  hipStream_t stream);

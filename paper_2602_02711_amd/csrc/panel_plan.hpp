@@ -33,7 +33,6 @@ inline PanelPlan plan_panel(int64_t M, int64_t K, int64_t N) {
     if (M < 2 || M > 16) return p;
     const int groups = (int)(K / kGroup), tiles = (int)(N / kTileRows);
     constexpr size_t kLds = 160 * 1024;
-    constexpr int kCus = 256;
     p.MT = 1;
     p.R = 1;
     p.WAVES = 16;

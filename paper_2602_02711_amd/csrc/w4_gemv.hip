@@ -251,6 +251,22 @@ GemvPlan plan_for(int groups, int tiles, int cus) {
 
 }  // namespace
 
+// Whether the decode kernel takes the shape with its default launch plan (x staging within eight loads per
+// thread; activations, reduction buffer and the parked residual within 64 KB of LDS).  Longer rows go to the
+// direct-from-L2 kernel.  Pure host arithmetic.
+bool w4_gemv_fits(int64_t K, int64_t N, bool with_residual) {
+    const int groups = (int)(K / kGroup), tiles = (int)(N / kTileRows);
+    const GemvPlan plan = plan_for(groups, tiles, compute_units());
+    const int nw = plan.S * plan.TW;
+    if ((groups * 16 + nw * 64 - 1) / (nw * 64) > 8) return false;
+    const int t_step = plan.grid * plan.TW;
+    const int nT_max = (tiles + t_step - 1) / t_step;
+    const size_t lds = (size_t)groups * 16 * sizeof(uint4) + (size_t)((groups + 3) & ~3) * sizeof(float) +
+                       (plan.S > 1 ? (size_t)nT_max * nw * 16 * sizeof(float) : 0) + 16 * sizeof(float) +
+                       (with_residual ? (size_t)nw * 64 * sizeof(float) : 0);
+    return lds <= 64 * 1024;
+}
+
 hipError_t launch_w4_gemv(const LayerView &L, const uint16_t *x, void *y, bool out_f32,
                           hipStream_t stream) {
     return launch_w4_gemv_fused(L, x, y, out_f32, Fusion{}, stream);

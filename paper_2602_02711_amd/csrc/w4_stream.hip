@@ -230,10 +230,10 @@ bool w4_stream_fits(int64_t M, int64_t K, int64_t N) {
     const int groups = (int)(K / kGroup), tiles = (int)(N / kTileRows);
     const size_t xbytes = (size_t)M * (groups * 16 + 1) * sizeof(uint4) + (size_t)groups * 4 * sizeof(f32x4);
     int nw = 16, S = 16;
-    if (tiles >= 4 * 256) {
+    if (tiles >= 4 * kCus) {
         nw = 8;
         S = 2;
-    } else if (tiles > 256) {
+    } else if (tiles > kCus) {
         nw = 8;
         S = 4;
     }

@@ -145,3 +145,35 @@ def test_binding_refuses_host_tensors():
     with pytest.raises(TypeError):
         binding.dmr_qlinear_bf16_forward(torch.zeros(16, 128, dtype=torch.bfloat16),
                                          torch.zeros(1, 128, dtype=torch.bfloat16))
+
+
+def test_w3_size_query_and_kernel_paths(lib):
+    q3 = lib.dmr_qlinear_w3_workspace_bytes
+    # shapes the library does not take get no workspace answer
+    assert q3(8, 1000, 4096) == 0 and q3(8, 4096, 1000) == 0 and q3(0, 4096, 4096) == 0
+    # decode and 2..16 rows of the decoder layers: native streaming kernels, no scratch
+    assert q3(1, 4096, 4096) == 0 and q3(1, 14336, 4096) == 0 and q3(16, 4096, 28672) == 0
+    # a decode row too long for the GEMV's LDS budget: the rollout-batch kernel with K split, whose fp32
+    # partials need the workspace; the query must say so (the forward refuses a smaller one)
+    path = lib.dmr_qlinear_kernel_path
+    assert path(binding.DMR_FMT_W3_G128, 1, 32768, 528) == b"w3_mid"
+    need = q3(1, 32768, 528)
+    assert need > 0 and need % (528 * 4) == 0
+    assert path(binding.DMR_FMT_W3_G128, 1, 4096, 4096) == b"w3_gemv"
+    # the rollout-batch sizes share the 4-bit plan; prefill sizes hold the dequantised layer first
+    assert q3(64, 4096, 4096) == lib.dmr_qlinear_workspace_bytes(64, 4096, 4096)
+    assert q3(1200, 512, 4096) == 4096 * 512 * 2 + lib.dmr_qlinear_bf16_workspace_bytes(1200, 512, 4096)
+    assert path(binding.DMR_FMT_W3_G128, 1200, 512, 4096) == b"w3_dequant"
+    # the kernel classes of the four decoder shapes at the sizes of the benchmark configurations
+    assert path(binding.DMR_FMT_W4_G128, 1, 4096, 28672) == b"w4_gemv"
+    assert path(binding.DMR_FMT_W4_G128, 8, 14336, 4096) == b"w4_panel"
+    assert path(binding.DMR_FMT_W4_G128, 64, 4096, 28672) == b"w4_wide"
+    assert path(binding.DMR_FMT_W4_G128, 64, 4096, 4096) == b"w4_mid"
+    assert path(binding.DMR_FMT_W4_G128, 8192, 4096, 28672) == b"w4_gemm128_exact"
+    assert path(binding.DMR_FMT_W4_PER_CHANNEL, 6400, 512, 1024) == b"w4_gemm128_exact"
+    assert path(binding.DMR_FMT_W4_G128, 1, 32768, 528) == b"w4_skinny"
+    assert path(binding.DMR_FMT_BF16, 1, 32768, 528) == b"bf16_skinny"
+    assert path(binding.DMR_FMT_BF16, 512, 4096, 4096) == b"bf16_mid"          # exactly 128 workgroups: not tiled yet
+    assert path(binding.DMR_FMT_BF16, 1024, 4096, 4096) == b"bf16_gemm128_dma"
+    assert path(binding.DMR_FMT_BF16, 8192, 4096, 4096) == b"bf16_gemm256"
+    assert path(binding.DMR_FMT_W4_G128, 4, 1000, 4096) == b"none"

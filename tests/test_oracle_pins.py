@@ -380,6 +380,28 @@ def test_w3_handworked_packing(golden):
     assert np.array_equal(orc.unpack3(words), q)
 
 
+def test_w3_handworked_quantizer(golden):
+    # the 3-bit quantiser against values worked by hand (ties, a scale that rounds up in bf16, a forced zero
+    # end point): a wrong divisor (range / 15), a wrong rounding of the scale or of the codes fails here
+    gd = golden("handworked_w3_quant.txt")
+    w = np.stack([_f(gd[f"w_row{r}"]) for r in range(3)]).astype(np.float32)
+    q, s, z = orc.quantize_bits(w, 8, 3)
+    assert np.array_equal(s.reshape(3).astype(np.uint64), _h(gd["s_bits"]))
+    assert np.array_equal(orc.bf16_to_f64(z).reshape(3), _f(gd["z"]))
+    for r in range(3):
+        assert np.array_equal(q[r].astype(np.float64), _f(gd[f"q_row{r}"])), r
+    # K = 8 is below one packed run of 32 codes, so the exact weights are formed here from the definition
+    w_hat = (q.astype(np.float64) - orc.bf16_to_f64(z)) * orc.bf16_to_f64(s)
+    assert np.array_equal(w_hat[1], _f(gd["what_row1"]))
+    assert np.array_equal(w_hat[2], w[2].astype(np.float64))          # power-of-two scale, no tie: exact
+    # the same rows through the packed path (padded to one run of 32 codes with zero weights)
+    w32 = np.zeros((3, 32), dtype=np.float32)
+    w32[:, :8] = w
+    q32, s32, z32 = orc.quantize_bits(w32, 32, 3)
+    assert np.array_equal(q32[:, :8], q) and np.array_equal(s32, s) and np.array_equal(z32, z)
+    assert np.array_equal(orc.dequantize_exact3(orc.pack3(q32), s32, z32, 32)[:, :8], w_hat)
+
+
 def test_w3_pack_bijection_and_twin():
     rng = np.random.default_rng(31)
     q = rng.integers(0, 8, size=(11, 160), dtype=np.uint8)
