@@ -106,6 +106,23 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
                                  void *stream);
 
 /*
+ * dmr_qlinear_forward for callers that cannot allocate device memory and therefore cannot bring the
+ * workspace: code running under HIP-graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results (bit for bit) and errors as dmr_qlinear_forward, minus d_ws / ws_bytes: the
+ * scratch (fp32 partial sums of the kernels that split K, re-ordered activations) is a fixed array of
+ * DMR_STATIC_SCRATCH_BYTES in device memory that belongs to the library itself; each GPU the library runs
+ * on holds one copy until the process ends.  The call allocates and frees nothing.  A shape whose
+ * dmr_qlinear_workspace_bytes (dmr_qlinear_w3_workspace_bytes for a 3-bit layer) exceeds that size is
+ * refused with DMR_ERR_WORKSPACE before anything is launched; such calls go through dmr_qlinear_forward.
+ * All calls on one GPU share the one array: two calls whose work overlaps in time on the same GPU (different
+ * streams, or threads) race on it; calls on one stream are ordered and safe.  Nothing needs clearing
+ * between calls.  The first call on a device looks up the array's address (one runtime query).
+ */
+#define DMR_STATIC_SCRATCH_BYTES ((size_t)8 << 20)
+dmr_status_t dmr_qlinear_forward_static(const dmr_qlinear_t *layer, const uint16_t *d_x, int64_t M,
+                                        void *d_y, dmr_out_t out, void *stream);
+
+/*
  * The same layer in the bf16 high-precision copy (Sec. 5.1; a step with r_t = high):
  *   y[m][n] = sum_k x[m][k] * W[n][k],  W bf16 [N][K], fp32 accumulation.
  * This is the denominator of the T_high / T_low ratio (Eq. 9).  Needs no handle; d_ws as

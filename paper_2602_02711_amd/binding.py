@@ -28,7 +28,7 @@ EXPORTS = (
     "dmr_qlinear_w3_create", "dmr_qlinear_quantize_w3", "dmr_qlinear_bits", "dmr_qlinear_create_per_channel",
     "dmr_glue_rmsnorm", "dmr_glue_swiglu", "dmr_qlinear_fused_workspace_bytes",
     "dmr_qlinear_bf16_fused_workspace_bytes", "dmr_qlinear_forward_fused", "dmr_qlinear_bf16_forward_fused",
-    "dmr_qlinear_kernel_path",
+    "dmr_qlinear_kernel_path", "dmr_qlinear_forward_static",
 )
 
 DMR_PRO_NONE, DMR_PRO_RMSNORM, DMR_PRO_SWIGLU = 0, 1, 2
@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
         L.dmr_qlinear_dequantize.argtypes = [vp, vp, vp]
         L.dmr_qlinear_forward.restype = ctypes.c_int
         L.dmr_qlinear_forward.argtypes = [vp, vp, i64, vp, ctypes.c_int, vp, sz, vp]
+        L.dmr_qlinear_forward_static.restype = ctypes.c_int
+        L.dmr_qlinear_forward_static.argtypes = [vp, vp, i64, vp, ctypes.c_int, vp]
         L.dmr_qlinear_bf16_forward.restype = ctypes.c_int
         L.dmr_qlinear_bf16_forward.argtypes = [vp, vp, i64, i64, i64, vp, ctypes.c_int, vp, sz, vp]
         L.dmr_qlinear_quantize.restype = ctypes.c_int
@@ -221,6 +223,26 @@ def dmr_qlinear_forward(layer: Layer, x: torch.Tensor, out: torch.Tensor | None 
     pw, wbytes = _workspace(workspace)
     _check(lib().dmr_qlinear_forward(layer.handle, px, M, po, _out_code(out.dtype), pw, wbytes,
                                      _stream(stream)), "dmr_qlinear_forward")
+    return out
+
+
+DMR_STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def dmr_qlinear_forward_static(layer: Layer, x: torch.Tensor, out: torch.Tensor | None = None,
+                               out_dtype=torch.bfloat16, stream=None) -> torch.Tensor:
+    """dmr_qlinear_forward on the library's own fixed scratch: no workspace is passed or allocated."""
+    px = _dev(x, "x", _BF16)
+    if x.dim() != 2 or x.shape[1] != layer.K:
+        raise ValueError("x must be [M][K]")
+    M = x.shape[0]
+    if out is None:
+        out = torch.empty((M, layer.N), dtype=out_dtype, device=x.device)
+    po = _dev(out, "out", (torch.bfloat16, torch.float32))
+    if tuple(out.shape) != (M, layer.N):
+        raise ValueError("out must be [M][N]")
+    _check(lib().dmr_qlinear_forward_static(layer.handle, px, M, po, _out_code(out.dtype), _stream(stream)),
+           "dmr_qlinear_forward_static")
     return out
 
 
