@@ -68,6 +68,10 @@ def full_step(args, dmr, synth, torch, dev):
     log(f"[bench] 129 layers resident after {time.time() - t0:.1f}s")
     stream = torch.cuda.Stream()
 
+    if not args.no_prefetch:           # every INT4 layer names the one the step reads after it
+        for i in range(len(int4_layers) - 1):
+            dmr.dmr_qlinear_set_next(int4_layers[i][1], int4_layers[i + 1][1])
+
     def step(low: bool):
         for i in range(len(int4_layers)):
             nm = int4_layers[i][0]
@@ -476,6 +480,79 @@ def w3_sweep(args, dmr, synth, torch, dev):
     print(json.dumps(result), flush=True)
 
 
+def launch_floor(args, dmr, synth, torch, dev):
+    """Where the time of a per-layer decode launch goes (M = 1, the four decoder shapes, HIP-graph replay of 200
+    launches each, weights rotating over >= 1 GiB): a kernel that does nothing in the launch shape of the real
+    one, a plain read of the layer's bytes from 256 and from 1024 workgroups, the real kernel on rotating
+    copies and on one hot copy (served by the Infinity Cache: no HBM), against bytes / 8 TB/s."""
+    import numpy as np
+    G, REPS = synth.GROUP, 200
+    stream = torch.cuda.Stream()
+    sink = torch.empty(4096 * 256, dtype=torch.int32, device=dev)
+
+    def graph_us(fn):
+        with torch.cuda.stream(stream):
+            for i in range(5):
+                fn(i)
+            stream.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                for i in range(REPS):
+                    fn(i)
+            graph.replay()
+            stream.synchronize()
+            best = []
+            for _ in range(5):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                graph.replay()
+                e1.record(stream)
+                torch.cuda.synchronize()
+                best.append(e0.elapsed_time(e1) * 1e3 / REPS)
+        return float(np.median(best))
+
+    rows = []
+    for idx, (name, K, N) in enumerate(synth.SWEEP_SHAPES):
+        w = torch.from_numpy(synth.weights_f32(synth.seed_for(1, idx, 0), N, K)).to(dev)
+        qw, s, z = dmr.dmr_qlinear_quantize(w, G)
+        copies = -(-CACHE_DEFEAT_BYTES // int4_bytes(K, N))
+        layers = [dmr.dmr_qlinear_create(qw, s, z, G) for _ in range(copies)]
+        x = torch.from_numpy(synth.activations_bf16(synth.seed_for(1, idx, 1), 1, K).view(np.int16)).to(dev).view(torch.bfloat16)
+        y = torch.empty((1, N), dtype=torch.bfloat16, device=dev)
+        del w, qw, s, z
+        # launch shape of the decode kernel for this layer (the rule of its planner: one 16-wave workgroup per
+        # row tile up to 512 tiles, else 512 workgroups of 8 waves looping over tiles)
+        groups, tiles = K // G, N // 16
+        wgs, threads = (tiles, 1024) if tiles <= 512 else (512, 512)
+        lds = groups * 256 + ((groups + 3) & ~3) * 4 + -(-tiles // wgs) * (threads // 64) * 64 + 64
+        nbytes = int4_bytes(K, N)
+        row = {
+            "shape": name, "K": K, "N": N, "bytes": nbytes, "us_at_8TBps": round(nbytes / 8e6, 2),
+            "launch_shape": {"workgroups": wgs, "threads": threads, "lds_bytes": lds},
+            "empty_same_shape_us": round(graph_us(lambda i: dmr.dmr_probe_empty_launch(wgs, threads, lds)), 3),
+            "empty_256x256_us": round(graph_us(lambda i: dmr.dmr_probe_empty_launch(256, 256, 0)), 3),
+            "read_256wg_us": round(graph_us(lambda i: dmr.dmr_probe_hbm_read(layers[i % copies].storage, sink, 256)), 3),
+            "read_1024wg_us": round(graph_us(lambda i: dmr.dmr_probe_hbm_read(layers[i % copies].storage, sink, 1024)), 3),
+            "kernel_us": round(graph_us(lambda i: dmr.dmr_qlinear_forward(layers[i % copies], x, out=y)), 3),
+            "kernel_hot_cache_us": round(graph_us(lambda i: dmr.dmr_qlinear_forward(layers[0], x, out=y)), 3),
+        }
+        row["kernel_frac_of_8TBps"] = round(row["us_at_8TBps"] / row["kernel_us"], 4)
+        rows.append(row)
+        log(f"[bench] {row}")
+        del layers
+    total = sum(r["kernel_us"] for r in rows)
+    result = {
+        "metric": "per-layer decode launch, M = 1: fixed cost vs traffic time (us per launch)",
+        "value": round(total, 2), "unit": "us", "n_gpus": 1, "steps": REPS, "warmup": 5,
+        "ms_per_step": round(total / 1e3, 6), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "launch floor of the decode GEMV sweep: empty / plain-read / real kernel per shape, "
+                               "hip-graph replay of 200 launches, rotating weight copies"},
+        "by_shape": rows,
+    }
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -486,8 +563,11 @@ def main():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the protocol extras (read ceiling, replay spread, hot-cache and single-launch "
                          "times) so that a profiler sees only the launches of the timed passes")
+    ap.add_argument("--no-prefetch", action="store_true",
+                    help="decode_sweep: do not name each layer's successor (dmr_qlinear_set_next), so that no launch "
+                         "requests the next layer's first blocks")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
-    ap.add_argument("--workload", choices=("decode_sweep", "full_step", "mixed_step", "chain_step", "layer_sweep", "w3_sweep"), default="decode_sweep",
+    ap.add_argument("--workload", choices=("decode_sweep", "full_step", "mixed_step", "chain_step", "layer_sweep", "w3_sweep", "launch_floor"), default="decode_sweep",
                     help="decode_sweep (default, the headline metric) or full_step: all 129 Linear layers of "
                          "a 32-layer 7B-class decoder per step")
     ap.add_argument("--m", type=int, default=1, help="rows of activations for --workload full_step / chain_step")
@@ -518,6 +598,8 @@ def main():
         return layer_sweep(args, dmr, synth, torch, dev)
     if args.workload == "w3_sweep":
         return w3_sweep(args, dmr, synth, torch, dev)
+    if args.workload == "launch_floor":
+        return launch_floor(args, dmr, synth, torch, dev)
     G = synth.GROUP
     M = 1
 
@@ -528,7 +610,9 @@ def main():
     for idx, (name, K, N) in enumerate(shapes):
         w = torch.from_numpy(synth.weights_f32(synth.seed_for(1, idx, 0), N, K)).to(dev)
         qw, s, z = dmr.dmr_qlinear_quantize(w, G)
-        r4 = -(-CACHE_DEFEAT_BYTES // int4_bytes(K, N))
+        # the same number of copies for every shape (what the smallest layer needs to reach 1 GiB), so that
+        # copy r of a shape is always followed by copy r of the next shape
+        r4 = max(-(-CACHE_DEFEAT_BYTES // int4_bytes(Ks, Ns)) for _, Ks, Ns in shapes)
         layers.append([dmr.dmr_qlinear_create(qw, s, z, G) for _ in range(r4)])
         wb = w.to(torch.bfloat16)      # storage conversion (round to nearest even) of the same weights
         rb = -(-CACHE_DEFEAT_BYTES // bf16_bytes(K, N))
@@ -542,6 +626,15 @@ def main():
     log(f"[bench] inputs resident after {time.time() - t0:.1f}s; copies per shape int4 "
         f"{[len(l) for l in layers]} bf16 {[len(l) for l in bf16_ws]}")
 
+    def name_successors(on: bool):
+        """Tell every INT4 layer which layer the sweep reads after it (the order of int4_step), or clear that."""
+        R = len(layers[0])
+        for idx in range(len(shapes)):
+            for r in range(R):
+                nxt = layers[idx + 1][r] if idx + 1 < len(shapes) else layers[0][(r + 1) % R]
+                dmr.dmr_qlinear_set_next(layers[idx][r], nxt if on else None)
+
+    name_successors(not args.no_prefetch)
     stream = torch.cuda.Stream()       # default priority
 
     def int4_step(i, only=None):
@@ -595,6 +688,7 @@ def main():
     bwall_ms, bev_ms = timed(bf16_step, args.steps, args.warmup)
     bstep_bytes = sum(bf16_bytes(K, N, M) for _, K, N in shapes)
     per_shape = []
+    name_successors(False)             # a shape on its own has no successor in the sweep's order
     for idx, (name, K, N) in enumerate(shapes):
         n_inner = max(args.steps, 100)
         _, e4 = timed(int4_step, n_inner, 10, only=idx)
@@ -607,6 +701,11 @@ def main():
             "speedup": round(eb / e4, 3),
         })
         log(f"[bench] {per_shape[-1]}")
+
+    # the sweep once more without the successor hints, for the record
+    nopf_ms = None
+    if not args.no_prefetch:
+        _, nopf_ms = timed(int4_step, args.steps, args.warmup)
 
     # ---- protocol extras (outside the timed region that defines `value`) -----------------------
     protocol = None
@@ -715,6 +814,9 @@ def main():
                         "forwards; weights rotate over >=1 GiB of resident copies per shape",
             "weights": "int4 asymmetric g128, fp32 0.02*N(0,1) quantised by the device RTN quantiser",
             "activations": "bf16 N(0,1)", "accumulate": "fp32", "output": "bf16",
+            "successors": "none named" if args.no_prefetch else
+                          "every layer's successor in the sweep named with dmr_qlinear_set_next (a launch requests "
+                          "the next layer's first blocks while its own tail is reduced)",
             "launch": "eager" if args.no_graph else "hip-graph replay of all timed steps (after W eager warm-up "
                       "steps and 3 untimed replays)",
             "algorithmic_bytes_per_step": step_bytes,
@@ -723,6 +825,8 @@ def main():
         "bf16_ms_per_step": round(bwall_ms, 6),
         "bf16_GBps": round(bstep_bytes / (bwall_ms * 1e-3) / 1e9, 1),
         "us_per_decode_sweep": round(wall_ms * 1e3, 2),
+        "next_layer_prefetch": not args.no_prefetch,
+        "us_per_decode_sweep_without_prefetch": None if nopf_ms is None else round(nopf_ms * 1e3, 2),
         "per_shape": per_shape,
         "protocol": protocol,
         "roofline": {

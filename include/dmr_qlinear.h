@@ -106,6 +106,16 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
                                  void *stream);
 
 /*
+ * Decode-step hint (App. B: a generated token streams every weight once, layer after layer): name the layer
+ * whose weights the same stream reads right after `layer` in a decode step (M = 1).  From then on an M = 1
+ * forward of `layer` (plain or fused) also requests the first blocks of `next` while its own last blocks are
+ * being reduced, so that the following launch finds its first bytes in cache instead of waiting for HBM.
+ * Results are unchanged; only 4-bit layers take part (others ignore the hint).  `next` must stay alive (or
+ * the hint be cleared with NULL) for as long as `layer` is used; it may be `layer` itself.  Host-side only.
+ */
+dmr_status_t dmr_qlinear_set_next(dmr_qlinear_t *layer, const dmr_qlinear_t *next);
+
+/*
  * dmr_qlinear_forward for callers that cannot allocate device memory and therefore cannot bring the
  * workspace: code running under HIP-graph capture, tight serving loops, harnesses that forbid hipMalloc.
  * Same arguments, results (bit for bit) and errors as dmr_qlinear_forward, minus d_ws / ws_bytes: the
@@ -224,6 +234,15 @@ int32_t dmr_qlinear_bits(const dmr_qlinear_t *layer);
  */
 dmr_status_t dmr_probe_hbm_read(const void *d_buf, size_t bytes, uint32_t *d_sink, int32_t blocks,
                                 void *stream);
+
+/*
+ * Measurement aid, not part of a routed step: launch a kernel that does nothing with `blocks` workgroups of
+ * `threads` threads (a multiple of 64, at most 1024) and `lds_bytes` (at most 64 KB) of dynamic LDS.  Its
+ * time in a replayed graph is the fixed cost that every per-layer launch of a decode step pays before its
+ * first byte (App. B: decode is one pass over the weights per token; at these layer sizes that pass is a few
+ * microseconds, so the fixed cost decides how close a layer gets to the memory rate).
+ */
+dmr_status_t dmr_probe_empty_launch(int32_t blocks, int32_t threads, size_t lds_bytes, void *stream);
 
 /*
  * Diagnostic, not part of a routed step: the name of the kernel class that serves M rows of a (K, N) layer

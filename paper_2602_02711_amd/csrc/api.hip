@@ -13,6 +13,7 @@ struct dmr_qlinear {
     const uint4 *wt;        // 4-bit streaming blocks
     const uint32_t *wt3;    // 3-bit streaming blocks
     const uint32_t *sz;
+    const dmr_qlinear *next;   // the layer read after this one in a decode step, or null (dmr_qlinear_set_next)
 };
 
 namespace {
@@ -91,6 +92,16 @@ dmr_status_t check_shape(int64_t K, int64_t N, int32_t g) {
 
 dmr_status_t hip_status(hipError_t e) { return e == hipSuccess ? DMR_OK : DMR_ERR_HIP; }
 
+// Hand the decode kernel the weights of the layer that follows, if the caller has named one.
+void set_next(dmr::Fusion &f, const dmr_qlinear *layer) {
+    const dmr_qlinear *n = layer->next;
+    if (n && n->bits == 4) {
+        f.next_wt = n->wt;
+        f.next_K = n->K;
+        f.next_N = n->N;
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -134,6 +145,7 @@ dmr_status_t dmr_qlinear_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32
     h->N = N;
     h->g = g;
     h->bits = 4;
+    h->next = nullptr;
     h->wt3 = nullptr;
     uint8_t *base = static_cast<uint8_t *>(d_storage);
     h->wt = reinterpret_cast<const uint4 *>(base);
@@ -166,6 +178,7 @@ dmr_status_t dmr_qlinear_create_per_channel(dmr_qlinear_t **out, int64_t K, int6
     h->N = N;
     h->g = (int32_t)K;      // one group spans the whole row
     h->bits = 4;
+    h->next = nullptr;
     h->wt3 = nullptr;
     uint8_t *base = static_cast<uint8_t *>(d_storage);
     h->wt = reinterpret_cast<const uint4 *>(base);
@@ -215,6 +228,7 @@ dmr_status_t dmr_qlinear_w3_create(dmr_qlinear_t **out, int64_t K, int64_t N, in
     h->N = N;
     h->g = g;
     h->bits = 3;
+    h->next = nullptr;
     h->wt = nullptr;
     uint8_t *base = static_cast<uint8_t *>(d_storage);
     h->wt3 = reinterpret_cast<const uint32_t *>(base);
@@ -287,7 +301,9 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
     const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz};
     const W4Path path = w4_path(M, layer->K, layer->N);
     if (path == W4Path::Gemv) {
-        const hipError_t e = dmr::launch_w4_gemv(L, d_x, d_y, f32, s);
+        dmr::Fusion f;
+        set_next(f, layer);
+        const hipError_t e = dmr::launch_w4_gemv_fused(L, d_x, d_y, f32, f, s);
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: shape outside its range
     }
     if (path == W4Path::Stream) {
@@ -445,6 +461,7 @@ dmr_status_t dmr_qlinear_forward_fused(const dmr_qlinear_t *layer, dmr_prologue_
         f.aux = d_gamma;
         f.eps = eps;
         f.res = d_residual;
+        set_next(f, layer);
         const hipError_t e = dmr::launch_w4_gemv_fused(L, d_in, d_y, out == DMR_OUT_FP32, f, s);
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: shape outside the GEMV's range
     }
@@ -575,6 +592,19 @@ const char *dmr_qlinear_kernel_path(dmr_format_t format, int64_t M, int64_t K, i
             }
     }
     return "none";
+}
+
+dmr_status_t dmr_probe_empty_launch(int32_t blocks, int32_t threads, size_t lds_bytes, void *stream) {
+    if (blocks <= 0 || blocks > (1 << 20) || threads <= 0 || threads > 1024 || threads % 64 != 0 ||
+        lds_bytes > 64 * 1024)
+        return DMR_ERR_SHAPE;
+    return hip_status(dmr::launch_empty_probe(blocks, threads, lds_bytes, static_cast<hipStream_t>(stream)));
+}
+
+dmr_status_t dmr_qlinear_set_next(dmr_qlinear_t *layer, const dmr_qlinear_t *next) {
+    if (!layer) return DMR_ERR_NULL;
+    layer->next = next;
+    return DMR_OK;
 }
 
 void dmr_qlinear_destroy(dmr_qlinear_t *layer) { delete layer; }

@@ -182,6 +182,7 @@ bool w3_gemv_fits(int64_t K, int64_t N);
 hipError_t launch_w3_gemv(const LayerView3 &L, const uint16_t *x, void *y, bool out_f32, hipStream_t stream);
 hipError_t launch_hbm_read_probe(const void *buf, size_t bytes, uint32_t *sink, int blocks,
                                  hipStream_t stream);
+hipError_t launch_empty_probe(int blocks, int threads, size_t lds_bytes, hipStream_t stream);
 hipError_t launch_w4_skinny(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
                             hipStream_t stream);
 hipError_t launch_bf16_skinny(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,

@@ -47,6 +47,30 @@ def trace_stats(trace_dir):
     return {k: (len(v), sum(v) / len(v), min(v), max(v)) for k, v in rows.items()}
 
 
+def trace_gaps(trace_dir, max_gap_us=20.0):
+    """End-to-start gaps between consecutive kernels of the trace (sorted by start time), keyed by the pair
+    (previous kernel, next kernel): count, median and mean gap, and the median start-to-start period, in
+    microseconds.  Gaps above `max_gap_us` (host-side pauses between graph replays, set-up work) are left out."""
+    rows = []
+    with open(_one(trace_dir, "*_kernel_trace.csv")) as fh:
+        for r in csv.DictReader(fh):
+            rows.append((int(r["Start_Timestamp"]), int(r["End_Timestamp"]),
+                         f'{short(r["Kernel_Name"])} [{int(r["Grid_Size_X"]) // max(int(r["Workgroup_Size_X"]), 1)} wg]'))
+    rows.sort()
+    pairs = collections.defaultdict(list)
+    for (s0, e0, n0), (s1, e1, n1) in zip(rows, rows[1:]):
+        gap = (s1 - e0) / 1e3
+        if gap <= max_gap_us:
+            pairs[(n0, n1)].append((gap, (s1 - s0) / 1e3, (e0 - s0) / 1e3))
+    out = {}
+    for key, v in pairs.items():
+        gaps = sorted(g for g, _, _ in v)
+        periods = sorted(p for _, p, _ in v)
+        durs = sorted(d for _, _, d in v)
+        out[key] = (len(v), gaps[len(gaps) // 2], sum(gaps) / len(gaps), periods[len(periods) // 2], durs[len(durs) // 2])
+    return out
+
+
 def counter_means(pmc_dir, counter):
     rows = collections.defaultdict(list)
     with open(_one(pmc_dir, "*_counter_collection.csv")) as fh:
@@ -79,6 +103,7 @@ def main():
     ap.add_argument("--command", required=True, help="the full profiled command, for the record")
     ap.add_argument("--kernel", default="w4_gemv_kernel", help="substring naming the dominant kernel")
     ap.add_argument("--title", default="decode GEMV sweep (bench.py)", help="what was profiled, for the heading")
+    ap.add_argument("--gaps", action="store_true", help="add the end-to-start gaps between consecutive kernels")
     ap.add_argument("--out-md", required=True)
     ap.add_argument("--out-json")
     args = ap.parse_args()
@@ -101,6 +126,16 @@ def main():
                   f"mean {dom_mean:.3f} us per launch.", ""]
 
     out = {"kernel": args.kernel, "mean_launch_us": dom_mean, "launches": int(dom_calls)}
+    if args.gaps:
+        lines += ["## End-to-start gaps between consecutive kernels (--kernel-trace timestamps), microseconds", "",
+                  "Gap = start of the next kernel minus end of the previous one; period = start to start.  Pairs with "
+                  "at least 50 occurrences; pauses above 20 us (between graph replays) left out.", "",
+                  "| previous kernel | next kernel | pairs | median gap | mean gap | median duration of previous | median period |",
+                  "|---|---|---|---|---|---|---|"]
+        for (n0, n1), (n, med, mean, period, dur) in sorted(trace_gaps(args.trace_dir).items(), key=lambda kv: -kv[1][0]):
+            if n >= 50:
+                lines.append(f"| {n0} | {n1} | {n} | {med:.2f} | {mean:.2f} | {dur:.2f} | {period:.2f} |")
+        lines.append("")
     if args.fetch_dir and args.write_dir:
         fetch = counter_means(args.fetch_dir, "FETCH_SIZE")
         write = counter_means(args.write_dir, "WRITE_SIZE")
