@@ -207,10 +207,9 @@ dmr_status_t dmr_qlinear_quantize(int64_t K, int64_t N, int32_t g, const float *
  * which it could only run fake-quantised and whose cost it projected as T_W4 / 1.15 (App. A).  Format:
  * codes 0..7, 32 per three words along k (code j in bits [3j, 3j+3) of the 96-bit little-endian run),
  * qweight3 uint32 [N][3K/32]; scales and zeros as for 4 bits, zero points 0..7.  The handle these
- * calls return is used with dmr_qlinear_dequantize / _forward / _destroy like a 4-bit one.  Decode and
- * rollout batches (M up to 128, more on narrow layers) run native kernels that unpack the 3-bit codes in
- * registers (d_ws only for fp32 partial sums where K is split); prefill-sized M dequantises the layer
- * into d_ws and takes the bf16 path.  d_ws as dmr_qlinear_w3_workspace_bytes says.
+ * calls return is used with dmr_qlinear_dequantize / _forward / _destroy like a 4-bit one.  Every size class
+ * runs native kernels that unpack the 3-bit codes in registers or on their way into LDS and keep them exact;
+ * d_ws only holds fp32 partial sums where K is split, as dmr_qlinear_w3_workspace_bytes says.
  */
 size_t dmr_qlinear_w3_storage_bytes(int64_t K, int64_t N, int32_t g);
 size_t dmr_qlinear_w3_workspace_bytes(int64_t M, int64_t K, int64_t N);
@@ -247,8 +246,7 @@ dmr_status_t dmr_probe_empty_launch(int32_t blocks, int32_t threads, size_t lds_
 /*
  * Diagnostic, not part of a routed step: the name of the kernel class that serves M rows of a (K, N) layer
  * held in `format` ("w4_gemv", "w4_stream", "w4_panel", "w4_wide", "w4_skinny2", "w4_mid",
- * "w4_gemm128_exact", the "w3_*" and "bf16_*" counterparts, "w3_dequant" for a 3-bit layer
- * that is dequantised and handed to the bf16 path; "none" for an unsupported shape).  Pure host arithmetic,
+ * "w4_gemm128_exact", the "w3_*" and "bf16_*" counterparts; "none" for an unsupported shape).  Pure host arithmetic,
  * the same the forward calls use; a decode row too long for the M = 1 kernels' LDS budget is served by a
  * fallback of the same name class.  Lets a test or a profile state which kernel it covers.
  */

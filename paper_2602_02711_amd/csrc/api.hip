@@ -36,13 +36,13 @@ W4Path w4_path(int64_t M, int64_t K, int64_t N) {
     if (M <= kSkinnyMaxM) return tiles >= 1024 ? W4Path::Skinny2 : W4Path::Mid;
     // the 128 x 128 GEMM needs about 300 workgroups before it wins (measured)
     const int64_t gemm_wgs = ((M + 127) / 128) * ((N + 127) / 128);
-    return (M <= 128 || gemm_wgs < 300) ? W4Path::Mid : W4Path::Gemm;
+    return (M <= 128 || gemm_wgs < dmr::env_int("DMR_W4_GEMM_MIN_WGS", 300)) ? W4Path::Mid : W4Path::Gemm;
 }
 
 // 3-bit layers: the 4-bit size classes on the native 3-bit kernels; a decode row too long for the GEMV's LDS
-// budget takes the rollout-batch kernel (which slices K), and what the 4-bit dispatch hands to a tiled GEMM
-// is dequantised to bf16 first.  The workspace query and the forward call both go through this.
-enum class W3Path { Gemv, Stream, Panel, Wide, Mid, Dequant };
+// budget takes the rollout-batch kernel (which slices K).  The workspace query and the forward call both go
+// through this.
+enum class W3Path { Gemv, Stream, Panel, Wide, Mid, Gemm };
 W3Path w3_path(int64_t M, int64_t K, int64_t N) {
     if (M == 1) return dmr::w3_gemv_fits(K, N) ? W3Path::Gemv : W3Path::Mid;
     if (M <= 16) {
@@ -51,7 +51,7 @@ W3Path w3_path(int64_t M, int64_t K, int64_t N) {
     }
     if (M <= kSkinnyMaxM && dmr::w4_wide_applies(M, K, N)) return W3Path::Wide;
     const int64_t gemm_wgs = ((M + 127) / 128) * ((N + 127) / 128);
-    return (M <= 128 || gemm_wgs < 300) ? W3Path::Mid : W3Path::Dequant;
+    return (M <= 128 || gemm_wgs < 300) ? W3Path::Mid : W3Path::Gemm;
 }
 
 // The bf16 twin: GEMV, the direct-from-L2 skinny kernel for 2..8 rows (measured faster there than the
@@ -204,8 +204,6 @@ size_t dmr_qlinear_w3_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     switch (w3_path(M, K, N)) {
         case W3Path::Panel: return dmr::w4_panel_workspace_bytes(M, K, N);   // fp32 partials of the k slices
         case W3Path::Mid: return dmr::w4_mid_workspace_bytes(M, K, N);       // fp32 partials when K is split
-        // the layer dequantised to bf16, then the bf16 path's own scratch
-        case W3Path::Dequant: return (size_t)N * (size_t)K * 2 + dmr_qlinear_bf16_workspace_bytes(M, K, N);
         default: return 0;
     }
 }
@@ -287,14 +285,9 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
             case W3Path::Panel: return hip_status(dmr::launch_w3_panel(L3, d_x, M, d_y, f32, d_ws, s));
             case W3Path::Wide: return hip_status(dmr::launch_w3_wide(L3, d_x, M, d_y, f32, s));
             case W3Path::Mid: return hip_status(dmr::launch_w3_mid(L3, d_x, M, d_y, f32, d_ws, s));
-            case W3Path::Dequant: break;
+            case W3Path::Gemm: return hip_status(dmr::launch_w3_gemm(L3, d_x, M, d_y, f32, s));
         }
-        // prefill-sized M: dequantise into the workspace, then the bf16 path
-        const hipError_t e = dmr::launch_dequantize3(L3, static_cast<uint16_t *>(d_ws), s);
-        if (e != hipSuccess) return DMR_ERR_HIP;
-        const size_t wbytes = (size_t)layer->N * (size_t)layer->K * 2;       // bf16 weights, then the twin's own scratch
-        return dmr_qlinear_bf16_forward(static_cast<const uint16_t *>(d_ws), d_x, M, layer->K, layer->N, d_y, out,
-                                        static_cast<uint8_t *>(d_ws) + wbytes, need3 - wbytes, stream);
+        return DMR_ERR_UNSUPPORTED;
     }
     const size_t need = dmr_qlinear_workspace_bytes(M, layer->K, layer->N);
     if (need > 0 && (!d_ws || ws_bytes < need)) return DMR_ERR_WORKSPACE;
@@ -577,7 +570,7 @@ const char *dmr_qlinear_kernel_path(dmr_format_t format, int64_t M, int64_t K, i
                 case W3Path::Panel: return "w3_panel";
                 case W3Path::Wide: return "w3_wide";
                 case W3Path::Mid: return "w3_mid";
-                default: return "w3_dequant";       // then whatever bf16_* serves the shape
+                default: return "w3_gemm128_exact";
             }
         case DMR_FMT_W4_G128:
         case DMR_FMT_W4_PER_CHANNEL:

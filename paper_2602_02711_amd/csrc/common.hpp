@@ -191,6 +191,8 @@ hipError_t launch_bf16_skinny(const uint16_t *w, const uint16_t *x, int64_t M, i
 // (per-channel layers), otherwise the weights are rounded to bf16 on their way into LDS.
 hipError_t launch_w4_gemm(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, bool exact,
                           hipStream_t stream);
+// The exact-code 128 x 128 kernel on a 3-bit layer.
+hipError_t launch_w3_gemm(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32, hipStream_t stream);
 hipError_t launch_bf16_gemm(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
                             void *y, bool out_f32, hipStream_t stream);
 // 256 x 256 tiling (direct-to-LDS operand loads, four-stage pipeline) for problems large enough to fill the

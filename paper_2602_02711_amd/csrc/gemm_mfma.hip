@@ -7,8 +7,10 @@
 //   kSrcW4Exact INT4 codes enter LDS as the exact small integers (q - z); the MFMAs of one group of
 //               128 k accumulate into a per-group tile that is folded into the result with the
 //               group's scale in fp32, acc += s[n][G] * D_G, so no weight is ever rounded.  About a
-//               third slower (fold work, 222 registers); used for per-channel layers, whose widely
-//               differing row scales make the rounded variant miss the bound.
+//               third slower (fold work, 222 registers); what every tiled INT4 launch takes (the rounded
+//               variant leaves the largest of 10^7 outputs at 0.8 .. 1.1 of the 1e-2 rms bound).
+//   kSrcW3Exact the same on the 3-bit streaming layout (768-byte blocks, unpacked with the byte masks of
+//               w3_unpack.hpp), so that a 3-bit layer needs no dequantised copy at prefill sizes.
 //
 // Workgroup tile 128 (m) x 128 (n) x 64 (k), 4 wavefronts in a 2 x 2 grid, each owning a 64 x 64
 // patch as 2 x 2 tiles of v_mfma_f32_32x32x16_bf16.  Global loads for step i+1 are issued into
@@ -17,20 +19,20 @@
 //
 // Operand layout of a 32x32x16 MFMA: lane l supplies row (l % 32), k = 8 (l / 32) .. + 7 of A and
 // of B; accumulator register r of lane l is (A row 8 (r / 4) + 4 (l / 32) + r % 4, B row l % 32).
-#include "common.hpp"
+#include "w3_unpack.hpp"
 
 namespace dmr {
 
 namespace {
 
 constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int kSrcBf16 = 0, kSrcW4 = 1, kSrcW4Exact = 2;
+constexpr int kSrcBf16 = 0, kSrcW4 = 1, kSrcW4Exact = 2, kSrcW3Exact = 3;
 constexpr int LDS_STRIDE = BK + 8;   // bf16 elements per padded LDS row (144 bytes)
 
 template <int SRC>
 struct Prefetch {
     uint4 xa[4];
-    uint4 wb[4];       // bf16 source: 4 x 16 bytes; INT4 source: wb[0] = 32 packed weights
+    uint4 wb[4];       // bf16 source: 4 x 16 bytes; INT4 source: wb[0] = 32 packed weights (3-bit: three words)
     uint32_t szw;
 };
 
@@ -55,7 +57,12 @@ __device__ __forceinline__ void load_global(Prefetch<SRC> &p, const void *__rest
         const int64_t T = n0 / kTileRows + (tid >> 5);
         const int l = half * 32 + (tid & 31);
         if (T * kTileRows < N) {
-            p.wb[0] = reinterpret_cast<const uint4 *>(wsrc)[(T * groups + G) * 64 + l];
+            if (SRC == kSrcW3Exact) {
+                const uint32_t *w3 = reinterpret_cast<const uint32_t *>(wsrc) + ((T * groups + G) * 64 + l) * 3;
+                p.wb[0] = make_uint4(w3[0], w3[1], w3[2], 0);
+            } else {
+                p.wb[0] = reinterpret_cast<const uint4 *>(wsrc)[(T * groups + G) * 64 + l];
+            }
             p.szw = sz[(T * groups + G) * kTileRows + (l & 15)];
         } else {
             p.wb[0] = make_uint4(0, 0, 0, 0);
@@ -90,18 +97,21 @@ __device__ __forceinline__ void store_lds(const Prefetch<SRC> &p, uint16_t *As, 
         const float s = __uint_as_float(p.szw << 16);
         const float czs = cz * s;                                // -(128 + z) s, exact in fp32
         const uint32_t words[4] = {p.wb[0].x, p.wb[0].y, p.wb[0].z, p.wb[0].w};
+        uint32_t r3[16];                                         // 3-bit: the lane's 16 (128 + q) pairs, k ascending
+        if (SRC == kSrcW3Exact) unpack3(words[0], words[1], words[2], r3);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             uint32_t o[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                // (128 + q) as fp32 straight from the bf16 magic pair.  Exact variant: adding
+                // (128 + q) as fp32 straight from the bf16 magic pair.  Exact variants: adding
                 // -(128 + z) leaves the integer q - z in [-15, 15], which bf16 holds exactly.
                 // Rounded variant: (128 + q) s - (128 + z) s = (q - z) s in one fma (exact in fp32), then RNE.
-                const uint32_t pair = ((words[t] >> (4 * i)) & 0x000F000Fu) | 0x43004300u;
+                const uint32_t pair = SRC == kSrcW3Exact ? r3[4 * t + i]
+                                                         : (((words[t] >> (4 * i)) & 0x000F000Fu) | 0x43004300u);
                 const float plo = __uint_as_float(pair << 16), phi = __uint_as_float(pair & 0xFFFF0000u);
-                const float lo = SRC == kSrcW4Exact ? plo + cz : fmaf(plo, s, czs);
-                const float hi = SRC == kSrcW4Exact ? phi + cz : fmaf(phi, s, czs);
+                const float lo = SRC != kSrcW4 ? plo + cz : fmaf(plo, s, czs);
+                const float hi = SRC != kSrcW4 ? phi + cz : fmaf(phi, s, czs);
                 o[i] = pack_bf16x2(lo, hi);
             }
             *reinterpret_cast<uint4 *>(Bs + row * LDS_STRIDE + kofs + t * 8) =
@@ -140,7 +150,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const void *__restrict__ w
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
     // exact INT4: per-group accumulators and this lane's two weight rows (one per n tile)
-    constexpr bool EXACT = SRC == kSrcW4Exact;
+    constexpr bool EXACT = SRC == kSrcW4Exact || SRC == kSrcW3Exact;
     f32x16 grp[2][2];
     if (EXACT) {
 #pragma unroll
@@ -240,6 +250,11 @@ hipError_t launch_w4_gemm(const LayerView &L, const uint16_t *x, int64_t M, void
                           hipStream_t stream) {
     return exact ? launch<kSrcW4Exact>(L.wt, L.sz, x, M, L.K, L.N, y, out_f32, stream)
                  : launch<kSrcW4>(L.wt, L.sz, x, M, L.K, L.N, y, out_f32, stream);
+}
+
+hipError_t launch_w3_gemm(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+                          hipStream_t stream) {
+    return launch<kSrcW3Exact>(L.wt, L.sz, x, M, L.K, L.N, y, out_f32, stream);
 }
 
 hipError_t launch_bf16_gemm(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,

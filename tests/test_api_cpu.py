@@ -160,10 +160,10 @@ def test_w3_size_query_and_kernel_paths(lib):
     need = q3(1, 32768, 528)
     assert need > 0 and need % (528 * 4) == 0
     assert path(binding.DMR_FMT_W3_G128, 1, 4096, 4096) == b"w3_gemv"
-    # the rollout-batch sizes share the 4-bit plan; prefill sizes hold the dequantised layer first
+    # the rollout-batch sizes share the 4-bit plan; prefill sizes take the tiled kernel, which needs no scratch
     assert q3(64, 4096, 4096) == lib.dmr_qlinear_workspace_bytes(64, 4096, 4096)
-    assert q3(1200, 512, 4096) == 4096 * 512 * 2 + lib.dmr_qlinear_bf16_workspace_bytes(1200, 512, 4096)
-    assert path(binding.DMR_FMT_W3_G128, 1200, 512, 4096) == b"w3_dequant"
+    assert q3(1200, 512, 4096) == 0
+    assert path(binding.DMR_FMT_W3_G128, 1200, 512, 4096) == b"w3_gemm128_exact"
     # the kernel classes of the four decoder shapes at the sizes of the benchmark configurations
     assert path(binding.DMR_FMT_W4_G128, 1, 4096, 28672) == b"w4_gemv"
     assert path(binding.DMR_FMT_W4_G128, 8, 14336, 4096) == b"w4_panel"
