@@ -454,6 +454,10 @@ def w3_sweep(args, dmr, synth, torch, dev):
         n = -(-(1 << 30) // w3_bytes(K, N, 1))
         l4 = [dmr.dmr_qlinear_create(*q4, G) for _ in range(n)]
         l3 = [dmr.dmr_qlinear_w3_create(*q3, G) for _ in range(n)]
+        # per-channel symmetric W4 (one scale per row, zero point 8): the codes of the group-wise copy stand in for
+        # its codes (timing depends on the bytes only); 0.5 byte per weight + 4 bytes per row
+        row_scale = q4[1][:, 0].contiguous()
+        lpc = [dmr.dmr_qlinear_create_per_channel(q4[0], row_scale) for _ in range(n)]
         del w, q4, q3
         for M in Ms:
             gen.manual_seed(synth.seed_for(2, si, 1) + M)
@@ -463,11 +467,15 @@ def w3_sweep(args, dmr, synth, torch, dev):
             ws3 = torch.empty(max(dmr.dmr_qlinear_w3_workspace_bytes(M, K, N), 16), dtype=torch.uint8, device=dev)
             t4 = timeit(lambda i: dmr.dmr_qlinear_forward(l4[i % n], x, out=y, workspace=ws4), 100)
             t3 = timeit(lambda i: dmr.dmr_qlinear_forward(l3[i % n], x, out=y, workspace=ws3), 100)
+            tpc = timeit(lambda i: dmr.dmr_qlinear_forward(lpc[i % n], x, out=y, workspace=ws4), 100)
+            pc_bytes = N * K // 2 + N * 4 + M * K * 2 + M * N * 2
             rows.append({"shape": name, "K": K, "N": N, "M": M, "w4_us": round(t4, 2), "w3_us": round(t3, 2),
                          "w4_over_w3": round(t4 / t3, 3), "w3_GBps": round(w3_bytes(K, N, M) / t3 / 1e3, 1),
-                         "w4_GBps": round(int4_bytes(K, N, M) / t4 / 1e3, 1)})
-            log(f"[bench] {name:9s} M={M:3d} W4 {t4:7.2f} us  W3 {t3:7.2f} us  W4/W3 {t4 / t3:5.3f}")
-        del l4, l3
+                         "w4_GBps": round(int4_bytes(K, N, M) / t4 / 1e3, 1),
+                         "w4_per_channel_us": round(tpc, 2), "w4_per_channel_GBps": round(pc_bytes / tpc / 1e3, 1)})
+            log(f"[bench] {name:9s} M={M:3d} W4 {t4:7.2f} us  W3 {t3:7.2f} us  W4/W3 {t4 / t3:5.3f}  "
+                f"W4 per-channel {tpc:7.2f} us")
+        del l4, l3, lpc
     tot4 = sum(r["w4_us"] for r in rows)
     tot3 = sum(r["w3_us"] for r in rows)
     result = {

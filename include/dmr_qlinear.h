@@ -83,9 +83,12 @@ dmr_status_t dmr_qlinear_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32
  * The paper's literal W4A16 setting, "default per-channel grouping" (App. E "Per-cell configuration"):
  * symmetric INT4 with one bf16 scale per output row and the fixed zero point 8,
  *   w^[n][k] = (q[n][k] - 8) * scales[n].
- * d_scales is bf16 [N].  The handle behaves like a group-wise one (g reported as K); in this build
- * the row scale is replicated into the per-group stream, so storage and traffic are those of g = 128.
+ * d_scales is bf16 [N].  The handle behaves like a group-wise one (g reported as K).  Storage
+ * (dmr_qlinear_per_channel_storage_bytes) is 0.5 byte per weight plus one 4-byte scale word per row: no per-group
+ * stream, so a decode step moves 0.5 instead of 0.53125 byte per weight.  The kernels are the group-wise ones
+ * reading the row's one word for every group.
  */
+size_t dmr_qlinear_per_channel_storage_bytes(int64_t K, int64_t N);
 dmr_status_t dmr_qlinear_create_per_channel(dmr_qlinear_t **out, int64_t K, int64_t N,
                                             const uint32_t *d_qweight, /* [N][K/8] */
                                             const uint16_t *d_scales,  /* bf16 [N] */

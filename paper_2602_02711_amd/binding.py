@@ -29,6 +29,7 @@ EXPORTS = (
     "dmr_glue_rmsnorm", "dmr_glue_swiglu", "dmr_qlinear_fused_workspace_bytes",
     "dmr_qlinear_bf16_fused_workspace_bytes", "dmr_qlinear_forward_fused", "dmr_qlinear_bf16_forward_fused",
     "dmr_qlinear_kernel_path", "dmr_qlinear_forward_static", "dmr_probe_empty_launch", "dmr_qlinear_set_next",
+    "dmr_qlinear_per_channel_storage_bytes",
 )
 
 DMR_PRO_NONE, DMR_PRO_RMSNORM, DMR_PRO_SWIGLU = 0, 1, 2
@@ -84,6 +85,8 @@ def lib() -> ctypes.CDLL:
         L.dmr_qlinear_w3_create.argtypes = [ctypes.POINTER(vp), i64, i64, i32, vp, vp, vp, vp, sz, vp]
         L.dmr_qlinear_quantize_w3.restype = ctypes.c_int
         L.dmr_qlinear_quantize_w3.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp]
+        L.dmr_qlinear_per_channel_storage_bytes.restype = sz
+        L.dmr_qlinear_per_channel_storage_bytes.argtypes = [i64, i64]
         L.dmr_qlinear_create_per_channel.restype = ctypes.c_int
         L.dmr_qlinear_create_per_channel.argtypes = [ctypes.POINTER(vp), i64, i64, vp, vp, vp, sz, vp]
         L.dmr_qlinear_bits.restype = i32
@@ -289,6 +292,10 @@ def dmr_qlinear_quantize(w: torch.Tensor, g: int = 128, stream=None):
     return qweight, scales, zeros
 
 
+def dmr_qlinear_per_channel_storage_bytes(K: int, N: int) -> int:
+    return int(lib().dmr_qlinear_per_channel_storage_bytes(K, N))
+
+
 def dmr_qlinear_create_per_channel(qweight: torch.Tensor, scales: torch.Tensor,
                                    storage: torch.Tensor | None = None, stream=None) -> Layer:
     """Symmetric per-channel INT4: qweight [N][K/8], one bf16 scale per row, zero point 8."""
@@ -298,7 +305,7 @@ def dmr_qlinear_create_per_channel(qweight: torch.Tensor, scales: torch.Tensor,
     K = K8 * 8
     if scales.numel() != N:
         raise ValueError("scales must hold one value per row")
-    need = dmr_qlinear_storage_bytes(K, N, 128)
+    need = dmr_qlinear_per_channel_storage_bytes(K, N)
     if storage is None:
         storage = torch.empty(max(need, 16), dtype=torch.uint8, device=qweight.device)
     pst = _dev(storage, "storage", (torch.uint8,))

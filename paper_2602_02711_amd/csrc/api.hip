@@ -13,6 +13,7 @@ struct dmr_qlinear {
     const uint4 *wt;        // 4-bit streaming blocks
     const uint32_t *wt3;    // 3-bit streaming blocks
     const uint32_t *sz;
+    int32_t szs;            // 1: a scale / zero word per (row, group); 0: one per row (per-channel layers)
     const dmr_qlinear *next;   // the layer read after this one in a decode step, or null (dmr_qlinear_set_next)
 };
 
@@ -145,6 +146,7 @@ dmr_status_t dmr_qlinear_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32
     h->N = N;
     h->g = g;
     h->bits = 4;
+    h->szs = 1;
     h->next = nullptr;
     h->wt3 = nullptr;
     uint8_t *base = static_cast<uint8_t *>(d_storage);
@@ -162,6 +164,11 @@ dmr_status_t dmr_qlinear_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32
     return DMR_OK;
 }
 
+size_t dmr_qlinear_per_channel_storage_bytes(int64_t K, int64_t N) {
+    if (check_shape(K, N, dmr::kGroup) != DMR_OK) return 0;
+    return dmr::weight_region_bytes(K, N) + dmr::sz_region_bytes_per_channel(N);
+}
+
 dmr_status_t dmr_qlinear_create_per_channel(dmr_qlinear_t **out, int64_t K, int64_t N,
                                             const uint32_t *d_qweight, const uint16_t *d_scales,
                                             void *d_storage, size_t storage_bytes, void *stream) {
@@ -171,13 +178,14 @@ dmr_status_t dmr_qlinear_create_per_channel(dmr_qlinear_t **out, int64_t K, int6
     if (shape != DMR_OK) return shape;
     if (!d_qweight || !d_scales || !d_storage) return DMR_ERR_NULL;
     if (!aligned16(d_qweight) || !aligned16(d_scales) || !aligned16(d_storage)) return DMR_ERR_ALIGN;
-    if (storage_bytes < dmr_qlinear_storage_bytes(K, N, dmr::kGroup)) return DMR_ERR_WORKSPACE;
+    if (storage_bytes < dmr_qlinear_per_channel_storage_bytes(K, N)) return DMR_ERR_WORKSPACE;
     dmr_qlinear *h = new (std::nothrow) dmr_qlinear;
     if (!h) return DMR_ERR_NULL;
     h->K = K;
     h->N = N;
     h->g = (int32_t)K;      // one group spans the whole row
     h->bits = 4;
+    h->szs = 0;             // one scale word per row behind the weights: 0.5 byte per weight + 4 bytes per row
     h->next = nullptr;
     h->wt3 = nullptr;
     uint8_t *base = static_cast<uint8_t *>(d_storage);
@@ -226,6 +234,7 @@ dmr_status_t dmr_qlinear_w3_create(dmr_qlinear_t **out, int64_t K, int64_t N, in
     h->N = N;
     h->g = g;
     h->bits = 3;
+    h->szs = 1;
     h->next = nullptr;
     h->wt = nullptr;
     uint8_t *base = static_cast<uint8_t *>(d_storage);
@@ -261,7 +270,7 @@ dmr_status_t dmr_qlinear_dequantize(const dmr_qlinear_t *layer, uint16_t *d_w_bf
         const dmr::LayerView3 L3{layer->K, layer->N, layer->wt3, layer->sz};
         return hip_status(dmr::launch_dequantize3(L3, d_w_bf16, static_cast<hipStream_t>(stream)));
     }
-    const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz};
+    const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz, layer->szs};
     return hip_status(dmr::launch_dequantize(L, d_w_bf16, static_cast<hipStream_t>(stream)));
 }
 
@@ -291,7 +300,7 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
     }
     const size_t need = dmr_qlinear_workspace_bytes(M, layer->K, layer->N);
     if (need > 0 && (!d_ws || ws_bytes < need)) return DMR_ERR_WORKSPACE;
-    const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz};
+    const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz, layer->szs};
     const W4Path path = w4_path(M, layer->K, layer->N);
     if (path == W4Path::Gemv) {
         dmr::Fusion f;
@@ -448,7 +457,7 @@ dmr_status_t dmr_qlinear_forward_fused(const dmr_qlinear_t *layer, dmr_prologue_
     if (need > 0 && (!d_ws || ws_bytes < need)) return DMR_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (M == 1 && layer->bits == 4) {
-        const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz};
+        const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz, layer->szs};
         dmr::Fusion f;
         f.pro = (int)pro;
         f.aux = d_gamma;
@@ -459,7 +468,7 @@ dmr_status_t dmr_qlinear_forward_fused(const dmr_qlinear_t *layer, dmr_prologue_
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: shape outside the GEMV's range
     }
     if (M >= 2 && M <= 16 && layer->bits == 4 && dmr::w4_stream_fits(M, layer->K, layer->N)) {
-        const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz};
+        const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz, layer->szs};
         dmr::Fusion f;
         f.pro = (int)pro;
         f.aux = d_gamma;

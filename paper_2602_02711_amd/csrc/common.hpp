@@ -119,7 +119,14 @@ struct LayerView {
     int64_t K, N;
     const uint4 *wt;       // streaming weight blocks
     const uint32_t *sz;    // streaming scale / zero words
+    int szs = 1;           // 1: one scale / zero word per (row, group); 0: one per row (per-channel layers)
 };
+
+// Index of the scale / zero word of row j of tile `tile` for group g: [tile][group][16] with one word per group
+// (szs = 1), or [tile][16] with one word per row, whatever the group (szs = 0).
+__host__ __device__ __forceinline__ int64_t sz_index(int64_t tile, int64_t g, int64_t groups, int szs, int j) {
+    return (tile * (szs * (groups - 1) + 1) + g * szs) * kTileRows + j;
+}
 
 struct LayerView3 {       // 3-bit variant: 64 lanes x 3 words per block
     int64_t K, N;
@@ -130,6 +137,7 @@ struct LayerView3 {       // 3-bit variant: 64 lanes x 3 words per block
 inline size_t weight3_region_bytes(int64_t K, int64_t N) { return (size_t)N * (size_t)K / 32 * 12; }
 inline size_t weight_region_bytes(int64_t K, int64_t N) { return (size_t)N * (size_t)K / 2; }
 inline size_t sz_region_bytes(int64_t K, int64_t N) { return (size_t)N * (size_t)(K / kGroup) * 4; }
+inline size_t sz_region_bytes_per_channel(int64_t N) { return (size_t)N * 4; }
 
 // Kernel launchers (each returns hipGetLastError() after its launch).
 hipError_t launch_retile(int64_t K, int64_t N, const uint32_t *qweight, const uint16_t *scales,

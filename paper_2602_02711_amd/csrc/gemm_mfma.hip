@@ -40,7 +40,7 @@ template <int SRC>
 __device__ __forceinline__ void load_global(Prefetch<SRC> &p, const void *__restrict__ wsrc,
                                             const uint32_t *__restrict__ sz,
                                             const uint16_t *__restrict__ x, int64_t M, int64_t K,
-                                            int64_t N, int64_t m0, int64_t n0, int64_t k0, int tid) {
+                                            int64_t N, int64_t m0, int64_t n0, int64_t k0, int tid, int szs) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int idx = tid + 256 * i;
@@ -63,7 +63,7 @@ __device__ __forceinline__ void load_global(Prefetch<SRC> &p, const void *__rest
             } else {
                 p.wb[0] = reinterpret_cast<const uint4 *>(wsrc)[(T * groups + G) * 64 + l];
             }
-            p.szw = sz[(T * groups + G) * kTileRows + (l & 15)];
+            p.szw = sz[sz_index(T, G, groups, szs, l & 15)];
         } else {
             p.wb[0] = make_uint4(0, 0, 0, 0);
             p.szw = 0xC3000000u;   // s = 0, -(128 + z) = -128: contributes zeros
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const void *__restrict__ w
                                                    const uint32_t *__restrict__ sz,
                                                    const uint16_t *__restrict__ x,
                                                    void *__restrict__ y, int64_t M, int64_t K,
-                                                   int64_t N) {
+                                                   int64_t N, int szs) {
     __shared__ __attribute__((aligned(16))) uint16_t As[BM * LDS_STRIDE];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * LDS_STRIDE];
     const int tid = threadIdx.x;
@@ -166,21 +166,21 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const void *__restrict__ w
     for (int j = 0; j < 2; ++j) {
         const int64_t n = n0 + wn * 64 + j * 32 + (lane & 31);
         const int64_t nc = n < N ? n : N - 1;                         // clamped: never stored
-        srow[j] = ((nc / kTileRows) * groups) * kTileRows + (nc % kTileRows);   // sz index of (row, G = 0)
+        srow[j] = sz_index(nc / kTileRows, 0, groups, szs, (int)(nc % kTileRows));   // sz index of (row, G = 0)
     }
 
     Prefetch<SRC> pre;
-    load_global<SRC>(pre, wsrc, sz, x, M, K, N, m0, n0, 0, tid);
+    load_global<SRC>(pre, wsrc, sz, x, M, K, N, m0, n0, 0, tid, szs);
     for (int64_t k0 = 0; k0 < K; k0 += BK) {
         store_lds<SRC>(pre, As, Bs, tid);
         __syncthreads();
-        if (k0 + BK < K) load_global<SRC>(pre, wsrc, sz, x, M, K, N, m0, n0, k0 + BK, tid);
+        if (k0 + BK < K) load_global<SRC>(pre, wsrc, sz, x, M, K, N, m0, n0, k0 + BK, tid, szs);
         float gscale[2] = {0.f, 0.f};
         const bool group_end = EXACT && ((k0 + BK) % kGroup == 0);
         if (group_end) {
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-                gscale[j] = __uint_as_float(sz[srow[j] + (k0 / kGroup) * kTileRows] << 16);
+                gscale[j] = __uint_as_float(sz[srow[j] + (k0 / kGroup) * kTileRows * szs] << 16);
         }
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
@@ -234,13 +234,13 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const void *__restrict__ w
 }
 
 template <int SRC>
-hipError_t launch(const void *wsrc, const uint32_t *sz, const uint16_t *x, int64_t M, int64_t K,
+hipError_t launch(const void *wsrc, const uint32_t *sz, int szs, const uint16_t *x, int64_t M, int64_t K,
                   int64_t N, void *y, bool out_f32, hipStream_t stream) {
     const dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
     if (out_f32)
-        hipLaunchKernelGGL((gemm_kernel<SRC, true>), grid, dim3(256), 0, stream, wsrc, sz, x, y, M, K, N);
+        hipLaunchKernelGGL((gemm_kernel<SRC, true>), grid, dim3(256), 0, stream, wsrc, sz, x, y, M, K, N, szs);
     else
-        hipLaunchKernelGGL((gemm_kernel<SRC, false>), grid, dim3(256), 0, stream, wsrc, sz, x, y, M, K, N);
+        hipLaunchKernelGGL((gemm_kernel<SRC, false>), grid, dim3(256), 0, stream, wsrc, sz, x, y, M, K, N, szs);
     return hipGetLastError();
 }
 
@@ -248,18 +248,18 @@ hipError_t launch(const void *wsrc, const uint32_t *sz, const uint16_t *x, int64
 
 hipError_t launch_w4_gemm(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, bool exact,
                           hipStream_t stream) {
-    return exact ? launch<kSrcW4Exact>(L.wt, L.sz, x, M, L.K, L.N, y, out_f32, stream)
-                 : launch<kSrcW4>(L.wt, L.sz, x, M, L.K, L.N, y, out_f32, stream);
+    return exact ? launch<kSrcW4Exact>(L.wt, L.sz, L.szs, x, M, L.K, L.N, y, out_f32, stream)
+                 : launch<kSrcW4>(L.wt, L.sz, L.szs, x, M, L.K, L.N, y, out_f32, stream);
 }
 
 hipError_t launch_w3_gemm(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
                           hipStream_t stream) {
-    return launch<kSrcW3Exact>(L.wt, L.sz, x, M, L.K, L.N, y, out_f32, stream);
+    return launch<kSrcW3Exact>(L.wt, L.sz, 1, x, M, L.K, L.N, y, out_f32, stream);
 }
 
 hipError_t launch_bf16_gemm(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
                             void *y, bool out_f32, hipStream_t stream) {
-    return launch<kSrcBf16>(w, nullptr, x, M, K, N, y, out_f32, stream);
+    return launch<kSrcBf16>(w, nullptr, 1, x, M, K, N, y, out_f32, stream);
 }
 
 }  // namespace dmr

@@ -35,12 +35,12 @@ __global__ __launch_bounds__(256) void retile_kernel(int64_t K, int64_t N,
         out[t] = w;
     }
     wt[slot] = make_uint4(out[0], out[1], out[2], out[3]);
-    if (c == 0) {
-        // per-channel symmetric layers carry one scale per row and the fixed zero point 8
+    if (c == 0 && (!per_channel || G == 0)) {
+        // per-channel symmetric layers carry one scale per row and the fixed zero point 8: one word per row
         const uint32_t s_bits = per_channel ? scales[n] : scales[n * groups + G];
         const float z = per_channel ? 8.0f : bf16_bits_to_f32(zeros[n * groups + G]);
         const uint32_t cz_bits = __float_as_uint(-(128.0f + z)) >> 16;   // exact in bf16
-        sz[block * kTileRows + j] = s_bits | (cz_bits << 16);
+        sz[sz_index(T, G, groups, per_channel ? 0 : 1, j)] = s_bits | (cz_bits << 16);
     }
 }
 
@@ -58,7 +58,7 @@ hipError_t launch_retile(int64_t K, int64_t N, const uint32_t *qweight, const ui
 __global__ __launch_bounds__(256) void dequantize_kernel(int64_t K, int64_t N,
                                                          const uint4 *__restrict__ wt,
                                                          const uint32_t *__restrict__ sz,
-                                                         uint16_t *__restrict__ w_bf16) {
+                                                         uint16_t *__restrict__ w_bf16, int szs) {
     const int64_t groups = K / kGroup;
     const int64_t slot = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (slot >= N * K / 32) return;
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(int64_t K, int64_t N,
     const int c = l >> 4, j = l & 15;
     const int64_t n = T * kTileRows + j;
     const uint4 src = wt[slot];
-    const uint32_t szw = sz[block * kTileRows + j];
+    const uint32_t szw = sz[sz_index(T, G, groups, szs, j)];
     const float s = bf16_bits_to_f32(szw & 0xFFFFu);
     const float z = -bf16_bits_to_f32(szw >> 16) - 128.0f;
     const uint32_t in[4] = {src.x, src.y, src.z, src.w};
@@ -91,7 +91,7 @@ hipError_t launch_dequantize(const LayerView &L, uint16_t *w_bf16, hipStream_t s
     const int64_t slots = L.N * L.K / 32;
     const unsigned blocks = (unsigned)((slots + 255) / 256);
     hipLaunchKernelGGL(dequantize_kernel, dim3(blocks), dim3(256), 0, stream, L.K, L.N, L.wt, L.sz,
-                       w_bf16);
+                       w_bf16, L.szs);
     return hipGetLastError();
 }
 

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
                                                        void *__restrict__ y, int groups, int tiles,
                                                        int lgS, int lgTW, int nT_max, int out_f32,
                                                        const uint16_t *__restrict__ aux, float eps,
-                                                       const uint16_t *__restrict__ res, NextPlan nx) {
+                                                       const uint16_t *__restrict__ res, NextPlan nx, int szs) {
     extern __shared__ uint4 smem[];          // x (16 uint4 per group), X[groups], red[nT_max][TW][S][16], 16 floats
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform (SGPR)
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
         const int tile = min(t_first + it * t_step, tiles - 1);
         const int64_t block = (int64_t)tile * groups + (g0 + ig);
         dst.w = load_stream(wt + block * 64 + lane);
-        dst.szw = load_stream(sz + block * kTileRows + j);
+        dst.szw = load_stream(sz + sz_index(tile, g0 + ig, groups, szs, j));
         if (issued + 1 < items) {
             ++issued;
             if (++ig == GW) {
@@ -382,7 +382,7 @@ hipError_t launch_w4_gemv_fused(const LayerView &L, const uint16_t *x, void *y, 
     }
 #define DMR_GEMV_LAUNCH_PF(PP, XX, PRO, PFN)                                                           \
     hipLaunchKernelGGL((w4_gemv_kernel<PP, XX, PRO, PFN>), g, b, lds, stream, L.wt, L.sz, x, y, groups, tiles, \
-                       lgS, lgTW, nT_max, of, f.aux, f.eps, f.res, nx)
+                       lgS, lgTW, nT_max, of, f.aux, f.eps, f.res, nx, L.szs)
 #define DMR_GEMV_LAUNCH_PRO(PP, XX, PRO)                                                               \
     do {                                                                                               \
         if ((PP == 4 || PP == 2) && PF == 2) DMR_GEMV_LAUNCH_PF(PP, XX, PRO, ((PP == 4 || PP == 2) ? 2 : 0)); \

@@ -34,7 +34,7 @@ constexpr int ROW_BYTES = 272;   // one activation row of a group in LDS: 128 bf
 template <int MTW, int WM, int NW, int R, int BITS>
 __global__ __launch_bounds__(64 * WM * NW, (WM * NW == 4) ? 2 : 1) void w4_mid_kernel(
     const void *__restrict__ wt, const uint32_t *__restrict__ sz, const uint16_t *__restrict__ x,
-    void *__restrict__ y, int M, int64_t K, int64_t N, int groups, int tiles, int gps, int out_mode) {
+    void *__restrict__ y, int M, int64_t K, int64_t N, int groups, int tiles, int gps, int out_mode, int szs) {
     constexpr int THREADS = 64 * WM * NW;
     constexpr int BM = 16 * MTW * WM;
     constexpr int ROWS_PER_PASS = THREADS / 16;
@@ -53,8 +53,14 @@ __global__ __launch_bounds__(64 * WM * NW, (WM * NW == 4) ? 2 : 1) void w4_mid_k
 
     const int tile0 = ((int)blockIdx.x * NW + wn) * R;
     int64_t wbase[R];          // block index of (tile, group 0); ragged last column block re-reads the last tile
+    int64_t sbase[R];          // its first scale / zero word (wave-uniform, like wbase)
 #pragma unroll
-    for (int rt = 0; rt < R; ++rt) wbase[rt] = (int64_t)min(tile0 + rt, tiles - 1) * groups;
+    for (int rt = 0; rt < R; ++rt) {
+        wbase[rt] = (int64_t)min(tile0 + rt, tiles - 1) * groups;
+        sbase[rt] = sz_index(min(tile0 + rt, tiles - 1), 0, groups, szs, 0);
+    }
+    const uint32_t *szj = sz + j;
+    const int sstep = szs * kTileRows;
 
     struct Slot {
         uint4 w[R];            // BITS == 3: .x .y .z hold the lane's three words
@@ -73,7 +79,7 @@ __global__ __launch_bounds__(64 * WM * NW, (WM * NW == 4) ? 2 : 1) void w4_mid_k
                 s.w[rt].y = load_stream(pw + 1);
                 s.w[rt].z = load_stream(pw + 2);
             }
-            s.s[rt] = sz[block * kTileRows + j];
+            s.s[rt] = szj[sbase[rt] + (int64_t)g * sstep];
         }
     };
 
@@ -224,7 +230,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 }
 
 template <int MTW, int WM, int NW, int R, int BITS>
-hipError_t launch_cfg(const void *wt, const uint32_t *sz, int64_t K, int64_t N, const uint16_t *x, int M, void *dst,
+hipError_t launch_cfg(const void *wt, const uint32_t *sz, int szs, int64_t K, int64_t N, const uint16_t *x, int M, void *dst,
                       int out_mode, const MidPlan &p, hipStream_t stream) {
     constexpr int BM = 16 * MTW * WM;
     constexpr size_t lds = 2ull * BM * ROW_BYTES;
@@ -236,21 +242,21 @@ hipError_t launch_cfg(const void *wt, const uint32_t *sz, int64_t K, int64_t N, 
     const int groups = (int)(K / kGroup), tiles = (int)(N / kTileRows);
     const dim3 grid((unsigned)((tiles + NW * R - 1) / (NW * R)), (unsigned)((M + BM - 1) / BM), (unsigned)p.SK);
     hipLaunchKernelGGL((w4_mid_kernel<MTW, WM, NW, R, BITS>), grid, dim3(64 * WM * NW), lds, stream, wt, sz, x, dst, M,
-                       K, N, groups, tiles, p.gps, out_mode);
+                       K, N, groups, tiles, p.gps, out_mode, szs);
     return hipGetLastError();
 }
 
 template <int MTW, int WM, int NW, int BITS>
-hipError_t launch_r(const void *wt, const uint32_t *sz, int64_t K, int64_t N, const uint16_t *x, int M, void *dst,
+hipError_t launch_r(const void *wt, const uint32_t *sz, int szs, int64_t K, int64_t N, const uint16_t *x, int M, void *dst,
                     int out_mode, const MidPlan &p, hipStream_t stream) {
     // R = 4 was measured too: never faster, and with 4 row tiles per wave it needs more than the 256
     // registers that two waves per SIMD leave
-    return p.R == 2 ? launch_cfg<MTW, WM, NW, 2, BITS>(wt, sz, K, N, x, M, dst, out_mode, p, stream)
-                    : launch_cfg<MTW, WM, NW, 1, BITS>(wt, sz, K, N, x, M, dst, out_mode, p, stream);
+    return p.R == 2 ? launch_cfg<MTW, WM, NW, 2, BITS>(wt, sz, szs, K, N, x, M, dst, out_mode, p, stream)
+                    : launch_cfg<MTW, WM, NW, 1, BITS>(wt, sz, szs, K, N, x, M, dst, out_mode, p, stream);
 }
 
 template <int BITS>
-hipError_t launch_mid(const void *wt, const uint32_t *sz, int64_t K, int64_t N, const uint16_t *x, int64_t M, void *y,
+hipError_t launch_mid(const void *wt, const uint32_t *sz, int szs, int64_t K, int64_t N, const uint16_t *x, int64_t M, void *y,
                       bool out_f32, void *ws, hipStream_t stream) {
     const MidPlan p = plan_mid(M, K, N);
     const bool split = p.SK > 1;
@@ -261,14 +267,14 @@ hipError_t launch_mid(const void *wt, const uint32_t *sz, int64_t K, int64_t N, 
     hipError_t e;
     if (p.WM == 1) {
         switch (p.MTW) {
-            case 1: e = launch_r<1, 1, 4, BITS>(wt, sz, K, N, x, iM, dst, out_mode, p, stream); break;
-            case 2: e = launch_r<2, 1, 4, BITS>(wt, sz, K, N, x, iM, dst, out_mode, p, stream); break;
-            case 3: e = launch_r<3, 1, 4, BITS>(wt, sz, K, N, x, iM, dst, out_mode, p, stream); break;
-            default: e = launch_r<4, 1, 4, BITS>(wt, sz, K, N, x, iM, dst, out_mode, p, stream); break;
+            case 1: e = launch_r<1, 1, 4, BITS>(wt, sz, szs, K, N, x, iM, dst, out_mode, p, stream); break;
+            case 2: e = launch_r<2, 1, 4, BITS>(wt, sz, szs, K, N, x, iM, dst, out_mode, p, stream); break;
+            case 3: e = launch_r<3, 1, 4, BITS>(wt, sz, szs, K, N, x, iM, dst, out_mode, p, stream); break;
+            default: e = launch_r<4, 1, 4, BITS>(wt, sz, szs, K, N, x, iM, dst, out_mode, p, stream); break;
         }
     } else {
-        e = p.MTW == 3 ? launch_r<3, 2, 2, BITS>(wt, sz, K, N, x, iM, dst, out_mode, p, stream)
-                       : launch_r<4, 2, 2, BITS>(wt, sz, K, N, x, iM, dst, out_mode, p, stream);
+        e = p.MTW == 3 ? launch_r<3, 2, 2, BITS>(wt, sz, szs, K, N, x, iM, dst, out_mode, p, stream)
+                       : launch_r<4, 2, 2, BITS>(wt, sz, szs, K, N, x, iM, dst, out_mode, p, stream);
     }
     if (e != hipSuccess || !split) return e;
     return launch_splitk_reduce(static_cast<const float *>(ws), y, M * N, p.SK, out_f32, stream);
@@ -290,12 +296,12 @@ size_t w4_mid_workspace_bytes(int64_t M, int64_t K, int64_t N) {
 
 hipError_t launch_w4_mid(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
                          hipStream_t stream) {
-    return launch_mid<4>(L.wt, L.sz, L.K, L.N, x, M, y, out_f32, ws, stream);
+    return launch_mid<4>(L.wt, L.sz, L.szs, L.K, L.N, x, M, y, out_f32, ws, stream);
 }
 
 hipError_t launch_w3_mid(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
                          hipStream_t stream) {
-    return launch_mid<3>(L.wt, L.sz, L.K, L.N, x, M, y, out_f32, ws, stream);
+    return launch_mid<3>(L.wt, L.sz, 1, L.K, L.N, x, M, y, out_f32, ws, stream);
 }
 
 }  // namespace dmr

@@ -61,7 +61,7 @@ __global__ __launch_bounds__(64 * WAVES) void w4_panel_kernel(const void *__rest
                                                               const uint16_t *__restrict__ x,
                                                               void *__restrict__ y, int M, int64_t K, int64_t N,
                                                               int groups, int tiles, int gq, int lgS,
-                                                              int out_mode, uint32_t x16_magic) {
+                                                              int out_mode, uint32_t x16_magic, int szs) {
     extern __shared__ uint4 smem[];   // panel [M][gq * 16 + 1] uint4, then xs [gq][MT][4] f32x4
     constexpr int P = 4;
     const int lane = threadIdx.x & 63;
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(64 * WAVES) void w4_panel_kernel(const void *__rest
                 dst.w[r].y = load_stream(pw + 1);
                 dst.w[r].z = load_stream(pw + 2);
             }
-            dst.szw[r] = load_stream(sz + block * kTileRows + j);
+            dst.szw[r] = load_stream(sz + sz_index(tile, g, groups, szs, j));
         }
     };
 #pragma unroll
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(64 * WAVES) void w4_panel_kernel(const void *__rest
 }
 
 template <int MT, int R, int WAVES, int BITS>
-hipError_t launch_cfg(int64_t K, int64_t N, const void *wt, const uint32_t *sz, const uint16_t *x, int M, void *dst,
+hipError_t launch_cfg(int64_t K, int64_t N, const void *wt, const uint32_t *sz, int szs, const uint16_t *x, int M, void *dst,
                       int out_mode, const PanelPlan &p, hipStream_t stream) {
     // once per process and kernel instantiation (thread-safe static initialisation)
     static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4_panel_kernel<MT, R, WAVES, BITS>),
@@ -265,7 +265,7 @@ hipError_t launch_cfg(int64_t K, int64_t N, const void *wt, const uint32_t *sz, 
     const uint32_t x16_magic = (uint32_t)(((uint64_t(1) << 32) + (uint64_t)p.gq * 16 - 1) / ((uint64_t)p.gq * 16));
     const dim3 grid((unsigned)((tiles + TW * R - 1) / (TW * R)), (unsigned)p.SK);
     hipLaunchKernelGGL((w4_panel_kernel<MT, R, WAVES, BITS>), grid, dim3(64 * WAVES), p.lds, stream, wt, sz, x, dst, M,
-                       K, N, groups, tiles, p.gq, lgS, out_mode, x16_magic);
+                       K, N, groups, tiles, p.gq, lgS, out_mode, x16_magic, szs);
     return hipGetLastError();
 }
 
@@ -280,7 +280,7 @@ bool w4_panel_applies(int64_t M, int64_t K, int64_t N) { return plan_panel(M, K,
 
 namespace {
 
-hipError_t launch_panel(int bits, int64_t K, int64_t N, const void *wt, const uint32_t *sz, const uint16_t *x,
+hipError_t launch_panel(int bits, int64_t K, int64_t N, const void *wt, const uint32_t *sz, int szs, const uint16_t *x,
                         int64_t M, void *y, bool out_f32, void *ws, hipStream_t stream) {
     const PanelPlan p = plan_panel(M, K, N);
     if (!p.ok) return hipErrorInvalidValue;
@@ -291,8 +291,8 @@ hipError_t launch_panel(int bits, int64_t K, int64_t N, const void *wt, const ui
     // the planner only produces one tile per wave in 16-wave workgroups; the kernel itself is written
     // for MT row tiles x R weight tiles per wave (MT * R <= 2 fits the 128 registers of 16 waves)
     if (p.MT != 1 || p.R != 1 || p.WAVES != 16) return hipErrorInvalidValue;
-    const hipError_t e = bits == 3 ? launch_cfg<1, 1, 16, 3>(K, N, wt, sz, x, (int)M, dst, out_mode, p, stream)
-                                   : launch_cfg<1, 1, 16, 4>(K, N, wt, sz, x, (int)M, dst, out_mode, p, stream);
+    const hipError_t e = bits == 3 ? launch_cfg<1, 1, 16, 3>(K, N, wt, sz, szs, x, (int)M, dst, out_mode, p, stream)
+                                   : launch_cfg<1, 1, 16, 4>(K, N, wt, sz, szs, x, (int)M, dst, out_mode, p, stream);
     if (e != hipSuccess || !split) return e;
     return launch_splitk_reduce(static_cast<const float *>(ws), y, M * N, p.SK, out_f32, stream);
 }
@@ -301,12 +301,12 @@ hipError_t launch_panel(int bits, int64_t K, int64_t N, const void *wt, const ui
 
 hipError_t launch_w4_panel(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
                            hipStream_t stream) {
-    return launch_panel(4, L.K, L.N, L.wt, L.sz, x, M, y, out_f32, ws, stream);
+    return launch_panel(4, L.K, L.N, L.wt, L.sz, L.szs, x, M, y, out_f32, ws, stream);
 }
 
 hipError_t launch_w3_panel(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
                            hipStream_t stream) {
-    return launch_panel(3, L.K, L.N, L.wt, L.sz, x, M, y, out_f32, ws, stream);
+    return launch_panel(3, L.K, L.N, L.wt, L.sz, 1, x, M, y, out_f32, ws, stream);
 }
 
 }  // namespace dmr

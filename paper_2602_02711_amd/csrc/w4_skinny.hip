@@ -30,11 +30,11 @@ struct GroupRegs {
 template <int MT>
 __device__ __forceinline__ void load_group(GroupRegs<MT> &r, const uint4 *__restrict__ wt,
                                            const uint32_t *__restrict__ sz,
-                                           const uint16_t *__restrict__ x, int64_t block, int lane,
+                                           const uint16_t *__restrict__ x, int64_t block, int64_t sz_at, int lane,
                                            int64_t M, int64_t K, int64_t k0) {
     const int c = lane >> 4, j = lane & 15;
     r.w = load_stream(wt + block * 64 + lane);
-    r.szw = sz[block * kTileRows + j];
+    r.szw = sz[sz_at + j];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int64_t m = mt * 16 + j;
@@ -85,7 +85,7 @@ constexpr int max_waves() { return MT == 1 ? 16 : (MT == 2 ? 8 : 4); }
 template <int MT, bool OUT_F32>
 __global__ __launch_bounds__(max_waves<MT>() * 64) void w4_skinny_kernel(const uint4 *__restrict__ wt, const uint32_t *__restrict__ sz,
                                  const uint16_t *__restrict__ x, void *__restrict__ y, int64_t M,
-                                 int64_t K, int64_t N) {
+                                 int64_t K, int64_t N, int szs) {
     extern __shared__ float red[];   // [S][MT * 4][64]
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -105,13 +105,14 @@ __global__ __launch_bounds__(max_waves<MT>() * 64) void w4_skinny_kernel(const u
         GroupRegs<MT> regs[U];
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            load_group<MT>(regs[u], wt, sz, x, T * groups + g + u, lane, M, K, (int64_t)(g + u) * kGroup);
+            load_group<MT>(regs[u], wt, sz, x, T * groups + g + u, sz_index(T, g + u, groups, szs, 0), lane, M, K,
+                           (int64_t)(g + u) * kGroup);
 #pragma unroll
         for (int u = 0; u < U; ++u) compute_group<MT>(regs[u], acc);
     }
     for (; g < g1; ++g) {
         GroupRegs<MT> regs;
-        load_group<MT>(regs, wt, sz, x, T * groups + g, lane, M, K, (int64_t)g * kGroup);
+        load_group<MT>(regs, wt, sz, x, T * groups + g, sz_index(T, g, groups, szs, 0), lane, M, K, (int64_t)g * kGroup);
         compute_group<MT>(regs, acc);
     }
 
@@ -152,10 +153,10 @@ hipError_t launch_mt(const LayerView &L, const uint16_t *x, int64_t M, void *y, 
     const size_t lds = (size_t)S * MT * 4 * 64 * sizeof(float);
     if (out_f32)
         hipLaunchKernelGGL((w4_skinny_kernel<MT, true>), dim3((unsigned)tiles), dim3(S * 64), lds, stream,
-                           L.wt, L.sz, x, y, M, L.K, L.N);
+                           L.wt, L.sz, x, y, M, L.K, L.N, L.szs);
     else
         hipLaunchKernelGGL((w4_skinny_kernel<MT, false>), dim3((unsigned)tiles), dim3(S * 64), lds, stream,
-                           L.wt, L.sz, x, y, M, L.K, L.N);
+                           L.wt, L.sz, x, y, M, L.K, L.N, L.szs);
     return hipGetLastError();
 }
 

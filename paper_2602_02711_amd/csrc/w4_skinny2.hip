@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void w4_skinny2_kernel(const uint4 *__restrict
                                                          const uint4 *__restrict__ xf,
                                                          const float *__restrict__ xg,
                                                          void *__restrict__ y, int M, int64_t N, int groups,
-                                                         int tiles, int out_f32) {
+                                                         int tiles, int out_f32, int szs) {
     extern __shared__ float red[];   // [S][R][MT][4][64]
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256) void w4_skinny2_kernel(const uint4 *__restrict
             tile = tile < tiles ? tile : tiles - 1;          // ragged last workgroup: re-read, never stored
             const int64_t block = (int64_t)tile * groups + g;
             w[rt] = load_stream(wt + block * 64 + lane);
-            szw[rt] = sz[block * kTileRows + j];
+            szw[rt] = sz[sz_index(tile, g, groups, szs, j)];
         }
         Frag a[MT][4];
         f32x4 xs[MT];
@@ -164,7 +164,7 @@ hipError_t launch_main(const LayerView &L, const uint4 *xf, const float *xg, int
     if (attr_status != hipSuccess) return attr_status;
     const unsigned grid = (unsigned)((tiles + R - 1) / R);
     hipLaunchKernelGGL((w4_skinny2_kernel<MT, R>), dim3(grid), dim3(S * 64), lds, stream, L.wt, L.sz, xf, xg, y,
-                       M, L.N, groups, tiles, out_f32 ? 1 : 0);
+                       M, L.N, groups, tiles, out_f32 ? 1 : 0, L.szs);
     return hipGetLastError();
 }
 

@@ -55,7 +55,7 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
                                                          void *__restrict__ y, int M, int64_t N,
                                                          int groups, int tiles, int lgS, int lgTW,
                                                          int nT_max, int gw_max, int out_f32,
-                                                         const uint16_t *__restrict__ res, uint32_t x16_magic) {
+                                                         const uint16_t *__restrict__ res, uint32_t x16_magic, int szs) {
     extern __shared__ uint4 smem[];   // x rows [M][groups * 16 + 1] uint4, xs[groups][4] float4, red[TW][S][64] float4
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(1024) void w4_stream_kernel(const uint4 *__restrict
         g = g < 0 ? 0 : (g < groups ? g : groups - 1);
         const int64_t block = (int64_t)tile * groups + g;
         dst.w = load_stream(wt + block * 64 + lane);
-        dst.szw = load_stream(sz + block * kTileRows + j);
+        dst.szw = load_stream(sz + sz_index(tile, g, groups, szs, j));
         if (++ig == gw_max) {
             ig = 0;
             if (is + 1 < nT_max) ++is;      // saturate at the last step
@@ -319,7 +319,7 @@ hipError_t launch_w4_stream_fused(const LayerView &L, const uint16_t *x, int64_t
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); \
         if (attr_status != hipSuccess) return attr_status; \
         hipLaunchKernelGGL((w4_stream_kernel<PP, false>), dim3(grid), dim3(nw * 64), lds, stream, L.wt, L.sz, x, y, \
-                           iM, L.N, groups, tiles, lgS, lgTW, nT_max, gw_max, of, f.res, x16_magic);          \
+                           iM, L.N, groups, tiles, lgS, lgTW, nT_max, gw_max, of, f.res, x16_magic, L.szs);   \
     } break;
     // Group sums from a table when a wave streams at least sixteen blocks and the table costs it at most
     // a quarter as many MFMA passes as it saves (the widest layers: 0.3-0.9 us of 17 on gate+up; on the
@@ -331,7 +331,7 @@ hipError_t launch_w4_stream_fused(const LayerView &L, const uint16_t *x, int64_t
                                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (attr_status != hipSuccess) return attr_status;
         hipLaunchKernelGGL((w4_stream_kernel<4, true>), dim3(grid), dim3(nw * 64), lds, stream, L.wt, L.sz, x, y, iM, L.N,
-                           groups, tiles, lgS, lgTW, nT_max, gw_max, of, f.res, x16_magic);
+                           groups, tiles, lgS, lgTW, nT_max, gw_max, of, f.res, x16_magic, L.szs);
         return hipGetLastError();
     }
     switch (P) {

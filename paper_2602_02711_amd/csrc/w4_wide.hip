@@ -34,7 +34,7 @@ constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v / 2); }
 template <int MT, int R, int S, int CG, int BITS>
 __global__ __launch_bounds__(512) void w4_wide_kernel(const void *__restrict__ wt, const uint32_t *__restrict__ sz,
                                                       const uint16_t *__restrict__ x, void *__restrict__ y, int M,
-                                                      int64_t K, int64_t N, int groups, int tiles, int out_f32) {
+                                                      int64_t K, int64_t N, int groups, int tiles, int out_f32, int szs) {
     constexpr int WAVES = 8, THREADS = 512, TW = WAVES / S, GWc = CG / S, P = GWc;
     constexpr int ROW = CG * 16 + 1;                  // uint4 per panel row
     constexpr int ROWS = MT * 16;
@@ -71,7 +71,7 @@ __global__ __launch_bounds__(512) void w4_wide_kernel(const void *__restrict__ w
                 dst.w[r].y = load_stream(pw + 1);
                 dst.w[r].z = load_stream(pw + 2);
             }
-            dst.szw[r] = load_stream(sz + block * kTileRows + j);
+            dst.szw[r] = load_stream(sz + sz_index(tile, g, groups, szs, j));
         }
     };
 
@@ -233,7 +233,7 @@ __global__ __launch_bounds__(512) void w4_wide_kernel(const void *__restrict__ w
 }
 
 template <int MT, int R, int S, int CG, int BITS>
-hipError_t launch_cfg(const void *wt, const uint32_t *sz, int64_t K, int64_t N, const uint16_t *x, int M, void *y,
+hipError_t launch_cfg(const void *wt, const uint32_t *sz, int szs, int64_t K, int64_t N, const uint16_t *x, int M, void *y,
                       bool out_f32, hipStream_t stream) {
     // once per process and kernel instantiation (thread-safe static initialisation)
     static const hipError_t attr_status = hipFuncSetAttribute(
@@ -245,20 +245,20 @@ hipError_t launch_cfg(const void *wt, const uint32_t *sz, int64_t K, int64_t N, 
     static_assert(TW * R == kWideTilesPerWg && CG == kWideChunk, "the planner assumes this shape");
     const unsigned grid = (unsigned)((tiles + TW * R - 1) / (TW * R));
     hipLaunchKernelGGL((w4_wide_kernel<MT, R, S, CG, BITS>), dim3(grid), dim3(512), wide_lds_bytes(MT, R, S, CG), stream,
-                       wt, sz, x, y, M, K, N, groups, tiles, out_f32 ? 1 : 0);
+                       wt, sz, x, y, M, K, N, groups, tiles, out_f32 ? 1 : 0, szs);
     return hipGetLastError();
 }
 
 template <int BITS>
-hipError_t launch_wide(const void *wt, const uint32_t *sz, int64_t K, int64_t N, const uint16_t *x, int64_t M, void *y,
+hipError_t launch_wide(const void *wt, const uint32_t *sz, int szs, int64_t K, int64_t N, const uint16_t *x, int64_t M, void *y,
                        bool out_f32, hipStream_t stream) {
     const WidePlan p = plan_wide(M, K, N);
     if (!p.ok) return hipErrorInvalidValue;
     const int iM = (int)M;
     switch (p.MT) {
-        case 2: return launch_cfg<2, 2, 2, 4, BITS>(wt, sz, K, N, x, iM, y, out_f32, stream);
-        case 3: return launch_cfg<3, 2, 2, 4, BITS>(wt, sz, K, N, x, iM, y, out_f32, stream);
-        case 4: return launch_cfg<4, 2, 2, 4, BITS>(wt, sz, K, N, x, iM, y, out_f32, stream);
+        case 2: return launch_cfg<2, 2, 2, 4, BITS>(wt, sz, szs, K, N, x, iM, y, out_f32, stream);
+        case 3: return launch_cfg<3, 2, 2, 4, BITS>(wt, sz, szs, K, N, x, iM, y, out_f32, stream);
+        case 4: return launch_cfg<4, 2, 2, 4, BITS>(wt, sz, szs, K, N, x, iM, y, out_f32, stream);
         default: return hipErrorInvalidValue;
     }
 }
@@ -269,12 +269,12 @@ bool w4_wide_applies(int64_t M, int64_t K, int64_t N) { return plan_wide(M, K, N
 
 hipError_t launch_w4_wide(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
                           hipStream_t stream) {
-    return launch_wide<4>(L.wt, L.sz, L.K, L.N, x, M, y, out_f32, stream);
+    return launch_wide<4>(L.wt, L.sz, L.szs, L.K, L.N, x, M, y, out_f32, stream);
 }
 
 hipError_t launch_w3_wide(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
                           hipStream_t stream) {
-    return launch_wide<3>(L.wt, L.sz, L.K, L.N, x, M, y, out_f32, stream);
+    return launch_wide<3>(L.wt, L.sz, 1, L.K, L.N, x, M, y, out_f32, stream);
 }
 
 }  // namespace dmr

@@ -107,7 +107,12 @@ def test_w3_one_hot_and_exact_cases():
 # ------------------------------------------------------------------ per-channel symmetric W4 (g = K, z = 8)
 
 @pytest.mark.parametrize("K,N,M", [(1024, 1024, 1), (384, 48, 7), (4096, 4096, 1), (1920, 272, 33), (512, 256, 200),
-                                   (512, 1024, 6400)])      # the last one is large enough for the tiled GEMM
+                                   (512, 1024, 6400),      # large enough for the tiled GEMM
+                                   # one case per kernel class that reads the row's single scale word: streaming (2..16),
+                                   # k-sliced panels, wide-layer, its variant for odd group counts, rollout batch with K
+                                   # split, and the direct-from-L2 kernel that very long decode rows fall back to
+                                   (4096, 4096, 16), (14336, 528, 8), (512, 16400, 24), (640, 16400, 40), (2048, 1024, 64),
+                                   (32768, 64, 1), (4096, 28672, 1)])
 def test_per_channel_symmetric_layer(K, N, M):
     rng = np.random.default_rng(90 + K + M)
     q = rng.integers(0, 16, size=(N, K), dtype=np.uint8)
@@ -116,6 +121,9 @@ def test_per_channel_symmetric_layer(K, N, M):
     words = orc.pack(q)
     layer = dmr.dmr_qlinear_create_per_channel(u32_dev(words), bf16_dev(s_row.reshape(N)))
     assert layer.g == K
+    # half a byte per weight and one scale word per row, nothing per group
+    assert dmr.dmr_qlinear_per_channel_storage_bytes(K, N) == N * K // 2 + 4 * N
+    assert layer.storage.numel() == max(N * K // 2 + 4 * N, 16)
     # the oracle takes any group size that divides K: one group per row, zero point 8
     assert np.array_equal(bits_host(dmr.dmr_qlinear_dequantize(layer)), orc.dequantize(words, s_row, z_row, K))
     x = synth.activations_bf16(92 + K, M, K)
