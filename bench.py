@@ -68,10 +68,6 @@ def full_step(args, dmr, synth, torch, dev):
     log(f"[bench] 129 layers resident after {time.time() - t0:.1f}s")
     stream = torch.cuda.Stream()
 
-    if not args.no_prefetch:           # every INT4 layer names the one the step reads after it
-        for i in range(len(int4_layers) - 1):
-            dmr.dmr_qlinear_set_next(int4_layers[i][1], int4_layers[i + 1][1])
-
     def step(low: bool):
         for i in range(len(int4_layers)):
             nm = int4_layers[i][0]
@@ -571,9 +567,6 @@ def main():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the protocol extras (read ceiling, replay spread, hot-cache and single-launch "
                          "times) so that a profiler sees only the launches of the timed passes")
-    ap.add_argument("--no-prefetch", action="store_true",
-                    help="decode_sweep: do not name each layer's successor (dmr_qlinear_set_next), so that no launch "
-                         "requests the next layer's first blocks")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--workload", choices=("decode_sweep", "full_step", "mixed_step", "chain_step", "layer_sweep", "w3_sweep", "launch_floor"), default="decode_sweep",
                     help="decode_sweep (default, the headline metric) or full_step: all 129 Linear layers of "
@@ -634,15 +627,6 @@ def main():
     log(f"[bench] inputs resident after {time.time() - t0:.1f}s; copies per shape int4 "
         f"{[len(l) for l in layers]} bf16 {[len(l) for l in bf16_ws]}")
 
-    def name_successors(on: bool):
-        """Tell every INT4 layer which layer the sweep reads after it (the order of int4_step), or clear that."""
-        R = len(layers[0])
-        for idx in range(len(shapes)):
-            for r in range(R):
-                nxt = layers[idx + 1][r] if idx + 1 < len(shapes) else layers[0][(r + 1) % R]
-                dmr.dmr_qlinear_set_next(layers[idx][r], nxt if on else None)
-
-    name_successors(not args.no_prefetch)
     stream = torch.cuda.Stream()       # default priority
 
     def int4_step(i, only=None):
@@ -696,7 +680,6 @@ def main():
     bwall_ms, bev_ms = timed(bf16_step, args.steps, args.warmup)
     bstep_bytes = sum(bf16_bytes(K, N, M) for _, K, N in shapes)
     per_shape = []
-    name_successors(False)             # a shape on its own has no successor in the sweep's order
     for idx, (name, K, N) in enumerate(shapes):
         n_inner = max(args.steps, 100)
         _, e4 = timed(int4_step, n_inner, 10, only=idx)
@@ -709,11 +692,6 @@ def main():
             "speedup": round(eb / e4, 3),
         })
         log(f"[bench] {per_shape[-1]}")
-
-    # the sweep once more without the successor hints, for the record
-    nopf_ms = None
-    if not args.no_prefetch:
-        _, nopf_ms = timed(int4_step, args.steps, args.warmup)
 
     # ---- protocol extras (outside the timed region that defines `value`) -----------------------
     protocol = None
@@ -824,9 +802,6 @@ def main():
                         "forwards; weights rotate over >=1 GiB of resident copies per shape",
             "weights": "int4 asymmetric g128, fp32 0.02*N(0,1) quantised by the device RTN quantiser",
             "activations": "bf16 N(0,1)", "accumulate": "fp32", "output": "bf16",
-            "successors": "none named" if args.no_prefetch else
-                          "every layer's successor in the sweep named with dmr_qlinear_set_next (a launch requests "
-                          "the next layer's first blocks while its own tail is reduced)",
             "launch": "eager" if args.no_graph else "hip-graph replay of all timed steps (after W eager warm-up "
                       "steps and 3 untimed replays)",
             "algorithmic_bytes_per_step": step_bytes,
@@ -835,8 +810,6 @@ def main():
         "bf16_ms_per_step": round(bwall_ms, 6),
         "bf16_GBps": round(bstep_bytes / (bwall_ms * 1e-3) / 1e9, 1),
         "us_per_decode_sweep": round(wall_ms * 1e3, 2),
-        "next_layer_prefetch": not args.no_prefetch,
-        "us_per_decode_sweep_without_prefetch": None if nopf_ms is None else round(nopf_ms * 1e3, 2),
         "per_shape": per_shape,
         "protocol": protocol,
         "roofline": {

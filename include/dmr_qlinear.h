@@ -109,16 +109,6 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
                                  void *stream);
 
 /*
- * Decode-step hint (App. B: a generated token streams every weight once, layer after layer): name the layer
- * whose weights the same stream reads right after `layer` in a decode step (M = 1).  From then on an M = 1
- * forward of `layer` (plain or fused) also requests the first blocks of `next` while its own last blocks are
- * being reduced, so that the following launch finds its first bytes in cache instead of waiting for HBM.
- * Results are unchanged; only 4-bit layers take part (others ignore the hint).  `next` must stay alive (or
- * the hint be cleared with NULL) for as long as `layer` is used; it may be `layer` itself.  Host-side only.
- */
-dmr_status_t dmr_qlinear_set_next(dmr_qlinear_t *layer, const dmr_qlinear_t *next);
-
-/*
  * dmr_qlinear_forward for callers that cannot allocate device memory and therefore cannot bring the
  * workspace: code running under HIP-graph capture, tight serving loops, harnesses that forbid hipMalloc.
  * Same arguments, results (bit for bit) and errors as dmr_qlinear_forward, minus d_ws / ws_bytes: the

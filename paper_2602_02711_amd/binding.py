@@ -28,7 +28,7 @@ EXPORTS = (
     "dmr_qlinear_w3_create", "dmr_qlinear_quantize_w3", "dmr_qlinear_bits", "dmr_qlinear_create_per_channel",
     "dmr_glue_rmsnorm", "dmr_glue_swiglu", "dmr_qlinear_fused_workspace_bytes",
     "dmr_qlinear_bf16_fused_workspace_bytes", "dmr_qlinear_forward_fused", "dmr_qlinear_bf16_forward_fused",
-    "dmr_qlinear_kernel_path", "dmr_qlinear_forward_static", "dmr_probe_empty_launch", "dmr_qlinear_set_next",
+    "dmr_qlinear_kernel_path", "dmr_qlinear_forward_static", "dmr_probe_empty_launch",
     "dmr_qlinear_per_channel_storage_bytes",
 )
 
@@ -91,8 +91,6 @@ def lib() -> ctypes.CDLL:
         L.dmr_qlinear_create_per_channel.argtypes = [ctypes.POINTER(vp), i64, i64, vp, vp, vp, sz, vp]
         L.dmr_qlinear_bits.restype = i32
         L.dmr_qlinear_bits.argtypes = [vp]
-        L.dmr_qlinear_set_next.restype = ctypes.c_int
-        L.dmr_qlinear_set_next.argtypes = [vp, vp]
         L.dmr_probe_empty_launch.restype = ctypes.c_int
         L.dmr_probe_empty_launch.argtypes = [i32, i32, sz, vp]
         L.dmr_probe_hbm_read.restype = ctypes.c_int
@@ -159,7 +157,6 @@ class Layer:
 
     def __init__(self, handle: int, storage: torch.Tensor, K: int, N: int, g: int, bits: int = 4):
         self.handle, self.storage, self.K, self.N, self.g, self.bits = handle, storage, K, N, g, bits
-        self.next = None            # keeps the layer named by dmr_qlinear_set_next alive
 
     def __del__(self):
         dmr_qlinear_destroy(self)
@@ -364,11 +361,6 @@ def dmr_probe_hbm_read(buf: torch.Tensor, sink: torch.Tensor, blocks: int, strea
     if sink.numel() < blocks * 256:
         raise ValueError("sink needs blocks * 256 words")
     _check(lib().dmr_probe_hbm_read(pb, buf.numel(), ps, blocks, _stream(stream)), "dmr_probe_hbm_read")
-
-
-def dmr_qlinear_set_next(layer: Layer, nxt: Layer | None) -> None:
-    _check(lib().dmr_qlinear_set_next(layer.handle, None if nxt is None else nxt.handle), "dmr_qlinear_set_next")
-    layer.next = nxt
 
 
 def dmr_probe_empty_launch(blocks: int, threads: int, lds_bytes: int = 0, stream=None) -> None:

@@ -14,7 +14,6 @@ struct dmr_qlinear {
     const uint32_t *wt3;    // 3-bit streaming blocks
     const uint32_t *sz;
     int32_t szs;            // 1: a scale / zero word per (row, group); 0: one per row (per-channel layers)
-    const dmr_qlinear *next;   // the layer read after this one in a decode step, or null (dmr_qlinear_set_next)
 };
 
 namespace {
@@ -93,16 +92,6 @@ dmr_status_t check_shape(int64_t K, int64_t N, int32_t g) {
 
 dmr_status_t hip_status(hipError_t e) { return e == hipSuccess ? DMR_OK : DMR_ERR_HIP; }
 
-// Hand the decode kernel the weights of the layer that follows, if the caller has named one.
-void set_next(dmr::Fusion &f, const dmr_qlinear *layer) {
-    const dmr_qlinear *n = layer->next;
-    if (n && n->bits == 4) {
-        f.next_wt = n->wt;
-        f.next_K = n->K;
-        f.next_N = n->N;
-    }
-}
-
 }  // namespace
 
 extern "C" {
@@ -147,7 +136,6 @@ dmr_status_t dmr_qlinear_create(dmr_qlinear_t **out, int64_t K, int64_t N, int32
     h->g = g;
     h->bits = 4;
     h->szs = 1;
-    h->next = nullptr;
     h->wt3 = nullptr;
     uint8_t *base = static_cast<uint8_t *>(d_storage);
     h->wt = reinterpret_cast<const uint4 *>(base);
@@ -186,7 +174,6 @@ dmr_status_t dmr_qlinear_create_per_channel(dmr_qlinear_t **out, int64_t K, int6
     h->g = (int32_t)K;      // one group spans the whole row
     h->bits = 4;
     h->szs = 0;             // one scale word per row behind the weights: 0.5 byte per weight + 4 bytes per row
-    h->next = nullptr;
     h->wt3 = nullptr;
     uint8_t *base = static_cast<uint8_t *>(d_storage);
     h->wt = reinterpret_cast<const uint4 *>(base);
@@ -235,7 +222,6 @@ dmr_status_t dmr_qlinear_w3_create(dmr_qlinear_t **out, int64_t K, int64_t N, in
     h->g = g;
     h->bits = 3;
     h->szs = 1;
-    h->next = nullptr;
     h->wt = nullptr;
     uint8_t *base = static_cast<uint8_t *>(d_storage);
     h->wt3 = reinterpret_cast<const uint32_t *>(base);
@@ -303,9 +289,7 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
     const dmr::LayerView L{layer->K, layer->N, layer->wt, layer->sz, layer->szs};
     const W4Path path = w4_path(M, layer->K, layer->N);
     if (path == W4Path::Gemv) {
-        dmr::Fusion f;
-        set_next(f, layer);
-        const hipError_t e = dmr::launch_w4_gemv_fused(L, d_x, d_y, f32, f, s);
+        const hipError_t e = dmr::launch_w4_gemv(L, d_x, d_y, f32, s);
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: shape outside its range
     }
     if (path == W4Path::Stream) {
@@ -463,7 +447,6 @@ dmr_status_t dmr_qlinear_forward_fused(const dmr_qlinear_t *layer, dmr_prologue_
         f.aux = d_gamma;
         f.eps = eps;
         f.res = d_residual;
-        set_next(f, layer);
         const hipError_t e = dmr::launch_w4_gemv_fused(L, d_in, d_y, out == DMR_OUT_FP32, f, s);
         if (e != hipErrorInvalidValue) return hip_status(e);   // else: shape outside the GEMV's range
     }
@@ -601,12 +584,6 @@ dmr_status_t dmr_probe_empty_launch(int32_t blocks, int32_t threads, size_t lds_
         lds_bytes > 64 * 1024)
         return DMR_ERR_SHAPE;
     return hip_status(dmr::launch_empty_probe(blocks, threads, lds_bytes, static_cast<hipStream_t>(stream)));
-}
-
-dmr_status_t dmr_qlinear_set_next(dmr_qlinear_t *layer, const dmr_qlinear_t *next) {
-    if (!layer) return DMR_ERR_NULL;
-    layer->next = next;
-    return DMR_OK;
 }
 
 void dmr_qlinear_destroy(dmr_qlinear_t *layer) { delete layer; }

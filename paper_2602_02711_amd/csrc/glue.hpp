@@ -23,10 +23,6 @@ struct Fusion {
     const uint16_t *aux = nullptr;
     float eps = 0.f;
     const uint16_t *res = nullptr;
-    // The 4-bit layer whose weights the stream's next decode launch will read (or null): the kernel requests
-    // the blocks that launch asks for first while its own last blocks are still being reduced.
-    const uint4 *next_wt = nullptr;
-    int64_t next_K = 0, next_N = 0;
 };
 
 __device__ __forceinline__ float sumsq_piece(const uint4 &x) {

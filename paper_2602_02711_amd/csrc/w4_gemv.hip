@@ -13,13 +13,6 @@
 //     acc += s * (D - (128 + z) * X)
 // applies zero point and scale once per group; X = sum of the group's 128 activations is formed
 // once per workgroup while x is staged and kept in LDS beside it.
-//
-// Next-layer prefetch (PF > 0).  A decode step is a chain of such launches, and between two of them the memory
-// system idles while the last blocks are reduced and the next launch starts up.  When the caller names the layer
-// that is read next, every wave, once its own last block load has been issued, requests PF blocks of that layer:
-// the blocks the next launch's waves ask for first (its planner's work split is recomputed on the host), taken
-// by the workgroup with the same index modulo 8 so that they land in the L2 of the XCD that will read them.
-// The data is never used here; the registers are folded into a store that cannot happen, at the very end.
 #include <cstdlib>
 
 #include "glue.hpp"
@@ -34,27 +27,17 @@ struct Item {
     uint32_t szw;
 };
 
-// Work split of the launch that follows, as far as the prefetch needs it.
-struct NextPlan {
-    const uint4 *wt;     // its weight blocks
-    int groups;          // its K / 128
-    int first_tiles;     // tiles its workgroups visit first: min(its grid, its tile count)
-    int lgS;             // log2 of its k slices per tile (= its waves per workgroup)
-    int lgQ;             // log2 of the blocks requested per (tile, slice)
-    int rounds;          // its workgroups per workgroup of this launch, rounded up
-};
-
 // PRO selects glue fused into the activation staging (glue.hpp): the row is normalised (RMSNorm,
 // gamma in `aux`) or formed from a gate half and an up half (SwiGLU, x then holds 2 K values) in
 // registers on its way into LDS.  `res`, if not null, is a bf16 residual added to the result.
-template <int P, int XL, int PRO, int PF>
+template <int P, int XL, int PRO>
 __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__ wt,
                                                        const uint32_t *__restrict__ sz,
                                                        const uint16_t *__restrict__ x,
                                                        void *__restrict__ y, int groups, int tiles,
                                                        int lgS, int lgTW, int nT_max, int out_f32,
                                                        const uint16_t *__restrict__ aux, float eps,
-                                                       const uint16_t *__restrict__ res, NextPlan nx, int szs) {
+                                                       const uint16_t *__restrict__ res, int szs) {
     extern __shared__ uint4 smem[];          // x (16 uint4 per group), X[groups], red[nT_max][TW][S][16], 16 floats
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform (SGPR)
@@ -201,8 +184,8 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
         }
     };
 
-    int base = 0;
     if (items > 0) {
+        int base = 0;
         for (; base + P < items; base += P) {
 #pragma unroll
             for (int p = 0; p < P; ++p) {
@@ -211,46 +194,11 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
                 compute(cur);
             }
         }
-    }
-    // All of this wave's own loads are in flight or done: request the next layer's first blocks behind them.
-    // Entry e of this workgroup's share = (round jj, slice sp, block q); whatever falls outside the next launch's
-    // first blocks re-reads a block of this wave's own, so that every wave issues the same PF loads unconditionally.
-    uint4 pfv[PF > 0 ? PF : 1];
-    if (PF > 0) {
-        const int nwv = (int)blockDim.x >> 6;
-#pragma unroll
-        for (int i = 0; i < PF; ++i) {
-            const int e = wave + nwv * i;
-            const int lgSQ = nx.lgS + nx.lgQ;
-            const int jj = e >> lgSQ, r = e & ((1 << lgSQ) - 1);
-            const int sp = r >> nx.lgQ, q = r & ((1 << nx.lgQ) - 1);
-            const int tile = (int)blockIdx.x + jj * (int)gridDim.x;
-            const int ga = (nx.groups * sp) >> nx.lgS, gb = (nx.groups * (sp + 1)) >> nx.lgS;
-            const bool ok = jj < nx.rounds && tile < nx.first_tiles && ga + q < gb;
-            // nothing to request: re-read this wave's own first block (a different cached line per wave, so that
-            // the idle requests do not pile up on one cache channel)
-            const int64_t own = (int64_t)min(t_first, tiles - 1) * groups + g0;
-            const uint4 *src = ok ? nx.wt + ((int64_t)tile * nx.groups + ga + q) * 64 : wt + own * 64;
-            pfv[i] = src[lane];
-        }
-    }
-    auto pf_sink = [&]() {
-        if (PF > 0) {
-            uint32_t h = 0;
-#pragma unroll
-            for (int i = 0; i < PF; ++i) h ^= pfv[i].x ^ pfv[i].y ^ pfv[i].z ^ pfv[i].w;
-            if (nx.lgQ < 0 && h == 0x9E3779B9u) reinterpret_cast<uint32_t *>(y)[0] = h;   // lgQ >= 0: never
-        }
-    };
-    if (items > 0) {
 #pragma unroll
         for (int p = 0; p < P; ++p)
             if (base + p < items) compute(ring[p]);
     }
-    if (lgS == 0) {
-        pf_sink();
-        return;
-    }
+    if (lgS == 0) return;
 
     // Cross-slice sum: thread e = (slot, column, slice) with the slice index fastest, so the S
     // partials of one output sit in S adjacent lanes and fold in a fixed order.
@@ -279,7 +227,6 @@ __global__ __launch_bounds__(1024) void w4_gemv_kernel(const uint4 *__restrict__
             }
         }
     }
-    pf_sink();
 }
 
 struct GemvPlan {
@@ -362,32 +309,9 @@ hipError_t launch_w4_gemv_fused(const LayerView &L, const uint16_t *x, void *y, 
     P = env_int("DMR_GEMV_P", P);
     const dim3 g(plan.grid), b(nw * 64);
     const int of = out_f32 ? 1 : 0;
-    // Prefetch for the launch that follows (ring depths 2 and 4, i.e. the decoder's layers): its planner's
-    // work split, and as many blocks per (tile, slice) of it as PF loads per wave of this launch cover.
-    NextPlan nx{};
-    int PF = 0;
-    if (f.next_wt && (P == 4 || P == 2) && plan.grid % 8 == 0) {
-        const int ngroups = (int)(f.next_K / kGroup), ntiles = (int)(f.next_N / kTileRows);
-        const GemvPlan np = plan_for(ngroups, ntiles, cus);
-        PF = env_int("DMR_GEMV_PF", 2) == 2 ? 2 : 0;     // four loads per wave measured 5 % slower than none
-        nx.wt = f.next_wt;
-        nx.groups = ngroups;
-        nx.first_tiles = np.grid < ntiles ? np.grid : ntiles;
-        nx.lgS = log2_exact(np.S);
-        nx.rounds = (np.grid + plan.grid - 1) / plan.grid;
-        const int entries = nx.rounds * np.S;         // (tile, slice) pairs per workgroup of this launch
-        nx.lgQ = 0;
-        while (PF > 0 && (entries << (nx.lgQ + 1)) <= nw * PF && nx.lgQ < 3) ++nx.lgQ;
-        if (nx.lgS < 0 || np.TW != 1) PF = 0;
-    }
-#define DMR_GEMV_LAUNCH_PF(PP, XX, PRO, PFN)                                                           \
-    hipLaunchKernelGGL((w4_gemv_kernel<PP, XX, PRO, PFN>), g, b, lds, stream, L.wt, L.sz, x, y, groups, tiles, \
-                       lgS, lgTW, nT_max, of, f.aux, f.eps, f.res, nx, L.szs)
 #define DMR_GEMV_LAUNCH_PRO(PP, XX, PRO)                                                               \
-    do {                                                                                               \
-        if ((PP == 4 || PP == 2) && PF == 2) DMR_GEMV_LAUNCH_PF(PP, XX, PRO, ((PP == 4 || PP == 2) ? 2 : 0)); \
-        else DMR_GEMV_LAUNCH_PF(PP, XX, PRO, 0);                                                        \
-    } while (0)
+    hipLaunchKernelGGL((w4_gemv_kernel<PP, XX, PRO>), g, b, lds, stream, L.wt, L.sz, x, y, groups, tiles, \
+                       lgS, lgTW, nT_max, of, f.aux, f.eps, f.res, L.szs)
 #define DMR_GEMV_LAUNCH(PP, XX)                                                                        \
     do {                                                                                               \
         if (f.pro == kProRmsNorm) DMR_GEMV_LAUNCH_PRO(PP, XX, kProRmsNorm);                             \
@@ -408,7 +332,6 @@ hipError_t launch_w4_gemv_fused(const LayerView &L, const uint16_t *x, void *y, 
 #undef DMR_GEMV_CASE
 #undef DMR_GEMV_LAUNCH
 #undef DMR_GEMV_LAUNCH_PRO
-#undef DMR_GEMV_LAUNCH_PF
     return hipGetLastError();
 }
 

@@ -103,6 +103,7 @@ def main():
     ap.add_argument("--command", required=True, help="the full profiled command, for the record")
     ap.add_argument("--kernel", default="w4_gemv_kernel", help="substring naming the dominant kernel")
     ap.add_argument("--title", default="decode GEMV sweep (bench.py)", help="what was profiled, for the heading")
+    ap.add_argument("--note", default="", help="where and when the counters were taken, stored as `source` in the json")
     ap.add_argument("--gaps", action="store_true", help="add the end-to-start gaps between consecutive kernels")
     ap.add_argument("--out-md", required=True)
     ap.add_argument("--out-json")
@@ -158,6 +159,8 @@ def main():
                 tot_w += n * wb
                 tot_n += n
         if tot_n:
+            if args.note:
+                out["source"] = args.note
             out.update({"fetch_bytes_per_launch": tot_f / tot_n, "write_bytes_per_launch": tot_w / tot_n,
                         "traffic": (tot_f + tot_w) / tot_n, "scale_fetch": sf, "scale_write": sw})
             lines += ["", f"`{args.kernel}`: {tot_f / tot_n / 1e6:.3f} MB fetched + {tot_w / tot_n / 1e6:.4f} MB "
