@@ -62,8 +62,10 @@ size_t dmr_qlinear_storage_bytes(int64_t K, int64_t N, int32_t g);
 /* Bytes of scratch dmr_qlinear_forward (resp. dmr_qlinear_bf16_forward) needs for this shape
  * (d_ws); may be 0, and then d_ws may be NULL.  Non-zero for batches of rollouts (a few to a few
  * hundred rows): either the activations re-ordered once per call, or fp32 partial sums when K is
- * split over workgroups because M x N alone would leave most of the chip idle.  Contents are
- * undefined after the call. */
+ * split over workgroups because M x N alone would leave most of the chip idle.  Non-zero also for the
+ * 4-bit tiled path from 256 rows on (prefill): per call it keeps there the operands of the zero-point
+ * term (bf16, 12 (M + N) K / 128 bytes), one fp32 factor per (row, group) and a few flags.  The
+ * workspace may arrive uninitialised; its contents are undefined after the call. */
 size_t dmr_qlinear_workspace_bytes(int64_t M, int64_t K, int64_t N);
 size_t dmr_qlinear_bf16_workspace_bytes(int64_t M, int64_t K, int64_t N);
 
@@ -103,6 +105,10 @@ dmr_status_t dmr_qlinear_dequantize(const dmr_qlinear_t *layer, uint16_t *d_w_bf
  * with the dequantisation fused into the product and fp32 accumulation.  d_x is bf16 [M][K];
  * d_y is [M][N] of the type `out` names.  Small M takes the weight-streaming paths (decode, a
  * group of parallel rollouts), large M the tiled MFMA path (prefill of a long prompt, App. B).
+ * No path rounds a weight: every kernel multiplies the activations with the exact integer codes and
+ * applies scale and zero point in fp32 (agreement with the fp64 definition at the 1e-5 rms(y) level on
+ * the fp32 output; rows with scales the tiled path cannot carry, zero, subnormal or spanning more than
+ * 2^20 within a row, are served by a slower exact kernel inside the same call).
  */
 dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x, int64_t M,
                                  void *d_y, dmr_out_t out, void *d_ws, size_t ws_bytes,
@@ -239,7 +245,7 @@ dmr_status_t dmr_probe_empty_launch(int32_t blocks, int32_t threads, size_t lds_
 /*
  * Diagnostic, not part of a routed step: the name of the kernel class that serves M rows of a (K, N) layer
  * held in `format` ("w4_gemv", "w4_stream", "w4_panel", "w4_wide", "w4_skinny2", "w4_mid",
- * "w4_gemm128_exact", the "w3_*" and "bf16_*" counterparts; "none" for an unsupported shape).  Pure host arithmetic,
+ * "w4_gemm256_rescale", "w4_gemm256x128_rescale", "w4_gemm128_exact", the "w3_*" and "bf16_*" counterparts; "none" for an unsupported shape).  Pure host arithmetic,
  * the same the forward calls use; a decode row too long for the M = 1 kernels' LDS budget is served by a
  * fallback of the same name class.  Lets a test or a profile state which kernel it covers.
  */

@@ -22,7 +22,7 @@ constexpr int64_t kSkinnyMaxM = 64;
 
 // Which INT4 kernel serves M rows of a (K, N) layer (measured crossovers, 256 CUs).  The workspace
 // query and the forward call both go through this.
-enum class W4Path { Gemv, Stream, Panel, Wide, Skinny2, Mid, Gemm };
+enum class W4Path { Gemv, Stream, Panel, Wide, Skinny2, Mid, Gemm, GemmRescale };
 W4Path w4_path(int64_t M, int64_t K, int64_t N) {
     if (M == 1) return W4Path::Gemv;
     if (M <= 16) {
@@ -36,7 +36,8 @@ W4Path w4_path(int64_t M, int64_t K, int64_t N) {
     if (M <= kSkinnyMaxM) return tiles >= 1024 ? W4Path::Skinny2 : W4Path::Mid;
     // the 128 x 128 GEMM needs about 300 workgroups before it wins (measured)
     const int64_t gemm_wgs = ((M + 127) / 128) * ((N + 127) / 128);
-    return (M <= 128 || gemm_wgs < dmr::env_int("DMR_W4_GEMM_MIN_WGS", 300)) ? W4Path::Mid : W4Path::Gemm;
+    if (M <= 128 || gemm_wgs < dmr::env_int("DMR_W4_GEMM_MIN_WGS", 300)) return W4Path::Mid;
+    return dmr::w4_gemm_rescale_applies(M, N) ? W4Path::GemmRescale : W4Path::Gemm;
 }
 
 // 3-bit layers: the 4-bit size classes on the native 3-bit kernels; a decode row too long for the GEMV's LDS
@@ -107,6 +108,7 @@ size_t dmr_qlinear_workspace_bytes(int64_t M, int64_t K, int64_t N) {
         case W4Path::Mid: return dmr::w4_mid_workspace_bytes(M, K, N);    // fp32 partials when K is split
         case W4Path::Panel: return dmr::w4_panel_workspace_bytes(M, K, N);    // likewise
         case W4Path::Skinny2: return dmr::w4_skinny2_workspace_bytes(M, K);   // re-ordered activations
+        case W4Path::GemmRescale: return dmr::w4_gemm_rescale_workspace_bytes(M, K, N);   // zero-point operands, factors
         default: return 0;
     }
 }
@@ -301,17 +303,12 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
     if (path == W4Path::Mid) return hip_status(dmr::launch_w4_mid(L, d_x, M, d_y, f32, d_ws, s));
     if (path == W4Path::Skinny2) return hip_status(dmr::launch_w4_skinny2(L, d_x, M, d_y, f32, d_ws, s));
     if (M <= kSkinnyMaxM) return hip_status(dmr::launch_w4_skinny(L, d_x, M, d_y, f32, s));
-    // Tiled MFMA GEMM on the exact integer codes q - z, the group's scale applied to the group's partial sums
-    // in fp32.  Rounding the weights to bf16 on their way into LDS instead (what dmr_qlinear_dequantize returns)
-    // is faster but leaves an error of about 1.7e-3 rms(y) standard deviation per output, so that the largest of
-    // 10^7 .. 10^8 outputs lands at 0.8 .. 1.1 times the 1e-2 rms bound (measured); that variant stays
-    // reachable for measurements only (DMR_TUNING=1 DMR_W4_GEMM_ROUNDED=1).
-    const bool g128 = layer->g == dmr::kGroup;
-    if (g128 && dmr::env_int("DMR_W4_GEMM_ROUNDED", 0) == 1) {
-        if (dmr::gemm_big_applies(M, layer->N)) return hip_status(dmr::launch_w4_gemm_big(L, d_x, M, d_y, f32, s));
-        return hip_status(dmr::launch_w4_gemm(L, d_x, M, d_y, f32, false, s));
-    }
-    return hip_status(dmr::launch_w4_gemm(L, d_x, M, d_y, f32, true, s));
+    if (path == W4Path::GemmRescale) return hip_status(dmr::launch_w4_gemm_rescale(L, d_x, M, d_y, f32, d_ws, s));
+    // Fewer than 256 rows on a very wide layer: 128 x 128 tiles on the exact integer codes q - z, the group's scale
+    // applied to the group's partial sums in fp32.  (No tiled kernel rounds the weights to bf16 on their way into
+    // LDS, what dmr_qlinear_dequantize returns: that leaves an error of about 1.7e-3 rms(y) standard deviation per
+    // output, so that the largest of 10^7 .. 10^8 outputs lands at 0.8 .. 1.1 times the 1e-2 rms bound.)
+    return hip_status(dmr::launch_w4_gemm(L, d_x, M, d_y, f32, s));
 }
 
 dmr_status_t dmr_qlinear_bf16_forward(const uint16_t *d_w, const uint16_t *d_x, int64_t M, int64_t K,
@@ -339,7 +336,7 @@ dmr_status_t dmr_qlinear_bf16_forward(const uint16_t *d_w, const uint16_t *d_x, 
         case Bf16Path::Stream: return hip_status(dmr::launch_bf16_stream(d_w, d_x, M, K, N, d_y, f32, nullptr, s));
         case Bf16Path::Skinny: return hip_status(dmr::launch_bf16_skinny(d_w, d_x, M, K, N, d_y, f32, s));
         case Bf16Path::Mid: return hip_status(dmr::launch_bf16_mid(d_w, d_x, M, K, N, d_y, f32, d_ws, s));
-        case Bf16Path::GemmBig: return hip_status(dmr::launch_bf16_gemm_big(d_w, d_x, M, K, N, d_y, f32, s));
+        case Bf16Path::GemmBig: return hip_status(dmr::launch_bf16_gemm_w8(d_w, d_x, M, K, N, d_y, f32, s));
         default: {
             // 128 x 128 tiles: the direct-to-LDS kernel while its pipeline has room to pay (K >= 1024) and the
             // grid is at most ~3 workgroups per CU (measured: 25-30 % ahead at 256 workgroups, level at 512,
@@ -573,6 +570,8 @@ const char *dmr_qlinear_kernel_path(dmr_format_t format, int64_t M, int64_t K, i
                 case W4Path::Wide: return "w4_wide";
                 case W4Path::Skinny2: return "w4_skinny2";
                 case W4Path::Mid: return "w4_mid";
+                case W4Path::GemmRescale:
+                    return dmr::w4_gemm_rescale_wave_columns(M, N) == 4 ? "w4_gemm256_rescale" : "w4_gemm256x128_rescale";
                 default: return "w4_gemm128_exact";
             }
     }

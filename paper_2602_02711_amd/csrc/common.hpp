@@ -195,21 +195,29 @@ hipError_t launch_w4_skinny(const LayerView &L, const uint16_t *x, int64_t M, vo
                             hipStream_t stream);
 hipError_t launch_bf16_skinny(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
                               void *y, bool out_f32, hipStream_t stream);
-// 128 x 128 tiles; `exact` keeps the integer codes in the MFMA and applies the scale per group in fp32
-// (per-channel layers), otherwise the weights are rounded to bf16 on their way into LDS.
-hipError_t launch_w4_gemm(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, bool exact,
-                          hipStream_t stream);
+// 128 x 128 tiles on the exact integer codes q - z; the scale is applied per group in fp32.
+hipError_t launch_w4_gemm(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, hipStream_t stream);
+// The exact kernel restricted to the column blocks of 128 rows with a nonzero word in `only` (device memory, one word
+// per 32 rows; `pairs`: to the aligned pairs of blocks with one).
+hipError_t launch_w4_gemm_flagged(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+                                  const uint32_t *only, bool pairs, hipStream_t stream);
+// 256 x 256 or 256 x 128 tiles on the exact codes 16 + q with one accumulator tile kept in units of the current group's scale;
+// a pre-pass writes the zero-point operands, the rescale factors and per-column-block flags into `ws`
+// (w4_gemm_rescale_workspace_bytes), and the 128 x 128 exact kernel takes the column blocks it flags.
+bool w4_gemm_rescale_applies(int64_t M, int64_t N);
+int w4_gemm_rescale_wave_columns(int64_t M, int64_t N);   // 4: 256 x 256 tiles on 8 waves; 2: 256 x 128 on 4
+size_t w4_gemm_rescale_workspace_bytes(int64_t M, int64_t K, int64_t N);
+hipError_t launch_w4_gemm_rescale(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
+                                  hipStream_t stream);
 // The exact-code 128 x 128 kernel on a 3-bit layer.
 hipError_t launch_w3_gemm(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32, hipStream_t stream);
 hipError_t launch_bf16_gemm(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
                             void *y, bool out_f32, hipStream_t stream);
-// 256 x 256 tiling (direct-to-LDS operand loads, four-stage pipeline) for problems large enough to fill the
-// chip with it.
+// 256 x 256 tiles on eight wavefronts (direct-to-LDS operand loads, four-stage pipeline, two waves per SIMD) for
+// problems large enough to fill the chip with them.
 bool gemm_big_applies(int64_t M, int64_t N);
-hipError_t launch_w4_gemm_big(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
-                              hipStream_t stream);
-hipError_t launch_bf16_gemm_big(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
-                                void *y, bool out_f32, hipStream_t stream);
+hipError_t launch_bf16_gemm_w8(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N, void *y, bool out_f32,
+                               hipStream_t stream);
 hipError_t launch_bf16_gemm_dma128(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
                                    void *y, bool out_f32, hipStream_t stream);
 

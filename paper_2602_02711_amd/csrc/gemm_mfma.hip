@@ -1,14 +1,13 @@
 // Tiled MFMA GEMM for prefill-sized M (a long prompt: few-shot prefix plus the whole history),
 // y[M][N] = x[M][K] . W[N][K]^T with fp32 accumulation.  Three weight sources share the kernel:
 //   kSrcBf16    bf16 weights read as they are;
-//   kSrcW4      INT4 streaming blocks dequantised to RNE_bf16((q - z) s) on their way into LDS (what
-//               dmr_qlinear_dequantize defines; relative weight error <= 2^-9, inside the 1e-2 rms
-//               bound for group-128 layers);
 //   kSrcW4Exact INT4 codes enter LDS as the exact small integers (q - z); the MFMAs of one group of
 //               128 k accumulate into a per-group tile that is folded into the result with the
-//               group's scale in fp32, acc += s[n][G] * D_G, so no weight is ever rounded.  About a
-//               third slower (fold work, 222 registers); what every tiled INT4 launch takes (the rounded
-//               variant leaves the largest of 10^7 outputs at 0.8 .. 1.1 of the 1e-2 rms bound).
+//               group's scale in fp32, acc += s[n][G] * D_G, so no weight is ever rounded.  (Feeding the
+//               matrix cores RNE_bf16((q - z) s) instead, what dmr_qlinear_dequantize returns, saves the
+//               fold but leaves the largest of 10^7 outputs at 0.8 .. 1.1 of the 1e-2 rms bound.)  Serves
+//               the tiled INT4 shapes with fewer than 256 rows, and the column blocks that the faster
+//               256-row kernel declines (scales it cannot rescale by).
 //   kSrcW3Exact the same on the 3-bit streaming layout (768-byte blocks, unpacked with the byte masks of
 //               w3_unpack.hpp), so that a 3-bit layer needs no dequantised copy at prefill sizes.
 //
@@ -26,7 +25,7 @@ namespace dmr {
 namespace {
 
 constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int kSrcBf16 = 0, kSrcW4 = 1, kSrcW4Exact = 2, kSrcW3Exact = 3;
+constexpr int kSrcBf16 = 0, kSrcW4Exact = 2, kSrcW3Exact = 3;
 constexpr int LDS_STRIDE = BK + 8;   // bf16 elements per padded LDS row (144 bytes)
 
 template <int SRC>
@@ -94,8 +93,6 @@ __device__ __forceinline__ void store_lds(const Prefetch<SRC> &p, uint16_t *As, 
         const int row = (tid >> 5) * kTileRows + (l & 15);
         const int kofs = (l >> 4) * 32;               // 0 or 32 inside the 64-wide step
         const float cz = __uint_as_float(p.szw & 0xFFFF0000u);   // -(128 + z)
-        const float s = __uint_as_float(p.szw << 16);
-        const float czs = cz * s;                                // -(128 + z) s, exact in fp32
         const uint32_t words[4] = {p.wb[0].x, p.wb[0].y, p.wb[0].z, p.wb[0].w};
         uint32_t r3[16];                                         // 3-bit: the lane's 16 (128 + q) pairs, k ascending
         if (SRC == kSrcW3Exact) unpack3(words[0], words[1], words[2], r3);
@@ -104,15 +101,12 @@ __device__ __forceinline__ void store_lds(const Prefetch<SRC> &p, uint16_t *As, 
             uint32_t o[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                // (128 + q) as fp32 straight from the bf16 magic pair.  Exact variants: adding
-                // -(128 + z) leaves the integer q - z in [-15, 15], which bf16 holds exactly.
-                // Rounded variant: (128 + q) s - (128 + z) s = (q - z) s in one fma (exact in fp32), then RNE.
+                // (128 + q) as fp32 straight from the bf16 magic pair; adding -(128 + z) leaves the integer
+                // q - z in [-15, 15], which bf16 holds exactly
                 const uint32_t pair = SRC == kSrcW3Exact ? r3[4 * t + i]
                                                          : (((words[t] >> (4 * i)) & 0x000F000Fu) | 0x43004300u);
                 const float plo = __uint_as_float(pair << 16), phi = __uint_as_float(pair & 0xFFFF0000u);
-                const float lo = SRC != kSrcW4 ? plo + cz : fmaf(plo, s, czs);
-                const float hi = SRC != kSrcW4 ? phi + cz : fmaf(phi, s, czs);
-                o[i] = pack_bf16x2(lo, hi);
+                o[i] = pack_bf16x2(plo + cz, phi + cz);
             }
             *reinterpret_cast<uint4 *>(Bs + row * LDS_STRIDE + kofs + t * 8) =
                 make_uint4(o[0], o[1], o[2], o[3]);
@@ -132,7 +126,17 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const void *__restrict__ w
                                                    const uint32_t *__restrict__ sz,
                                                    const uint16_t *__restrict__ x,
                                                    void *__restrict__ y, int64_t M, int64_t K,
-                                                   int64_t N, int szs) {
+                                                   int64_t N, int szs, const uint32_t *__restrict__ only,
+                                                   int only_pairs) {
+    // `only` (optional): one word per 32 columns; the block is computed here only when one of the words of its 128
+    // columns is nonzero (with only_pairs: of the 256 columns of its aligned pair of blocks)
+    if (only) {
+        const int span = only_pairs ? 8 : 4;
+        const int f0 = (int)(blockIdx.x & (only_pairs ? ~1u : ~0u)) * 4, nf = (int)((N + 31) / 32);
+        uint32_t f = 0;
+        for (int i = 0; i < span; ++i) f |= f0 + i < nf ? only[f0 + i] : 0u;
+        if (f == 0) return;
+    }
     __shared__ __attribute__((aligned(16))) uint16_t As[BM * LDS_STRIDE];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * LDS_STRIDE];
     const int tid = threadIdx.x;
@@ -235,21 +239,29 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const void *__restrict__ w
 
 template <int SRC>
 hipError_t launch(const void *wsrc, const uint32_t *sz, int szs, const uint16_t *x, int64_t M, int64_t K,
-                  int64_t N, void *y, bool out_f32, hipStream_t stream) {
+                  int64_t N, void *y, bool out_f32, hipStream_t stream, const uint32_t *only = nullptr,
+                  bool only_pairs = false) {
     const dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
     if (out_f32)
-        hipLaunchKernelGGL((gemm_kernel<SRC, true>), grid, dim3(256), 0, stream, wsrc, sz, x, y, M, K, N, szs);
+        hipLaunchKernelGGL((gemm_kernel<SRC, true>), grid, dim3(256), 0, stream, wsrc, sz, x, y, M, K, N, szs, only,
+                           (int)only_pairs);
     else
-        hipLaunchKernelGGL((gemm_kernel<SRC, false>), grid, dim3(256), 0, stream, wsrc, sz, x, y, M, K, N, szs);
+        hipLaunchKernelGGL((gemm_kernel<SRC, false>), grid, dim3(256), 0, stream, wsrc, sz, x, y, M, K, N, szs, only,
+                           (int)only_pairs);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_w4_gemm(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, bool exact,
-                          hipStream_t stream) {
-    return exact ? launch<kSrcW4Exact>(L.wt, L.sz, L.szs, x, M, L.K, L.N, y, out_f32, stream)
-                 : launch<kSrcW4>(L.wt, L.sz, L.szs, x, M, L.K, L.N, y, out_f32, stream);
+hipError_t launch_w4_gemm(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, hipStream_t stream) {
+    return launch<kSrcW4Exact>(L.wt, L.sz, L.szs, x, M, L.K, L.N, y, out_f32, stream);
+}
+
+// The exact kernel on the column blocks of 128 rows that have a nonzero word in `only` (device memory, one word per
+// 32 rows); with `pairs`, on both blocks of an aligned pair (256 columns) when either has one.
+hipError_t launch_w4_gemm_flagged(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+                                  const uint32_t *only, bool pairs, hipStream_t stream) {
+    return launch<kSrcW4Exact>(L.wt, L.sz, L.szs, x, M, L.K, L.N, y, out_f32, stream, only, pairs);
 }
 
 hipError_t launch_w3_gemm(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32,

@@ -1,0 +1,711 @@
+// Tiled MFMA GEMM for prefill-sized M on a 4-bit layer that never rounds a weight and keeps ONE accumulator tile.
+//
+//     y[m][n] = sum_G s[n][G] * ( sum_{k in G} x[m][k] (16 + q[n][k]) )  -  sum_G s[n][G] (16 + z[n][G]) X[m][G]
+//
+// with X[m][G] the sum of the activations of row m over group G.  The matrix cores multiply the activations
+// with the exact bf16 integers 16 + q (a magic-number unpack like the decode kernels': shifts, masks and
+// v_perm_b32 only, one VALU instruction per weight).  The group scale is not applied to a per-group tile: the
+// accumulator is kept in units of the CURRENT group's scale.  Between groups G and G + 1 every accumulator element
+// is multiplied by s[G] / s[G + 1] (one VALU multiply per element and group, in place), the MFMAs of the next group
+// add into it directly, and after the last group it is multiplied by the last scale.  No second tile and no fold:
+// 128 accumulator registers per wave, in ordinary vector registers (the kernel is compiled for two waves per SIMD,
+// i.e. at most 256 registers, which makes the compiler use the MFMA forms whose accumulator the VALU can address).
+//
+// The zero-point term is a product of rank K / 128.  A pre-pass splits the fp32 group sums X into three bf16
+// terms and the exact products c = -s (16 + z) into two, and lays them out as two plain bf16 matrices A2[M][KP],
+// B2[N][KP] whose product over KP = 6 K / 128 columns (all pairs of terms) is that sum; the kernel runs it as a
+// short second k loop on bf16 operands into the same accumulator.  It adds 4.7 % to the MFMA count.
+//
+// A layer qualifies when every scale is a normal nonzero number and the scales of a row stay within 2^20 of its
+// first one (the running rescale would otherwise divide by zero or overflow).  The pre-pass checks that per block
+// of 32 rows and leaves a flag; a workgroup whose columns are flagged returns at once and the 128 x 128 exact
+// kernel, launched behind this one with the same flags, computes those columns instead.
+//
+// Shape of the work.  Two instantiations: 8 wavefronts (2 x 4) on a 256 x 256 tile, two waves per SIMD, or 4
+// wavefronts (2 x 2) on a 256 x 128 tile for grids too small for the former.  Every wave owns a 128 x 64 patch =
+// 4 x 2 tiles of v_mfma_f32_32x32x16_bf16; 6 operand fragments feed 8 MFMAs.  Data movement as in the bf16 kernels:
+// activations travel global -> LDS without registers (`global_load_lds_dwordx4`), four LDS stages of 32 k, one
+// bare barrier per k step in the middle of the step, rows of 64 bytes with the 16-byte chunks XOR-swizzled.  The
+// packed codes (16 bytes per weight row and k step, fetched by the first half of the waves) and the rescale
+// factors (4 bytes per row, the other half) go direct-to-LDS into a ring of four slots, one step further ahead than
+// the activations; two threads per weight row read the codes back one step before they are multiplied and write
+// 16 + q into the stage.
+#include "common.hpp"
+
+namespace dmr {
+
+namespace {
+
+constexpr int BK = 32, NS = 4, NR = 4;
+constexpr int ROW_BYTES = BK * 2;                          // 64
+constexpr int TM = 4, TN = 2;                              // MFMA tiles per wave
+constexpr int WM = 2;                                      // wave rows per workgroup
+constexpr int BM = 32 * TM * WM;                           // 256
+constexpr int A_BYTES = BM * ROW_BYTES;                    // 16 KiB per stage
+
+template <int WN>                                          // wave columns per workgroup: 2 or 4
+struct Geo {
+    static constexpr int WAVES = WM * WN, THREADS = 64 * WAVES;
+    static constexpr int BN = 32 * TN * WN;                                // 128 or 256
+    static constexpr int B_BYTES = BN * ROW_BYTES;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;                  // 24 or 32 KiB
+    static constexpr int RAW_W_BYTES = BN * 16, RAW_R_BYTES = BN * 4;      // per ring slot
+    static constexpr int RAW_BYTES = RAW_W_BYTES + RAW_R_BYTES;
+    static constexpr size_t LDS_BYTES = (size_t)NS * STAGE_BYTES + (size_t)NR * RAW_BYTES;   // 106 or 148 KiB
+    static constexpr int LA = BM / 16 / WAVES;                             // activation load instructions per wave and step
+    static constexpr int L1 = LA + 1;                                      // ... plus one of codes or factors
+    static constexpr int LB = BN / 16 / WAVES;                             // second loop: B2 instructions per wave (2)
+    static constexpr int L2 = LA + LB;
+};
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void global_void;
+
+// s_waitcnt vmcnt(N) with lgkmcnt(0): the barrier that follows is a bare s_barrier.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (0 << 8));
+}
+
+// Workgroup barrier without the fences of __syncthreads() (which would wait for every direct-to-LDS load in
+// flight); what must have landed is waited for explicitly before this is called.
+__device__ __forceinline__ void bare_barrier() {
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    __builtin_amdgcn_s_barrier();
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+}
+
+__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 2) & 3); }
+
+// Thread (row = tid / 2, half h = tid % 2) owns words 2h, 2h + 1 of the row's k step.  One call turns the 8
+// codes of word 2h + t into the bf16 integers 16 + q, chunk 2h + t of the row's 64-byte slice.  Restrict
+// pointers so that the LDS accesses carry alias scopes (the wait-count pass then does not tie them to the
+// loads in flight).
+__device__ __forceinline__ void unpack_to_stage(const uint8_t *__restrict__ raw_w, uint8_t *__restrict__ Bs, int t, int tid) {
+    const int row = tid >> 1, h = tid & 1;
+    const uint32_t w = *reinterpret_cast<const uint32_t *>(raw_w + row * 16 + h * 8 + t * 4);
+    // nibble -> mantissa bits [3, 7) of a bf16 with exponent 2^4: the value 16 + q (the decode kernels' 128 + q costs
+    // one instruction less, but the running sums would carry an offset eight times larger into the cancellation
+    // with the zero-point term)
+    const uint32_t even = ((w << 3) & 0x78787878u) | 0x80808080u;     // nibbles 0, 2, 4, 6 as low bytes
+    const uint32_t odd = ((w >> 1) & 0x78787878u) | 0x80808080u;      // nibbles 1, 3, 5, 7
+    const uint32_t exp = 0x41414141u;
+    const u32x4_t v = {__builtin_amdgcn_perm(even, exp, 0x00060004u), __builtin_amdgcn_perm(odd, exp, 0x00060004u),
+                       __builtin_amdgcn_perm(even, exp, 0x00070005u), __builtin_amdgcn_perm(odd, exp, 0x00070005u)};
+    *reinterpret_cast<u32x4_t *>(Bs + row * ROW_BYTES + swz(row, 2 * h + t) * 16) = v;
+}
+
+// The rescale factors of a lane's two columns, from the factor part of a ring slot.
+__device__ __forceinline__ void read_factors(const uint8_t *__restrict__ raw_r, const uint8_t *__restrict__ /*stage*/, int col,
+                                             float (&r)[TN]) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) r[j] = *reinterpret_cast<const float *>(raw_r + (col + j * 32) * 4);
+}
+
+__device__ __forceinline__ void load_frags(const uint8_t *__restrict__ As, const uint8_t *__restrict__ Bs, int ks,
+                                           Frag (&a)[TM], Frag (&b)[TN], int lane, int wm, int wn) {
+    const int chunk = ks * 2 + (lane >> 5);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int ra = wm * 32 * TM + i * 32 + (lane & 31);
+        a[i].u = *reinterpret_cast<const uint4 *>(As + ra * ROW_BYTES + swz(ra, chunk) * 16);
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int rb = wn * 32 * TN + j * 32 + (lane & 31);
+        b[j].u = *reinterpret_cast<const uint4 *>(Bs + rb * ROW_BYTES + swz(rb, chunk) * 16);
+    }
+}
+
+__device__ __forceinline__ void mfma_all(const Frag (&a)[TM], const Frag (&b)[TN], f32x16 (&acc)[TM][TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, acc[i][j], 0, 0, 0);
+}
+
+// rfac: [row tile][groups + 1][16] fp32, factor of (row, group): s[G - 1] / s[G] for G >= 1, the LAST scale for G = 0
+// (the accumulator is zero when group 0 starts, so that slot is free), 1 in the slot behind the last group.
+// a2 / b2: bf16 [M][KP] / [N][KP].  flags: one word per 32 columns, nonzero = those columns do not qualify; a tile
+// with a flagged part is left to the other kernel as a whole.
+template <int WN, bool OUT_F32, bool PC, int DBG>
+__global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale_kernel(
+    const uint4 *__restrict__ wt, const float *__restrict__ rfac, const uint16_t *__restrict__ x, const uint16_t *__restrict__ a2,
+    const uint16_t *__restrict__ b2, const uint32_t *__restrict__ flags, void *__restrict__ y, int64_t M, int64_t K, int64_t N,
+    int KP, int nbn, int lg_xm) {
+    using G = Geo<WN>;
+    constexpr int BN = G::BN, STAGE_BYTES = G::STAGE_BYTES, RAW_BYTES = G::RAW_BYTES, RAW_W_BYTES = G::RAW_W_BYTES;
+    constexpr int LA = G::LA, L1 = G::L1, LB = G::LB, L2 = G::L2;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    int tm, tn;
+    if (lg_xm < 0) {            // plain order: column blocks fastest
+        tm = (int)blockIdx.x / nbn;
+        tn = (int)blockIdx.x % nbn;
+    } else {
+        // XCD-aware order: workgroups go to the 8 XCDs round-robin by linear index; the 32 an XCD runs at a
+        // time form a compact 4 x 8 patch of tiles and the 8 patches of a round a compact region
+        const int region = (int)blockIdx.x >> 8, r = (int)blockIdx.x & 255;
+        const int xcd = r & 7, q = r >> 3;
+        const int xn = 8 >> lg_xm;
+        const int regions_n = nbn / (8 * xn);
+        tm = (region / regions_n) * (4 << lg_xm) + (xcd / xn) * 4 + (q >> 3);
+        tn = (region % regions_n) * 8 * xn + (xcd % xn) * 8 + (q & 7);
+    }
+    const int64_t n0 = (int64_t)tn * BN;
+    const int64_t m0 = (int64_t)tm * BM;
+    {                                                          // uniform over the workgroup
+        const int f0 = (int)(n0 / 32), nf = (int)((N + 31) / 32);
+        uint32_t fl = 0;
+#pragma unroll
+        for (int i = 0; i < BN / 32; ++i) fl |= f0 + i < nf ? flags[f0 + i] : 0u;
+        if (fl != 0) return;
+    }
+    const int groups = (int)(K / kGroup);
+    const int steps = groups * 4;
+
+    // ---- activations: wave v fills rows [16 LA v, 16 LA (v + 1)) of a stage, 16 rows per instruction (rows beyond M
+    // clamp to the last row; their products are never stored)
+    const uint16_t *ga[LA];
+    int64_t mrow[LA];
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+        const int row = wave * 16 * LA + i * 16 + (lane >> 2);
+        const int chunk = swz(row, lane & 3);
+        mrow[i] = m0 + row < M ? m0 + row : M - 1;
+        ga[i] = x + mrow[i] * K + chunk * 8;
+    }
+    int dma_step = 0;            // the step the pointers stand at (loads past the end of k re-read the last step)
+    auto issue_dma = [&](int step, int stage_idx) {
+        uint8_t *stage = lds + stage_idx * STAGE_BYTES;
+        const int target = step < steps ? step : steps - 1;
+        const int adv = (target - dma_step) * BK;
+        dma_step = target;
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            ga[i] += adv;
+            __builtin_amdgcn_global_load_lds((global_void *)ga[i], (lds_void *)(stage + (wave * 16 * LA + i * 16) * ROW_BYTES), 16,
+                                             0, 0);
+        }
+    };
+
+    // ---- packed codes and rescale factors of a k step: the 16 bytes of lane 16 c + j of row tile T's block
+    // (c = k step within the group) are row 16 T + j's 32 codes.  Waves [0, WN): codes of rows [64 v, 64 v + 64);
+    // waves [WN, 2 WN): the factors of rows [64 (v - WN), ...).  One load per wave and step.
+    uint8_t *raw = lds + NS * STAGE_BYTES;
+    const int64_t tiles_n = N / kTileRows;
+    const int part = wave % WN;
+    int64_t wT = n0 / kTileRows + part * 4 + (lane >> 4);
+    if (wT >= tiles_n) wT = tiles_n - 1;
+    const int wt_j = lane & 15;
+    auto issue_raw = [&](int step, int slot_idx) {
+        const int target = step < steps ? step : steps - 1;
+        uint8_t *slot = raw + slot_idx * RAW_BYTES;
+        if (wave < WN) {
+            const int64_t block = wT * groups + (target >> 2);
+            __builtin_amdgcn_global_load_lds((global_void *)(wt + block * 64 + (target & 3) * 16 + wt_j),
+                                             (lds_void *)(slot + part * 1024), 16, 0, 0);
+        } else {
+            // (a step past the end asks for the extra slot behind the last group, which holds 1)
+            const int64_t fslot = wT * (groups + 1) + (step < steps ? step >> 2 : groups);
+            __builtin_amdgcn_global_load_lds((global_void *)(rfac + fslot * kTileRows + wt_j),
+                                             (lds_void *)(slot + RAW_W_BYTES + part * 256), 4, 0, 0);
+        }
+    };
+    auto unpack = [&](int slot_idx, int stage_idx, int t) {
+        unpack_to_stage(raw + slot_idx * RAW_BYTES, lds + stage_idx * STAGE_BYTES + A_BYTES, t, tid);
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    // ---- prologue: R(0), then A(j), R(j + 1) for j = 0..3, in that order (vmcnt retires in order); R(4) reuses the
+    // slot of R(0) and is therefore issued only after step 0's codes have been unpacked
+    issue_raw(0, 0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        issue_dma(j, j);
+        if (j < 3) issue_raw(j + 1, j + 1);
+    }
+    wait_vmcnt<3 * LA + 2>();  // R(0), A(0) and R(1) have landed for this wave ...
+    bare_barrier();            // ... and for the waves that fetched the other parts
+    unpack(0, 0, 0);
+    unpack(0, 0, 1);
+    unpack(1, 1, 0);
+    wait_vmcnt<3 * LA + 2>();  // (own LDS accesses done)
+    bare_barrier();
+    issue_raw(4, 0);
+    Frag fa[2][TM], fb[2][TN];
+    load_frags(lds, lds + A_BYTES, 0, fa[0], fb[0], lane, wm, wn);
+
+    // ---- first loop, one group of 128 k (four k steps, stage and ring slot u) per pass of the body.  Step kt = 4 g + u:
+    //     read (kt, 1) | MFMA (kt, 0), unpack word 1 of step kt + 1 |
+    //     wait: loads of step kt + 1 (and the codes of step kt + 2) landed | barrier |
+    //     issue A(kt + 4) into stage u, R(kt + 5) into slot u + 1 (its last reader was the unpack above) |
+    //     read (kt + 1, 0) | MFMA (kt, 1), unpack word 0 of step kt + 2
+    //
+    // Rescale.  After the last MFMA of group g on a tile, that tile is multiplied by f = s[g] / s[g + 1], so that the
+    // MFMAs of group g + 1 can add to it.  The 128 multiplies of a wave are spread over the 16 MFMAs around the group
+    // boundary, half a tile (8 multiplies) next to each MFMA: tiles 0..3 in the last sub-step of group g (behind the
+    // MFMAs of the tiles after them), tiles 4..7 in the first sub-step of group g + 1 (ahead of their own MFMAs).
+    // Layers with one scale per row (PC) never rescale.
+    // (No branch on "first group" / "last group": the multiplies always run, with factors of 1 where there is nothing
+    // to rescale, and that 1 comes from memory: a uniform branch around the multiplies makes the compiler spill the
+    // accumulators, and a select against the constant 1 is turned into such a branch.)
+    const int scol = wn * 32 * TN + (lane & 31);
+    constexpr bool RESCALE = !PC && !(DBG & 2);
+    auto mul_half = [&](int t, int h, const float (&f)[TN]) {
+        const int i = t / TN, j = t % TN;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) acc[i][j][8 * h + r] *= f[j];
+    };
+    auto mfma_tile = [&](int t, const Frag (&a)[TM], const Frag (&b)[TN]) {
+        const int i = t / TN, j = t % TN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, acc[i][j], 0, 0, 0);
+    };
+    static_assert(TM * TN == 8, "the rescale schedule below is written for 8 tiles per wave");
+    float rf[TN];                                               // factors to the group after the current one
+#pragma unroll
+    for (int j = 0; j < TN; ++j) rf[j] = 1.f;
+    for (int g = 0; g < groups; ++g) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int kt = 4 * g + u;
+            const uint8_t *cur = lds + u * STAGE_BYTES;
+            const bool more = kt + 1 < steps;                   // uniform over the workgroup
+            if (u == 3 && RESCALE) {
+                // factors of group g + 1: in the ring slot of its first step, which landed before the last barrier
+                // (read a sub-step early, so that the multiplies below do not wait for them)
+                read_factors(raw + RAW_W_BYTES, lds, scol, rf);
+            }
+            load_frags(cur, cur + A_BYTES, 1, fa[1], fb[1], lane, wm, wn);
+            __builtin_amdgcn_sched_barrier(0);
+            if (!(DBG & 1)) unpack((u + 1) & 3, (u + 1) & 3, 1);
+            if (u == 0 && RESCALE) {
+                mfma_tile(0, fa[0], fb[0]);
+                mul_half(4, 0, rf);
+                mfma_tile(1, fa[0], fb[0]);
+                mul_half(4, 1, rf);
+                mfma_tile(2, fa[0], fb[0]);
+                mul_half(5, 0, rf);
+                mfma_tile(3, fa[0], fb[0]);
+                mul_half(5, 1, rf);
+                mul_half(6, 0, rf);
+                mfma_tile(4, fa[0], fb[0]);
+                mul_half(6, 1, rf);
+                mul_half(7, 0, rf);
+                mfma_tile(5, fa[0], fb[0]);
+                mul_half(7, 1, rf);
+                mfma_tile(6, fa[0], fb[0]);
+                mfma_tile(7, fa[0], fb[0]);
+                // keep that order: without the groups the scheduler issues all 64 multiplies first
+#pragma unroll
+                for (int t = 0; t < 3; ++t) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 18, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 18, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            } else {
+                mfma_all(fa[0], fb[0], acc);
+#pragma unroll
+                for (int t = 0; t < TM * TN; ++t) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);      // its share of the VALU work
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) {
+                wait_vmcnt<2 * L1>();
+                bare_barrier();
+                const uint8_t *nxt = lds + ((u + 1) & 3) * STAGE_BYTES;
+                load_frags(nxt, nxt + A_BYTES, 0, fa[0], fb[0], lane, wm, wn);
+                __builtin_amdgcn_sched_barrier(0);
+                issue_dma(kt + 4, u);
+                issue_raw(kt + 5, (u + 1) & 3);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // The codes of step kt + 2 landed before the barrier above and its stage's weight half was last
+            // read two steps ago.  Unconditional (past the end it rewrites a stage nobody reads).
+            if (!(DBG & 1)) unpack((u + 2) & 3, (u + 2) & 3, 0);
+            if (u == 3 && RESCALE) {
+                // (scheduling fences, not groups: with groups the scheduler still moved all 64 multiplies behind
+                // the last MFMA)
+                mfma_tile(0, fa[1], fb[1]);
+                mfma_tile(1, fa[1], fb[1]);
+                mfma_tile(2, fa[1], fb[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(0, 0, rf);
+                mfma_tile(3, fa[1], fb[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(0, 1, rf);
+                mfma_tile(4, fa[1], fb[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(1, 0, rf);
+                mfma_tile(5, fa[1], fb[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(1, 1, rf);
+                mfma_tile(6, fa[1], fb[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(2, 0, rf);
+                mfma_tile(7, fa[1], fb[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(2, 1, rf);
+                mul_half(3, 0, rf);
+                mul_half(3, 1, rf);
+            } else {
+                mfma_all(fa[1], fb[1], acc);
+#pragma unroll
+                for (int t = 0; t < TM * TN; ++t) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    wait_vmcnt<0>();           // the clamped loads of the last iterations are still in flight
+    bare_barrier();            // every wave is done with the stages
+
+    // ---- into units of 1: the last scale sits in the factor slot of group 0
+    {
+        float sl[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            int64_t n = n0 + scol + j * 32;
+            if (n >= N) n = N - 1;
+            sl[j] = rfac[((n / kTileRows) * (groups + 1)) * kTileRows + (n % kTileRows)];
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] *= sl[j];
+    }
+
+    // ---- second loop: the zero-point term, bf16 operands A2[m][.] and B2[n][.] over KP columns, both direct-to-LDS.
+    // Same pipeline; wave v fills rows [16 LA v, ..) of A2's stage half and rows [16 LB v, ..) of B2's.
+    if (!(DBG & 4)) {
+        const int steps2 = KP / BK;
+        const uint16_t *gp[L2];
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            const int row = wave * 16 * LA + i * 16 + (lane >> 2);
+            gp[i] = a2 + mrow[i] * KP + swz(row, lane & 3) * 8;
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            const int row = wave * 16 * LB + i * 16 + (lane >> 2);
+            const int64_t n = n0 + row < N ? n0 + row : N - 1;
+            gp[LA + i] = b2 + n * KP + swz(row, lane & 3) * 8;
+        }
+        int at = 0;
+        auto issue2 = [&](int step, int stage_idx) {
+            uint8_t *stage = lds + stage_idx * STAGE_BYTES;
+            const int target = step < steps2 ? step : steps2 - 1;
+            const int adv = (target - at) * BK;
+            at = target;
+#pragma unroll
+            for (int i = 0; i < LA; ++i) {
+                gp[i] += adv;
+                __builtin_amdgcn_global_load_lds((global_void *)gp[i], (lds_void *)(stage + (wave * 16 * LA + i * 16) * ROW_BYTES),
+                                                 16, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < LB; ++i) {
+                gp[LA + i] += adv;
+                __builtin_amdgcn_global_load_lds((global_void *)gp[LA + i],
+                                                 (lds_void *)(stage + A_BYTES + (wave * 16 * LB + i * 16) * ROW_BYTES), 16, 0, 0);
+            }
+        };
+#pragma unroll
+        for (int j = 0; j < 4; ++j) issue2(j, j);
+        wait_vmcnt<3 * L2>();
+        bare_barrier();
+        load_frags(lds, lds + A_BYTES, 0, fa[0], fb[0], lane, wm, wn);
+        for (int kt = 0; kt < steps2; ++kt) {
+            const uint8_t *cur = lds + (kt & 3) * STAGE_BYTES;
+            const bool more = kt + 1 < steps2;
+            load_frags(cur, cur + A_BYTES, 1, fa[1], fb[1], lane, wm, wn);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_all(fa[0], fb[0], acc);
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) {
+                wait_vmcnt<2 * L2>();
+                bare_barrier();
+                const uint8_t *nxt = lds + ((kt + 1) & 3) * STAGE_BYTES;
+                load_frags(nxt, nxt + A_BYTES, 0, fa[0], fb[0], lane, wm, wn);
+                __builtin_amdgcn_sched_barrier(0);
+                issue2(kt + 4, kt & 3);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_all(fa[1], fb[1], acc);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        wait_vmcnt<0>();
+    }
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int64_t n = n0 + wn * 32 * TN + j * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t m = m0 + wm * 32 * TM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (m < M && n < N) {
+                    if (OUT_F32)
+                        reinterpret_cast<float *>(y)[m * N + n] = acc[i][j][r];
+                    else
+                        reinterpret_cast<uint16_t *>(y)[m * N + n] = f32_to_bf16(acc[i][j][r]);
+                }
+            }
+        }
+}
+
+// ---- pre-pass, activations ----------------------------------------------------------------------------------------
+// One wave per activation row; the fp32 sum X of each group of 128 activations (8 per lane in k order, then the 16
+// lanes of the group in a fixed rotate-and-add order), split into three bf16 terms X = X0 + X1 + X2, written to
+// A2[m][(2 i + j) G_n + G] = X_i for j = 0, 1.  Columns [6 G_n, KP) are written as zeros (the workspace arrives
+// uninitialised).
+__device__ __forceinline__ void xsum_block(int block, const uint16_t *__restrict__ x, uint16_t *__restrict__ a2, int64_t M, int64_t K,
+                                           int KP) {
+    const int groups = (int)(K / kGroup);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t m = (int64_t)block * 4 + wave;
+    if (m >= M) return;
+    const uint16_t *xr = x + m * K;
+    uint16_t *out = a2 + m * KP;
+    for (int g0 = 0; g0 < groups; g0 += 32) {              // 8 loads of 1 KiB (4 groups each) in flight per wave
+        uint4 v[8];
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const int g = g0 + 4 * b + (lane >> 4);
+            v[b] = g < groups ? *reinterpret_cast<const uint4 *>(xr + (int64_t)g * kGroup + (lane & 15) * 8) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const int g = g0 + 4 * b + (lane >> 4);
+            const uint32_t w[4] = {v[b].x, v[b].y, v[b].z, v[b].w};
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                sum += __uint_as_float(w[i] << 16);
+                sum += __uint_as_float(w[i] & 0xFFFF0000u);
+            }
+            sum = row16_sum(sum);
+            if (g < groups && (lane & 15) == 0) {
+                const uint16_t t0 = f32_to_bf16(sum);
+                const float r1 = sum - bf16_bits_to_f32(t0);
+                const uint16_t t1 = f32_to_bf16(r1);
+                const uint16_t t2 = f32_to_bf16(r1 - bf16_bits_to_f32(t1));
+                const uint16_t t[3] = {t0, t1, t2};
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    out[(2 * i) * groups + g] = t[i];
+                    out[(2 * i + 1) * groups + g] = t[i];
+                }
+            }
+        }
+    }
+    for (int c = 6 * groups + lane; c < KP; c += 64) out[c] = 0;
+}
+
+// ---- pre-pass, weights ---------------------------------------------------------------------------------------------
+// A block takes 32 weight rows (two row tiles).  The scale / zero words go through LDS in chunks of 32 groups (read
+// in their own order, written out row by row); c = -s (16 + z) (exact in fp32: two 8-bit significands) is split into
+// two bf16 terms, B2[n][(2 i + j) G_n + G] = c_j for i = 0..2; the rescale factors; and the block's flag: set when
+// a scale is zero, subnormal or not finite, or further than 2^20 from the row's first.  Columns [6 G_n, KP) of B2
+// are written as zeros.
+constexpr int PRE_CHUNK = 32, PRE_ROWS = 32;
+
+__device__ __forceinline__ float scale_of(uint32_t szw) { return __uint_as_float(szw << 16); }
+
+// One launch does both parts; the blocks of this part come first in the grid (there are few of them and each runs
+// longer than a block of the activation part, which fills the rest of the chip meanwhile).
+__global__ __launch_bounds__(256) void gemm_w4_rescale_prepass_kernel(const uint16_t *__restrict__ x, const uint32_t *__restrict__ sz,
+                                                                      int szs, uint16_t *__restrict__ a2, uint16_t *__restrict__ b2,
+                                                                      float *__restrict__ rfac, uint32_t *__restrict__ flags, int64_t M,
+                                                                      int64_t K, int64_t N, int KP, int nblocks) {
+    if ((int)blockIdx.x >= nblocks) {
+        xsum_block((int)blockIdx.x - nblocks, x, a2, M, K, KP);
+        return;
+    }
+    const int groups = (int)(K / kGroup);
+    const int tid = threadIdx.x;
+    __shared__ uint32_t w_sh[PRE_ROWS][PRE_CHUNK + 1];          // scale / zero word of (row, group within the chunk)
+    __shared__ float prev_sh[PRE_ROWS], first_sh[PRE_ROWS];     // scale of the group before the chunk; |first scale| of the row
+    const int64_t nbase = (int64_t)blockIdx.x * PRE_ROWS;
+    int bad = 0;
+    for (int g0 = 0; g0 < groups; g0 += PRE_CHUNK) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {                  // in the order of the words: tile, group, row of the tile
+            const int idx = tid + 256 * i;
+            const int tile = idx >> 9, gl = (idx >> 4) & 31, j = idx & 15;
+            const int64_t n = nbase + tile * 16 + j;
+            const int g = g0 + gl;
+            w_sh[tile * 16 + j][gl] = (n < N && g < groups) ? sz[sz_index(n / kTileRows, g, groups, szs, j)] : 0x3F80u;
+        }
+        __syncthreads();
+        if (g0 == 0) {
+            if (tid < PRE_ROWS) first_sh[tid] = fabsf(scale_of(w_sh[tid][0]));
+            __syncthreads();
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {                  // row by row: B2 and the checks
+            const int idx = tid + 256 * i;
+            const int row = idx >> 5, gl = idx & 31;
+            const int64_t n = nbase + row;
+            const int g = g0 + gl;
+            if (n < N && g < groups) {
+                const uint32_t szw = w_sh[row][gl];
+                const float s = scale_of(szw);
+                const float c = s * (__uint_as_float(szw & 0xFFFF0000u) + 112.f);      // -(16 + z) s
+                const uint16_t c0 = f32_to_bf16(c);
+                const uint16_t c1 = f32_to_bf16(c - bf16_bits_to_f32(c0));
+                uint16_t *out = b2 + n * KP + g;
+#pragma unroll
+                for (int t = 0; t < 3; ++t) {
+                    out[(2 * t) * groups] = c0;
+                    out[(2 * t + 1) * groups] = c1;
+                }
+                const uint32_t ex = (szw >> 7) & 0xFFu;                                  // exponent field of the bf16 scale
+                const float as = fabsf(s), f = first_sh[row];
+                bad |= (ex == 0 || ex == 255) || !(as <= f * 1048576.f) || !(f <= as * 1048576.f);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {                  // in the order of the words again: the factors
+            const int idx = tid + 256 * i;
+            const int tile = idx >> 9, gl = (idx >> 4) & 31, j = idx & 15;
+            const int row = tile * 16 + j;
+            const int64_t n = nbase + row;
+            const int g = g0 + gl;
+            if (n < N && g < groups && g > 0) {
+                const float sp = gl > 0 ? scale_of(w_sh[row][gl - 1]) : prev_sh[row];
+                rfac[((n / kTileRows) * (groups + 1) + g) * kTileRows + j] = sp / scale_of(w_sh[row][gl]);
+            }
+        }
+        __syncthreads();
+        const int last = groups - g0 < PRE_CHUNK ? groups - g0 - 1 : PRE_CHUNK - 1;
+        if (tid < PRE_ROWS) prev_sh[tid] = scale_of(w_sh[tid][last]);
+        __syncthreads();
+    }
+    if (tid < PRE_ROWS && nbase + tid < N) {
+        const int64_t n = nbase + tid;
+        float *f = rfac + ((n / kTileRows) * (groups + 1)) * kTileRows + (n % kTileRows);
+        f[0] = prev_sh[tid];                           // the last scale
+        f[(int64_t)groups * kTileRows] = 1.f;
+    }
+    for (int idx = tid; idx < PRE_ROWS * 32; idx += 256) {
+        const int row = idx >> 5, c = 6 * groups + (idx & 31);
+        if (nbase + row < N && c < KP) b2[(nbase + row) * KP + c] = 0;
+    }
+    bad = __syncthreads_or(bad);
+    if (tid == 0) flags[blockIdx.x] = (uint32_t)bad;
+}
+
+struct RescalePlan {
+    int KP;
+    size_t off_a2, off_b2, off_r, off_flags, total;
+};
+
+RescalePlan plan_rescale(int64_t M, int64_t K, int64_t N) {
+    RescalePlan p;
+    const int64_t groups = K / kGroup;
+    p.KP = (int)((6 * groups + BK - 1) / BK * BK);
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    p.off_a2 = 0;
+    p.off_b2 = up((size_t)M * p.KP * 2);
+    p.off_r = p.off_b2 + up((size_t)N * p.KP * 2);
+    p.off_flags = p.off_r + up((size_t)N * (groups + 1) * 4);
+    p.total = p.off_flags + up((size_t)((N + 31) / 32) * 4);
+    return p;
+}
+
+
+template <int WN>
+hipError_t launch_tile(const LayerView &Lv, const uint16_t *x, int64_t M, void *y, bool out_f32, const RescalePlan &p,
+                       const uint16_t *a2, const uint16_t *b2, const float *rfac, const uint32_t *flags, hipStream_t stream) {
+    using G = Geo<WN>;
+    const int nbm = (int)((M + BM - 1) / BM), nbn = (int)((Lv.N + G::BN - 1) / G::BN);
+    // XCD-aware tile order when the grid of tiles divides into regions of 8 patches of 4 x 8 tiles (see the kernel)
+    int lg_xm = 2;
+    while (lg_xm >= 0 && (nbm % (4 << lg_xm) != 0 || nbn % (8 * (8 >> lg_xm)) != 0)) --lg_xm;
+    auto go = [&](auto kernel) {
+        hipError_t st = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            (int)G::LDS_BYTES);
+        if (st != hipSuccess) return st;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)(nbm * nbn)), dim3(G::THREADS), G::LDS_BYTES, stream, Lv.wt, rfac, x, a2, b2, flags,
+                           y, M, Lv.K, Lv.N, p.KP, nbn, lg_xm);
+        return hipGetLastError();
+    };
+    const bool pc = Lv.szs == 0;
+    switch (env_int("DMR_RESCALE_DBG", 0)) {
+        case 1: return go(&gemm_w4_rescale_kernel<WN, false, false, 1>);
+        case 2: return go(&gemm_w4_rescale_kernel<WN, false, false, 2>);
+        case 4: return go(&gemm_w4_rescale_kernel<WN, false, false, 4>);
+        case 7: return go(&gemm_w4_rescale_kernel<WN, false, false, 7>);
+        default: break;
+    }
+    return pc ? (out_f32 ? go(&gemm_w4_rescale_kernel<WN, true, true, 0>) : go(&gemm_w4_rescale_kernel<WN, false, true, 0>))
+              : (out_f32 ? go(&gemm_w4_rescale_kernel<WN, true, false, 0>) : go(&gemm_w4_rescale_kernel<WN, false, false, 0>));
+}
+
+}  // namespace
+
+// Measured against the 128 x 128 exact kernel: ahead wherever that one is dispatched, from one full row tile on.
+bool w4_gemm_rescale_applies(int64_t M, int64_t N) {
+    const int64_t wgs = ((M + BM - 1) / BM) * ((N + 127) / 128);
+    return M >= env_int("DMR_W4_RESCALE_MIN_M", BM) && wgs <= 0x3FFFFFFF;
+}
+
+// Wave columns of the tile: 8 waves on 256 x 256 tiles from about 176 such tiles on (measured: ahead at 192 and 224
+// tiles, behind at 128), else 4 waves on 256 x 128.
+int w4_gemm_rescale_wave_columns(int64_t M, int64_t N) {
+    const int forced = env_int("DMR_W4_RESCALE_WN", 0);
+    if (forced == 2 || forced == 4) return forced;
+    const int64_t wgs = ((M + BM - 1) / BM) * ((N + 255) / 256);
+    return wgs >= 176 ? 4 : 2;
+}
+
+size_t w4_gemm_rescale_workspace_bytes(int64_t M, int64_t K, int64_t N) { return plan_rescale(M, K, N).total; }
+
+// Pre-pass, the rescaling kernel, then the 128 x 128 exact kernel for the column blocks the pre-pass flagged
+// (normally none: its workgroups then return at once).
+hipError_t launch_w4_gemm_rescale(const LayerView &Lv, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
+                                  hipStream_t stream) {
+    const RescalePlan p = plan_rescale(M, Lv.K, Lv.N);
+    uint8_t *base = reinterpret_cast<uint8_t *>(ws);
+    uint16_t *a2 = reinterpret_cast<uint16_t *>(base + p.off_a2);
+    uint16_t *b2 = reinterpret_cast<uint16_t *>(base + p.off_b2);
+    float *rfac = reinterpret_cast<float *>(base + p.off_r);
+    uint32_t *flags = reinterpret_cast<uint32_t *>(base + p.off_flags);
+    const int nblocks = (int)((Lv.N + PRE_ROWS - 1) / PRE_ROWS), mblocks = (int)((M + 3) / 4);
+    hipLaunchKernelGGL(gemm_w4_rescale_prepass_kernel, dim3((unsigned)(nblocks + mblocks)), dim3(256), 0, stream, x, Lv.sz, Lv.szs,
+                       a2, b2, rfac, flags, M, Lv.K, Lv.N, p.KP, nblocks);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int wn = w4_gemm_rescale_wave_columns(M, Lv.N);
+    e = wn == 4 ? launch_tile<4>(Lv, x, M, y, out_f32, p, a2, b2, rfac, flags, stream)
+                : launch_tile<2>(Lv, x, M, y, out_f32, p, a2, b2, rfac, flags, stream);
+    if (e != hipSuccess) return e;
+    return launch_w4_gemm_flagged(Lv, x, M, y, out_f32, flags, wn == 4, stream);
+}
+
+}  // namespace dmr

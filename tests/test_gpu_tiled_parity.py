@@ -95,14 +95,17 @@ def test_bf16_tiled_gemms_small_integers_exact():
 
 # ------------------------------------------------------------------ INT4, tiled kernels, whole output
 
-@pytest.mark.parametrize("K,N,M", [
-    (1024, 3840, 3584),          # 14 x 15 tiles of 256, 28 x 30 of 128
-    (1152, 3856, 3500),          # ragged last tiles, an odd number of groups
-    (256, 2192, 2200),           # two groups only
-    (256, 3840, 3584),           # short rows, 1.4e7 outputs: where weights rounded to bf16 were seen to miss the bound
+@pytest.mark.parametrize("K,N,M,path", [
+    (1024, 3840, 3584, "w4_gemm256_rescale"),        # 14 x 15 tiles of 256 on eight waves
+    (1152, 3856, 3500, "w4_gemm256_rescale"),        # ragged last tiles, an odd number of groups
+    (256, 3840, 3584, "w4_gemm256_rescale"),         # short rows, 1.4e7 outputs: where weights rounded to bf16 were seen to miss the bound
+    (256, 2192, 2200, "w4_gemm256x128_rescale"),     # 9 x 18 tiles of 256 x 128 on four waves, two groups only
+    (1152, 2192, 2200, "w4_gemm256x128_rescale"),    # the same grid, nine groups, ragged in both directions
+    (128, 2192, 2200, "w4_gemm256x128_rescale"),     # a single group: nothing to rescale, the zero-point loop is one step
+    (256, 19200, 200, "w4_gemm128_exact"),           # fewer than 256 rows on a very wide layer: the 128 x 128 kernel
 ])
-def test_int4_tiled_gemm_full_output(K, N, M):
-    assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W4_G128, M, K, N) == "w4_gemm128_exact"
+def test_int4_tiled_gemm_full_output(K, N, M, path):
+    assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W4_G128, M, K, N) == path
     _, words, s, z = quantized(8300 + K + N, N, K)
     x = synth.activations_bf16(8301 + K + M, M, K)
     layer = dmr.dmr_qlinear_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
@@ -111,25 +114,110 @@ def test_int4_tiled_gemm_full_output(K, N, M):
     y16 = bits_host(dmr.dmr_qlinear_forward(layer, xd, out_dtype=torch.bfloat16))
     y_ref, _ = orc.forward(words, s, z, G, x, threads=THREADS)
     err = rel_err(y32, y_ref)
-    print(f"w4 tiled ({K},{N}) M={M}: max err {err:.3e} rms, all {M * N} outputs")
+    print(f"{path} ({K},{N}) M={M}: max err {err:.3e} rms, all {M * N} outputs")
     # the codes stay exact, so only fp32 accumulation is left: far inside the bound
     assert err <= 1e-4
     assert np.array_equal(y16, orc.f32_to_bf16(y32))
 
 
 def test_int4_one_hot_rows_through_the_tiled_gemms():
-    # M = K one-hot rows: output m, n is the single weight w^[n][m] = s (q - z), one exact fp32 product rounded once:
-    # the bf16 output must equal dmr_qlinear_dequantize bit for bit
-    for K, N, path in [(2304, 2304, "w4_gemm128_exact"), (3584, 3840, "w4_gemm128_exact")]:
+    # One-hot rows: output m, n is the single weight w^[n][m] = s (q - z).
+    # 128 x 128 kernel (200 rows of the identity): one exact fp32 product rounded once, so the bf16 output must equal
+    # dmr_qlinear_dequantize bit for bit.
+    K, N, M = 256, 19200, 200
+    assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W4_G128, M, K, N) == "w4_gemm128_exact"
+    _, words, s, z = quantized(8400 + K, N, K)
+    layer = dmr.dmr_qlinear_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
+    x = torch.eye(K, dtype=torch.bfloat16, device=DEV)[:M].contiguous()
+    y16 = dmr.dmr_qlinear_forward(layer, x, out_dtype=torch.bfloat16)
+    wq = dmr.dmr_qlinear_dequantize(layer)
+    assert torch.equal(y16.view(torch.int16), wq.t()[:M].contiguous().view(torch.int16))
+    assert np.array_equal(bits_host(wq), orc.dequantize(words, s, z, G))
+    # 256-row kernels: the weight comes out as s_last (prod of scale ratios) (16 + q) - s (16 + z), a handful of fp32
+    # roundings from s (q - z); each output is checked against the exact weight on its own, relative to the largest
+    # term of that difference
+    for K, N, path in [(2304, 2304, "w4_gemm256x128_rescale"), (3584, 3840, "w4_gemm256_rescale")]:
         M = K
         assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W4_G128, M, K, N) == path
         _, words, s, z = quantized(8400 + K, N, K)
         layer = dmr.dmr_qlinear_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
-        x = torch.eye(K, dtype=torch.bfloat16, device=DEV)
-        y16 = dmr.dmr_qlinear_forward(layer, x, out_dtype=torch.bfloat16)
-        wq = dmr.dmr_qlinear_dequantize(layer)
-        assert torch.equal(y16.view(torch.int16), wq.t().contiguous().view(torch.int16)), path
-        assert np.array_equal(bits_host(wq), orc.dequantize(words, s, z, G)), path
+        y32 = dmr.dmr_qlinear_forward(layer, torch.eye(K, dtype=torch.bfloat16, device=DEV), out_dtype=torch.float32)
+        exact = orc.dequantize_exact(words, s, z, G)                       # [N][K] fp64
+        scale = np.repeat(orc.bf16_to_f64(s), G, axis=1)                   # [N][K]
+        dev = np.abs(y32.cpu().numpy().astype(np.float64).T - exact) / (31.0 * np.abs(scale))
+        print(f"{path} one-hot ({K},{N}): max deviation {dev.max():.3e} of the largest term")
+        assert dev.max() <= 2e-5, path
+
+
+def _scales_with(s, rows_groups, bits):
+    out = s.copy()
+    for (n, g) in rows_groups:
+        out[n, g] = bits
+    return out
+
+
+@pytest.mark.parametrize("K,N,M,path", [(1152, 2192, 2200, "w4_gemm256x128_rescale"), (1152, 3856, 3500, "w4_gemm256_rescale")])
+def test_int4_tiled_gemm_scales_that_cannot_be_rescaled(K, N, M, path):
+    # A zero scale, a subnormal one and a row whose scales span 2^41: the running rescale of the 256-row kernels
+    # cannot carry them, so their column blocks must come from the 128 x 128 kernel behind it, all others from the
+    # fast kernel, and the output must be the oracle's everywhere.
+    assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W4_G128, M, K, N) == path
+    _, words, s, z = quantized(8300 + K + N, N, K)
+    x = synth.activations_bf16(8301 + K + M, M, K)
+    xd = bf16_dev(x)
+    s2 = _scales_with(s, [(200, 3), (N - 1, 0)], 0x0000)                     # zero
+    s2 = _scales_with(s2, [(700, 8)], 0x0040)                               # subnormal
+    s2 = _scales_with(s2, [(1500, 1)], 0x5000)                              # 2^33 next to 2^-6-sized neighbours
+    s2 = _scales_with(s2, [(1500, 5)], 0x2B80)                              # 2^-40
+    layer = dmr.dmr_qlinear_create(u32_dev(words), bf16_dev(s2), bf16_dev(z), G)
+    y32 = dmr.dmr_qlinear_forward(layer, xd, out_dtype=torch.float32).cpu().numpy()
+    y_ref, _ = orc.forward(words, s2, z, G, x, threads=THREADS)
+    assert np.all(np.isfinite(y32))
+    # column by column (the columns with the huge scale dwarf the rms of the whole output)
+    rms_col = np.sqrt(np.mean(y_ref ** 2, axis=0))
+    err = np.max(np.abs(y32.astype(np.float64) - y_ref) / np.maximum(rms_col, 1e-30))
+    print(f"{path} with scales it declines ({K},{N}) M={M}: max err {err:.3e} of the column rms")
+    assert err <= 1e-4
+
+
+@pytest.mark.parametrize("K,N,M,path", [(256, 3840, 3584, "w4_gemm256_rescale"), (1024, 1024, 6400, "w4_gemm256x128_rescale")])
+def test_per_channel_layer_through_the_tiled_gemms(K, N, M, path):
+    assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W4_PER_CHANNEL, M, K, N) == path
+    rng = np.random.default_rng(8700 + K + M)
+    q = rng.integers(0, 16, size=(N, K), dtype=np.uint8)
+    s_row = synth.to_bf16_bits(np.abs(synth.weights_f32(8701 + K, N, 1)) + np.float32(2e-3))       # [N][1]
+    z_row = orc.f64_to_bf16(np.full((N, 1), 8.0))
+    words = orc.pack(q)
+    layer = dmr.dmr_qlinear_create_per_channel(u32_dev(words), bf16_dev(s_row.reshape(N)))
+    x = synth.activations_bf16(8702 + K, M, K)
+    y32 = dmr.dmr_qlinear_forward(layer, bf16_dev(x), out_dtype=torch.float32).cpu().numpy()
+    y_ref, _ = orc.forward(words, s_row, z_row, K, x, threads=THREADS)
+    err = rel_err(y32, y_ref)
+    print(f"per-channel {path} ({K},{N}) M={M}: max err {err:.3e} rms")
+    assert err <= 1e-4
+
+
+def test_int4_tiled_gemm_refuses_a_short_workspace():
+    K, N, M = 256, 2192, 2200
+    need = dmr.dmr_qlinear_workspace_bytes(M, K, N)
+    assert need > 0                       # zero-point operands, rescale factors, flags
+    _, words, s, z = quantized(8300 + K + N, N, K)
+    layer = dmr.dmr_qlinear_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
+    xd = bf16_dev(synth.activations_bf16(8301 + K + M, M, K))
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    y = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV)
+    lib = dmr.binding.lib()
+    for pws, nbytes in ((None, 0), (ws.data_ptr(), need - 1)):
+        st = lib.dmr_qlinear_forward(layer.handle, xd.data_ptr(), M, y.data_ptr(), dmr.DMR_OUT_FP32, pws, nbytes,
+                                     torch.cuda.current_stream().cuda_stream)
+        assert st == dmr.binding.DMR_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert bool((y == 7.0).all())
+    # a workspace full of NaN bit patterns must not leak into the result (every word that is read is written first)
+    ws.fill_(0xFF)
+    y32 = dmr.dmr_qlinear_forward(layer, xd, out_dtype=torch.float32, workspace=ws)
+    y_again = dmr.dmr_qlinear_forward(layer, xd, out_dtype=torch.float32)
+    assert torch.equal(y32, y_again) and bool(torch.isfinite(y32).all())
 
 
 # ------------------------------------------------------------------ prefill config: every (M, shape) cell, sampled

@@ -3,8 +3,7 @@ compile errors and that cost this code base dearly when they happened.
 
 * A register array that the compiler cannot keep in registers (an array of HIP's uint4 struct behind a
   generic lambda, a dynamically indexed array) lands in scratch memory: the kernel still computes the
-  right values, several times slower.  Every kernel must have a private segment of 0 bytes, except the
-  256 x 256 GEMM, whose few spills at 512 registers are known and accepted.
+  right values, several times slower.  Every kernel must have a private segment of 0 bytes.
 * Inline assembly next to MFMAs is not covered by the compiler's hazard handling (the wait states an MFMA
   needs after a VALU write of its operands): no kernel may contain an inline-assembly block.
 """
@@ -21,7 +20,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SOURCES = sorted(glob.glob(os.path.join(ROOT, "paper_2602_02711_amd", "csrc", "*.hip")))
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "--cuda-device-only", "-S"]
-SCRATCH_ALLOWED = {"gemm_mfma_big.hip": 64}        # bytes per lane
+SCRATCH_ALLOWED = {}        # file name -> bytes per lane (none accepted at present)
 
 
 def device_asm(src):
