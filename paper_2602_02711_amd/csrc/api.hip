@@ -43,7 +43,7 @@ W4Path w4_path(int64_t M, int64_t K, int64_t N) {
 // 3-bit layers: the 4-bit size classes on the native 3-bit kernels; a decode row too long for the GEMV's LDS
 // budget takes the rollout-batch kernel (which slices K).  The workspace query and the forward call both go
 // through this.
-enum class W3Path { Gemv, Stream, Panel, Wide, Mid, Gemm };
+enum class W3Path { Gemv, Stream, Panel, Wide, Mid, Gemm, GemmRescale };
 W3Path w3_path(int64_t M, int64_t K, int64_t N) {
     if (M == 1) return dmr::w3_gemv_fits(K, N) ? W3Path::Gemv : W3Path::Mid;
     if (M <= 16) {
@@ -52,7 +52,8 @@ W3Path w3_path(int64_t M, int64_t K, int64_t N) {
     }
     if (M <= kSkinnyMaxM && dmr::w4_wide_applies(M, K, N)) return W3Path::Wide;
     const int64_t gemm_wgs = ((M + 127) / 128) * ((N + 127) / 128);
-    return (M <= 128 || gemm_wgs < 300) ? W3Path::Mid : W3Path::Gemm;
+    if (M <= 128 || gemm_wgs < 300) return W3Path::Mid;
+    return dmr::w4_gemm_rescale_applies(M, N) ? W3Path::GemmRescale : W3Path::Gemm;
 }
 
 // The bf16 twin: GEMV, the direct-from-L2 skinny kernel for 2..8 rows (measured faster there than the
@@ -201,6 +202,7 @@ size_t dmr_qlinear_w3_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     switch (w3_path(M, K, N)) {
         case W3Path::Panel: return dmr::w4_panel_workspace_bytes(M, K, N);   // fp32 partials of the k slices
         case W3Path::Mid: return dmr::w4_mid_workspace_bytes(M, K, N);       // fp32 partials when K is split
+        case W3Path::GemmRescale: return dmr::w4_gemm_rescale_workspace_bytes(M, K, N);   // zero-point operands, factors
         default: return 0;
     }
 }
@@ -283,6 +285,7 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
             case W3Path::Wide: return hip_status(dmr::launch_w3_wide(L3, d_x, M, d_y, f32, s));
             case W3Path::Mid: return hip_status(dmr::launch_w3_mid(L3, d_x, M, d_y, f32, d_ws, s));
             case W3Path::Gemm: return hip_status(dmr::launch_w3_gemm(L3, d_x, M, d_y, f32, s));
+            case W3Path::GemmRescale: return hip_status(dmr::launch_w3_gemm_rescale(L3, d_x, M, d_y, f32, d_ws, s));
         }
         return DMR_ERR_UNSUPPORTED;
     }
@@ -559,6 +562,8 @@ const char *dmr_qlinear_kernel_path(dmr_format_t format, int64_t M, int64_t K, i
                 case W3Path::Panel: return "w3_panel";
                 case W3Path::Wide: return "w3_wide";
                 case W3Path::Mid: return "w3_mid";
+                case W3Path::GemmRescale:
+                    return dmr::w4_gemm_rescale_wave_columns(M, N) == 4 ? "w3_gemm256_rescale" : "w3_gemm256x128_rescale";
                 default: return "w3_gemm128_exact";
             }
         case DMR_FMT_W4_G128:

@@ -209,8 +209,12 @@ int w4_gemm_rescale_wave_columns(int64_t M, int64_t N);   // 4: 256 x 256 tiles 
 size_t w4_gemm_rescale_workspace_bytes(int64_t M, int64_t K, int64_t N);
 hipError_t launch_w4_gemm_rescale(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
                                   hipStream_t stream);
-// The exact-code 128 x 128 kernel on a 3-bit layer.
+// The exact-code 128 x 128 kernel on a 3-bit layer; the 256-row kernel and its fallback for flagged column blocks.
 hipError_t launch_w3_gemm(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32, hipStream_t stream);
+hipError_t launch_w3_gemm_flagged(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+                                  const uint32_t *only, bool pairs, hipStream_t stream);
+hipError_t launch_w3_gemm_rescale(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
+                                  hipStream_t stream);
 hipError_t launch_bf16_gemm(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
                             void *y, bool out_f32, hipStream_t stream);
 // 256 x 256 tiles on eight wavefronts (direct-to-LDS operand loads, four-stage pipeline, two waves per SIMD) for

@@ -269,6 +269,11 @@ hipError_t launch_w3_gemm(const LayerView3 &L, const uint16_t *x, int64_t M, voi
     return launch<kSrcW3Exact>(L.wt, L.sz, 1, x, M, L.K, L.N, y, out_f32, stream);
 }
 
+hipError_t launch_w3_gemm_flagged(const LayerView3 &L, const uint16_t *x, int64_t M, void *y, bool out_f32,
+                                  const uint32_t *only, bool pairs, hipStream_t stream) {
+    return launch<kSrcW3Exact>(L.wt, L.sz, 1, x, M, L.K, L.N, y, out_f32, stream, only, pairs);
+}
+
 hipError_t launch_bf16_gemm(const uint16_t *w, const uint16_t *x, int64_t M, int64_t K, int64_t N,
                             void *y, bool out_f32, hipStream_t stream) {
     return launch<kSrcBf16>(w, nullptr, 1, x, M, K, N, y, out_f32, stream);

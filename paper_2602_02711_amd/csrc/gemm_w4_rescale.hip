@@ -43,13 +43,13 @@ constexpr int WM = 2;                                      // wave rows per work
 constexpr int BM = 32 * TM * WM;                           // 256
 constexpr int A_BYTES = BM * ROW_BYTES;                    // 16 KiB per stage
 
-template <int WN>                                          // wave columns per workgroup: 2 or 4
+template <int WN, int BITS>                                // wave columns per workgroup: 2 or 4; code width: 4 or 3
 struct Geo {
     static constexpr int WAVES = WM * WN, THREADS = 64 * WAVES;
     static constexpr int BN = 32 * TN * WN;                                // 128 or 256
     static constexpr int B_BYTES = BN * ROW_BYTES;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;                  // 24 or 32 KiB
-    static constexpr int RAW_W_BYTES = BN * 16, RAW_R_BYTES = BN * 4;      // per ring slot
+    static constexpr int RAW_W_BYTES = BN * 16, RAW_R_BYTES = BN * 4;      // per ring slot (3-bit rows use 12 of their 16 bytes)
     static constexpr int RAW_BYTES = RAW_W_BYTES + RAW_R_BYTES;
     static constexpr size_t LDS_BYTES = (size_t)NS * STAGE_BYTES + (size_t)NR * RAW_BYTES;   // 106 or 148 KiB
     static constexpr int LA = BM / 16 / WAVES;                             // activation load instructions per wave and step
@@ -96,6 +96,34 @@ __device__ __forceinline__ void unpack_to_stage(const uint8_t *__restrict__ raw_
     *reinterpret_cast<u32x4_t *>(Bs + row * ROW_BYTES + swz(row, 2 * h + t) * 16) = v;
 }
 
+// The 3-bit layout (three words per row and k step; chunks 0..2 of the row's slice are the two 3-bit fields of the
+// bytes of word 0..2, chunk 3 the spare top bits of all three words).  Call 0: thread h turns word h into chunk h.
+// Call 1: thread h writes half h of chunk 2 (field h of word 2) and half h of chunk 3 (spare bits: bit 6 + h of
+// word 2 is the code's third bit, the top two bits of word h its low two), so that both threads run the same
+// instructions.  Codes land in mantissa bits [3, 6) of a bf16 with exponent 2^4: 16 + q.
+__device__ __forceinline__ void unpack3_to_stage(const uint8_t *__restrict__ raw_w, uint8_t *__restrict__ Bs, int t, int tid) {
+    const int row = tid >> 1, h = tid & 1;
+    const uint32_t *w = reinterpret_cast<const uint32_t *>(raw_w + row * 16);
+    const uint32_t exp = 0x41414141u, one = 0x80808080u, m38 = 0x38383838u;
+    const uint32_t sel_a = 0x00060004u, sel_b = 0x00070005u;     // bytes (0, 2) resp. (1, 3) of the codes
+    if (t == 0) {
+        const uint32_t v = w[h];
+        const uint32_t f0 = ((v << 3) & m38) | one, f1 = (v & m38) | one;
+        const u32x4_t o = {__builtin_amdgcn_perm(f0, exp, sel_a), __builtin_amdgcn_perm(f0, exp, sel_b),
+                           __builtin_amdgcn_perm(f1, exp, sel_a), __builtin_amdgcn_perm(f1, exp, sel_b)};
+        *reinterpret_cast<u32x4_t *>(Bs + row * ROW_BYTES + swz(row, h) * 16) = o;
+    } else {
+        const uint32_t w2 = w[2], wl = w[h];
+        const uint32_t f = ((w2 << (h ? 0 : 3)) & m38) | one;
+        const uint32_t c = ((((w2 >> (6 + h)) & 0x01010101u) << 5) | (((wl >> 6) & 0x03030303u) << 3)) | one;
+        typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+        const u32x2_t o2 = {__builtin_amdgcn_perm(f, exp, sel_a), __builtin_amdgcn_perm(f, exp, sel_b)};
+        const u32x2_t o3 = {__builtin_amdgcn_perm(c, exp, sel_a), __builtin_amdgcn_perm(c, exp, sel_b)};
+        *reinterpret_cast<u32x2_t *>(Bs + row * ROW_BYTES + swz(row, 2) * 16 + h * 8) = o2;
+        *reinterpret_cast<u32x2_t *>(Bs + row * ROW_BYTES + swz(row, 3) * 16 + h * 8) = o3;
+    }
+}
+
 // The rescale factors of a lane's two columns, from the factor part of a ring slot.
 __device__ __forceinline__ void read_factors(const uint8_t *__restrict__ raw_r, const uint8_t *__restrict__ /*stage*/, int col,
                                              float (&r)[TN]) {
@@ -129,12 +157,12 @@ __device__ __forceinline__ void mfma_all(const Frag (&a)[TM], const Frag (&b)[TN
 // (the accumulator is zero when group 0 starts, so that slot is free), 1 in the slot behind the last group.
 // a2 / b2: bf16 [M][KP] / [N][KP].  flags: one word per 32 columns, nonzero = those columns do not qualify; a tile
 // with a flagged part is left to the other kernel as a whole.
-template <int WN, bool OUT_F32, bool PC, int DBG>
+template <int WN, int BITS, bool OUT_F32, bool PC, int DBG>
 __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale_kernel(
-    const uint4 *__restrict__ wt, const float *__restrict__ rfac, const uint16_t *__restrict__ x, const uint16_t *__restrict__ a2,
+    const void *__restrict__ wt, const float *__restrict__ rfac, const uint16_t *__restrict__ x, const uint16_t *__restrict__ a2,
     const uint16_t *__restrict__ b2, const uint32_t *__restrict__ flags, void *__restrict__ y, int64_t M, int64_t K, int64_t N,
     int KP, int nbn, int lg_xm) {
-    using G = Geo<WN>;
+    using G = Geo<WN, BITS>;
     constexpr int BN = G::BN, STAGE_BYTES = G::STAGE_BYTES, RAW_BYTES = G::RAW_BYTES, RAW_W_BYTES = G::RAW_W_BYTES;
     constexpr int LA = G::LA, L1 = G::L1, LB = G::LB, L2 = G::L2;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -207,8 +235,13 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
         uint8_t *slot = raw + slot_idx * RAW_BYTES;
         if (wave < WN) {
             const int64_t block = wT * groups + (target >> 2);
-            __builtin_amdgcn_global_load_lds((global_void *)(wt + block * 64 + (target & 3) * 16 + wt_j),
-                                             (lds_void *)(slot + part * 1024), 16, 0, 0);
+            const int64_t l = block * 64 + (target & 3) * 16 + wt_j;           // the lane's slot in the streaming layout
+            if constexpr (BITS == 4)
+                __builtin_amdgcn_global_load_lds((global_void *)(reinterpret_cast<const uint4 *>(wt) + l),
+                                                 (lds_void *)(slot + part * 1024), 16, 0, 0);
+            else   // 12 bytes per lane, fetched as 16 (the last lane of the layer reads 4 bytes into the scale words behind)
+                __builtin_amdgcn_global_load_lds((global_void *)(reinterpret_cast<const uint32_t *>(wt) + l * 3),
+                                                 (lds_void *)(slot + part * 1024), 16, 0, 0);
         } else {
             // (a step past the end asks for the extra slot behind the last group, which holds 1)
             const int64_t fslot = wT * (groups + 1) + (step < steps ? step >> 2 : groups);
@@ -217,7 +250,10 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
         }
     };
     auto unpack = [&](int slot_idx, int stage_idx, int t) {
-        unpack_to_stage(raw + slot_idx * RAW_BYTES, lds + stage_idx * STAGE_BYTES + A_BYTES, t, tid);
+        if constexpr (BITS == 4)
+            unpack_to_stage(raw + slot_idx * RAW_BYTES, lds + stage_idx * STAGE_BYTES + A_BYTES, t, tid);
+        else
+            unpack3_to_stage(raw + slot_idx * RAW_BYTES, lds + stage_idx * STAGE_BYTES + A_BYTES, t, tid);
     };
 
     f32x16 acc[TM][TN];
@@ -639,11 +675,17 @@ RescalePlan plan_rescale(int64_t M, int64_t K, int64_t N) {
 }
 
 
-template <int WN>
-hipError_t launch_tile(const LayerView &Lv, const uint16_t *x, int64_t M, void *y, bool out_f32, const RescalePlan &p,
-                       const uint16_t *a2, const uint16_t *b2, const float *rfac, const uint32_t *flags, hipStream_t stream) {
-    using G = Geo<WN>;
-    const int nbm = (int)((M + BM - 1) / BM), nbn = (int)((Lv.N + G::BN - 1) / G::BN);
+struct Operands {       // what the pre-pass leaves in the workspace
+    const uint16_t *a2, *b2;
+    const float *rfac;
+    const uint32_t *flags;
+};
+
+template <int WN, int BITS>
+hipError_t launch_tile(const void *wt, bool pc, const uint16_t *x, int64_t M, int64_t K, int64_t N, void *y, bool out_f32,
+                       const RescalePlan &p, const Operands &o, hipStream_t stream) {
+    using G = Geo<WN, BITS>;
+    const int nbm = (int)((M + BM - 1) / BM), nbn = (int)((N + G::BN - 1) / G::BN);
     // XCD-aware tile order when the grid of tiles divides into regions of 8 patches of 4 x 8 tiles (see the kernel)
     int lg_xm = 2;
     while (lg_xm >= 0 && (nbm % (4 << lg_xm) != 0 || nbn % (8 * (8 >> lg_xm)) != 0)) --lg_xm;
@@ -651,20 +693,45 @@ hipError_t launch_tile(const LayerView &Lv, const uint16_t *x, int64_t M, void *
         hipError_t st = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                             (int)G::LDS_BYTES);
         if (st != hipSuccess) return st;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)(nbm * nbn)), dim3(G::THREADS), G::LDS_BYTES, stream, Lv.wt, rfac, x, a2, b2, flags,
-                           y, M, Lv.K, Lv.N, p.KP, nbn, lg_xm);
+        hipLaunchKernelGGL(kernel, dim3((unsigned)(nbm * nbn)), dim3(G::THREADS), G::LDS_BYTES, stream, wt, o.rfac, x, o.a2, o.b2,
+                           o.flags, y, M, K, N, p.KP, nbn, lg_xm);
         return hipGetLastError();
     };
-    const bool pc = Lv.szs == 0;
-    switch (env_int("DMR_RESCALE_DBG", 0)) {
-        case 1: return go(&gemm_w4_rescale_kernel<WN, false, false, 1>);
-        case 2: return go(&gemm_w4_rescale_kernel<WN, false, false, 2>);
-        case 4: return go(&gemm_w4_rescale_kernel<WN, false, false, 4>);
-        case 7: return go(&gemm_w4_rescale_kernel<WN, false, false, 7>);
-        default: break;
+    if constexpr (BITS == 4) {
+        switch (env_int("DMR_RESCALE_DBG", 0)) {
+            case 1: return go(&gemm_w4_rescale_kernel<WN, 4, false, false, 1>);
+            case 2: return go(&gemm_w4_rescale_kernel<WN, 4, false, false, 2>);
+            case 4: return go(&gemm_w4_rescale_kernel<WN, 4, false, false, 4>);
+            case 7: return go(&gemm_w4_rescale_kernel<WN, 4, false, false, 7>);
+            default: break;
+        }
+        if (pc) return out_f32 ? go(&gemm_w4_rescale_kernel<WN, 4, true, true, 0>) : go(&gemm_w4_rescale_kernel<WN, 4, false, true, 0>);
     }
-    return pc ? (out_f32 ? go(&gemm_w4_rescale_kernel<WN, true, true, 0>) : go(&gemm_w4_rescale_kernel<WN, false, true, 0>))
-              : (out_f32 ? go(&gemm_w4_rescale_kernel<WN, true, false, 0>) : go(&gemm_w4_rescale_kernel<WN, false, false, 0>));
+    return out_f32 ? go(&gemm_w4_rescale_kernel<WN, BITS, true, false, 0>) : go(&gemm_w4_rescale_kernel<WN, BITS, false, false, 0>);
+}
+
+// Pre-pass, then the rescaling kernel; the caller launches the 128 x 128 exact kernel behind them for the column blocks
+// the pre-pass flagged (normally none: its workgroups then return at once).
+template <int BITS>
+hipError_t launch_rescale(const void *wt, const uint32_t *sz, int szs, int64_t K, int64_t N, const uint16_t *x, int64_t M, void *y,
+                          bool out_f32, void *ws, const uint32_t **flags_out, bool *pairs_out, hipStream_t stream) {
+    const RescalePlan p = plan_rescale(M, K, N);
+    uint8_t *base = reinterpret_cast<uint8_t *>(ws);
+    uint16_t *a2 = reinterpret_cast<uint16_t *>(base + p.off_a2);
+    uint16_t *b2 = reinterpret_cast<uint16_t *>(base + p.off_b2);
+    float *rfac = reinterpret_cast<float *>(base + p.off_r);
+    uint32_t *flags = reinterpret_cast<uint32_t *>(base + p.off_flags);
+    const int nblocks = (int)((N + PRE_ROWS - 1) / PRE_ROWS), mblocks = (int)((M + 3) / 4);
+    hipLaunchKernelGGL(gemm_w4_rescale_prepass_kernel, dim3((unsigned)(nblocks + mblocks)), dim3(256), 0, stream, x, sz, szs, a2, b2,
+                       rfac, flags, M, K, N, p.KP, nblocks);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int wn = w4_gemm_rescale_wave_columns(M, N);
+    const Operands o{a2, b2, rfac, flags};
+    *flags_out = flags;
+    *pairs_out = wn == 4;
+    return wn == 4 ? launch_tile<4, BITS>(wt, szs == 0, x, M, K, N, y, out_f32, p, o, stream)
+                   : launch_tile<2, BITS>(wt, szs == 0, x, M, K, N, y, out_f32, p, o, stream);
 }
 
 }  // namespace
@@ -675,6 +742,7 @@ bool w4_gemm_rescale_applies(int64_t M, int64_t N) {
     return M >= env_int("DMR_W4_RESCALE_MIN_M", BM) && wgs <= 0x3FFFFFFF;
 }
 
+// (The rules hold for 3-bit layers as well: same tiles, same pipeline.)
 // Wave columns of the tile: 8 waves on 256 x 256 tiles from about 176 such tiles on (measured: ahead at 192 and 224
 // tiles, behind at 128), else 4 waves on 256 x 128.
 int w4_gemm_rescale_wave_columns(int64_t M, int64_t N) {
@@ -686,26 +754,22 @@ int w4_gemm_rescale_wave_columns(int64_t M, int64_t N) {
 
 size_t w4_gemm_rescale_workspace_bytes(int64_t M, int64_t K, int64_t N) { return plan_rescale(M, K, N).total; }
 
-// Pre-pass, the rescaling kernel, then the 128 x 128 exact kernel for the column blocks the pre-pass flagged
-// (normally none: its workgroups then return at once).
 hipError_t launch_w4_gemm_rescale(const LayerView &Lv, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
                                   hipStream_t stream) {
-    const RescalePlan p = plan_rescale(M, Lv.K, Lv.N);
-    uint8_t *base = reinterpret_cast<uint8_t *>(ws);
-    uint16_t *a2 = reinterpret_cast<uint16_t *>(base + p.off_a2);
-    uint16_t *b2 = reinterpret_cast<uint16_t *>(base + p.off_b2);
-    float *rfac = reinterpret_cast<float *>(base + p.off_r);
-    uint32_t *flags = reinterpret_cast<uint32_t *>(base + p.off_flags);
-    const int nblocks = (int)((Lv.N + PRE_ROWS - 1) / PRE_ROWS), mblocks = (int)((M + 3) / 4);
-    hipLaunchKernelGGL(gemm_w4_rescale_prepass_kernel, dim3((unsigned)(nblocks + mblocks)), dim3(256), 0, stream, x, Lv.sz, Lv.szs,
-                       a2, b2, rfac, flags, M, Lv.K, Lv.N, p.KP, nblocks);
-    hipError_t e = hipGetLastError();
+    const uint32_t *flags = nullptr;
+    bool pairs = false;
+    const hipError_t e = launch_rescale<4>(Lv.wt, Lv.sz, Lv.szs, Lv.K, Lv.N, x, M, y, out_f32, ws, &flags, &pairs, stream);
     if (e != hipSuccess) return e;
-    const int wn = w4_gemm_rescale_wave_columns(M, Lv.N);
-    e = wn == 4 ? launch_tile<4>(Lv, x, M, y, out_f32, p, a2, b2, rfac, flags, stream)
-                : launch_tile<2>(Lv, x, M, y, out_f32, p, a2, b2, rfac, flags, stream);
+    return launch_w4_gemm_flagged(Lv, x, M, y, out_f32, flags, pairs, stream);
+}
+
+hipError_t launch_w3_gemm_rescale(const LayerView3 &Lv, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
+                                  hipStream_t stream) {
+    const uint32_t *flags = nullptr;
+    bool pairs = false;
+    const hipError_t e = launch_rescale<3>(Lv.wt, Lv.sz, 1, Lv.K, Lv.N, x, M, y, out_f32, ws, &flags, &pairs, stream);
     if (e != hipSuccess) return e;
-    return launch_w4_gemm_flagged(Lv, x, M, y, out_f32, flags, wn == 4, stream);
+    return launch_w3_gemm_flagged(Lv, x, M, y, out_f32, flags, pairs, stream);
 }
 
 }  // namespace dmr

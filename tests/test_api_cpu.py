@@ -162,10 +162,14 @@ def test_w3_size_query_and_kernel_paths(lib):
     need = q3(1, 32768, 528)
     assert need > 0 and need % (528 * 4) == 0
     assert path(binding.DMR_FMT_W3_G128, 1, 4096, 4096) == b"w3_gemv"
-    # the rollout-batch sizes share the 4-bit plan; prefill sizes take the tiled kernel, which needs no scratch
+    # the rollout-batch sizes share the 4-bit plan; fewer than 256 rows on the tiled kernel need no scratch
     assert q3(64, 4096, 4096) == lib.dmr_qlinear_workspace_bytes(64, 4096, 4096)
-    assert q3(1200, 512, 4096) == 0
-    assert path(binding.DMR_FMT_W3_G128, 1200, 512, 4096) == b"w3_gemm128_exact"
+    assert q3(200, 256, 19200) == 0
+    assert path(binding.DMR_FMT_W3_G128, 200, 256, 19200) == b"w3_gemm128_exact"
+    # from 256 rows on the 256-row kernels, with the 4-bit kernels' workspace
+    assert path(binding.DMR_FMT_W3_G128, 1200, 512, 4096) == b"w3_gemm256x128_rescale"
+    assert path(binding.DMR_FMT_W3_G128, 8192, 4096, 28672) == b"w3_gemm256_rescale"
+    assert q3(1200, 512, 4096) == lib.dmr_qlinear_workspace_bytes(1200, 512, 4096) > 0
     # the kernel classes of the four decoder shapes at the sizes of the benchmark configurations
     assert path(binding.DMR_FMT_W4_G128, 1, 4096, 28672) == b"w4_gemv"
     assert path(binding.DMR_FMT_W4_G128, 8, 14336, 4096) == b"w4_panel"

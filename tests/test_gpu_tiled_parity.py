@@ -245,10 +245,16 @@ def test_prefill_config_cells_sampled(idx, M):
 
 # ------------------------------------------------------------------ 3-bit layers at prefill sizes
 
-@pytest.mark.parametrize("K,N,M", [(512, 4096, 1200), (256, 3840, 3584), (1152, 2192, 2200)])
-def test_w3_prefill_size(K, N, M):
-    assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W3_G128, M, K, N) == "w3_gemm128_exact"
-    assert dmr.dmr_qlinear_w3_workspace_bytes(M, K, N) == 0
+@pytest.mark.parametrize("K,N,M,path", [
+    (512, 4096, 1200, "w3_gemm256x128_rescale"),
+    (1152, 2192, 2200, "w3_gemm256x128_rescale"),    # nine groups, ragged in both directions
+    (256, 3840, 3584, "w3_gemm256_rescale"),
+    (1152, 3856, 3500, "w3_gemm256_rescale"),
+    (256, 19200, 200, "w3_gemm128_exact"),           # fewer than 256 rows on a very wide layer
+])
+def test_w3_prefill_size(K, N, M, path):
+    assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W3_G128, M, K, N) == path
+    assert (dmr.dmr_qlinear_w3_workspace_bytes(M, K, N) > 0) == path.endswith("_rescale")
     _, words, s, z = quantized3(8500 + K + N, N, K)
     x = synth.activations_bf16(8501 + K + M, M, K)
     layer = dmr.dmr_qlinear_w3_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
@@ -257,20 +263,46 @@ def test_w3_prefill_size(K, N, M):
     y16 = bits_host(dmr.dmr_qlinear_forward(layer, xd, out_dtype=torch.bfloat16))
     y_ref, _ = orc.forward3(words, s, z, G, x, threads=THREADS)
     err = rel_err(y32, y_ref)
-    print(f"w3 prefill ({K},{N}) M={M}: max err {err:.3e} rms, all {M * N} outputs")
+    print(f"{path} ({K},{N}) M={M}: max err {err:.3e} rms, all {M * N} outputs")
     assert err <= 1e-4                      # exact codes: only fp32 accumulation is left
     assert np.array_equal(y16, orc.f32_to_bf16(y32))
 
 
-def test_w3_one_hot_rows_through_the_tiled_gemm():
-    K, N = 2304, 2304
-    assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W3_G128, K, K, N) == "w3_gemm128_exact"
+def test_w3_one_hot_rows_through_the_tiled_gemms():
+    # as for 4 bits: bit for bit on the 128 x 128 kernel, to a few fp32 roundings on the 256-row kernels
+    K, N, M = 256, 19200, 200
+    assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W3_G128, M, K, N) == "w3_gemm128_exact"
     _, words, s, z = quantized3(8550, N, K)
     layer = dmr.dmr_qlinear_w3_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
-    y16 = dmr.dmr_qlinear_forward(layer, torch.eye(K, dtype=torch.bfloat16, device=DEV), out_dtype=torch.bfloat16)
+    x = torch.eye(K, dtype=torch.bfloat16, device=DEV)[:M].contiguous()
+    y16 = dmr.dmr_qlinear_forward(layer, x, out_dtype=torch.bfloat16)
     wq = dmr.dmr_qlinear_dequantize(layer)
-    assert torch.equal(y16.view(torch.int16), wq.t().contiguous().view(torch.int16))
+    assert torch.equal(y16.view(torch.int16), wq.t()[:M].contiguous().view(torch.int16))
     assert np.array_equal(bits_host(wq), orc.dequantize3(words, s, z, G))
+    K, N = 2304, 2304
+    assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W3_G128, K, K, N) == "w3_gemm256x128_rescale"
+    _, words, s, z = quantized3(8551, N, K)
+    layer = dmr.dmr_qlinear_w3_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
+    y32 = dmr.dmr_qlinear_forward(layer, torch.eye(K, dtype=torch.bfloat16, device=DEV), out_dtype=torch.float32)
+    exact = orc.dequantize_exact3(words, s, z, G)
+    scale = np.repeat(orc.bf16_to_f64(s), G, axis=1)
+    dev = np.abs(y32.cpu().numpy().astype(np.float64).T - exact) / (23.0 * np.abs(scale))
+    assert dev.max() <= 2e-5
+
+
+def test_w3_tiled_gemm_scales_that_cannot_be_rescaled():
+    K, N, M = 1152, 2192, 2200
+    _, words, s, z = quantized3(8560, N, K)
+    x = synth.activations_bf16(8561, M, K)
+    s2 = s.copy()
+    s2[200, 3] = 0x0000
+    s2[1500, 1] = 0x5000
+    layer = dmr.dmr_qlinear_w3_create(u32_dev(words), bf16_dev(s2), bf16_dev(z), G)
+    y32 = dmr.dmr_qlinear_forward(layer, bf16_dev(x), out_dtype=torch.float32).cpu().numpy()
+    y_ref, _ = orc.forward3(words, s2, z, G, x, threads=THREADS)
+    rms_col = np.sqrt(np.mean(y_ref ** 2, axis=0))
+    err = np.max(np.abs(y32.astype(np.float64) - y_ref) / np.maximum(rms_col, 1e-30))
+    assert np.all(np.isfinite(y32)) and err <= 1e-4
 
 
 # ------------------------------------------------------------------ decode rows too long for the M = 1 kernels
