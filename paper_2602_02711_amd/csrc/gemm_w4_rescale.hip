@@ -157,7 +157,7 @@ __device__ __forceinline__ void mfma_all(const Frag (&a)[TM], const Frag (&b)[TN
 // (the accumulator is zero when group 0 starts, so that slot is free), 1 in the slot behind the last group.
 // a2 / b2: bf16 [M][KP] / [N][KP].  flags: one word per 32 columns, nonzero = those columns do not qualify; a tile
 // with a flagged part is left to the other kernel as a whole.
-template <int WN, int BITS, bool OUT_F32, bool PC, int DBG>
+template <int WN, int BITS, bool OUT_F32, bool PC>
 __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale_kernel(
     const void *__restrict__ wt, const float *__restrict__ rfac, const uint16_t *__restrict__ x, const uint16_t *__restrict__ a2,
     const uint16_t *__restrict__ b2, const uint32_t *__restrict__ flags, void *__restrict__ y, int64_t M, int64_t K, int64_t N,
@@ -298,7 +298,7 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
     // to rescale, and that 1 comes from memory: a uniform branch around the multiplies makes the compiler spill the
     // accumulators, and a select against the constant 1 is turned into such a branch.)
     const int scol = wn * 32 * TN + (lane & 31);
-    constexpr bool RESCALE = !PC && !(DBG & 2);
+    constexpr bool RESCALE = !PC;
     auto mul_half = [&](int t, int h, const float (&f)[TN]) {
         const int i = t / TN, j = t % TN;
 #pragma unroll
@@ -324,8 +324,8 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
                 read_factors(raw + RAW_W_BYTES, lds, scol, rf);
             }
             load_frags(cur, cur + A_BYTES, 1, fa[1], fb[1], lane, wm, wn);
-            __builtin_amdgcn_sched_barrier(0);
-            if (!(DBG & 1)) unpack((u + 1) & 3, (u + 1) & 3, 1);
+            if (u == 0 && RESCALE) __builtin_amdgcn_sched_barrier(0);
+            unpack((u + 1) & 3, (u + 1) & 3, 1);
             if (u == 0 && RESCALE) {
                 mfma_tile(0, fa[0], fb[0]);
                 mul_half(4, 0, rf);
@@ -362,6 +362,7 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
                 for (int t = 0; t < TM * TN; ++t) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
                     __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);      // its share of the VALU work
+                    __builtin_amdgcn_sched_group_barrier(0x080, 1, 0);      // ... and of the LDS accesses (fragments of sub-step 1)
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -377,7 +378,7 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
             __builtin_amdgcn_sched_barrier(0);
             // The codes of step kt + 2 landed before the barrier above and its stage's weight half was last
             // read two steps ago.  Unconditional (past the end it rewrites a stage nobody reads).
-            if (!(DBG & 1)) unpack((u + 2) & 3, (u + 2) & 3, 0);
+            unpack((u + 2) & 3, (u + 2) & 3, 0);
             if (u == 3 && RESCALE) {
                 // (scheduling fences, not groups: with groups the scheduler still moved all 64 multiplies behind
                 // the last MFMA)
@@ -436,7 +437,7 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
 
     // ---- second loop: the zero-point term, bf16 operands A2[m][.] and B2[n][.] over KP columns, both direct-to-LDS.
     // Same pipeline; wave v fills rows [16 LA v, ..) of A2's stage half and rows [16 LB v, ..) of B2's.
-    if (!(DBG & 4)) {
+    {
         const int steps2 = KP / BK;
         const uint16_t *gp[L2];
 #pragma unroll
@@ -698,16 +699,9 @@ hipError_t launch_tile(const void *wt, bool pc, const uint16_t *x, int64_t M, in
         return hipGetLastError();
     };
     if constexpr (BITS == 4) {
-        switch (env_int("DMR_RESCALE_DBG", 0)) {
-            case 1: return go(&gemm_w4_rescale_kernel<WN, 4, false, false, 1>);
-            case 2: return go(&gemm_w4_rescale_kernel<WN, 4, false, false, 2>);
-            case 4: return go(&gemm_w4_rescale_kernel<WN, 4, false, false, 4>);
-            case 7: return go(&gemm_w4_rescale_kernel<WN, 4, false, false, 7>);
-            default: break;
-        }
-        if (pc) return out_f32 ? go(&gemm_w4_rescale_kernel<WN, 4, true, true, 0>) : go(&gemm_w4_rescale_kernel<WN, 4, false, true, 0>);
+        if (pc) return out_f32 ? go(&gemm_w4_rescale_kernel<WN, 4, true, true>) : go(&gemm_w4_rescale_kernel<WN, 4, false, true>);
     }
-    return out_f32 ? go(&gemm_w4_rescale_kernel<WN, BITS, true, false, 0>) : go(&gemm_w4_rescale_kernel<WN, BITS, false, false, 0>);
+    return out_f32 ? go(&gemm_w4_rescale_kernel<WN, BITS, true, false>) : go(&gemm_w4_rescale_kernel<WN, BITS, false, false>);
 }
 
 // Pre-pass, then the rescaling kernel; the caller launches the 128 x 128 exact kernel behind them for the column blocks
