@@ -143,105 +143,108 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const void *__restrict__ w
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int64_t n0 = (int64_t)blockIdx.x * BN;
-    const int64_t m0 = (int64_t)blockIdx.y * BM;
-
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-
-    // exact INT4: per-group accumulators and this lane's two weight rows (one per n tile)
-    constexpr bool EXACT = SRC == kSrcW4Exact || SRC == kSrcW3Exact;
-    f32x16 grp[2][2];
-    if (EXACT) {
+    // row blocks blockIdx.y, blockIdx.y + gridDim.y, ...: one per workgroup in a full launch; the launch that only serves
+    // flagged column blocks uses a few workgroups per column block, so that the unflagged ones cost next to nothing
+    for (int64_t m0 = (int64_t)blockIdx.y * BM; m0 < M; m0 += (int64_t)gridDim.y * BM) {
+        f32x16 acc[2][2];
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) grp[a][b][r] = 0.f;
-    }
-    const int64_t groups = K / kGroup;
-    int64_t srow[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int64_t n = n0 + wn * 64 + j * 32 + (lane & 31);
-        const int64_t nc = n < N ? n : N - 1;                         // clamped: never stored
-        srow[j] = sz_index(nc / kTileRows, 0, groups, szs, (int)(nc % kTileRows));   // sz index of (row, G = 0)
-    }
+                for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    Prefetch<SRC> pre;
-    load_global<SRC>(pre, wsrc, sz, x, M, K, N, m0, n0, 0, tid, szs);
-    for (int64_t k0 = 0; k0 < K; k0 += BK) {
-        store_lds<SRC>(pre, As, Bs, tid);
-        __syncthreads();
-        if (k0 + BK < K) load_global<SRC>(pre, wsrc, sz, x, M, K, N, m0, n0, k0 + BK, tid, szs);
-        float gscale[2] = {0.f, 0.f};
-        const bool group_end = EXACT && ((k0 + BK) % kGroup == 0);
-        if (group_end) {
+        // exact INT4: per-group accumulators and this lane's two weight rows (one per n tile)
+        constexpr bool EXACT = SRC == kSrcW4Exact || SRC == kSrcW3Exact;
+        f32x16 grp[2][2];
+        if (EXACT) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                gscale[j] = __uint_as_float(sz[srow[j] + (k0 / kGroup) * kTileRows * szs] << 16);
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) grp[a][b][r] = 0.f;
         }
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            Frag a[2], b[2];
-            const int kk = ks * 16 + (lane >> 5) * 8;
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                a[i].u = *reinterpret_cast<const uint4 *>(As + (wm * 64 + i * 32 + (lane & 31)) * LDS_STRIDE + kk);
-                b[i].u = *reinterpret_cast<const uint4 *>(Bs + (wn * 64 + i * 32 + (lane & 31)) * LDS_STRIDE + kk);
-            }
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    if (EXACT)
-                        grp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, grp[i][j], 0, 0, 0);
-                    else
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, acc[i][j], 0, 0, 0);
-                }
-        }
-        if (group_end) {
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        acc[i][j][r] = fmaf(gscale[j], grp[i][j][r], acc[i][j][r]);
-                        grp[i][j][r] = 0.f;
-                    }
-        }
-        __syncthreads();
-    }
-
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
+        const int64_t groups = K / kGroup;
+        int64_t srow[2];
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int64_t n = n0 + wn * 64 + j * 32 + (lane & 31);
+            const int64_t nc = n < N ? n : N - 1;                         // clamped: never stored
+            srow[j] = sz_index(nc / kTileRows, 0, groups, szs, (int)(nc % kTileRows));   // sz index of (row, G = 0)
+        }
+
+        Prefetch<SRC> pre;
+        load_global<SRC>(pre, wsrc, sz, x, M, K, N, m0, n0, 0, tid, szs);
+        for (int64_t k0 = 0; k0 < K; k0 += BK) {
+            store_lds<SRC>(pre, As, Bs, tid);
+            __syncthreads();
+            if (k0 + BK < K) load_global<SRC>(pre, wsrc, sz, x, M, K, N, m0, n0, k0 + BK, tid, szs);
+            float gscale[2] = {0.f, 0.f};
+            const bool group_end = EXACT && ((k0 + BK) % kGroup == 0);
+            if (group_end) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (m < M && n < N) {
-                    if (OUT_F32)
-                        reinterpret_cast<float *>(y)[m * N + n] = acc[i][j][r];
-                    else
-                        reinterpret_cast<uint16_t *>(y)[m * N + n] = f32_to_bf16(acc[i][j][r]);
+                for (int j = 0; j < 2; ++j)
+                    gscale[j] = __uint_as_float(sz[srow[j] + (k0 / kGroup) * kTileRows * szs] << 16);
+            }
+#pragma unroll
+            for (int ks = 0; ks < BK / 16; ++ks) {
+                Frag a[2], b[2];
+                const int kk = ks * 16 + (lane >> 5) * 8;
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    a[i].u = *reinterpret_cast<const uint4 *>(As + (wm * 64 + i * 32 + (lane & 31)) * LDS_STRIDE + kk);
+                    b[i].u = *reinterpret_cast<const uint4 *>(Bs + (wn * 64 + i * 32 + (lane & 31)) * LDS_STRIDE + kk);
+                }
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        if (EXACT)
+                            grp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, grp[i][j], 0, 0, 0);
+                        else
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, acc[i][j], 0, 0, 0);
+                    }
+            }
+            if (group_end) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            acc[i][j][r] = fmaf(gscale[j], grp[i][j][r], acc[i][j][r]);
+                            grp[i][j][r] = 0.f;
+                        }
+            }
+            __syncthreads();
+        }
+
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int64_t n = n0 + wn * 64 + j * 32 + (lane & 31);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    if (m < M && n < N) {
+                        if (OUT_F32)
+                            reinterpret_cast<float *>(y)[m * N + n] = acc[i][j][r];
+                        else
+                            reinterpret_cast<uint16_t *>(y)[m * N + n] = f32_to_bf16(acc[i][j][r]);
+                    }
                 }
             }
-        }
+    }   // row blocks
 }
 
 template <int SRC>
 hipError_t launch(const void *wsrc, const uint32_t *sz, int szs, const uint16_t *x, int64_t M, int64_t K,
                   int64_t N, void *y, bool out_f32, hipStream_t stream, const uint32_t *only = nullptr,
                   bool only_pairs = false) {
-    const dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
+    const unsigned row_blocks = (unsigned)((M + BM - 1) / BM);
+    const dim3 grid((unsigned)((N + BN - 1) / BN), only ? (row_blocks < 4 ? row_blocks : 4) : row_blocks);
     if (out_f32)
         hipLaunchKernelGGL((gemm_kernel<SRC, true>), grid, dim3(256), 0, stream, wsrc, sz, x, y, M, K, N, szs, only,
                            (int)only_pairs);
