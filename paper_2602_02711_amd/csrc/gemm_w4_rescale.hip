@@ -79,12 +79,20 @@ __device__ __forceinline__ void bare_barrier() {
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 2) & 3); }
 
 // Thread (row = tid / 2, half h = tid % 2) owns words 2h, 2h + 1 of the row's k step.  One call turns the 8
-// codes of word 2h + t into the bf16 integers 16 + q, chunk 2h + t of the row's 64-byte slice.  Restrict
-// pointers so that the LDS accesses carry alias scopes (the wait-count pass then does not tie them to the
+// codes of word 2h + t into the bf16 integers 16 + q, chunk 2h + t of the row's 64-byte slice.  The call for t = 0
+// reads both words (one conflict-free 8-byte LDS read per lane; 4-byte reads at an 8-byte stride collide in pairs)
+// and leaves the second one in `held` for the call for t = 1, which always follows it before the next t = 0 call.
+// Restrict pointers so that the LDS accesses carry alias scopes (the wait-count pass then does not tie them to the
 // loads in flight).
-__device__ __forceinline__ void unpack_to_stage(const uint8_t *__restrict__ raw_w, uint8_t *__restrict__ Bs, int t, int tid) {
+__device__ __forceinline__ void unpack_to_stage(const uint8_t *__restrict__ raw_w, uint8_t *__restrict__ Bs, int t, int tid,
+                                                uint32_t &held) {
     const int row = tid >> 1, h = tid & 1;
-    const uint32_t w = *reinterpret_cast<const uint32_t *>(raw_w + row * 16 + h * 8 + t * 4);
+    uint32_t w = held;
+    if (t == 0) {
+        const uint2 both = *reinterpret_cast<const uint2 *>(raw_w + row * 16 + h * 8);
+        w = both.x;
+        held = both.y;
+    }
     // nibble -> mantissa bits [3, 7) of a bf16 with exponent 2^4: the value 16 + q (the decode kernels' 128 + q costs
     // one instruction less, but the running sums would carry an offset eight times larger into the cancellation
     // with the zero-point term)
@@ -249,9 +257,10 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
                                              (lds_void *)(slot + RAW_W_BYTES + part * 256), 4, 0, 0);
         }
     };
+    uint32_t held = 0;           // 4-bit: the second word of the k step whose first word was unpacked last
     auto unpack = [&](int slot_idx, int stage_idx, int t) {
         if constexpr (BITS == 4)
-            unpack_to_stage(raw + slot_idx * RAW_BYTES, lds + stage_idx * STAGE_BYTES + A_BYTES, t, tid);
+            unpack_to_stage(raw + slot_idx * RAW_BYTES, lds + stage_idx * STAGE_BYTES + A_BYTES, t, tid, held);
         else
             unpack3_to_stage(raw + slot_idx * RAW_BYTES, lds + stage_idx * STAGE_BYTES + A_BYTES, t, tid);
     };
