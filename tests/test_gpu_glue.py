@@ -99,6 +99,29 @@ def test_fused_forward_int4(pro, K, N, with_res, M):
     assert np.array_equal(y16, orc.f32_to_bf16(y32))          # bf16 output = one rounding of the same fp32 value
 
 
+@pytest.mark.parametrize("pro,with_res", [(dmr.DMR_PRO_RMSNORM, True), (dmr.DMR_PRO_SWIGLU, False)])
+def test_fused_forward_int4_at_a_prefill_size(pro, with_res):
+    # M large enough for the tiled kernel, whose own workspace (zero-point operands, rescale factors) sits behind the
+    # glue output and the fp32 result in the caller's workspace
+    K, N, M = 256, 2192, 2200
+    assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W4_G128, M, K, N) == "w4_gemm256x128_rescale"
+    _, words, s, z = quantized(8250 + K + N, N, K)
+    layer = dmr.dmr_qlinear_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
+    width = 2 * K if pro == dmr.DMR_PRO_SWIGLU else K
+    inp = synth.activations_bf16(8251 + K + M, M, width)
+    gm = gamma_bits(8252 + K, K)
+    res = synth.activations_bf16(8253 + N + M, M, N) if with_res else None
+    kw = dict(gamma=bf16_dev(gm) if pro == dmr.DMR_PRO_RMSNORM else None, eps=EPS,
+              residual=bf16_dev(res) if with_res else None)
+    y32 = dmr.dmr_qlinear_forward_fused(layer, pro, bf16_dev(inp), out_dtype=torch.float32, **kw).cpu().numpy()
+    y_ref = oracle_chain(pro, inp, gm, lambda xb: orc.forward(words, s, z, G, xb, threads=16)[0])
+    if with_res:
+        y_ref = y_ref + orc.bf16_to_f64(res)
+    err = rel_err(y32, y_ref)
+    print(f"fused int4 pro={pro} ({K},{N}) M={M} res={with_res}: max err {err:.3e} rms")
+    assert err <= TOL
+
+
 @pytest.mark.parametrize("M", [1, 8])
 @pytest.mark.parametrize("pro,K,N,with_res", CASES)
 def test_fused_kernels_match_unfused_composition(pro, K, N, with_res, M):
