@@ -78,8 +78,6 @@ CASES = [(dmr.DMR_PRO_RMSNORM, 4096, 6144, False), (dmr.DMR_PRO_RMSNORM, 4096, 4
 @pytest.mark.parametrize("M", [1, 5, 16, 40])
 @pytest.mark.parametrize("pro,K,N,with_res", CASES)
 def test_fused_forward_int4(pro, K, N, with_res, M):
-    if M > 5 and K * N > 4096 * 6144:
-        pytest.skip("oracle cost: the large shapes are checked at M <= 5")
     _, words, s, z = quantized(8200 + K + N, N, K)
     layer = dmr.dmr_qlinear_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
     width = 2 * K if pro == dmr.DMR_PRO_SWIGLU else K
@@ -150,8 +148,6 @@ def test_fused_kernels_match_unfused_composition(pro, K, N, with_res, M):
 @pytest.mark.parametrize("M", [1, 12])
 @pytest.mark.parametrize("pro,K,N,with_res", CASES)
 def test_fused_forward_bf16(pro, K, N, with_res, M):
-    if M > 1 and K * N > 4096 * 6144:
-        pytest.skip("oracle cost: the large shapes are checked at M = 1")
     w = synth.to_bf16_bits(synth.weights_f32(8400 + K + N, N, K))
     width = 2 * K if pro == dmr.DMR_PRO_SWIGLU else K
     inp = synth.activations_bf16(8401 + K + M, M, width)
