@@ -1,12 +1,16 @@
-// 256 x 256 tiles on eight wavefronts: the direct-to-LDS pipeline of the large-tile GEMM with two waves per SIMD.
+// 256 x 256 tiles on eight wavefronts: the direct-to-LDS pipeline of the tiled GEMMs with two waves per SIMD that take
+// turns at the matrix pipe.
 //
 // y[M][N] = x[M][K] . W[N][K]^T, bf16 operands, fp32 accumulation.  A workgroup of 8 wavefronts (2 x 4) owns a
 // 256 x 256 tile, every wave a 128 x 64 patch = 4 x 2 tiles of v_mfma_f32_32x32x16_bf16: 128 accumulator registers,
 // which together with the operand fragments fit the 256 registers a wave has at two waves per SIMD, so the
-// accumulators stay in ordinary vector registers.  While one wave of a SIMD waits (operand fragments from LDS, the
-// barrier of the k step), the other one's MFMAs keep the matrix pipe busy.  Data movement and LDS layout as in the
-// four-wave kernel: `global_load_lds_dwordx4`, four LDS stages of 32 k, rows of 64 bytes with the 16-byte chunks
-// XOR-swizzled, one bare barrier per k step, loads three to four steps ahead.
+// accumulators stay in ordinary vector registers.  The two waves of a SIMD alternate between a multiply phase (the 16
+// MFMAs of a k step, operands already in registers) and a fetch phase (the step's 12 fragment reads from LDS, the wave's
+// share of the global -> LDS loads), so that one of them always has MFMAs to issue: measured 3-9 % ahead of eight waves
+// that all run the same software pipeline, which in turn was 3-7 % ahead of four waves with 128 x 128 patches.
+// Data movement and LDS layout: `global_load_lds_dwordx4` (every lane names its own 16 global bytes, the wave's
+// 64 x 16 bytes land contiguously at a wave-uniform LDS address), four LDS stages of 32 k, rows of 64 bytes with the
+// 16-byte chunks XOR-swizzled on the global side, bare barriers, loads three to four steps ahead.
 #include "common.hpp"
 
 namespace dmr {
@@ -63,20 +67,24 @@ __device__ __forceinline__ void mfma_all(const Frag (&a)[TM], const Frag (&b)[TN
         for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, acc[i][j], 0, 0, 0);
 }
 
+// The two waves of a SIMD alternate roles.  Waves 0..3 (rows 0..127 of the tile) multiply step kt (16 MFMAs on fragments
+// already in registers, nothing to wait for) while waves 4..7 fetch their fragments of step kt from LDS and issue their
+// loads; then the roles swap.  Two barriers per k step, the same number on both paths.  A wave's fragments of a whole k
+// step (both sub-steps, 48 registers) live in registers from its fetch phase to its multiply phase.
 template <bool OUT_F32>
 __global__ __launch_bounds__(512) void gemm_w8_kernel(const uint16_t *__restrict__ w, const uint16_t *__restrict__ x,
-                                                      void *__restrict__ y, int64_t M, int64_t K, int64_t N, int nbn, int lg_xm) {
+                                                         void *__restrict__ y, int64_t M, int64_t K, int64_t N, int nbn, int lg_xm) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
+    const bool first = wm == 0;                      // role group: waves 0..3 multiply in the even phases
     int tm, tn;
-    if (lg_xm < 0) {            // plain order: column blocks fastest
+    if (lg_xm < 0) {
         tm = (int)blockIdx.x / nbn;
         tn = (int)blockIdx.x % nbn;
     } else {
-        // XCD-aware order (see the launcher): linear index -> (region, XCD, slot in the XCD's 4 x 8 patch)
         const int region = (int)blockIdx.x >> 8, r = (int)blockIdx.x & 255;
         const int xcd = r & 7, q = r >> 3;
         const int xn = 8 >> lg_xm;
@@ -88,7 +96,6 @@ __global__ __launch_bounds__(512) void gemm_w8_kernel(const uint16_t *__restrict
     const int64_t m0 = (int64_t)tm * BM;
     const int steps = (int)(K / BK);
 
-    // wave v fills rows [32 v, 32 v + 32) of each operand's stage half, 16 rows per instruction
     const uint16_t *gp[L];
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
@@ -103,8 +110,8 @@ __global__ __launch_bounds__(512) void gemm_w8_kernel(const uint16_t *__restrict
         gp[LA + i] = w + n * K + swz(row, lane & 3) * 8;
     }
     int at = 0;
-    auto issue = [&](int step, int stage_idx) {
-        uint8_t *stage = lds + stage_idx * STAGE_BYTES;
+    auto issue = [&](int step) {                       // this wave's share of a step's loads, into stage step % 4
+        uint8_t *stage = lds + (step & 3) * STAGE_BYTES;
         const int target = step < steps ? step : steps - 1;
         const int adv = (target - at) * BK;
         at = target;
@@ -128,38 +135,61 @@ __global__ __launch_bounds__(512) void gemm_w8_kernel(const uint16_t *__restrict
         for (int b = 0; b < TN; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-
-#pragma unroll
-    for (int j = 0; j < 4; ++j) issue(j, j);
-    wait_vmcnt<3 * L>();
-    bare_barrier();
     Frag fa[2][TM], fb[2][TN];
-    load_frags(lds, lds + A_BYTES, 0, fa[0], fb[0], lane, wm, wn);
-    for (int kt = 0; kt < steps; ++kt) {
-        const uint8_t *cur = lds + (kt & 3) * STAGE_BYTES;
-        const bool more = kt + 1 < steps;
-        // the fragment reads of sub-step 1 are spread over the MFMAs of sub-step 0 (one read behind each of the first
-        // six MFMAs: 3 % faster than all reads first)
-        load_frags(cur, cur + A_BYTES, 1, fa[1], fb[1], lane, wm, wn);
+    auto fetch = [&](int step) {
+        const uint8_t *st = lds + (step & 3) * STAGE_BYTES;
+        load_frags(st, st + A_BYTES, 0, fa[0], fb[0], lane, wm, wn);
+        load_frags(st, st + A_BYTES, 1, fa[1], fb[1], lane, wm, wn);
+    };
+    auto multiply = [&]() {        // (raising the wave's priority around this block measured 1-2 % slower)
         mfma_all(fa[0], fb[0], acc);
-#pragma unroll
-        for (int t = 0; t < TM + TN; ++t) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - TM - TN, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (more) {
-            wait_vmcnt<2 * L>();
-            bare_barrier();
-            const uint8_t *nxt = lds + ((kt + 1) & 3) * STAGE_BYTES;
-            load_frags(nxt, nxt + A_BYTES, 0, fa[0], fb[0], lane, wm, wn);
-            __builtin_amdgcn_sched_barrier(0);
-            issue(kt + 4, kt & 3);
-        }
-        __builtin_amdgcn_sched_barrier(0);
         mfma_all(fa[1], fb[1], acc);
-        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // Prologue.  Every wave issues its shares of steps 0..2, the first group also of step 3 (in the loop the first group
+    // issues step kt + 4 in the odd phase, the second group step kt + 3 in the even phase).
+    issue(0);
+    issue(1);
+    issue(2);
+    if (first) {
+        issue(3);
+        wait_vmcnt<3 * L>();       // step 0 landed
+    } else {
+        wait_vmcnt<2 * L>();
+    }
+    bare_barrier();
+    if (first) fetch(0);
+    wait_vmcnt<3 * L>();           // own LDS reads done (the load count is already satisfied)
+    bare_barrier();
+
+    // Two loops, one per role group, with the same number of barriers (two per k step): a single loop with the roles
+    // behind branches makes the compiler spill the accumulators at the joins.
+    if (first) {
+        for (int kt = 0; kt < steps; ++kt) {
+            multiply();                // even phase: step kt
+            __builtin_amdgcn_sched_barrier(0);
+            wait_vmcnt<2 * L>();       // shares of step kt + 1 landed (two younger shares may be in flight)
+            bare_barrier();
+            fetch(kt + 1);             // odd phase (past the end: the clamped stage, never used)
+            __builtin_amdgcn_sched_barrier(0);
+            issue(kt + 4);
+            __builtin_amdgcn_sched_barrier(0);
+            wait_vmcnt<3 * L>();       // own LDS reads done; no new share is needed yet
+            bare_barrier();
+        }
+    } else {
+        for (int kt = 0; kt < steps; ++kt) {
+            fetch(kt);                 // even phase
+            __builtin_amdgcn_sched_barrier(0);
+            issue(kt + 3);
+            __builtin_amdgcn_sched_barrier(0);
+            wait_vmcnt<2 * L>();       // shares of step kt + 1 landed, own LDS reads done
+            bare_barrier();
+            multiply();                // odd phase: step kt
+            __builtin_amdgcn_sched_barrier(0);
+            wait_vmcnt<3 * L>();
+            bare_barrier();
+        }
     }
     wait_vmcnt<0>();
 
