@@ -112,6 +112,20 @@ def test_forward_and_friends_reject_bad_arguments(lib):
     assert qz(1024, 8, 128, FAKE, FAKE, FAKE, FAKE, None) == binding.DMR_ERR_SHAPE
 
 
+def test_measurement_aids_reject_bad_arguments(lib):
+    # both probes check everything before their first HIP call
+    pe = lib.dmr_probe_empty_launch
+    for blocks, threads, lds in ((0, 256, 0), (1 << 21, 256, 0), (256, 0, 0), (256, 100, 0), (256, 2048, 0), (256, 256, 65 * 1024)):
+        assert pe(blocks, threads, lds, None) == binding.DMR_ERR_SHAPE
+    pr = lib.dmr_probe_hbm_read
+    assert pr(None, 1 << 20, FAKE, 256, None) == binding.DMR_ERR_NULL
+    assert pr(FAKE, 1 << 20, None, 256, None) == binding.DMR_ERR_NULL
+    assert pr(FAKE, 0, FAKE, 256, None) == binding.DMR_ERR_SHAPE
+    assert pr(FAKE, (1 << 20) + 8, FAKE, 256, None) == binding.DMR_ERR_SHAPE
+    assert pr(FAKE, 1 << 20, FAKE, 0, None) == binding.DMR_ERR_SHAPE
+    assert pr(FAKE + 4, 1 << 20, FAKE, 256, None) == binding.DMR_ERR_ALIGN
+
+
 def test_glue_and_fused_forwards_reject_bad_arguments(lib):
     rn, sw = lib.dmr_glue_rmsnorm, lib.dmr_glue_swiglu
     assert rn(FAKE, FAKE, 1e-6, 1, 1001, FAKE, None) == binding.DMR_ERR_SHAPE          # K not a multiple of 8
