@@ -149,6 +149,21 @@ def test_int4_one_hot_rows_through_the_tiled_gemms():
         assert dev.max() <= 2e-5, path
 
 
+def test_int4_tiled_gemm_very_long_rows_sampled():
+    # K = 32768: 256 groups, i.e. 255 rescales of the running sum and a zero-point loop of 48 k steps; N = 528 leaves the
+    # last column tile mostly empty
+    K, N, M = 32768, 528, 8192
+    assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W4_G128, M, K, N) == "w4_gemm256x128_rescale"
+    _, words, s, z = quantized(8350, N, K)
+    x = synth.activations_bf16(8351, M, K)
+    layer = dmr.dmr_qlinear_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
+    y32 = dmr.dmr_qlinear_forward(layer, bf16_dev(x), out_dtype=torch.float32)
+    ms, ns = sample_pairs(M, N, 8352)
+    err = sampled_err(y32, ms, ns, orc.forward_sampled(words, s, z, G, x, ms, ns))
+    print(f"w4_gemm256x128_rescale ({K},{N}) M={M}: sampled max err {err:.3e} rms over {len(ms)} outputs")
+    assert err <= 1e-4
+
+
 def _scales_with(s, rows_groups, bits):
     out = s.copy()
     for (n, g) in rows_groups:
