@@ -63,7 +63,7 @@ size_t dmr_qlinear_storage_bytes(int64_t K, int64_t N, int32_t g);
  * (d_ws); may be 0, and then d_ws may be NULL.  Non-zero for batches of rollouts (a few to a few
  * hundred rows): either the activations re-ordered once per call, or fp32 partial sums when K is
  * split over workgroups because M x N alone would leave most of the chip idle.  Non-zero also for the
- * 4-bit tiled path from 256 rows on (prefill): per call it keeps there the operands of the zero-point
+ * 4-bit and 3-bit tiled path (prefill, and more than 128 rows on very wide layers): per call it keeps there the operands of the zero-point
  * term (bf16, 12 (M + N) K / 128 bytes), one fp32 factor per (row, group) and a few flags.  The
  * workspace may arrive uninitialised; its contents are undefined after the call. */
 size_t dmr_qlinear_workspace_bytes(int64_t M, int64_t K, int64_t N);

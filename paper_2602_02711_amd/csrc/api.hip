@@ -307,7 +307,8 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
     if (path == W4Path::Skinny2) return hip_status(dmr::launch_w4_skinny2(L, d_x, M, d_y, f32, d_ws, s));
     if (M <= kSkinnyMaxM) return hip_status(dmr::launch_w4_skinny(L, d_x, M, d_y, f32, s));
     if (path == W4Path::GemmRescale) return hip_status(dmr::launch_w4_gemm_rescale(L, d_x, M, d_y, f32, d_ws, s));
-    // Fewer than 256 rows on a very wide layer: 128 x 128 tiles on the exact integer codes q - z, the group's scale
+    // Not reached with the present crossovers (the rescaling kernel takes every tiled shape and calls this kernel
+    // itself for the column blocks it declines): 128 x 128 tiles on the exact integer codes q - z, the group's scale
     // applied to the group's partial sums in fp32.  (No tiled kernel rounds the weights to bf16 on their way into
     // LDS, what dmr_qlinear_dequantize returns: that leaves an error of about 1.7e-3 rms(y) standard deviation per
     // output, so that the largest of 10^7 .. 10^8 outputs lands at 0.8 .. 1.1 times the 1e-2 rms bound.)

@@ -45,10 +45,10 @@ def test_size_queries(lib):
     assert lib.dmr_qlinear_workspace_bytes(17, 4096, 4096) == 4 * 17 * 4096 * 4
     assert lib.dmr_qlinear_workspace_bytes(65, 4096, 4096) == 4 * 65 * 4096 * 4
     assert lib.dmr_qlinear_workspace_bytes(8, 14336, 4096) == 4 * 8 * 4096 * 4    # rows exceed LDS: four k slices
-    # enough column blocks: no split; fewer than 256 rows on the tiled GEMM: the 128 x 128 kernel needs nothing
+    # enough column blocks: no split
     assert lib.dmr_qlinear_workspace_bytes(128, 4096, 28672) == 0
-    assert lib.dmr_qlinear_workspace_bytes(200, 4096, 28672) == 0
-    # from 256 rows on: the zero-point operands, rescale factors and flags of the 256-row kernels
+    # the tiled GEMM (more than 128 rows here): zero-point operands, rescale factors and flags
+    assert lib.dmr_qlinear_workspace_bytes(200, 4096, 28672) > 200 * 192 * 2 + 28672 * 192 * 2
     assert lib.dmr_qlinear_workspace_bytes(600, 4096, 28672) > 600 * 192 * 2 + 28672 * 192 * 2
     # the bf16 twin splits K under the same rule
     assert lib.dmr_qlinear_bf16_workspace_bytes(1, 4096, 4096) == 0
@@ -176,11 +176,10 @@ def test_w3_size_query_and_kernel_paths(lib):
     need = q3(1, 32768, 528)
     assert need > 0 and need % (528 * 4) == 0
     assert path(binding.DMR_FMT_W3_G128, 1, 4096, 4096) == b"w3_gemv"
-    # the rollout-batch sizes share the 4-bit plan; fewer than 256 rows on the tiled kernel need no scratch
+    # the rollout-batch sizes share the 4-bit plan
     assert q3(64, 4096, 4096) == lib.dmr_qlinear_workspace_bytes(64, 4096, 4096)
-    assert q3(200, 256, 19200) == 0
-    assert path(binding.DMR_FMT_W3_G128, 200, 256, 19200) == b"w3_gemm128_exact"
-    # from 256 rows on the 256-row kernels, with the 4-bit kernels' workspace
+    # the tiled kernels, with the 4-bit kernels' workspace
+    assert path(binding.DMR_FMT_W3_G128, 200, 256, 19200) == b"w3_gemm256x128_rescale"
     assert path(binding.DMR_FMT_W3_G128, 1200, 512, 4096) == b"w3_gemm256x128_rescale"
     assert path(binding.DMR_FMT_W3_G128, 8192, 4096, 28672) == b"w3_gemm256_rescale"
     assert q3(1200, 512, 4096) == lib.dmr_qlinear_workspace_bytes(1200, 512, 4096) > 0
@@ -192,13 +191,13 @@ def test_w3_size_query_and_kernel_paths(lib):
     assert path(binding.DMR_FMT_W4_G128, 8192, 4096, 28672) == b"w4_gemm256_rescale"
     assert path(binding.DMR_FMT_W4_G128, 2048, 4096, 4096) == b"w4_gemm256x128_rescale"     # 128 tiles of 256 x 256 only
     assert path(binding.DMR_FMT_W4_PER_CHANNEL, 6400, 512, 1024) == b"w4_gemm256x128_rescale"
-    assert path(binding.DMR_FMT_W4_G128, 200, 256, 19200) == b"w4_gemm128_exact"            # fewer than 256 rows
+    assert path(binding.DMR_FMT_W4_G128, 200, 256, 19200) == b"w4_gemm256x128_rescale"      # a half-empty row tile
     # the 256-row kernels keep their zero-point operands, rescale factors and flags in the workspace
     G_n, KP = 4096 // 128, 192
     need = lib.dmr_qlinear_workspace_bytes(8192, 4096, 28672)
     assert need >= 8192 * KP * 2 + 28672 * KP * 2 + 28672 * (G_n + 1) * 4 + (28672 // 32) * 4
     assert need <= 1.01 * (8192 * KP * 2 + 28672 * KP * 2 + 28672 * (G_n + 1) * 4 + (28672 // 32) * 4) + 2048
-    assert lib.dmr_qlinear_workspace_bytes(200, 256, 19200) == 0
+    assert lib.dmr_qlinear_workspace_bytes(200, 256, 19200) > 0
     assert path(binding.DMR_FMT_W4_G128, 1, 32768, 528) == b"w4_skinny"
     assert path(binding.DMR_FMT_BF16, 1, 32768, 528) == b"bf16_skinny"
     assert path(binding.DMR_FMT_BF16, 512, 4096, 4096) == b"bf16_mid"          # exactly 128 workgroups: not tiled yet

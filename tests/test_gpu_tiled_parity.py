@@ -102,7 +102,7 @@ def test_bf16_tiled_gemms_small_integers_exact():
     (256, 2192, 2200, "w4_gemm256x128_rescale"),     # 9 x 18 tiles of 256 x 128 on four waves, two groups only
     (1152, 2192, 2200, "w4_gemm256x128_rescale"),    # the same grid, nine groups, ragged in both directions
     (128, 2192, 2200, "w4_gemm256x128_rescale"),     # a single group: nothing to rescale, the zero-point loop is one step
-    (256, 19200, 200, "w4_gemm128_exact"),           # fewer than 256 rows on a very wide layer: the 128 x 128 kernel
+    (256, 19200, 200, "w4_gemm256x128_rescale"),     # fewer than 256 rows on a very wide layer: a half-empty row tile
 ])
 def test_int4_tiled_gemm_full_output(K, N, M, path):
     assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W4_G128, M, K, N) == path
@@ -120,20 +120,29 @@ def test_int4_tiled_gemm_full_output(K, N, M, path):
     assert np.array_equal(y16, orc.f32_to_bf16(y32))
 
 
+def _one_zero_scale_per_32_rows(s):
+    """Scales with group 0 of every 32nd row set to zero: every block of 32 rows is flagged, so the whole output comes
+    from the 128 x 128 kernel that serves the blocks the rescaling kernel declines."""
+    out = s.copy()
+    out[::32, 0] = 0
+    return out
+
+
 def test_int4_one_hot_rows_through_the_tiled_gemms():
     # One-hot rows: output m, n is the single weight w^[n][m] = s (q - z).
-    # 128 x 128 kernel (200 rows of the identity): one exact fp32 product rounded once, so the bf16 output must equal
-    # dmr_qlinear_dequantize bit for bit.
+    # 128 x 128 kernel (every column block flagged; 200 rows of the identity): one exact fp32 product rounded once, so
+    # the bf16 output must equal dmr_qlinear_dequantize bit for bit.
     K, N, M = 256, 19200, 200
-    assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W4_G128, M, K, N) == "w4_gemm128_exact"
     _, words, s, z = quantized(8400 + K, N, K)
+    s = _one_zero_scale_per_32_rows(s)
     layer = dmr.dmr_qlinear_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
     x = torch.eye(K, dtype=torch.bfloat16, device=DEV)[:M].contiguous()
     y16 = dmr.dmr_qlinear_forward(layer, x, out_dtype=torch.bfloat16)
     wq = dmr.dmr_qlinear_dequantize(layer)
-    assert torch.equal(y16.view(torch.int16), wq.t()[:M].contiguous().view(torch.int16))
+    # (compared as values: a zero scale dequantises (q - z) < 0 to -0, a sum that starts at +0 ends at +0)
+    assert torch.equal(y16, wq.t()[:M].contiguous())
     assert np.array_equal(bits_host(wq), orc.dequantize(words, s, z, G))
-    # 256-row kernels: the weight comes out as s_last (prod of scale ratios) (16 + q) - s (16 + z), a handful of fp32
+    # rescaling kernels: the weight comes out as s_last (prod of scale ratios) (16 + q) - s (16 + z), a handful of fp32
     # roundings from s (q - z); each output is checked against the exact weight on its own, relative to the largest
     # term of that difference
     for K, N, path in [(2304, 2304, "w4_gemm256x128_rescale"), (3584, 3840, "w4_gemm256_rescale")]:
@@ -147,6 +156,20 @@ def test_int4_one_hot_rows_through_the_tiled_gemms():
         dev = np.abs(y32.cpu().numpy().astype(np.float64).T - exact) / (31.0 * np.abs(scale))
         print(f"{path} one-hot ({K},{N}): max deviation {dev.max():.3e} of the largest term")
         assert dev.max() <= 2e-5, path
+
+
+@pytest.mark.parametrize("K,N,M", [(1024, 3840, 3584), (1152, 2192, 1100)])
+def test_int4_128_tile_kernel_whole_output(K, N, M):
+    # the kernel with a per-group tile, reached through flags on every block of 32 rows, on its own merits
+    _, words, s, z = quantized(8300 + K + N, N, K)
+    s = _one_zero_scale_per_32_rows(s)
+    x = synth.activations_bf16(8301 + K + M, M, K)
+    layer = dmr.dmr_qlinear_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
+    y32 = dmr.dmr_qlinear_forward(layer, bf16_dev(x), out_dtype=torch.float32).cpu().numpy()
+    y_ref, _ = orc.forward(words, s, z, G, x, threads=THREADS)
+    err = rel_err(y32, y_ref)
+    print(f"128 x 128 exact kernel ({K},{N}) M={M}: max err {err:.3e} rms, all {M * N} outputs")
+    assert err <= 1e-4
 
 
 def test_int4_tiled_gemm_very_long_rows_sampled():
@@ -265,7 +288,7 @@ def test_prefill_config_cells_sampled(idx, M):
     (1152, 2192, 2200, "w3_gemm256x128_rescale"),    # nine groups, ragged in both directions
     (256, 3840, 3584, "w3_gemm256_rescale"),
     (1152, 3856, 3500, "w3_gemm256_rescale"),
-    (256, 19200, 200, "w3_gemm128_exact"),           # fewer than 256 rows on a very wide layer
+    (256, 19200, 200, "w3_gemm256x128_rescale"),     # fewer than 256 rows on a very wide layer: a half-empty row tile
 ])
 def test_w3_prefill_size(K, N, M, path):
     assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W3_G128, M, K, N) == path
@@ -284,15 +307,15 @@ def test_w3_prefill_size(K, N, M, path):
 
 
 def test_w3_one_hot_rows_through_the_tiled_gemms():
-    # as for 4 bits: bit for bit on the 128 x 128 kernel, to a few fp32 roundings on the 256-row kernels
+    # as for 4 bits: bit for bit on the 128 x 128 kernel (every block flagged), to a few fp32 roundings on the rescaling one
     K, N, M = 256, 19200, 200
-    assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W3_G128, M, K, N) == "w3_gemm128_exact"
     _, words, s, z = quantized3(8550, N, K)
+    s = _one_zero_scale_per_32_rows(s)
     layer = dmr.dmr_qlinear_w3_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
     x = torch.eye(K, dtype=torch.bfloat16, device=DEV)[:M].contiguous()
     y16 = dmr.dmr_qlinear_forward(layer, x, out_dtype=torch.bfloat16)
     wq = dmr.dmr_qlinear_dequantize(layer)
-    assert torch.equal(y16.view(torch.int16), wq.t()[:M].contiguous().view(torch.int16))
+    assert torch.equal(y16, wq.t()[:M].contiguous())
     assert np.array_equal(bits_host(wq), orc.dequantize3(words, s, z, G))
     K, N = 2304, 2304
     assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W3_G128, K, K, N) == "w3_gemm256x128_rescale"
@@ -303,6 +326,17 @@ def test_w3_one_hot_rows_through_the_tiled_gemms():
     scale = np.repeat(orc.bf16_to_f64(s), G, axis=1)
     dev = np.abs(y32.cpu().numpy().astype(np.float64).T - exact) / (23.0 * np.abs(scale))
     assert dev.max() <= 2e-5
+
+
+def test_w3_128_tile_kernel_whole_output():
+    K, N, M = 1152, 2192, 1100
+    _, words, s, z = quantized3(8570, N, K)
+    s = _one_zero_scale_per_32_rows(s)
+    x = synth.activations_bf16(8571, M, K)
+    layer = dmr.dmr_qlinear_w3_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
+    y32 = dmr.dmr_qlinear_forward(layer, bf16_dev(x), out_dtype=torch.float32).cpu().numpy()
+    y_ref, _ = orc.forward3(words, s, z, G, x, threads=THREADS)
+    assert rel_err(y32, y_ref) <= 1e-4
 
 
 def test_w3_tiled_gemm_scales_that_cannot_be_rescaled():
