@@ -103,6 +103,8 @@ def test_bf16_tiled_gemms_small_integers_exact():
     (1152, 2192, 2200, "w4_gemm256x128_rescale"),    # the same grid, nine groups, ragged in both directions
     (128, 2192, 2200, "w4_gemm256x128_rescale"),     # a single group: nothing to rescale, the zero-point loop is one step
     (256, 19200, 200, "w4_gemm256x128_rescale"),     # fewer than 256 rows on a very wide layer: a half-empty row tile
+    (128, 112, 40000, "w4_gemm256x128_rescale"),     # one column tile, not even full (7 row tiles of 16), 157 row blocks
+    (256, 272, 45100, "w4_gemm256_rescale"),         # two column tiles of 256, the second with 16 columns; ragged rows
 ])
 def test_int4_tiled_gemm_full_output(K, N, M, path):
     assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W4_G128, M, K, N) == path
