@@ -118,7 +118,8 @@ dmr_status_t dmr_qlinear_forward(const dmr_qlinear_t *layer, const uint16_t *d_x
  * dmr_qlinear_forward for callers that cannot allocate device memory and therefore cannot bring the
  * workspace: code running under HIP-graph capture, tight serving loops, harnesses that forbid hipMalloc.
  * Same arguments, results (bit for bit) and errors as dmr_qlinear_forward, minus d_ws / ws_bytes: the
- * scratch (fp32 partial sums of the kernels that split K, re-ordered activations) is a fixed array of
+ * scratch (fp32 partial sums of the kernels that split K, re-ordered activations, the tiled path's
+ * zero-point operands) is a fixed array of
  * DMR_STATIC_SCRATCH_BYTES in device memory that belongs to the library itself; each GPU the library runs
  * on holds one copy until the process ends.  The call allocates and frees nothing.  A shape whose
  * dmr_qlinear_workspace_bytes (dmr_qlinear_w3_workspace_bytes for a 3-bit layer) exceeds that size is
@@ -208,7 +209,8 @@ dmr_status_t dmr_qlinear_quantize(int64_t K, int64_t N, int32_t g, const float *
  * qweight3 uint32 [N][3K/32]; scales and zeros as for 4 bits, zero points 0..7.  The handle these
  * calls return is used with dmr_qlinear_dequantize / _forward / _destroy like a 4-bit one.  Every size class
  * runs native kernels that unpack the 3-bit codes in registers or on their way into LDS and keep them exact;
- * d_ws only holds fp32 partial sums where K is split, as dmr_qlinear_w3_workspace_bytes says.
+ * d_ws holds fp32 partial sums where K is split and, on the tiled path, the zero-point operands, factors
+ * and flags described at dmr_qlinear_workspace_bytes; dmr_qlinear_w3_workspace_bytes gives the size.
  */
 size_t dmr_qlinear_w3_storage_bytes(int64_t K, int64_t N, int32_t g);
 size_t dmr_qlinear_w3_workspace_bytes(int64_t M, int64_t K, int64_t N);

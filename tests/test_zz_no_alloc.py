@@ -28,6 +28,16 @@ def test_forward_static_matches_forward_on_consecutive_calls():
     _, w3, s3, z3 = quantized3(9702, 4096, 4096)
     calls.append((dmr.dmr_qlinear_w3_create(u32_dev(w3), bf16_dev(s3), bf16_dev(z3), G), 33))
     calls.append((layer, 1))
+    # the tiled path keeps its zero-point operands, factors and flags there: a layer with one zero scale (its
+    # 32 columns are flagged and go to the second kernel), then the clean layer, whose flags must read clear
+    Kt, Nt = 1024, 16384
+    _, wt, st, zt = quantized(9703, Nt, Kt)
+    sf = st.copy()
+    sf[70, 3] = 0
+    flagged = dmr.dmr_qlinear_create(u32_dev(wt), bf16_dev(sf), bf16_dev(zt), G)
+    clean = dmr.dmr_qlinear_create(u32_dev(wt), bf16_dev(st), bf16_dev(zt), G)
+    calls += [(flagged, 300), (clean, 260)]
+    assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W4_G128, 260, Kt, Nt).endswith("_rescale")
     xs = [bf16_dev(synth.activations_bf16(9710 + i, M, L.K)) for i, (L, M) in enumerate(calls)]
     outs = [torch.full((M, L.N), float("nan"), dtype=torch.float32, device=DEV) for L, M in calls]
     want = []
