@@ -747,13 +747,16 @@ bool w4_gemm_rescale_applies(int64_t M, int64_t N) {
 }
 
 // (The rules hold for 3-bit layers as well: same tiles, same pipeline.)
-// Wave columns of the tile: 8 waves on 256 x 256 tiles from about 176 such tiles on (measured: ahead at 192 and 224
-// tiles, behind at 128), else 4 waves on 256 x 128.
+// Wave columns of the tile.  Either tile's LDS use leaves one workgroup per CU, so a launch runs in rounds of 256
+// tiles; a round of 256 x 256 tiles (8 waves) takes about 1.5 times a round of 256 x 128 tiles (4 waves).  One round
+// of the narrow tiles is therefore the fastest where it covers the layer, and from there on the wide tiles, which
+// need half the rounds (measured on K = 4096: 288 narrow tiles 159 us against 144 wide ones 132 us; 256 narrow tiles
+// 90 us against 128 wide ones 125 us; level at 576 against 288).
 int w4_gemm_rescale_wave_columns(int64_t M, int64_t N) {
     const int forced = env_int("DMR_W4_RESCALE_WN", 0);
     if (forced == 2 || forced == 4) return forced;
-    const int64_t wgs = ((M + BM - 1) / BM) * ((N + 255) / 256);
-    return wgs >= 176 ? 4 : 2;
+    const int64_t narrow = ((M + BM - 1) / BM) * ((N + 127) / 128);
+    return narrow > compute_units() ? 4 : 2;
 }
 
 size_t w4_gemm_rescale_workspace_bytes(int64_t M, int64_t K, int64_t N) { return plan_rescale(M, K, N).total; }
