@@ -524,6 +524,454 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
         }
 }
 
+// ---- the same product with the weight operand kept out of LDS --------------------------------------------------------
+// The codes of a weight row are private to the waves that own its column: nothing has to be unpacked INTO a shared
+// stage.  Here the packed codes travel global -> LDS as they are (32 bytes per weight row and 64 k, one instruction per
+// wave and stage), every wave reads the 16 bytes of its own columns back and unpacks them in registers straight into
+// MFMA B operands, one word (8 codes, one operand) per MFMA k step.  LDS then carries per 64 k and workgroup 32 KiB of
+// activations once in and 16 fragment reads per wave out: two thirds of the fragment reads and half of the writes of
+// the kernel above (and of the bf16 twin), whose LDS port is as busy as its matrix cores.
+//
+// A stage is 64 k: lane half h of an MFMA operand takes the k step 2 v + h of the group's half v, word w of it in the
+// w-th MFMA of the stage, so that a lane's 16 code bytes are exactly its four B operands; the activation fragment of
+// that MFMA is 16-byte chunk 4 h + w of the row's 128-byte slice (chunks XOR-swizzled with bits 1..3 of the row number:
+// 16 consecutive rows then cover the 16 bank groups of 16 bytes).
+// Three stages of 32 KiB + the codes, requested two stages ahead; one bare barrier per stage, behind the third of its
+// four MFMA rounds.  The rescale factors of a wave's 64 columns come direct-to-LDS into a slot of the wave's own, one
+// instruction per group.  The zero-point loop and the store are those of the kernel above.
+constexpr int BK2 = 64, ROW2 = BK2 * 2, NS2 = 3;
+constexpr int A2S_BYTES = BM * ROW2;                           // 32 KiB
+
+template <int WN, int BITS>
+struct GeoR {
+    using G1 = Geo<WN, BITS>;
+    static constexpr int WAVES = G1::WAVES, THREADS = G1::THREADS, BN = G1::BN;
+    static constexpr int RAWB = BN * 32;                                   // two 16-byte units per weight row and stage
+    static constexpr int STAGE = A2S_BYTES + RAWB;                         // 40 or 36 KiB
+    static constexpr int FAC_OFF = NS2 * STAGE;                            // 256 bytes of factors per wave
+    static constexpr int MAIN_BYTES = FAC_OFF + WAVES * 256;
+    static constexpr int PH2_BYTES = NS * G1::STAGE_BYTES;                 // the zero-point loop's four stages of 32 k
+    static constexpr size_t LDS_BYTES = MAIN_BYTES > PH2_BYTES ? MAIN_BYTES : PH2_BYTES;   // 128 or 109 KiB
+    static constexpr int LA = A2S_BYTES / 1024 / WAVES;                    // activation load instructions per wave and stage
+    static constexpr int L = LA + 1;                                       // ... plus the codes
+    static_assert(BN / kTileRows == 2 * WAVES, "one code instruction (two row tiles) per wave");
+};
+
+// One word of a lane's codes -> the 8 bf16 values (16 + q) / 2 = 8 + q / 2 of an MFMA B operand: as in unpack_to_stage,
+// but with the exponent's lowest bit (the top bit of the low byte) left clear, which saves the OR; the factor 2 goes
+// into the last scale.
+__device__ __forceinline__ void unpack4_word(uint32_t w, Frag &f) {
+    const uint32_t even = (w << 3) & 0x78787878u;
+    const uint32_t odd = (w >> 1) & 0x78787878u;
+    const uint32_t exp = 0x41414141u;
+    f.w[0] = __builtin_amdgcn_perm(even, exp, 0x00060004u);
+    f.w[1] = __builtin_amdgcn_perm(odd, exp, 0x00060004u);
+    f.w[2] = __builtin_amdgcn_perm(even, exp, 0x00070005u);
+    f.w[3] = __builtin_amdgcn_perm(odd, exp, 0x00070005u);
+}
+
+// The 3-bit unit (three words; see unpack3_to_stage): chunk c < 3 is the two 3-bit fields of the bytes of word c,
+// chunk 3 the spare top bits of all three words.  Values (16 + q) / 2 as for four bits.
+__device__ __forceinline__ void unpack3_chunk(const u32x4_t &u, int c, Frag &f) {
+    const uint32_t exp = 0x41414141u, m38 = 0x38383838u;
+    const uint32_t sel_a = 0x00060004u, sel_b = 0x00070005u;
+    uint32_t f0, f1;
+    if (c < 3) {
+        const uint32_t v = u[c];
+        f0 = (v << 3) & m38;
+        f1 = v & m38;
+    } else {
+        f0 = (((u[2] >> 6) & 0x01010101u) << 5) | (((u[0] >> 6) & 0x03030303u) << 3);
+        f1 = (((u[2] >> 7) & 0x01010101u) << 5) | (((u[1] >> 6) & 0x03030303u) << 3);
+    }
+    f.w[0] = __builtin_amdgcn_perm(f0, exp, sel_a);
+    f.w[1] = __builtin_amdgcn_perm(f0, exp, sel_b);
+    f.w[2] = __builtin_amdgcn_perm(f1, exp, sel_a);
+    f.w[3] = __builtin_amdgcn_perm(f1, exp, sel_b);
+}
+
+// LDS reads through restrict pointers: the alias scopes they carry keep the wait-count pass from tying them to the
+// direct-to-LDS loads in flight, whose completion the kernel waits for explicitly.  (A scope only appears for a restrict
+// parameter that is used and has another one to be distinct from, and only survives on a load of a vector type; hence
+// two pointers into the same buffer.)
+__device__ __forceinline__ void read_a_frags(const uint8_t *__restrict__ p, const uint8_t *__restrict__ q, Frag (&a)[TM]) {
+    static_assert(TM == 4, "two tiles through each pointer");
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const u32x4_t lo = *reinterpret_cast<const u32x4_t *>(p + i * 32 * ROW2);
+        const u32x4_t hi = *reinterpret_cast<const u32x4_t *>(q + i * 32 * ROW2);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            a[i].w[c] = lo[c];
+            a[2 + i].w[c] = hi[c];
+        }
+    }
+}
+__device__ __forceinline__ void read_code_units(const uint8_t *__restrict__ p, const uint8_t *__restrict__ q, u32x4_t (&rw)[TN]) {
+    static_assert(TN == 2, "one unit through each pointer");
+    rw[0] = *reinterpret_cast<const u32x4_t *>(p);
+    rw[1] = *reinterpret_cast<const u32x4_t *>(q);
+}
+__device__ __forceinline__ void read_wave_factors(const uint8_t *__restrict__ p, const uint8_t *__restrict__ q, float (&rf)[TN]) {
+    rf[0] = *reinterpret_cast<const float *>(p);
+    rf[1] = *reinterpret_cast<const float *>(q);
+}
+
+template <int WN, int BITS, bool OUT_F32, bool PC>
+__global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_regb_kernel(
+    const void *__restrict__ wt, const float *__restrict__ rfac, const uint16_t *__restrict__ x, const uint16_t *__restrict__ a2,
+    const uint16_t *__restrict__ b2, const uint32_t *__restrict__ flags, void *__restrict__ y, int64_t M, int64_t K, int64_t N,
+    int KP, int nbn, int lg_xm) {
+    using G = Geo<WN, BITS>;
+    using R = GeoR<WN, BITS>;
+    constexpr int BN = G::BN, STAGE_BYTES = G::STAGE_BYTES;
+    constexpr int LA = G::LA, LB = G::LB, L2 = G::L2;
+    constexpr int RA = R::LA, RL = R::L, RSTAGE = R::STAGE;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    int tm, tn;
+    if (lg_xm < 0) {
+        tm = (int)blockIdx.x / nbn;
+        tn = (int)blockIdx.x % nbn;
+    } else {                    // XCD-aware order, as in the kernel above
+        const int region = (int)blockIdx.x >> 8, r = (int)blockIdx.x & 255;
+        const int xcd = r & 7, q = r >> 3;
+        const int xn = 8 >> lg_xm;
+        const int regions_n = nbn / (8 * xn);
+        tm = (region / regions_n) * (4 << lg_xm) + (xcd / xn) * 4 + (q >> 3);
+        tn = (region % regions_n) * 8 * xn + (xcd % xn) * 8 + (q & 7);
+    }
+    const int64_t n0 = (int64_t)tn * BN;
+    const int64_t m0 = (int64_t)tm * BM;
+    {
+        const int f0 = (int)(n0 / 32), nf = (int)((N + 31) / 32);
+        uint32_t fl = 0;
+#pragma unroll
+        for (int i = 0; i < BN / 32; ++i) fl |= f0 + i < nf ? flags[f0 + i] : 0u;
+        if (fl != 0) return;
+    }
+    const int groups = (int)(K / kGroup);
+    const int stages = groups * 2;
+
+    // ---- activations: wave v fills rows [8 RA v, 8 RA (v + 1)) of a stage, 8 rows of 128 bytes per instruction
+    const uint16_t *ga[RA];
+#pragma unroll
+    for (int i = 0; i < RA; ++i) {
+        const int row = wave * 8 * RA + i * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+        const int64_t m = m0 + row < M ? m0 + row : M - 1;
+        ga[i] = x + m * K + chunk * 8;
+    }
+    // ---- codes: the wave's two row tiles, lanes [32 v, 32 v + 32) of their block (k steps 2 v and 2 v + 1)
+    const int64_t tiles_n = N / kTileRows;
+    int64_t wT = n0 / kTileRows + 2 * wave + (lane >> 5);
+    if (wT >= tiles_n) wT = tiles_n - 1;
+    const int64_t unit0 = wT * groups * 64 + (lane & 31);
+    int at = 0;                  // the stage the activation pointers stand at
+    auto issue_stage = [&](int t, int off) {
+        const int target = t < stages ? t : stages - 1;        // past the end: the last stage again, never read
+        const int adv = (target - at) * BK2;
+        at = target;
+#pragma unroll
+        for (int i = 0; i < RA; ++i) {
+            ga[i] += adv;
+            __builtin_amdgcn_global_load_lds((global_void *)ga[i], (lds_void *)(lds + off + (wave * 8 * RA + i * 8) * ROW2), 16, 0, 0);
+        }
+        const int64_t unit = unit0 + (int64_t)(target >> 1) * 64 + (target & 1) * 32;
+        if constexpr (BITS == 4)
+            __builtin_amdgcn_global_load_lds((global_void *)(reinterpret_cast<const uint4 *>(wt) + unit),
+                                             (lds_void *)(lds + off + A2S_BYTES + wave * 1024), 16, 0, 0);
+        else   // 12 bytes per unit, fetched as 16
+            __builtin_amdgcn_global_load_lds((global_void *)(reinterpret_cast<const uint32_t *>(wt) + unit * 3),
+                                             (lds_void *)(lds + off + A2S_BYTES + wave * 1024), 16, 0, 0);
+    };
+    // ---- factors of the wave's 64 columns (lane = column), slot g + 1 of the table: s[g] / s[g + 1]
+    constexpr bool RESCALE = !PC;
+    const float *fptr;
+    {
+        int64_t n = n0 + wn * 32 * TN + lane;
+        if (n >= N) n = N - 1;
+        fptr = rfac + ((n / kTileRows) * (groups + 1)) * kTileRows + (n % kTileRows);
+    }
+    auto issue_factors = [&](int slot) {
+        __builtin_amdgcn_global_load_lds((global_void *)(fptr + (int64_t)slot * kTileRows), (lds_void *)(lds + R::FAC_OFF + wave * 256), 4,
+                                         0, 0);
+    };
+
+    // ---- what a lane reads back: its fragment addresses within a stage
+    const int arow = wm * 32 * TM + (lane & 31);
+    const int abase = arow * ROW2 + (((4 * (lane >> 5)) ^ ((lane >> 1) & 7)) * 16);    // MFMA round w: abase ^ (16 w)
+    const int rbase = A2S_BYTES + (wn * 4 + ((lane & 31) >> 4)) * 512 + (lane >> 5) * 256 + (lane & 15) * 16;
+    auto read_a = [&](int off, int w, Frag (&a)[TM]) { const uint8_t *p = lds + off + (abase ^ (w << 4));
+        read_a_frags(p, p + 2 * 32 * ROW2, a); };
+    auto read_raw = [&](int off, u32x4_t (&rw)[TN]) { read_code_units(lds + off + rbase, lds + off + rbase + 1024, rw); };
+    auto unpack_b = [&](const u32x4_t (&rw)[TN], int w, Frag (&b)[TN]) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            if constexpr (BITS == 4)
+                unpack4_word(rw[j][w], b[j]);
+            else
+                unpack3_chunk(rw[j], w, b[j]);
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+    auto mul_half = [&](int t, int h, const float (&f)[TN]) {
+        const int i = t / TN, j = t % TN;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) acc[i][j][8 * h + r] *= f[j];
+    };
+    auto mfma_tile = [&](int t, const Frag (&a)[TM], const Frag (&b)[TN]) {
+        const int i = t / TN, j = t % TN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, acc[i][j], 0, 0, 0);
+    };
+    // an MFMA round with the next round's fragment reads and unpack spread between its MFMAs
+    auto round_plain = [&](const Frag (&a)[TM], const Frag (&b)[TN]) {
+        mfma_all(a, b, acc);
+#pragma unroll
+        for (int t = 0; t < TM * TN; ++t) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+    };
+
+    // ---- prologue
+    int off_c = 0, off_n = RSTAGE, off_nn = 2 * RSTAGE;
+    issue_stage(0, off_c);
+    issue_stage(1, off_n);
+    issue_stage(2, off_nn);
+    wait_vmcnt<2 * RL>();
+    bare_barrier();
+    u32x4_t rw[TN];
+    Frag fa[2][TM], fb[2][TN];
+    read_raw(off_c, rw);
+    read_a(off_c, 0, fa[0]);
+    unpack_b(rw, 0, fb[0]);
+    float rf[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) rf[j] = 1.f;
+    const int fcol = R::FAC_OFF + wave * 256 + (lane & 31) * 4;
+
+    for (int g = 0; g < groups; ++g) {
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+            const int t = 2 * g + v;
+            // round 0
+            read_a(off_c, 1, fa[1]);
+            unpack_b(rw, 1, fb[1]);
+            if (v == 0 && RESCALE) {
+                // tiles 4..7 into the units of this group, ahead of their first MFMA (factor 1 in the first group)
+                mfma_tile(0, fa[0], fb[0]);
+                mul_half(4, 0, rf);
+                mfma_tile(1, fa[0], fb[0]);
+                mul_half(4, 1, rf);
+                mfma_tile(2, fa[0], fb[0]);
+                mul_half(5, 0, rf);
+                mfma_tile(3, fa[0], fb[0]);
+                mul_half(5, 1, rf);
+                mul_half(6, 0, rf);
+                mfma_tile(4, fa[0], fb[0]);
+                mul_half(6, 1, rf);
+                mul_half(7, 0, rf);
+                mfma_tile(5, fa[0], fb[0]);
+                mul_half(7, 1, rf);
+                mfma_tile(6, fa[0], fb[0]);
+                mfma_tile(7, fa[0], fb[0]);
+#pragma unroll
+                for (int q = 0; q < 3; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 11, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 19, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 19, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 11, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            } else {
+                round_plain(fa[0], fb[0]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // round 1
+            read_a(off_c, 2, fa[0]);
+            unpack_b(rw, 2, fb[0]);
+            round_plain(fa[1], fb[1]);
+            __builtin_amdgcn_sched_barrier(0);
+            // round 2
+            read_a(off_c, 3, fa[1]);
+            unpack_b(rw, 3, fb[1]);
+            round_plain(fa[0], fb[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            // stage t + 1 has landed (and, in the second half of a group, the factors to the next group); every wave
+            // has read its last fragments of stage t
+            wait_vmcnt<RL>();
+            if (v == 1 && RESCALE) read_wave_factors(lds + fcol, lds + fcol + 128, rf);   // the wave's own slot: no barrier needed
+            bare_barrier();
+            // round 3 starts at once; the requests for stage t + 3 and the first reads of stage t + 1 go between its MFMAs
+            mfma_tile(0, fa[1], fb[1]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (v == 0 && RESCALE) issue_factors(g + 1);
+            issue_stage(t + 3, off_c);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_tile(1, fa[1], fb[1]);
+            __builtin_amdgcn_sched_barrier(0);
+            read_raw(off_n, rw);
+            read_a(off_n, 0, fa[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_tile(2, fa[1], fb[1]);
+            if (v == 1 && RESCALE) {
+                // tiles 0..3 into the units of the next group, behind their last MFMA
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(0, 0, rf);
+                mfma_tile(3, fa[1], fb[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(0, 1, rf);
+                mfma_tile(4, fa[1], fb[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(1, 0, rf);
+                mfma_tile(5, fa[1], fb[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(1, 1, rf);
+                mfma_tile(6, fa[1], fb[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(2, 0, rf);
+                mfma_tile(7, fa[1], fb[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(2, 1, rf);
+                mul_half(3, 0, rf);
+                mul_half(3, 1, rf);
+                unpack_b(rw, 0, fb[0]);
+            } else {
+                __builtin_amdgcn_sched_barrier(0);
+                unpack_b(rw, 0, fb[0]);
+#pragma unroll
+                for (int q = 3; q < TM * TN; ++q) mfma_tile(q, fa[1], fb[1]);
+#pragma unroll
+                for (int q = 3; q < TM * TN; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const int o = off_c;
+            off_c = off_n;
+            off_n = off_nn;
+            off_nn = o;
+        }
+    }
+    wait_vmcnt<0>();
+    bare_barrier();
+
+    const int scol = wn * 32 * TN + (lane & 31);
+    {
+        float sl[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            int64_t n = n0 + scol + j * 32;
+            if (n >= N) n = N - 1;
+            sl[j] = 2.f * rfac[((n / kTileRows) * (groups + 1)) * kTileRows + (n % kTileRows)];   // the operands were (16 + q) / 2
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] *= sl[j];
+    }
+
+    // ---- the zero-point term: the second loop of the kernel above (stages of 32 k, both operands direct-to-LDS)
+    {
+        const int steps2 = KP / BK;
+        const uint16_t *gp[L2];
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            const int row = wave * 16 * LA + i * 16 + (lane >> 2);
+            const int64_t m = m0 + row < M ? m0 + row : M - 1;
+            gp[i] = a2 + m * KP + swz(row, lane & 3) * 8;
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            const int row = wave * 16 * LB + i * 16 + (lane >> 2);
+            const int64_t n = n0 + row < N ? n0 + row : N - 1;
+            gp[LA + i] = b2 + n * KP + swz(row, lane & 3) * 8;
+        }
+        int at2 = 0;
+        auto issue2 = [&](int step, int stage_idx) {
+            uint8_t *stage = lds + stage_idx * STAGE_BYTES;
+            const int target = step < steps2 ? step : steps2 - 1;
+            const int adv = (target - at2) * BK;
+            at2 = target;
+#pragma unroll
+            for (int i = 0; i < LA; ++i) {
+                gp[i] += adv;
+                __builtin_amdgcn_global_load_lds((global_void *)gp[i], (lds_void *)(stage + (wave * 16 * LA + i * 16) * ROW_BYTES),
+                                                 16, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < LB; ++i) {
+                gp[LA + i] += adv;
+                __builtin_amdgcn_global_load_lds((global_void *)gp[LA + i],
+                                                 (lds_void *)(stage + A_BYTES + (wave * 16 * LB + i * 16) * ROW_BYTES), 16, 0, 0);
+            }
+        };
+#pragma unroll
+        for (int j = 0; j < 4; ++j) issue2(j, j);
+        wait_vmcnt<3 * L2>();
+        bare_barrier();
+        load_frags(lds, lds + A_BYTES, 0, fa[0], fb[0], lane, wm, wn);
+        for (int kt = 0; kt < steps2; ++kt) {
+            const uint8_t *cur = lds + (kt & 3) * STAGE_BYTES;
+            const bool more = kt + 1 < steps2;
+            load_frags(cur, cur + A_BYTES, 1, fa[1], fb[1], lane, wm, wn);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_all(fa[0], fb[0], acc);
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) {
+                wait_vmcnt<2 * L2>();
+                bare_barrier();
+                const uint8_t *nxt = lds + ((kt + 1) & 3) * STAGE_BYTES;
+                load_frags(nxt, nxt + A_BYTES, 0, fa[0], fb[0], lane, wm, wn);
+                __builtin_amdgcn_sched_barrier(0);
+                issue2(kt + 4, kt & 3);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_all(fa[1], fb[1], acc);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        wait_vmcnt<0>();
+    }
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int64_t n = n0 + wn * 32 * TN + j * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t m = m0 + wm * 32 * TM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (m < M && n < N) {
+                    if (OUT_F32)
+                        reinterpret_cast<float *>(y)[m * N + n] = acc[i][j][r];
+                    else
+                        reinterpret_cast<uint16_t *>(y)[m * N + n] = f32_to_bf16(acc[i][j][r]);
+                }
+            }
+        }
+}
+
 // ---- pre-pass, activations ----------------------------------------------------------------------------------------
 // One wave per activation row; the fp32 sum X of each group of 128 activations (8 per lane in k order, then the 16
 // lanes of the group in a fixed rotate-and-add order), split into three bf16 terms X = X0 + X1 + X2, written to
@@ -695,22 +1143,28 @@ template <int WN, int BITS>
 hipError_t launch_tile(const void *wt, bool pc, const uint16_t *x, int64_t M, int64_t K, int64_t N, void *y, bool out_f32,
                        const RescalePlan &p, const Operands &o, hipStream_t stream) {
     using G = Geo<WN, BITS>;
+    using R = GeoR<WN, BITS>;
+    const bool regb = env_int("DMR_W4_RESCALE_REGB", 1) != 0;
     const int nbm = (int)((M + BM - 1) / BM), nbn = (int)((N + G::BN - 1) / G::BN);
     // XCD-aware tile order when the grid of tiles divides into regions of 8 patches of 4 x 8 tiles (see the kernel)
     int lg_xm = 2;
     while (lg_xm >= 0 && (nbm % (4 << lg_xm) != 0 || nbn % (8 * (8 >> lg_xm)) != 0)) --lg_xm;
-    auto go = [&](auto kernel) {
-        hipError_t st = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                            (int)G::LDS_BYTES);
+    auto go = [&](auto kernel, auto kernel_r) {
+        const void *fn = regb ? reinterpret_cast<const void *>(kernel_r) : reinterpret_cast<const void *>(kernel);
+        const size_t lds_bytes = regb ? R::LDS_BYTES : G::LDS_BYTES;
+        hipError_t st = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (st != hipSuccess) return st;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)(nbm * nbn)), dim3(G::THREADS), G::LDS_BYTES, stream, wt, o.rfac, x, o.a2, o.b2,
-                           o.flags, y, M, K, N, p.KP, nbn, lg_xm);
+        hipLaunchKernelGGL(regb ? kernel_r : kernel, dim3((unsigned)(nbm * nbn)), dim3(G::THREADS), lds_bytes, stream, wt, o.rfac, x,
+                           o.a2, o.b2, o.flags, y, M, K, N, p.KP, nbn, lg_xm);
         return hipGetLastError();
     };
     if constexpr (BITS == 4) {
-        if (pc) return out_f32 ? go(&gemm_w4_rescale_kernel<WN, 4, true, true>) : go(&gemm_w4_rescale_kernel<WN, 4, false, true>);
+        if (pc)
+            return out_f32 ? go(&gemm_w4_rescale_kernel<WN, 4, true, true>, &gemm_w4_regb_kernel<WN, 4, true, true>)
+                           : go(&gemm_w4_rescale_kernel<WN, 4, false, true>, &gemm_w4_regb_kernel<WN, 4, false, true>);
     }
-    return out_f32 ? go(&gemm_w4_rescale_kernel<WN, BITS, true, false>) : go(&gemm_w4_rescale_kernel<WN, BITS, false, false>);
+    return out_f32 ? go(&gemm_w4_rescale_kernel<WN, BITS, true, false>, &gemm_w4_regb_kernel<WN, BITS, true, false>)
+                   : go(&gemm_w4_rescale_kernel<WN, BITS, false, false>, &gemm_w4_regb_kernel<WN, BITS, false, false>);
 }
 
 // Pre-pass, then the rescaling kernel; the caller launches the 128 x 128 exact kernel behind them for the column blocks
