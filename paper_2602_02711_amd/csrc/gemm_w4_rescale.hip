@@ -1,15 +1,16 @@
-// Tiled MFMA GEMM for prefill-sized M on a 4-bit layer that never rounds a weight and keeps ONE accumulator tile.
+// Tiled MFMA GEMM for prefill-sized M on a 4-bit (or 3-bit) layer that never rounds a weight and keeps ONE accumulator tile.
 //
 //     y[m][n] = sum_G s[n][G] * ( sum_{k in G} x[m][k] (16 + q[n][k]) )  -  sum_G s[n][G] (16 + z[n][G]) X[m][G]
 //
 // with X[m][G] the sum of the activations of row m over group G.  The matrix cores multiply the activations
-// with the exact bf16 integers 16 + q (a magic-number unpack like the decode kernels': shifts, masks and
-// v_perm_b32 only, one VALU instruction per weight).  The group scale is not applied to a per-group tile: the
-// accumulator is kept in units of the CURRENT group's scale.  Between groups G and G + 1 every accumulator element
-// is multiplied by s[G] / s[G + 1] (one VALU multiply per element and group, in place), the MFMAs of the next group
-// add into it directly, and after the last group it is multiplied by the last scale.  No second tile and no fold:
-// 128 accumulator registers per wave, in ordinary vector registers (the kernel is compiled for two waves per SIMD,
-// i.e. at most 256 registers, which makes the compiler use the MFMA forms whose accumulator the VALU can address).
+// with exact bf16 values (16 + q) / 2 (a magic-number unpack like the decode kernels': shifts, masks and
+// v_perm_b32 only, one VALU instruction per weight; the factor 2 goes into the last scale).  The group scale is not
+// applied to a per-group tile: the accumulator is kept in units of the CURRENT group's scale.  Between groups G and
+// G + 1 every accumulator element is multiplied by s[G] / s[G + 1] (one VALU multiply per element and group, in place),
+// the MFMAs of the next group add into it directly, and after the last group it is multiplied by the last scale.  No
+// second tile and no fold: 128 accumulator registers per wave, in ordinary vector registers (the kernel is compiled
+// for two waves per SIMD, i.e. at most 256 registers, which makes the compiler use the MFMA forms whose accumulator
+// the VALU can address).
 //
 // The zero-point term is a product of rank K / 128.  A pre-pass splits the fp32 group sums X into three bf16
 // terms and the exact products c = -s (16 + z) into two, and lays them out as two plain bf16 matrices A2[M][KP],
@@ -22,40 +23,64 @@
 // kernel, launched behind this one with the same flags, computes those columns instead.
 //
 // Shape of the work.  Two instantiations: 8 wavefronts (2 x 4) on a 256 x 256 tile, two waves per SIMD, or 4
-// wavefronts (2 x 2) on a 256 x 128 tile for grids too small for the former.  Every wave owns a 128 x 64 patch =
-// 4 x 2 tiles of v_mfma_f32_32x32x16_bf16; 6 operand fragments feed 8 MFMAs.  Data movement as in the bf16 kernels:
-// activations travel global -> LDS without registers (`global_load_lds_dwordx4`), four LDS stages of 32 k, one
-// bare barrier per k step in the middle of the step, rows of 64 bytes with the 16-byte chunks XOR-swizzled.  The
-// packed codes (16 bytes per weight row and k step, fetched by the first half of the waves) and the rescale
-// factors (4 bytes per row, the other half) go direct-to-LDS into a ring of four slots, one step further ahead than
-// the activations; two threads per weight row read the codes back one step before they are multiplied and write
-// 16 + q into the stage.
+// wavefronts (2 x 2) on a 256 x 128 tile for grids that one round of those covers.  Every wave owns a 128 x 64 patch
+// = 4 x 2 tiles of v_mfma_f32_32x32x16_bf16.
+//
+// The weight operand never sits in LDS unpacked.  The codes of a weight row are private to the waves that own its
+// column, so nothing has to be unpacked INTO a shared stage: the packed codes travel global -> LDS as they are (32 bytes
+// per weight row and 64 k, one `global_load_lds_dwordx4` per wave and stage), every wave reads the 16 bytes of its own
+// columns back and unpacks them in registers straight into MFMA B operands, one word (8 codes, one operand) per MFMA
+// round.  LDS then carries, per 64 k and workgroup, 32 KiB of activations in (direct-to-LDS as well) and 16 fragment
+// reads per wave out: two thirds of the fragment reads and half of the writes of a kernel that stages both operands
+// (the bf16 twin; the first version of this one, which unpacked into the stage: 1740 -> 1530 us on gate+up at 8192
+// rows), whose LDS port is as busy as its matrix cores.
+//
+// A stage is 64 k = four MFMA rounds: lane half h of an MFMA operand takes the k step 2 v + h of the group's half v,
+// word w of it in round w, so that a lane's 16 code bytes are exactly its four B operands; the activation fragment of
+// that round is 16-byte chunk 4 h + w of the row's 128-byte slice (chunks XOR-swizzled with bits 1..3 of the row
+// number: 16 consecutive rows then cover the 16 bank groups of 16 bytes; swizzling with bits 0..2 measured 1.2e8
+// conflict cycles per launch, this none).  Three stages of 32 KiB + the codes, requested two stages ahead; one bare
+// barrier per stage, behind the third round, the fourth round's MFMAs starting at once with the next requests and the
+// first reads of the next stage between them.  The rescale factors of a wave's 64 columns come direct-to-LDS into a
+// slot of the wave's own, one instruction per group.  The zero-point loop runs on four stages of 32 k with both
+// operands direct-to-LDS (rows of 64 bytes, chunks swizzled with bits 2..3 of the row number).
 #include "common.hpp"
 
 namespace dmr {
 
 namespace {
 
-constexpr int BK = 32, NS = 4, NR = 4;
-constexpr int ROW_BYTES = BK * 2;                          // 64
 constexpr int TM = 4, TN = 2;                              // MFMA tiles per wave
 constexpr int WM = 2;                                      // wave rows per workgroup
 constexpr int BM = 32 * TM * WM;                           // 256
+// first loop: stages of 64 k, activations and packed codes
+constexpr int BK2 = 64, ROW2 = BK2 * 2, NS2 = 3;
+constexpr int A2S_BYTES = BM * ROW2;                       // 32 KiB
+// second loop (zero-point term): stages of 32 k, both operands as bf16
+constexpr int BK = 32, NS = 4;
+constexpr int ROW_BYTES = BK * 2;                          // 64
 constexpr int A_BYTES = BM * ROW_BYTES;                    // 16 KiB per stage
 
 template <int WN, int BITS>                                // wave columns per workgroup: 2 or 4; code width: 4 or 3
 struct Geo {
     static constexpr int WAVES = WM * WN, THREADS = 64 * WAVES;
     static constexpr int BN = 32 * TN * WN;                                // 128 or 256
+    // first loop
+    static constexpr int RAWB = BN * 32;                                   // two 16-byte units per weight row and stage
+    static constexpr int STAGE = A2S_BYTES + RAWB;                         // 40 or 36 KiB
+    static constexpr int FAC_OFF = NS2 * STAGE;                            // 256 bytes of factors per wave
+    static constexpr int MAIN_BYTES = FAC_OFF + WAVES * 256;
+    static constexpr int RA = A2S_BYTES / 1024 / WAVES;                    // activation load instructions per wave and stage
+    static constexpr int RL = RA + 1;                                      // ... plus the codes
+    static_assert(BN / kTileRows == 2 * WAVES, "one code instruction (two row tiles) per wave");
+    // second loop
     static constexpr int B_BYTES = BN * ROW_BYTES;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;                  // 24 or 32 KiB
-    static constexpr int RAW_W_BYTES = BN * 16, RAW_R_BYTES = BN * 4;      // per ring slot (3-bit rows use 12 of their 16 bytes)
-    static constexpr int RAW_BYTES = RAW_W_BYTES + RAW_R_BYTES;
-    static constexpr size_t LDS_BYTES = (size_t)NS * STAGE_BYTES + (size_t)NR * RAW_BYTES;   // 106 or 148 KiB
-    static constexpr int LA = BM / 16 / WAVES;                             // activation load instructions per wave and step
-    static constexpr int L1 = LA + 1;                                      // ... plus one of codes or factors
-    static constexpr int LB = BN / 16 / WAVES;                             // second loop: B2 instructions per wave (2)
+    static constexpr int PH2_BYTES = NS * STAGE_BYTES;
+    static constexpr int LA = BM / 16 / WAVES;                             // A2 load instructions per wave and step
+    static constexpr int LB = BN / 16 / WAVES;                             // B2 load instructions per wave and step (2)
     static constexpr int L2 = LA + LB;
+    static constexpr size_t LDS_BYTES = MAIN_BYTES > PH2_BYTES ? MAIN_BYTES : PH2_BYTES;   // 128 or 109 KiB
 };
 
 typedef __attribute__((address_space(3))) void lds_void;
@@ -78,67 +103,7 @@ __device__ __forceinline__ void bare_barrier() {
 
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 2) & 3); }
 
-// Thread (row = tid / 2, half h = tid % 2) owns words 2h, 2h + 1 of the row's k step.  One call turns the 8
-// codes of word 2h + t into the bf16 integers 16 + q, chunk 2h + t of the row's 64-byte slice.  The call for t = 0
-// reads both words (one conflict-free 8-byte LDS read per lane; 4-byte reads at an 8-byte stride collide in pairs)
-// and leaves the second one in `held` for the call for t = 1, which always follows it before the next t = 0 call.
-// Restrict pointers so that the LDS accesses carry alias scopes (the wait-count pass then does not tie them to the
-// loads in flight).
-__device__ __forceinline__ void unpack_to_stage(const uint8_t *__restrict__ raw_w, uint8_t *__restrict__ Bs, int t, int tid,
-                                                uint32_t &held) {
-    const int row = tid >> 1, h = tid & 1;
-    uint32_t w = held;
-    if (t == 0) {
-        const uint2 both = *reinterpret_cast<const uint2 *>(raw_w + row * 16 + h * 8);
-        w = both.x;
-        held = both.y;
-    }
-    // nibble -> mantissa bits [3, 7) of a bf16 with exponent 2^4: the value 16 + q (the decode kernels' 128 + q costs
-    // one instruction less, but the running sums would carry an offset eight times larger into the cancellation
-    // with the zero-point term)
-    const uint32_t even = ((w << 3) & 0x78787878u) | 0x80808080u;     // nibbles 0, 2, 4, 6 as low bytes
-    const uint32_t odd = ((w >> 1) & 0x78787878u) | 0x80808080u;      // nibbles 1, 3, 5, 7
-    const uint32_t exp = 0x41414141u;
-    const u32x4_t v = {__builtin_amdgcn_perm(even, exp, 0x00060004u), __builtin_amdgcn_perm(odd, exp, 0x00060004u),
-                       __builtin_amdgcn_perm(even, exp, 0x00070005u), __builtin_amdgcn_perm(odd, exp, 0x00070005u)};
-    *reinterpret_cast<u32x4_t *>(Bs + row * ROW_BYTES + swz(row, 2 * h + t) * 16) = v;
-}
-
-// The 3-bit layout (three words per row and k step; chunks 0..2 of the row's slice are the two 3-bit fields of the
-// bytes of word 0..2, chunk 3 the spare top bits of all three words).  Call 0: thread h turns word h into chunk h.
-// Call 1: thread h writes half h of chunk 2 (field h of word 2) and half h of chunk 3 (spare bits: bit 6 + h of
-// word 2 is the code's third bit, the top two bits of word h its low two), so that both threads run the same
-// instructions.  Codes land in mantissa bits [3, 6) of a bf16 with exponent 2^4: 16 + q.
-__device__ __forceinline__ void unpack3_to_stage(const uint8_t *__restrict__ raw_w, uint8_t *__restrict__ Bs, int t, int tid) {
-    const int row = tid >> 1, h = tid & 1;
-    const uint32_t *w = reinterpret_cast<const uint32_t *>(raw_w + row * 16);
-    const uint32_t exp = 0x41414141u, one = 0x80808080u, m38 = 0x38383838u;
-    const uint32_t sel_a = 0x00060004u, sel_b = 0x00070005u;     // bytes (0, 2) resp. (1, 3) of the codes
-    if (t == 0) {
-        const uint32_t v = w[h];
-        const uint32_t f0 = ((v << 3) & m38) | one, f1 = (v & m38) | one;
-        const u32x4_t o = {__builtin_amdgcn_perm(f0, exp, sel_a), __builtin_amdgcn_perm(f0, exp, sel_b),
-                           __builtin_amdgcn_perm(f1, exp, sel_a), __builtin_amdgcn_perm(f1, exp, sel_b)};
-        *reinterpret_cast<u32x4_t *>(Bs + row * ROW_BYTES + swz(row, h) * 16) = o;
-    } else {
-        const uint32_t w2 = w[2], wl = w[h];
-        const uint32_t f = ((w2 << (h ? 0 : 3)) & m38) | one;
-        const uint32_t c = ((((w2 >> (6 + h)) & 0x01010101u) << 5) | (((wl >> 6) & 0x03030303u) << 3)) | one;
-        typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
-        const u32x2_t o2 = {__builtin_amdgcn_perm(f, exp, sel_a), __builtin_amdgcn_perm(f, exp, sel_b)};
-        const u32x2_t o3 = {__builtin_amdgcn_perm(c, exp, sel_a), __builtin_amdgcn_perm(c, exp, sel_b)};
-        *reinterpret_cast<u32x2_t *>(Bs + row * ROW_BYTES + swz(row, 2) * 16 + h * 8) = o2;
-        *reinterpret_cast<u32x2_t *>(Bs + row * ROW_BYTES + swz(row, 3) * 16 + h * 8) = o3;
-    }
-}
-
-// The rescale factors of a lane's two columns, from the factor part of a ring slot.
-__device__ __forceinline__ void read_factors(const uint8_t *__restrict__ raw_r, const uint8_t *__restrict__ /*stage*/, int col,
-                                             float (&r)[TN]) {
-#pragma unroll
-    for (int j = 0; j < TN; ++j) r[j] = *reinterpret_cast<const float *>(raw_r + (col + j * 32) * 4);
-}
-
+// Fragments of the second loop's stages.  (Restrict pointers: see read_a_frags.)
 __device__ __forceinline__ void load_frags(const uint8_t *__restrict__ As, const uint8_t *__restrict__ Bs, int ks,
                                            Frag (&a)[TM], Frag (&b)[TN], int lane, int wm, int wn) {
     const int chunk = ks * 2 + (lane >> 5);
@@ -161,408 +126,15 @@ __device__ __forceinline__ void mfma_all(const Frag (&a)[TM], const Frag (&b)[TN
         for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, acc[i][j], 0, 0, 0);
 }
 
-// rfac: [row tile][groups + 1][16] fp32, factor of (row, group): s[G - 1] / s[G] for G >= 1, the LAST scale for G = 0
-// (the accumulator is zero when group 0 starts, so that slot is free), 1 in the slot behind the last group.
-// a2 / b2: bf16 [M][KP] / [N][KP].  flags: one word per 32 columns, nonzero = those columns do not qualify; a tile
-// with a flagged part is left to the other kernel as a whole.
-template <int WN, int BITS, bool OUT_F32, bool PC>
-__global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale_kernel(
-    const void *__restrict__ wt, const float *__restrict__ rfac, const uint16_t *__restrict__ x, const uint16_t *__restrict__ a2,
-    const uint16_t *__restrict__ b2, const uint32_t *__restrict__ flags, void *__restrict__ y, int64_t M, int64_t K, int64_t N,
-    int KP, int nbn, int lg_xm) {
-    using G = Geo<WN, BITS>;
-    constexpr int BN = G::BN, STAGE_BYTES = G::STAGE_BYTES, RAW_BYTES = G::RAW_BYTES, RAW_W_BYTES = G::RAW_W_BYTES;
-    constexpr int LA = G::LA, L1 = G::L1, LB = G::LB, L2 = G::L2;
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WN, wn = wave % WN;
-    int tm, tn;
-    if (lg_xm < 0) {            // plain order: column blocks fastest
-        tm = (int)blockIdx.x / nbn;
-        tn = (int)blockIdx.x % nbn;
-    } else {
-        // XCD-aware order: workgroups go to the 8 XCDs round-robin by linear index; the 32 an XCD runs at a
-        // time form a compact 4 x 8 patch of tiles and the 8 patches of a round a compact region
-        const int region = (int)blockIdx.x >> 8, r = (int)blockIdx.x & 255;
-        const int xcd = r & 7, q = r >> 3;
-        const int xn = 8 >> lg_xm;
-        const int regions_n = nbn / (8 * xn);
-        tm = (region / regions_n) * (4 << lg_xm) + (xcd / xn) * 4 + (q >> 3);
-        tn = (region % regions_n) * 8 * xn + (xcd % xn) * 8 + (q & 7);
-    }
-    const int64_t n0 = (int64_t)tn * BN;
-    const int64_t m0 = (int64_t)tm * BM;
-    {                                                          // uniform over the workgroup
-        const int f0 = (int)(n0 / 32), nf = (int)((N + 31) / 32);
-        uint32_t fl = 0;
-#pragma unroll
-        for (int i = 0; i < BN / 32; ++i) fl |= f0 + i < nf ? flags[f0 + i] : 0u;
-        if (fl != 0) return;
-    }
-    const int groups = (int)(K / kGroup);
-    const int steps = groups * 4;
-
-    // ---- activations: wave v fills rows [16 LA v, 16 LA (v + 1)) of a stage, 16 rows per instruction (rows beyond M
-    // clamp to the last row; their products are never stored)
-    const uint16_t *ga[LA];
-    int64_t mrow[LA];
-#pragma unroll
-    for (int i = 0; i < LA; ++i) {
-        const int row = wave * 16 * LA + i * 16 + (lane >> 2);
-        const int chunk = swz(row, lane & 3);
-        mrow[i] = m0 + row < M ? m0 + row : M - 1;
-        ga[i] = x + mrow[i] * K + chunk * 8;
-    }
-    int dma_step = 0;            // the step the pointers stand at (loads past the end of k re-read the last step)
-    auto issue_dma = [&](int step, int stage_idx) {
-        uint8_t *stage = lds + stage_idx * STAGE_BYTES;
-        const int target = step < steps ? step : steps - 1;
-        const int adv = (target - dma_step) * BK;
-        dma_step = target;
-#pragma unroll
-        for (int i = 0; i < LA; ++i) {
-            ga[i] += adv;
-            __builtin_amdgcn_global_load_lds((global_void *)ga[i], (lds_void *)(stage + (wave * 16 * LA + i * 16) * ROW_BYTES), 16,
-                                             0, 0);
-        }
-    };
-
-    // ---- packed codes and rescale factors of a k step: the 16 bytes of lane 16 c + j of row tile T's block
-    // (c = k step within the group) are row 16 T + j's 32 codes.  Waves [0, WN): codes of rows [64 v, 64 v + 64);
-    // waves [WN, 2 WN): the factors of rows [64 (v - WN), ...).  One load per wave and step.
-    uint8_t *raw = lds + NS * STAGE_BYTES;
-    const int64_t tiles_n = N / kTileRows;
-    const int part = wave % WN;
-    int64_t wT = n0 / kTileRows + part * 4 + (lane >> 4);
-    if (wT >= tiles_n) wT = tiles_n - 1;
-    const int wt_j = lane & 15;
-    auto issue_raw = [&](int step, int slot_idx) {
-        const int target = step < steps ? step : steps - 1;
-        uint8_t *slot = raw + slot_idx * RAW_BYTES;
-        if (wave < WN) {
-            const int64_t block = wT * groups + (target >> 2);
-            const int64_t l = block * 64 + (target & 3) * 16 + wt_j;           // the lane's slot in the streaming layout
-            if constexpr (BITS == 4)
-                __builtin_amdgcn_global_load_lds((global_void *)(reinterpret_cast<const uint4 *>(wt) + l),
-                                                 (lds_void *)(slot + part * 1024), 16, 0, 0);
-            else   // 12 bytes per lane, fetched as 16 (the last lane of the layer reads 4 bytes into the scale words behind)
-                __builtin_amdgcn_global_load_lds((global_void *)(reinterpret_cast<const uint32_t *>(wt) + l * 3),
-                                                 (lds_void *)(slot + part * 1024), 16, 0, 0);
-        } else {
-            // (a step past the end asks for the extra slot behind the last group, which holds 1)
-            const int64_t fslot = wT * (groups + 1) + (step < steps ? step >> 2 : groups);
-            __builtin_amdgcn_global_load_lds((global_void *)(rfac + fslot * kTileRows + wt_j),
-                                             (lds_void *)(slot + RAW_W_BYTES + part * 256), 4, 0, 0);
-        }
-    };
-    uint32_t held = 0;           // 4-bit: the second word of the k step whose first word was unpacked last
-    auto unpack = [&](int slot_idx, int stage_idx, int t) {
-        if constexpr (BITS == 4)
-            unpack_to_stage(raw + slot_idx * RAW_BYTES, lds + stage_idx * STAGE_BYTES + A_BYTES, t, tid, held);
-        else
-            unpack3_to_stage(raw + slot_idx * RAW_BYTES, lds + stage_idx * STAGE_BYTES + A_BYTES, t, tid);
-    };
-
-    f32x16 acc[TM][TN];
-#pragma unroll
-    for (int a = 0; a < TM; ++a)
-#pragma unroll
-        for (int b = 0; b < TN; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-
-    // ---- prologue: R(0), then A(j), R(j + 1) for j = 0..3, in that order (vmcnt retires in order); R(4) reuses the
-    // slot of R(0) and is therefore issued only after step 0's codes have been unpacked
-    issue_raw(0, 0);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        issue_dma(j, j);
-        if (j < 3) issue_raw(j + 1, j + 1);
-    }
-    wait_vmcnt<3 * LA + 2>();  // R(0), A(0) and R(1) have landed for this wave ...
-    bare_barrier();            // ... and for the waves that fetched the other parts
-    unpack(0, 0, 0);
-    unpack(0, 0, 1);
-    unpack(1, 1, 0);
-    wait_vmcnt<3 * LA + 2>();  // (own LDS accesses done)
-    bare_barrier();
-    issue_raw(4, 0);
-    Frag fa[2][TM], fb[2][TN];
-    load_frags(lds, lds + A_BYTES, 0, fa[0], fb[0], lane, wm, wn);
-
-    // ---- first loop, one group of 128 k (four k steps, stage and ring slot u) per pass of the body.  Step kt = 4 g + u:
-    //     read (kt, 1) | MFMA (kt, 0), unpack word 1 of step kt + 1 |
-    //     wait: loads of step kt + 1 (and the codes of step kt + 2) landed | barrier |
-    //     issue A(kt + 4) into stage u, R(kt + 5) into slot u + 1 (its last reader was the unpack above) |
-    //     read (kt + 1, 0) | MFMA (kt, 1), unpack word 0 of step kt + 2
-    //
-    // Rescale.  After the last MFMA of group g on a tile, that tile is multiplied by f = s[g] / s[g + 1], so that the
-    // MFMAs of group g + 1 can add to it.  The 128 multiplies of a wave are spread over the 16 MFMAs around the group
-    // boundary, half a tile (8 multiplies) next to each MFMA: tiles 0..3 in the last sub-step of group g (behind the
-    // MFMAs of the tiles after them), tiles 4..7 in the first sub-step of group g + 1 (ahead of their own MFMAs).
-    // Layers with one scale per row (PC) never rescale.
-    // (No branch on "first group" / "last group": the multiplies always run, with factors of 1 where there is nothing
-    // to rescale, and that 1 comes from memory: a uniform branch around the multiplies makes the compiler spill the
-    // accumulators, and a select against the constant 1 is turned into such a branch.)
-    const int scol = wn * 32 * TN + (lane & 31);
-    constexpr bool RESCALE = !PC;
-    auto mul_half = [&](int t, int h, const float (&f)[TN]) {
-        const int i = t / TN, j = t % TN;
-#pragma unroll
-        for (int r = 0; r < 8; ++r) acc[i][j][8 * h + r] *= f[j];
-    };
-    auto mfma_tile = [&](int t, const Frag (&a)[TM], const Frag (&b)[TN]) {
-        const int i = t / TN, j = t % TN;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, acc[i][j], 0, 0, 0);
-    };
-    static_assert(TM * TN == 8, "the rescale schedule below is written for 8 tiles per wave");
-    float rf[TN];                                               // factors to the group after the current one
-#pragma unroll
-    for (int j = 0; j < TN; ++j) rf[j] = 1.f;
-    for (int g = 0; g < groups; ++g) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int kt = 4 * g + u;
-            const uint8_t *cur = lds + u * STAGE_BYTES;
-            const bool more = kt + 1 < steps;                   // uniform over the workgroup
-            if (u == 3 && RESCALE) {
-                // factors of group g + 1: in the ring slot of its first step, which landed before the last barrier
-                // (read a sub-step early, so that the multiplies below do not wait for them)
-                read_factors(raw + RAW_W_BYTES, lds, scol, rf);
-            }
-            load_frags(cur, cur + A_BYTES, 1, fa[1], fb[1], lane, wm, wn);
-            if (u == 0 && RESCALE) __builtin_amdgcn_sched_barrier(0);
-            unpack((u + 1) & 3, (u + 1) & 3, 1);
-            if (u == 0 && RESCALE) {
-                mfma_tile(0, fa[0], fb[0]);
-                mul_half(4, 0, rf);
-                mfma_tile(1, fa[0], fb[0]);
-                mul_half(4, 1, rf);
-                mfma_tile(2, fa[0], fb[0]);
-                mul_half(5, 0, rf);
-                mfma_tile(3, fa[0], fb[0]);
-                mul_half(5, 1, rf);
-                mul_half(6, 0, rf);
-                mfma_tile(4, fa[0], fb[0]);
-                mul_half(6, 1, rf);
-                mul_half(7, 0, rf);
-                mfma_tile(5, fa[0], fb[0]);
-                mul_half(7, 1, rf);
-                mfma_tile(6, fa[0], fb[0]);
-                mfma_tile(7, fa[0], fb[0]);
-                // keep that order: without the groups the scheduler issues all 64 multiplies first
-#pragma unroll
-                for (int t = 0; t < 3; ++t) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);
-                }
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 18, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 18, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            } else {
-                mfma_all(fa[0], fb[0], acc);
-#pragma unroll
-                for (int t = 0; t < TM * TN; ++t) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);      // its share of the VALU work
-                    __builtin_amdgcn_sched_group_barrier(0x080, 1, 0);      // ... and of the LDS accesses (fragments of sub-step 1)
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            if (more) {
-                wait_vmcnt<2 * L1>();
-                bare_barrier();
-                const uint8_t *nxt = lds + ((u + 1) & 3) * STAGE_BYTES;
-                load_frags(nxt, nxt + A_BYTES, 0, fa[0], fb[0], lane, wm, wn);
-                __builtin_amdgcn_sched_barrier(0);
-                issue_dma(kt + 4, u);
-                issue_raw(kt + 5, (u + 1) & 3);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            // The codes of step kt + 2 landed before the barrier above and its stage's weight half was last
-            // read two steps ago.  Unconditional (past the end it rewrites a stage nobody reads).
-            unpack((u + 2) & 3, (u + 2) & 3, 0);
-            if (u == 3 && RESCALE) {
-                // (scheduling fences, not groups: with groups the scheduler still moved all 64 multiplies behind
-                // the last MFMA)
-                mfma_tile(0, fa[1], fb[1]);
-                mfma_tile(1, fa[1], fb[1]);
-                mfma_tile(2, fa[1], fb[1]);
-                __builtin_amdgcn_sched_barrier(0);
-                mul_half(0, 0, rf);
-                mfma_tile(3, fa[1], fb[1]);
-                __builtin_amdgcn_sched_barrier(0);
-                mul_half(0, 1, rf);
-                mfma_tile(4, fa[1], fb[1]);
-                __builtin_amdgcn_sched_barrier(0);
-                mul_half(1, 0, rf);
-                mfma_tile(5, fa[1], fb[1]);
-                __builtin_amdgcn_sched_barrier(0);
-                mul_half(1, 1, rf);
-                mfma_tile(6, fa[1], fb[1]);
-                __builtin_amdgcn_sched_barrier(0);
-                mul_half(2, 0, rf);
-                mfma_tile(7, fa[1], fb[1]);
-                __builtin_amdgcn_sched_barrier(0);
-                mul_half(2, 1, rf);
-                mul_half(3, 0, rf);
-                mul_half(3, 1, rf);
-            } else {
-                mfma_all(fa[1], fb[1], acc);
-#pragma unroll
-                for (int t = 0; t < TM * TN; ++t) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-    wait_vmcnt<0>();           // the clamped loads of the last iterations are still in flight
-    bare_barrier();            // every wave is done with the stages
-
-    // ---- into units of 1: the last scale sits in the factor slot of group 0
-    {
-        float sl[TN];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            int64_t n = n0 + scol + j * 32;
-            if (n >= N) n = N - 1;
-            sl[j] = rfac[((n / kTileRows) * (groups + 1)) * kTileRows + (n % kTileRows)];
-        }
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] *= sl[j];
-    }
-
-    // ---- second loop: the zero-point term, bf16 operands A2[m][.] and B2[n][.] over KP columns, both direct-to-LDS.
-    // Same pipeline; wave v fills rows [16 LA v, ..) of A2's stage half and rows [16 LB v, ..) of B2's.
-    {
-        const int steps2 = KP / BK;
-        const uint16_t *gp[L2];
-#pragma unroll
-        for (int i = 0; i < LA; ++i) {
-            const int row = wave * 16 * LA + i * 16 + (lane >> 2);
-            gp[i] = a2 + mrow[i] * KP + swz(row, lane & 3) * 8;
-        }
-#pragma unroll
-        for (int i = 0; i < LB; ++i) {
-            const int row = wave * 16 * LB + i * 16 + (lane >> 2);
-            const int64_t n = n0 + row < N ? n0 + row : N - 1;
-            gp[LA + i] = b2 + n * KP + swz(row, lane & 3) * 8;
-        }
-        int at = 0;
-        auto issue2 = [&](int step, int stage_idx) {
-            uint8_t *stage = lds + stage_idx * STAGE_BYTES;
-            const int target = step < steps2 ? step : steps2 - 1;
-            const int adv = (target - at) * BK;
-            at = target;
-#pragma unroll
-            for (int i = 0; i < LA; ++i) {
-                gp[i] += adv;
-                __builtin_amdgcn_global_load_lds((global_void *)gp[i], (lds_void *)(stage + (wave * 16 * LA + i * 16) * ROW_BYTES),
-                                                 16, 0, 0);
-            }
-#pragma unroll
-            for (int i = 0; i < LB; ++i) {
-                gp[LA + i] += adv;
-                __builtin_amdgcn_global_load_lds((global_void *)gp[LA + i],
-                                                 (lds_void *)(stage + A_BYTES + (wave * 16 * LB + i * 16) * ROW_BYTES), 16, 0, 0);
-            }
-        };
-#pragma unroll
-        for (int j = 0; j < 4; ++j) issue2(j, j);
-        wait_vmcnt<3 * L2>();
-        bare_barrier();
-        load_frags(lds, lds + A_BYTES, 0, fa[0], fb[0], lane, wm, wn);
-        for (int kt = 0; kt < steps2; ++kt) {
-            const uint8_t *cur = lds + (kt & 3) * STAGE_BYTES;
-            const bool more = kt + 1 < steps2;
-            load_frags(cur, cur + A_BYTES, 1, fa[1], fb[1], lane, wm, wn);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_all(fa[0], fb[0], acc);
-            __builtin_amdgcn_sched_barrier(0);
-            if (more) {
-                wait_vmcnt<2 * L2>();
-                bare_barrier();
-                const uint8_t *nxt = lds + ((kt + 1) & 3) * STAGE_BYTES;
-                load_frags(nxt, nxt + A_BYTES, 0, fa[0], fb[0], lane, wm, wn);
-                __builtin_amdgcn_sched_barrier(0);
-                issue2(kt + 4, kt & 3);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_all(fa[1], fb[1], acc);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        wait_vmcnt<0>();
-    }
-
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int64_t n = n0 + wn * 32 * TN + j * 32 + (lane & 31);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t m = m0 + wm * 32 * TM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (m < M && n < N) {
-                    if (OUT_F32)
-                        reinterpret_cast<float *>(y)[m * N + n] = acc[i][j][r];
-                    else
-                        reinterpret_cast<uint16_t *>(y)[m * N + n] = f32_to_bf16(acc[i][j][r]);
-                }
-            }
-        }
-}
-
-// ---- the same product with the weight operand kept out of LDS --------------------------------------------------------
-// The codes of a weight row are private to the waves that own its column: nothing has to be unpacked INTO a shared
-// stage.  Here the packed codes travel global -> LDS as they are (32 bytes per weight row and 64 k, one instruction per
-// wave and stage), every wave reads the 16 bytes of its own columns back and unpacks them in registers straight into
-// MFMA B operands, one word (8 codes, one operand) per MFMA k step.  LDS then carries per 64 k and workgroup 32 KiB of
-// activations once in and 16 fragment reads per wave out: two thirds of the fragment reads and half of the writes of
-// the kernel above (and of the bf16 twin), whose LDS port is as busy as its matrix cores.
-//
-// A stage is 64 k: lane half h of an MFMA operand takes the k step 2 v + h of the group's half v, word w of it in the
-// w-th MFMA of the stage, so that a lane's 16 code bytes are exactly its four B operands; the activation fragment of
-// that MFMA is 16-byte chunk 4 h + w of the row's 128-byte slice (chunks XOR-swizzled with bits 1..3 of the row number:
-// 16 consecutive rows then cover the 16 bank groups of 16 bytes).
-// Three stages of 32 KiB + the codes, requested two stages ahead; one bare barrier per stage, behind the third of its
-// four MFMA rounds.  The rescale factors of a wave's 64 columns come direct-to-LDS into a slot of the wave's own, one
-// instruction per group.  The zero-point loop and the store are those of the kernel above.
-constexpr int BK2 = 64, ROW2 = BK2 * 2, NS2 = 3;
-constexpr int A2S_BYTES = BM * ROW2;                           // 32 KiB
-
-template <int WN, int BITS>
-struct GeoR {
-    using G1 = Geo<WN, BITS>;
-    static constexpr int WAVES = G1::WAVES, THREADS = G1::THREADS, BN = G1::BN;
-    static constexpr int RAWB = BN * 32;                                   // two 16-byte units per weight row and stage
-    static constexpr int STAGE = A2S_BYTES + RAWB;                         // 40 or 36 KiB
-    static constexpr int FAC_OFF = NS2 * STAGE;                            // 256 bytes of factors per wave
-    static constexpr int MAIN_BYTES = FAC_OFF + WAVES * 256;
-    static constexpr int PH2_BYTES = NS * G1::STAGE_BYTES;                 // the zero-point loop's four stages of 32 k
-    static constexpr size_t LDS_BYTES = MAIN_BYTES > PH2_BYTES ? MAIN_BYTES : PH2_BYTES;   // 128 or 109 KiB
-    static constexpr int LA = A2S_BYTES / 1024 / WAVES;                    // activation load instructions per wave and stage
-    static constexpr int L = LA + 1;                                       // ... plus the codes
-    static_assert(BN / kTileRows == 2 * WAVES, "one code instruction (two row tiles) per wave");
-};
-
-// One word of a lane's codes -> the 8 bf16 values (16 + q) / 2 = 8 + q / 2 of an MFMA B operand: as in unpack_to_stage,
-// but with the exponent's lowest bit (the top bit of the low byte) left clear, which saves the OR; the factor 2 goes
-// into the last scale.
+// One word of a lane's codes -> the 8 bf16 values (16 + q) / 2 = 8 + q / 2 of an MFMA B operand.  Each nibble goes to
+// mantissa bits [3, 7) of a bf16 whose high byte is 0x41 and whose exponent's lowest bit (the top bit of the low byte)
+// stays clear: 2^3 (1 + q / 16).  (With that bit set the value would be 16 + q; leaving it saves an OR per four
+// weights.  The decode kernels' 128 + q would carry an offset eight times larger into the cancellation with the
+// zero-point term.)  In the streaming layout word w of a lane's unit holds the 8 codes of k = 8 w .. 8 w + 7 of its k
+// step, the nibbles in the order 0, 4, 1, 5, 2, 6, 3, 7 that the four permutes below undo.
 __device__ __forceinline__ void unpack4_word(uint32_t w, Frag &f) {
-    const uint32_t even = (w << 3) & 0x78787878u;
-    const uint32_t odd = (w >> 1) & 0x78787878u;
+    const uint32_t even = (w << 3) & 0x78787878u;     // nibbles 0, 2, 4, 6 as low bytes
+    const uint32_t odd = (w >> 1) & 0x78787878u;      // nibbles 1, 3, 5, 7
     const uint32_t exp = 0x41414141u;
     f.w[0] = __builtin_amdgcn_perm(even, exp, 0x00060004u);
     f.w[1] = __builtin_amdgcn_perm(odd, exp, 0x00060004u);
@@ -570,8 +142,10 @@ __device__ __forceinline__ void unpack4_word(uint32_t w, Frag &f) {
     f.w[3] = __builtin_amdgcn_perm(odd, exp, 0x00070005u);
 }
 
-// The 3-bit unit (three words; see unpack3_to_stage): chunk c < 3 is the two 3-bit fields of the bytes of word c,
-// chunk 3 the spare top bits of all three words.  Values (16 + q) / 2 as for four bits.
+// The 3-bit unit (three words per weight row and k step): chunk c < 3 of the row's 32 k is the two 3-bit fields of
+// the bytes of word c, chunk 3 the spare top bits of all three words (bit 6 + h of word 2 is the third bit of a code
+// in half h of the chunk, the top two bits of word h its low two).  Codes land in mantissa bits [3, 6): values
+// (16 + q) / 2 as for four bits.
 __device__ __forceinline__ void unpack3_chunk(const u32x4_t &u, int c, Frag &f) {
     const uint32_t exp = 0x41414141u, m38 = 0x38383838u;
     const uint32_t sel_a = 0x00060004u, sel_b = 0x00070005u;
@@ -617,16 +191,20 @@ __device__ __forceinline__ void read_wave_factors(const uint8_t *__restrict__ p,
     rf[1] = *reinterpret_cast<const float *>(q);
 }
 
+// wt: the layer's codes in the streaming layout (1 KiB, 3-bit 768 B, per row tile of 16 and group; the unit of lane
+// 16 c + j of a block is row j's 32 codes of k step c).  rfac: [row tile][groups + 1][16] fp32, factor of (row, group):
+// s[G - 1] / s[G] for G >= 1, the LAST scale for G = 0 (the accumulator is zero when group 0 starts, so that slot is
+// free), 1 in the slot behind the last group.  a2 / b2: bf16 [M][KP] / [N][KP].  flags: one word per 32 columns,
+// nonzero = those columns do not qualify; a tile with a flagged part is left to the other kernel as a whole.
 template <int WN, int BITS, bool OUT_F32, bool PC>
-__global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_regb_kernel(
+__global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale_kernel(
     const void *__restrict__ wt, const float *__restrict__ rfac, const uint16_t *__restrict__ x, const uint16_t *__restrict__ a2,
     const uint16_t *__restrict__ b2, const uint32_t *__restrict__ flags, void *__restrict__ y, int64_t M, int64_t K, int64_t N,
     int KP, int nbn, int lg_xm) {
     using G = Geo<WN, BITS>;
-    using R = GeoR<WN, BITS>;
     constexpr int BN = G::BN, STAGE_BYTES = G::STAGE_BYTES;
     constexpr int LA = G::LA, LB = G::LB, L2 = G::L2;
-    constexpr int RA = R::LA, RL = R::L, RSTAGE = R::STAGE;
+    constexpr int RA = G::RA, RL = G::RL, RSTAGE = G::STAGE;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -636,7 +214,9 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_regb_ke
     if (lg_xm < 0) {
         tm = (int)blockIdx.x / nbn;
         tn = (int)blockIdx.x % nbn;
-    } else {                    // XCD-aware order, as in the kernel above
+    } else {
+        // XCD-aware order: workgroups go to the 8 XCDs round-robin by linear index; the 32 an XCD runs at a
+        // time form a compact 4 x 8 patch of tiles and the 8 patches of a round a compact region
         const int region = (int)blockIdx.x >> 8, r = (int)blockIdx.x & 255;
         const int xcd = r & 7, q = r >> 3;
         const int xn = 8 >> lg_xm;
@@ -697,7 +277,7 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_regb_ke
         fptr = rfac + ((n / kTileRows) * (groups + 1)) * kTileRows + (n % kTileRows);
     }
     auto issue_factors = [&](int slot) {
-        __builtin_amdgcn_global_load_lds((global_void *)(fptr + (int64_t)slot * kTileRows), (lds_void *)(lds + R::FAC_OFF + wave * 256), 4,
+        __builtin_amdgcn_global_load_lds((global_void *)(fptr + (int64_t)slot * kTileRows), (lds_void *)(lds + G::FAC_OFF + wave * 256), 4,
                                          0, 0);
     };
 
@@ -760,7 +340,7 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_regb_ke
     float rf[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) rf[j] = 1.f;
-    const int fcol = R::FAC_OFF + wave * 256 + (lane & 31) * 4;
+    const int fcol = G::FAC_OFF + wave * 256 + (lane & 31) * 4;
 
     for (int g = 0; g < groups; ++g) {
 #pragma unroll
@@ -892,7 +472,8 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_regb_ke
                 for (int r = 0; r < 16; ++r) acc[i][j][r] *= sl[j];
     }
 
-    // ---- the zero-point term: the second loop of the kernel above (stages of 32 k, both operands direct-to-LDS)
+    // ---- second loop: the zero-point term, bf16 operands A2[m][.] and B2[n][.] over KP columns, both direct-to-LDS in
+    // stages of 32 k; wave v fills rows [16 LA v, ..) of A2's stage half and rows [16 LB v, ..) of B2's
     {
         const int steps2 = KP / BK;
         const uint16_t *gp[L2];
@@ -1143,28 +724,22 @@ template <int WN, int BITS>
 hipError_t launch_tile(const void *wt, bool pc, const uint16_t *x, int64_t M, int64_t K, int64_t N, void *y, bool out_f32,
                        const RescalePlan &p, const Operands &o, hipStream_t stream) {
     using G = Geo<WN, BITS>;
-    using R = GeoR<WN, BITS>;
-    const bool regb = env_int("DMR_W4_RESCALE_REGB", 1) != 0;
     const int nbm = (int)((M + BM - 1) / BM), nbn = (int)((N + G::BN - 1) / G::BN);
     // XCD-aware tile order when the grid of tiles divides into regions of 8 patches of 4 x 8 tiles (see the kernel)
     int lg_xm = 2;
     while (lg_xm >= 0 && (nbm % (4 << lg_xm) != 0 || nbn % (8 * (8 >> lg_xm)) != 0)) --lg_xm;
-    auto go = [&](auto kernel, auto kernel_r) {
-        const void *fn = regb ? reinterpret_cast<const void *>(kernel_r) : reinterpret_cast<const void *>(kernel);
-        const size_t lds_bytes = regb ? R::LDS_BYTES : G::LDS_BYTES;
-        hipError_t st = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    auto go = [&](auto kernel) {
+        hipError_t st = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            (int)G::LDS_BYTES);
         if (st != hipSuccess) return st;
-        hipLaunchKernelGGL(regb ? kernel_r : kernel, dim3((unsigned)(nbm * nbn)), dim3(G::THREADS), lds_bytes, stream, wt, o.rfac, x,
-                           o.a2, o.b2, o.flags, y, M, K, N, p.KP, nbn, lg_xm);
+        hipLaunchKernelGGL(kernel, dim3((unsigned)(nbm * nbn)), dim3(G::THREADS), G::LDS_BYTES, stream, wt, o.rfac, x, o.a2, o.b2,
+                           o.flags, y, M, K, N, p.KP, nbn, lg_xm);
         return hipGetLastError();
     };
     if constexpr (BITS == 4) {
-        if (pc)
-            return out_f32 ? go(&gemm_w4_rescale_kernel<WN, 4, true, true>, &gemm_w4_regb_kernel<WN, 4, true, true>)
-                           : go(&gemm_w4_rescale_kernel<WN, 4, false, true>, &gemm_w4_regb_kernel<WN, 4, false, true>);
+        if (pc) return out_f32 ? go(&gemm_w4_rescale_kernel<WN, 4, true, true>) : go(&gemm_w4_rescale_kernel<WN, 4, false, true>);
     }
-    return out_f32 ? go(&gemm_w4_rescale_kernel<WN, BITS, true, false>, &gemm_w4_regb_kernel<WN, BITS, true, false>)
-                   : go(&gemm_w4_rescale_kernel<WN, BITS, false, false>, &gemm_w4_regb_kernel<WN, BITS, false, false>);
+    return out_f32 ? go(&gemm_w4_rescale_kernel<WN, BITS, true, false>) : go(&gemm_w4_rescale_kernel<WN, BITS, false, false>);
 }
 
 // Pre-pass, then the rescaling kernel; the caller launches the 128 x 128 exact kernel behind them for the column blocks
