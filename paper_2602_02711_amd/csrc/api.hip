@@ -23,6 +23,7 @@ constexpr int64_t kSkinnyMaxM = 64;
 // Which INT4 kernel serves M rows of a (K, N) layer (measured crossovers, 256 CUs).  The workspace
 // query and the forward call both go through this.
 enum class W4Path { Gemv, Stream, Panel, Wide, Skinny2, Mid, Gemm, GemmRescale };
+constexpr int kTiledMinBlocks = 280;
 W4Path w4_path(int64_t M, int64_t K, int64_t N) {
     if (M == 1) return W4Path::Gemv;
     if (M <= 16) {
@@ -34,9 +35,10 @@ W4Path w4_path(int64_t M, int64_t K, int64_t N) {
     const int64_t tiles = N / dmr::kTileRows;
     // wide layers already give the register-blocked streaming kernel 4 tiles per workgroup
     if (M <= kSkinnyMaxM) return tiles >= 1024 ? W4Path::Skinny2 : W4Path::Mid;
-    // the 128 x 128 GEMM needs about 300 workgroups before it wins (measured)
+    // the tiled GEMM wins from about 280 blocks of 128 x 128 on (measured: ahead at 288 on all three narrow layers,
+    // behind at 256)
     const int64_t gemm_wgs = ((M + 127) / 128) * ((N + 127) / 128);
-    if (M <= 128 || gemm_wgs < dmr::env_int("DMR_W4_GEMM_MIN_WGS", 300)) return W4Path::Mid;
+    if (M <= 128 || gemm_wgs < dmr::env_int("DMR_W4_GEMM_MIN_WGS", kTiledMinBlocks)) return W4Path::Mid;
     return dmr::w4_gemm_rescale_applies(M, N) ? W4Path::GemmRescale : W4Path::Gemm;
 }
 
@@ -52,7 +54,7 @@ W3Path w3_path(int64_t M, int64_t K, int64_t N) {
     }
     if (M <= kSkinnyMaxM && dmr::w4_wide_applies(M, K, N)) return W3Path::Wide;
     const int64_t gemm_wgs = ((M + 127) / 128) * ((N + 127) / 128);
-    if (M <= 128 || gemm_wgs < 300) return W3Path::Mid;
+    if (M <= 128 || gemm_wgs < kTiledMinBlocks) return W3Path::Mid;
     return dmr::w4_gemm_rescale_applies(M, N) ? W3Path::GemmRescale : W3Path::Gemm;
 }
 
