@@ -22,9 +22,10 @@
 // of 32 rows and leaves a flag; a workgroup whose columns are flagged returns at once and the 128 x 128 exact
 // kernel, launched behind this one with the same flags, computes those columns instead.
 //
-// Shape of the work.  Two instantiations: 8 wavefronts (2 x 4) on a 256 x 256 tile, two waves per SIMD, or 4
-// wavefronts (2 x 2) on a 256 x 128 tile for grids that one round of those covers.  Every wave owns a 128 x 64 patch
-// = 4 x 2 tiles of v_mfma_f32_32x32x16_bf16.
+// Shape of the work.  Eight wavefronts (2 x 4), two per SIMD, in two instantiations: a 256 x 256 tile with a 128 x 64
+// patch per wave (4 x 2 tiles of v_mfma_f32_32x32x16_bf16), or, for grids that one round of them covers, a 256 x 128
+// tile with 128 x 32 per wave (4 x 1).  (The kernel is written for WM x WN waves of TM x TN tiles; 256 x 128 on four
+// waves of 128 x 64 and on eight of 64 x 64 were measured 0-8 % behind and are not instantiated.)
 //
 // The weight operand never sits in LDS unpacked.  The codes of a weight row are private to the waves that own its
 // column, so nothing has to be unpacked INTO a shared stage: the packed codes travel global -> LDS as they are (32 bytes
@@ -50,37 +51,42 @@ namespace dmr {
 
 namespace {
 
-constexpr int TM = 4, TN = 2;                              // MFMA tiles per wave
-constexpr int WM = 2;                                      // wave rows per workgroup
-constexpr int BM = 32 * TM * WM;                           // 256
+constexpr int kMaxBM = 256;                                // rows of the largest tile
 // first loop: stages of 64 k, activations and packed codes
 constexpr int BK2 = 64, ROW2 = BK2 * 2, NS2 = 3;
-constexpr int A2S_BYTES = BM * ROW2;                       // 32 KiB
 // second loop (zero-point term): stages of 32 k, both operands as bf16
 constexpr int BK = 32, NS = 4;
 constexpr int ROW_BYTES = BK * 2;                          // 64
-constexpr int A_BYTES = BM * ROW_BYTES;                    // 16 KiB per stage
 
-template <int WN, int BITS>                                // wave columns per workgroup: 2 or 4; code width: 4 or 3
+// WM x WN wavefronts, each on TM x TN MFMA tiles of 32 x 32; code width BITS (4 or 3).
+template <int WM, int WN, int TM, int TN, int BITS>
 struct Geo {
     static constexpr int WAVES = WM * WN, THREADS = 64 * WAVES;
+    static constexpr int BM = 32 * TM * WM;                                // 256 (or 128)
     static constexpr int BN = 32 * TN * WN;                                // 128 or 256
     // first loop
-    static constexpr int RAWB = BN * 32;                                   // two 16-byte units per weight row and stage
-    static constexpr int STAGE = A2S_BYTES + RAWB;                         // 40 or 36 KiB
+    static constexpr int A2S_BYTES = BM * ROW2;                            // 32 KiB (16)
+    // the codes of a stage: 32 bytes per weight row, two row tiles of 16 per load instruction.  Where one instruction
+    // per wave covers the tile's columns exactly once, every wave reads its columns from whichever wave fetched them;
+    // otherwise every wave fetches the 2 TN row tiles of its own columns into a slot of its own.
+    static constexpr bool PRIVATE_CODES = BN / kTileRows != 2 * WAVES;
+    static constexpr int RI = PRIVATE_CODES ? TN : 1;                      // code load instructions per wave and stage
+    static constexpr int RAWB = WAVES * RI * 1024;
+    static constexpr int STAGE = A2S_BYTES + RAWB;                         // 40 or 36 KiB (48 with private codes)
     static constexpr int FAC_OFF = NS2 * STAGE;                            // 256 bytes of factors per wave
     static constexpr int MAIN_BYTES = FAC_OFF + WAVES * 256;
     static constexpr int RA = A2S_BYTES / 1024 / WAVES;                    // activation load instructions per wave and stage
-    static constexpr int RL = RA + 1;                                      // ... plus the codes
-    static_assert(BN / kTileRows == 2 * WAVES, "one code instruction (two row tiles) per wave");
+    static constexpr int RL = RA + RI;                                     // ... plus the codes
+    static_assert(RA >= 1 && RA * WAVES * 1024 == A2S_BYTES, "whole load instructions");
     // second loop
-    static constexpr int B_BYTES = BN * ROW_BYTES;
+    static constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;                  // 24 or 32 KiB
     static constexpr int PH2_BYTES = NS * STAGE_BYTES;
     static constexpr int LA = BM / 16 / WAVES;                             // A2 load instructions per wave and step
-    static constexpr int LB = BN / 16 / WAVES;                             // B2 load instructions per wave and step (2)
+    static constexpr int LB = BN / 16 / WAVES;                             // B2 load instructions per wave and step
     static constexpr int L2 = LA + LB;
-    static constexpr size_t LDS_BYTES = MAIN_BYTES > PH2_BYTES ? MAIN_BYTES : PH2_BYTES;   // 128 or 109 KiB
+    static_assert(LA >= 1 && LB >= 1, "whole load instructions");
+    static constexpr size_t LDS_BYTES = MAIN_BYTES > PH2_BYTES ? MAIN_BYTES : PH2_BYTES;
 };
 
 typedef __attribute__((address_space(3))) void lds_void;
@@ -104,6 +110,7 @@ __device__ __forceinline__ void bare_barrier() {
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 2) & 3); }
 
 // Fragments of the second loop's stages.  (Restrict pointers: see read_a_frags.)
+template <int TM, int TN>
 __device__ __forceinline__ void load_frags(const uint8_t *__restrict__ As, const uint8_t *__restrict__ Bs, int ks,
                                            Frag (&a)[TM], Frag (&b)[TN], int lane, int wm, int wn) {
     const int chunk = ks * 2 + (lane >> 5);
@@ -119,6 +126,7 @@ __device__ __forceinline__ void load_frags(const uint8_t *__restrict__ As, const
     }
 }
 
+template <int TM, int TN>
 __device__ __forceinline__ void mfma_all(const Frag (&a)[TM], const Frag (&b)[TN], f32x16 (&acc)[TM][TN]) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -168,27 +176,40 @@ __device__ __forceinline__ void unpack3_chunk(const u32x4_t &u, int c, Frag &f) 
 // direct-to-LDS loads in flight, whose completion the kernel waits for explicitly.  (A scope only appears for a restrict
 // parameter that is used and has another one to be distinct from, and only survives on a load of a vector type; hence
 // two pointers into the same buffer.)
+template <int TM>
 __device__ __forceinline__ void read_a_frags(const uint8_t *__restrict__ p, const uint8_t *__restrict__ q, Frag (&a)[TM]) {
-    static_assert(TM == 4, "two tiles through each pointer");
+    static_assert(TM % 2 == 0, "half of the tiles through each pointer (q = p + TM / 2 tiles)");
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < TM / 2; ++i) {
         const u32x4_t lo = *reinterpret_cast<const u32x4_t *>(p + i * 32 * ROW2);
         const u32x4_t hi = *reinterpret_cast<const u32x4_t *>(q + i * 32 * ROW2);
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             a[i].w[c] = lo[c];
-            a[2 + i].w[c] = hi[c];
+            a[TM / 2 + i].w[c] = hi[c];
         }
     }
 }
+template <int TN>
 __device__ __forceinline__ void read_code_units(const uint8_t *__restrict__ p, const uint8_t *__restrict__ q, u32x4_t (&rw)[TN]) {
-    static_assert(TN == 2, "one unit through each pointer");
-    rw[0] = *reinterpret_cast<const u32x4_t *>(p);
-    rw[1] = *reinterpret_cast<const u32x4_t *>(q);
+    if constexpr (TN == 2) {            // one unit through each pointer (q = p + 1 KiB)
+        rw[0] = *reinterpret_cast<const u32x4_t *>(p);
+        rw[1] = *reinterpret_cast<const u32x4_t *>(q);
+    } else {                            // one unit, half through each pointer (q = p + 8)
+        typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+        const u32x2_t lo = *reinterpret_cast<const u32x2_t *>(p);
+        const u32x2_t hi = *reinterpret_cast<const u32x2_t *>(q);
+        rw[0] = u32x4_t{lo[0], lo[1], hi[0], hi[1]};
+    }
 }
+template <int TN>
 __device__ __forceinline__ void read_wave_factors(const uint8_t *__restrict__ p, const uint8_t *__restrict__ q, float (&rf)[TN]) {
     rf[0] = *reinterpret_cast<const float *>(p);
-    rf[1] = *reinterpret_cast<const float *>(q);
+    const float other = *reinterpret_cast<const float *>(q);      // q = p + 128: the factor of the column 32 further on
+    if constexpr (TN == 2)
+        rf[1] = other;
+    else                                                          // (a use that folds away: the scope needs one)
+        rf[0] = __uint_as_float(__float_as_uint(rf[0]) | (__float_as_uint(other) & 0u));
 }
 
 // wt: the layer's codes in the streaming layout (1 KiB, 3-bit 768 B, per row tile of 16 and group; the unit of lane
@@ -196,15 +217,15 @@ __device__ __forceinline__ void read_wave_factors(const uint8_t *__restrict__ p,
 // s[G - 1] / s[G] for G >= 1, the LAST scale for G = 0 (the accumulator is zero when group 0 starts, so that slot is
 // free), 1 in the slot behind the last group.  a2 / b2: bf16 [M][KP] / [N][KP].  flags: one word per 32 columns,
 // nonzero = those columns do not qualify; a tile with a flagged part is left to the other kernel as a whole.
-template <int WN, int BITS, bool OUT_F32, bool PC>
-__global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale_kernel(
+template <int WM, int WN, int TM, int TN, int BITS, bool OUT_F32, bool PC>
+__global__ __launch_bounds__(64 * WM * WN, 512 / (64 * WM * WN) > 1 ? 2 : 1) void gemm_w4_rescale_kernel(
     const void *__restrict__ wt, const float *__restrict__ rfac, const uint16_t *__restrict__ x, const uint16_t *__restrict__ a2,
     const uint16_t *__restrict__ b2, const uint32_t *__restrict__ flags, void *__restrict__ y, int64_t M, int64_t K, int64_t N,
     int KP, int nbn, int lg_xm) {
-    using G = Geo<WN, BITS>;
-    constexpr int BN = G::BN, STAGE_BYTES = G::STAGE_BYTES;
+    using G = Geo<WM, WN, TM, TN, BITS>;
+    constexpr int BM = G::BM, BN = G::BN, STAGE_BYTES = G::STAGE_BYTES, A_BYTES = G::A_BYTES, A2S_BYTES = G::A2S_BYTES;
     constexpr int LA = G::LA, LB = G::LB, L2 = G::L2;
-    constexpr int RA = G::RA, RL = G::RL, RSTAGE = G::STAGE;
+    constexpr int RA = G::RA, RI = G::RI, RL = G::RL, RSTAGE = G::STAGE;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -245,11 +266,15 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
         const int64_t m = m0 + row < M ? m0 + row : M - 1;
         ga[i] = x + m * K + chunk * 8;
     }
-    // ---- codes: the wave's two row tiles, lanes [32 v, 32 v + 32) of their block (k steps 2 v and 2 v + 1)
+    // ---- codes: per instruction two row tiles, lanes [32 v, 32 v + 32) of their block (k steps 2 v and 2 v + 1)
     const int64_t tiles_n = N / kTileRows;
-    int64_t wT = n0 / kTileRows + 2 * wave + (lane >> 5);
-    if (wT >= tiles_n) wT = tiles_n - 1;
-    const int64_t unit0 = wT * groups * 64 + (lane & 31);
+    int64_t unit0[RI];
+#pragma unroll
+    for (int i = 0; i < RI; ++i) {
+        int64_t wT = n0 / kTileRows + (G::PRIVATE_CODES ? wn * 2 * TN + 2 * i : 2 * wave) + (lane >> 5);
+        if (wT >= tiles_n) wT = tiles_n - 1;
+        unit0[i] = wT * groups * 64 + (lane & 31);
+    }
     int at = 0;                  // the stage the activation pointers stand at
     auto issue_stage = [&](int t, int off) {
         const int target = t < stages ? t : stages - 1;        // past the end: the last stage again, never read
@@ -260,13 +285,15 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
             ga[i] += adv;
             __builtin_amdgcn_global_load_lds((global_void *)ga[i], (lds_void *)(lds + off + (wave * 8 * RA + i * 8) * ROW2), 16, 0, 0);
         }
-        const int64_t unit = unit0 + (int64_t)(target >> 1) * 64 + (target & 1) * 32;
-        if constexpr (BITS == 4)
-            __builtin_amdgcn_global_load_lds((global_void *)(reinterpret_cast<const uint4 *>(wt) + unit),
-                                             (lds_void *)(lds + off + A2S_BYTES + wave * 1024), 16, 0, 0);
-        else   // 12 bytes per unit, fetched as 16
-            __builtin_amdgcn_global_load_lds((global_void *)(reinterpret_cast<const uint32_t *>(wt) + unit * 3),
-                                             (lds_void *)(lds + off + A2S_BYTES + wave * 1024), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < RI; ++i) {
+            const int64_t unit = unit0[i] + (int64_t)(target >> 1) * 64 + (target & 1) * 32;
+            lds_void *dst = (lds_void *)(lds + off + A2S_BYTES + (wave * RI + i) * 1024);
+            if constexpr (BITS == 4)
+                __builtin_amdgcn_global_load_lds((global_void *)(reinterpret_cast<const uint4 *>(wt) + unit), dst, 16, 0, 0);
+            else   // 12 bytes per unit, fetched as 16
+                __builtin_amdgcn_global_load_lds((global_void *)(reinterpret_cast<const uint32_t *>(wt) + unit * 3), dst, 16, 0, 0);
+        }
     };
     // ---- factors of the wave's 64 columns (lane = column), slot g + 1 of the table: s[g] / s[g + 1]
     constexpr bool RESCALE = !PC;
@@ -284,10 +311,10 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
     // ---- what a lane reads back: its fragment addresses within a stage
     const int arow = wm * 32 * TM + (lane & 31);
     const int abase = arow * ROW2 + (((4 * (lane >> 5)) ^ ((lane >> 1) & 7)) * 16);    // MFMA round w: abase ^ (16 w)
-    const int rbase = A2S_BYTES + (wn * 4 + ((lane & 31) >> 4)) * 512 + (lane >> 5) * 256 + (lane & 15) * 16;
+    const int rbase = A2S_BYTES + ((G::PRIVATE_CODES ? wave : wn) * 2 * TN + ((lane & 31) >> 4)) * 512 + (lane >> 5) * 256 + (lane & 15) * 16;
     auto read_a = [&](int off, int w, Frag (&a)[TM]) { const uint8_t *p = lds + off + (abase ^ (w << 4));
-        read_a_frags(p, p + 2 * 32 * ROW2, a); };
-    auto read_raw = [&](int off, u32x4_t (&rw)[TN]) { read_code_units(lds + off + rbase, lds + off + rbase + 1024, rw); };
+        read_a_frags<TM>(p, p + (TM / 2) * 32 * ROW2, a); };
+    auto read_raw = [&](int off, u32x4_t (&rw)[TN]) { read_code_units<TN>(lds + off + rbase, lds + off + rbase + (TN == 2 ? 1024 : 8), rw); };
     auto unpack_b = [&](const u32x4_t (&rw)[TN], int w, Frag (&b)[TN]) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
@@ -305,6 +332,9 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
         for (int b = 0; b < TN; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+    constexpr int TILES = TM * TN;
+    static_assert(TILES == 8 || TILES == 4, "the schedules below are written for 8 or 4 tiles per wave");
+    static_assert(TILES == 8 ? TN == 2 : true, "the 8-tile schedule pairs the halves of a tile row");
     auto mul_half = [&](int t, int h, const float (&f)[TN]) {
         const int i = t / TN, j = t % TN;
 #pragma unroll
@@ -318,9 +348,9 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
     auto round_plain = [&](const Frag (&a)[TM], const Frag (&b)[TN]) {
         mfma_all(a, b, acc);
 #pragma unroll
-        for (int t = 0; t < TM * TN; ++t) {
+        for (int t = 0; t < TILES; ++t) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, TILES == 8 ? 3 : 5, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
     };
@@ -349,7 +379,19 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
             // round 0
             read_a(off_c, 1, fa[1]);
             unpack_b(rw, 1, fb[1]);
-            if (v == 0 && RESCALE) {
+            if (v == 0 && RESCALE && TILES == 4) {
+                // the second half of the tiles into the units of this group, ahead of their first MFMA
+                mfma_tile(0, fa[0], fb[0]);
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(2, 0, rf);
+                mul_half(2, 1, rf);
+                mfma_tile(1, fa[0], fb[0]);
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(3, 0, rf);
+                mul_half(3, 1, rf);
+                mfma_tile(2, fa[0], fb[0]);
+                mfma_tile(3, fa[0], fb[0]);
+            } else if (v == 0 && RESCALE) {
                 // tiles 4..7 into the units of this group, ahead of their first MFMA (factor 1 in the first group)
                 mfma_tile(0, fa[0], fb[0]);
                 mul_half(4, 0, rf);
@@ -398,7 +440,7 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
             // stage t + 1 has landed (and, in the second half of a group, the factors to the next group); every wave
             // has read its last fragments of stage t
             wait_vmcnt<RL>();
-            if (v == 1 && RESCALE) read_wave_factors(lds + fcol, lds + fcol + 128, rf);   // the wave's own slot: no barrier needed
+            if (v == 1 && RESCALE) read_wave_factors<TN>(lds + fcol, lds + fcol + 128, rf);   // the wave's own slot: no barrier needed
             bare_barrier();
             // round 3 starts at once; the requests for stage t + 3 and the first reads of stage t + 1 go between its MFMAs
             mfma_tile(0, fa[1], fb[1]);
@@ -412,7 +454,17 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
             read_a(off_n, 0, fa[0]);
             __builtin_amdgcn_sched_barrier(0);
             mfma_tile(2, fa[1], fb[1]);
-            if (v == 1 && RESCALE) {
+            if (v == 1 && RESCALE && TILES == 4) {
+                // the first half of the tiles into the units of the next group, behind their last MFMA
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(0, 0, rf);
+                mul_half(0, 1, rf);
+                mfma_tile(3, fa[1], fb[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(1, 0, rf);
+                mul_half(1, 1, rf);
+                unpack_b(rw, 0, fb[0]);
+            } else if (v == 1 && RESCALE) {
                 // tiles 0..3 into the units of the next group, behind their last MFMA
                 __builtin_amdgcn_sched_barrier(0);
                 mul_half(0, 0, rf);
@@ -438,9 +490,9 @@ __global__ __launch_bounds__(64 * WM * WN, WN == 2 ? 2 : 1) void gemm_w4_rescale
                 __builtin_amdgcn_sched_barrier(0);
                 unpack_b(rw, 0, fb[0]);
 #pragma unroll
-                for (int q = 3; q < TM * TN; ++q) mfma_tile(q, fa[1], fb[1]);
+                for (int q = 3; q < TILES; ++q) mfma_tile(q, fa[1], fb[1]);
 #pragma unroll
-                for (int q = 3; q < TM * TN; ++q) {
+                for (int q = 3; q < TILES; ++q) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                     __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
                 }
@@ -720,11 +772,11 @@ struct Operands {       // what the pre-pass leaves in the workspace
     const uint32_t *flags;
 };
 
-template <int WN, int BITS>
+template <int WM, int WN, int TM, int TN, int BITS>
 hipError_t launch_tile(const void *wt, bool pc, const uint16_t *x, int64_t M, int64_t K, int64_t N, void *y, bool out_f32,
                        const RescalePlan &p, const Operands &o, hipStream_t stream) {
-    using G = Geo<WN, BITS>;
-    const int nbm = (int)((M + BM - 1) / BM), nbn = (int)((N + G::BN - 1) / G::BN);
+    using G = Geo<WM, WN, TM, TN, BITS>;
+    const int nbm = (int)((M + G::BM - 1) / G::BM), nbn = (int)((N + G::BN - 1) / G::BN);
     // XCD-aware tile order when the grid of tiles divides into regions of 8 patches of 4 x 8 tiles (see the kernel)
     int lg_xm = 2;
     while (lg_xm >= 0 && (nbm % (4 << lg_xm) != 0 || nbn % (8 * (8 >> lg_xm)) != 0)) --lg_xm;
@@ -737,9 +789,12 @@ hipError_t launch_tile(const void *wt, bool pc, const uint16_t *x, int64_t M, in
         return hipGetLastError();
     };
     if constexpr (BITS == 4) {
-        if (pc) return out_f32 ? go(&gemm_w4_rescale_kernel<WN, 4, true, true>) : go(&gemm_w4_rescale_kernel<WN, 4, false, true>);
+        if (pc)
+            return out_f32 ? go(&gemm_w4_rescale_kernel<WM, WN, TM, TN, 4, true, true>)
+                           : go(&gemm_w4_rescale_kernel<WM, WN, TM, TN, 4, false, true>);
     }
-    return out_f32 ? go(&gemm_w4_rescale_kernel<WN, BITS, true, false>) : go(&gemm_w4_rescale_kernel<WN, BITS, false, false>);
+    return out_f32 ? go(&gemm_w4_rescale_kernel<WM, WN, TM, TN, BITS, true, false>)
+                   : go(&gemm_w4_rescale_kernel<WM, WN, TM, TN, BITS, false, false>);
 }
 
 // Pre-pass, then the rescaling kernel; the caller launches the 128 x 128 exact kernel behind them for the column blocks
@@ -762,8 +817,9 @@ hipError_t launch_rescale(const void *wt, const uint32_t *sz, int szs, int64_t K
     const Operands o{a2, b2, rfac, flags};
     *flags_out = flags;
     *pairs_out = wn == 4;
-    return wn == 4 ? launch_tile<4, BITS>(wt, szs == 0, x, M, K, N, y, out_f32, p, o, stream)
-                   : launch_tile<2, BITS>(wt, szs == 0, x, M, K, N, y, out_f32, p, o, stream);
+    if (wn == 4) return launch_tile<2, 4, 4, 2, BITS>(wt, szs == 0, x, M, K, N, y, out_f32, p, o, stream);
+    // 256 x 128 tiles: eight waves of 128 x 32 (measured 0-8 % ahead of four waves of 128 x 64 and of eight of 64 x 64)
+    return launch_tile<2, 4, 4, 1, BITS>(wt, szs == 0, x, M, K, N, y, out_f32, p, o, stream);
 }
 
 }  // namespace
@@ -771,8 +827,8 @@ hipError_t launch_rescale(const void *wt, const uint32_t *sz, int szs, int64_t K
 // Measured against the 128 x 128 exact kernel: ahead wherever the tiled path is dispatched, also with a row tile that
 // is only half full (gate+up at 144 .. 240 rows: 93-96 against 101 us).
 bool w4_gemm_rescale_applies(int64_t M, int64_t N) {
-    const int64_t wgs = ((M + BM - 1) / BM) * ((N + 127) / 128);
-    return M > env_int("DMR_W4_RESCALE_MIN_M", BM / 2) && wgs <= 0x3FFFFFFF;
+    const int64_t wgs = ((M + kMaxBM - 1) / kMaxBM) * ((N + 127) / 128);
+    return M > env_int("DMR_W4_RESCALE_MIN_M", kMaxBM / 2) && wgs <= 0x3FFFFFFF;
 }
 
 // (The rules hold for 3-bit layers as well: same tiles, same pipeline.)
@@ -784,7 +840,7 @@ bool w4_gemm_rescale_applies(int64_t M, int64_t N) {
 int w4_gemm_rescale_wave_columns(int64_t M, int64_t N) {
     const int forced = env_int("DMR_W4_RESCALE_WN", 0);
     if (forced == 2 || forced == 4) return forced;
-    const int64_t narrow = ((M + BM - 1) / BM) * ((N + 127) / 128);
+    const int64_t narrow = ((M + kMaxBM - 1) / kMaxBM) * ((N + 127) / 128);
     return narrow > compute_units() ? 4 : 2;
 }
 
