@@ -247,7 +247,7 @@ dmr_status_t dmr_probe_empty_launch(int32_t blocks, int32_t threads, size_t lds_
 /*
  * Diagnostic, not part of a routed step: the name of the kernel class that serves M rows of a (K, N) layer
  * held in `format` ("w4_gemv", "w4_stream", "w4_panel", "w4_wide", "w4_skinny2", "w4_mid",
- * "w4_gemm256_rescale", "w4_gemm256x128_rescale", "w4_gemm128_exact", the "w3_*" and "bf16_*" counterparts; "none" for an unsupported shape).  Pure host arithmetic,
+ * "w4_gemm256_rescale", "w4_gemm256x128_rescale", "w4_gemm128_rescale", "w4_gemm128_exact", the "w3_*" and "bf16_*" counterparts; "none" for an unsupported shape).  Pure host arithmetic,
  * the same the forward calls use; a decode row too long for the M = 1 kernels' LDS budget is served by a
  * fallback of the same name class.  Lets a test or a profile state which kernel it covers.
  */

@@ -23,7 +23,7 @@ constexpr int64_t kSkinnyMaxM = 64;
 // Which INT4 kernel serves M rows of a (K, N) layer (measured crossovers, 256 CUs).  The workspace
 // query and the forward call both go through this.
 enum class W4Path { Gemv, Stream, Panel, Wide, Skinny2, Mid, Gemm, GemmRescale };
-constexpr int kTiledMinBlocks = 280;
+constexpr int kTiledMinBlocks = 140;
 W4Path w4_path(int64_t M, int64_t K, int64_t N) {
     if (M == 1) return W4Path::Gemv;
     if (M <= 16) {
@@ -35,8 +35,8 @@ W4Path w4_path(int64_t M, int64_t K, int64_t N) {
     const int64_t tiles = N / dmr::kTileRows;
     // wide layers already give the register-blocked streaming kernel 4 tiles per workgroup
     if (M <= kSkinnyMaxM) return tiles >= 1024 ? W4Path::Skinny2 : W4Path::Mid;
-    // the tiled GEMM wins from about 280 blocks of 128 x 128 on (measured: ahead at 288 on all three narrow layers,
-    // behind at 256)
+    // the tiled GEMM wins from about 140 output blocks of 128 x 128 on (measured: ahead at 144 and from there on, on
+    // 128-row tiles up to 256 blocks and on 256-row tiles beyond; behind at 128)
     const int64_t gemm_wgs = ((M + 127) / 128) * ((N + 127) / 128);
     if (M <= 128 || gemm_wgs < dmr::env_int("DMR_W4_GEMM_MIN_WGS", kTiledMinBlocks)) return W4Path::Mid;
     return dmr::w4_gemm_rescale_applies(M, N) ? W4Path::GemmRescale : W4Path::Gemm;
@@ -566,6 +566,7 @@ const char *dmr_qlinear_kernel_path(dmr_format_t format, int64_t M, int64_t K, i
                 case W3Path::Wide: return "w3_wide";
                 case W3Path::Mid: return "w3_mid";
                 case W3Path::GemmRescale:
+                    if (dmr::w4_gemm_rescale_tile_rows(M, N) == 128) return "w3_gemm128_rescale";
                     return dmr::w4_gemm_rescale_wave_columns(M, N) == 4 ? "w3_gemm256_rescale" : "w3_gemm256x128_rescale";
                 default: return "w3_gemm128_exact";
             }
@@ -579,6 +580,7 @@ const char *dmr_qlinear_kernel_path(dmr_format_t format, int64_t M, int64_t K, i
                 case W4Path::Skinny2: return "w4_skinny2";
                 case W4Path::Mid: return "w4_mid";
                 case W4Path::GemmRescale:
+                    if (dmr::w4_gemm_rescale_tile_rows(M, N) == 128) return "w4_gemm128_rescale";
                     return dmr::w4_gemm_rescale_wave_columns(M, N) == 4 ? "w4_gemm256_rescale" : "w4_gemm256x128_rescale";
                 default: return "w4_gemm128_exact";
             }

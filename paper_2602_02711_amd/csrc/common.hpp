@@ -205,7 +205,8 @@ hipError_t launch_w4_gemm_flagged(const LayerView &L, const uint16_t *x, int64_t
 // a pre-pass writes the zero-point operands, the rescale factors and per-column-block flags into `ws`
 // (w4_gemm_rescale_workspace_bytes), and the 128 x 128 exact kernel takes the column blocks it flags.
 bool w4_gemm_rescale_applies(int64_t M, int64_t N);
-int w4_gemm_rescale_wave_columns(int64_t M, int64_t N);   // 4: 256 x 256 tiles on 8 waves; 2: 256 x 128 on 4
+int w4_gemm_rescale_tile_rows(int64_t M, int64_t N);      // 128: 128 x 128 tiles (then the next function does not apply); 256
+int w4_gemm_rescale_wave_columns(int64_t M, int64_t N);   // 4: 256 x 256 tiles; 2: 256 x 128
 size_t w4_gemm_rescale_workspace_bytes(int64_t M, int64_t K, int64_t N);
 hipError_t launch_w4_gemm_rescale(const LayerView &L, const uint16_t *x, int64_t M, void *y, bool out_f32, void *ws,
                                   hipStream_t stream);

@@ -22,9 +22,10 @@
 // of 32 rows and leaves a flag; a workgroup whose columns are flagged returns at once and the 128 x 128 exact
 // kernel, launched behind this one with the same flags, computes those columns instead.
 //
-// Shape of the work.  Eight wavefronts (2 x 4), two per SIMD, in two instantiations: a 256 x 256 tile with a 128 x 64
-// patch per wave (4 x 2 tiles of v_mfma_f32_32x32x16_bf16), or, for grids that one round of them covers, a 256 x 128
-// tile with 128 x 32 per wave (4 x 1).  (The kernel is written for WM x WN waves of TM x TN tiles; 256 x 128 on four
+// Shape of the work.  Eight wavefronts (2 x 4), two per SIMD, in three instantiations: a 256 x 256 tile with a 128 x 64
+// patch per wave (4 x 2 tiles of v_mfma_f32_32x32x16_bf16), for grids that one round of them covers a 256 x 128
+// tile with 128 x 32 per wave (4 x 1), and for outputs of at most 256 blocks of 128 x 128 a 128 x 128 tile with 64 x 32
+// per wave (2 x 1; 82 registers and 74 KiB of LDS, so two workgroups share a CU).  (The kernel is written for WM x WN waves of TM x TN tiles; 256 x 128 on four
 // waves of 128 x 64 and on eight of 64 x 64 were measured 0-8 % behind and are not instantiated.)
 //
 // The weight operand never sits in LDS unpacked.  The codes of a weight row are private to the waves that own its
@@ -218,7 +219,7 @@ __device__ __forceinline__ void read_wave_factors(const uint8_t *__restrict__ p,
 // free), 1 in the slot behind the last group.  a2 / b2: bf16 [M][KP] / [N][KP].  flags: one word per 32 columns,
 // nonzero = those columns do not qualify; a tile with a flagged part is left to the other kernel as a whole.
 template <int WM, int WN, int TM, int TN, int BITS, bool OUT_F32, bool PC>
-__global__ __launch_bounds__(64 * WM * WN, 512 / (64 * WM * WN) > 1 ? 2 : 1) void gemm_w4_rescale_kernel(
+__global__ __launch_bounds__(64 * WM * WN, TM * TN <= 2 ? 2 : 1) void gemm_w4_rescale_kernel(
     const void *__restrict__ wt, const float *__restrict__ rfac, const uint16_t *__restrict__ x, const uint16_t *__restrict__ a2,
     const uint16_t *__restrict__ b2, const uint32_t *__restrict__ flags, void *__restrict__ y, int64_t M, int64_t K, int64_t N,
     int KP, int nbn, int lg_xm) {
@@ -333,7 +334,7 @@ __global__ __launch_bounds__(64 * WM * WN, 512 / (64 * WM * WN) > 1 ? 2 : 1) voi
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
     constexpr int TILES = TM * TN;
-    static_assert(TILES == 8 || TILES == 4, "the schedules below are written for 8 or 4 tiles per wave");
+    static_assert(TILES == 8 || TILES == 4 || TILES == 2, "the schedules below are written for 8, 4 or 2 tiles per wave");
     static_assert(TILES == 8 ? TN == 2 : true, "the 8-tile schedule pairs the halves of a tile row");
     auto mul_half = [&](int t, int h, const float (&f)[TN]) {
         const int i = t / TN, j = t % TN;
@@ -350,7 +351,7 @@ __global__ __launch_bounds__(64 * WM * WN, 512 / (64 * WM * WN) > 1 ? 2 : 1) voi
 #pragma unroll
         for (int t = 0; t < TILES; ++t) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, TILES == 8 ? 3 : 5, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, TILES == 8 ? 3 : (TILES == 4 ? 5 : 9), 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
     };
@@ -379,7 +380,14 @@ __global__ __launch_bounds__(64 * WM * WN, 512 / (64 * WM * WN) > 1 ? 2 : 1) voi
             // round 0
             read_a(off_c, 1, fa[1]);
             unpack_b(rw, 1, fb[1]);
-            if (v == 0 && RESCALE && TILES == 4) {
+            if (v == 0 && RESCALE && TILES == 2) {
+                // the second tile into the units of this group, ahead of its first MFMA
+                mfma_tile(0, fa[0], fb[0]);
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(1, 0, rf);
+                mul_half(1, 1, rf);
+                mfma_tile(1, fa[0], fb[0]);
+            } else if (v == 0 && RESCALE && TILES == 4) {
                 // the second half of the tiles into the units of this group, ahead of their first MFMA
                 mfma_tile(0, fa[0], fb[0]);
                 __builtin_amdgcn_sched_barrier(0);
@@ -453,8 +461,14 @@ __global__ __launch_bounds__(64 * WM * WN, 512 / (64 * WM * WN) > 1 ? 2 : 1) voi
             read_raw(off_n, rw);
             read_a(off_n, 0, fa[0]);
             __builtin_amdgcn_sched_barrier(0);
-            mfma_tile(2, fa[1], fb[1]);
-            if (v == 1 && RESCALE && TILES == 4) {
+            if constexpr (TILES > 2) mfma_tile(2, fa[1], fb[1]);
+            if (v == 1 && RESCALE && TILES == 2) {
+                // the first tile into the units of the next group, behind its last MFMA
+                __builtin_amdgcn_sched_barrier(0);
+                mul_half(0, 0, rf);
+                mul_half(0, 1, rf);
+                unpack_b(rw, 0, fb[0]);
+            } else if (v == 1 && RESCALE && TILES == 4) {
                 // the first half of the tiles into the units of the next group, behind their last MFMA
                 __builtin_amdgcn_sched_barrier(0);
                 mul_half(0, 0, rf);
@@ -813,11 +827,12 @@ hipError_t launch_rescale(const void *wt, const uint32_t *sz, int szs, int64_t K
                        rfac, flags, M, K, N, p.KP, nblocks);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int wn = w4_gemm_rescale_wave_columns(M, N);
+    const int wn = w4_gemm_rescale_tile_rows(M, N) == 128 ? 2 : w4_gemm_rescale_wave_columns(M, N);
     const Operands o{a2, b2, rfac, flags};
     *flags_out = flags;
     *pairs_out = wn == 4;
     if (wn == 4) return launch_tile<2, 4, 4, 2, BITS>(wt, szs == 0, x, M, K, N, y, out_f32, p, o, stream);
+    if (w4_gemm_rescale_tile_rows(M, N) == 128) return launch_tile<2, 4, 2, 1, BITS>(wt, szs == 0, x, M, K, N, y, out_f32, p, o, stream);
     // 256 x 128 tiles: eight waves of 128 x 32 (measured 0-8 % ahead of four waves of 128 x 64 and of eight of 64 x 64)
     return launch_tile<2, 4, 4, 1, BITS>(wt, szs == 0, x, M, K, N, y, out_f32, p, o, stream);
 }
@@ -842,6 +857,17 @@ int w4_gemm_rescale_wave_columns(int64_t M, int64_t N) {
     if (forced == 2 || forced == 4) return forced;
     const int64_t narrow = ((M + kMaxBM - 1) / kMaxBM) * ((N + 127) / 128);
     return narrow > compute_units() ? 4 : 2;
+}
+
+// Rows of the tile: 128 while one round of 128 x 128 tiles (eight waves of 64 x 32, up to two workgroups per CU) covers
+// the output; measured there against the rollout-batch kernel and the 256-row tiles: attn-out at 768 / 1024 rows 48 / 52
+// against 55 / 64 us, qkv at 384 / 512 rows 49 / 50 against 55 / 55, down at 768 / 1024 rows 146 / 152 against 173 / 191;
+// behind both from 288 blocks on.
+int w4_gemm_rescale_tile_rows(int64_t M, int64_t N) {
+    const int forced = env_int("DMR_W4_RESCALE_BM", 0);
+    if (forced == 128 || forced == 256) return forced;
+    const int64_t blocks = ((M + 127) / 128) * ((N + 127) / 128);
+    return blocks <= compute_units() ? 128 : 256;
 }
 
 size_t w4_gemm_rescale_workspace_bytes(int64_t M, int64_t K, int64_t N) { return plan_rescale(M, K, N).total; }

@@ -192,6 +192,9 @@ def test_w3_size_query_and_kernel_paths(lib):
     assert path(binding.DMR_FMT_W4_G128, 2048, 4096, 4096) == b"w4_gemm256x128_rescale"     # 128 tiles of 256 x 256 only
     assert path(binding.DMR_FMT_W4_PER_CHANNEL, 6400, 512, 1024) == b"w4_gemm256x128_rescale"
     assert path(binding.DMR_FMT_W4_G128, 200, 256, 19200) == b"w4_gemm256x128_rescale"      # a half-empty row tile
+    assert path(binding.DMR_FMT_W4_G128, 1024, 4096, 4096) == b"w4_gemm128_rescale"         # 256 blocks of 128 x 128: one round
+    assert path(binding.DMR_FMT_W3_G128, 768, 14336, 4096) == b"w3_gemm128_rescale"
+    assert path(binding.DMR_FMT_W4_G128, 512, 4096, 4096) == b"w4_mid"                      # 128 blocks: too few
     # the 256-row kernels keep their zero-point operands, rescale factors and flags in the workspace
     G_n, KP = 4096 // 128, 192
     need = lib.dmr_qlinear_workspace_bytes(8192, 4096, 28672)

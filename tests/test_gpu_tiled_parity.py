@@ -105,6 +105,8 @@ def test_bf16_tiled_gemms_small_integers_exact():
     (256, 19200, 200, "w4_gemm256x128_rescale"),     # fewer than 256 rows on a very wide layer: a half-empty row tile
     (128, 112, 40000, "w4_gemm256x128_rescale"),     # one column tile, not even full (7 row tiles of 16), 157 row blocks
     (256, 272, 45100, "w4_gemm256_rescale"),         # two column tiles of 256, the second with 16 columns; ragged rows
+    (1152, 2064, 1500, "w4_gemm128_rescale"),        # 12 x 17 tiles of 128 x 128 (at most 256 of them: one round), ragged both ways
+    (128, 4096, 520, "w4_gemm128_rescale"),          # 5 x 32 tiles, a single group, 8 rows in the last row tile
 ])
 def test_int4_tiled_gemm_full_output(K, N, M, path):
     assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W4_G128, M, K, N) == path
@@ -147,7 +149,8 @@ def test_int4_one_hot_rows_through_the_tiled_gemms():
     # rescaling kernels: the weight comes out as s_last (prod of scale ratios) (16 + q) - s (16 + z), a handful of fp32
     # roundings from s (q - z); each output is checked against the exact weight on its own, relative to the largest
     # term of that difference
-    for K, N, path in [(2304, 2304, "w4_gemm256x128_rescale"), (3584, 3840, "w4_gemm256_rescale")]:
+    for K, N, path in [(2304, 2304, "w4_gemm256x128_rescale"), (3584, 3840, "w4_gemm256_rescale"),
+                       (1536, 2048, "w4_gemm128_rescale")]:
         M = K
         assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W4_G128, M, K, N) == path
         _, words, s, z = quantized(8400 + K, N, K)
@@ -196,9 +199,10 @@ def _scales_with(s, rows_groups, bits):
     return out
 
 
-@pytest.mark.parametrize("K,N,M,path", [(1152, 2192, 2200, "w4_gemm256x128_rescale"), (1152, 3856, 3500, "w4_gemm256_rescale")])
+@pytest.mark.parametrize("K,N,M,path", [(1152, 2192, 2200, "w4_gemm256x128_rescale"), (1152, 3856, 3500, "w4_gemm256_rescale"),
+                                        (1152, 2064, 1500, "w4_gemm128_rescale")])
 def test_int4_tiled_gemm_scales_that_cannot_be_rescaled(K, N, M, path):
-    # A zero scale, a subnormal one and a row whose scales span 2^41: the running rescale of the 256-row kernels
+    # A zero scale, a subnormal one and a row whose scales span 2^41: the running rescale of the tiled kernels
     # cannot carry them, so their column blocks must come from the 128 x 128 kernel behind it, all others from the
     # fast kernel, and the output must be the oracle's everywhere.
     assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W4_G128, M, K, N) == path
@@ -220,7 +224,8 @@ def test_int4_tiled_gemm_scales_that_cannot_be_rescaled(K, N, M, path):
     assert err <= 1e-4
 
 
-@pytest.mark.parametrize("K,N,M,path", [(256, 3840, 3584, "w4_gemm256_rescale"), (1024, 1024, 6400, "w4_gemm256x128_rescale")])
+@pytest.mark.parametrize("K,N,M,path", [(256, 3840, 3584, "w4_gemm256_rescale"), (1024, 1024, 6400, "w4_gemm256x128_rescale"),
+                                        (512, 2064, 1500, "w4_gemm128_rescale")])
 def test_per_channel_layer_through_the_tiled_gemms(K, N, M, path):
     assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W4_PER_CHANNEL, M, K, N) == path
     rng = np.random.default_rng(8700 + K + M)
@@ -291,6 +296,7 @@ def test_prefill_config_cells_sampled(idx, M):
     (256, 3840, 3584, "w3_gemm256_rescale"),
     (1152, 3856, 3500, "w3_gemm256_rescale"),
     (256, 19200, 200, "w3_gemm256x128_rescale"),     # fewer than 256 rows on a very wide layer: a half-empty row tile
+    (1152, 2064, 1500, "w3_gemm128_rescale"),        # 12 x 17 tiles of 128 x 128, ragged both ways
 ])
 def test_w3_prefill_size(K, N, M, path):
     assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W3_G128, M, K, N) == path
