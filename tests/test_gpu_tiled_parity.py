@@ -242,6 +242,46 @@ def test_per_channel_layer_through_the_tiled_gemms(K, N, M, path):
     assert err <= 1e-4
 
 
+@pytest.mark.parametrize("K,N,M,path", [(512, 2064, 1500, "w4_gemm128_rescale"), (512, 2192, 2200, "w4_gemm256x128_rescale"),
+                                        (512, 3856, 3500, "w4_gemm256_rescale")])
+def test_int4_tiled_gemm_same_bits_every_time(K, N, M, path):
+    # no atomics and a fixed order of additions: the output must not depend on the run, on what the workspace held
+    # before the call, or on whether the launches are replayed from a graph
+    assert dmr.dmr_qlinear_kernel_path(dmr.DMR_FMT_W4_G128, M, K, N) == path
+    _, words, s, z = quantized(8800 + K + N, N, K)
+    layer = dmr.dmr_qlinear_create(u32_dev(words), bf16_dev(s), bf16_dev(z), G)
+    xd = bf16_dev(synth.activations_bf16(8801 + K + M, M, K))
+    need = dmr.dmr_qlinear_workspace_bytes(M, K, N)
+    torch.cuda.synchronize()
+    first = None
+    for fill in (0x00, 0xFF, 0x7F, 0xAA, 0x00):
+        ws = torch.full((need,), fill, dtype=torch.uint8, device=DEV)
+        y = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV)
+        dmr.dmr_qlinear_forward(layer, xd, out=y, workspace=ws)
+        torch.cuda.synchronize()
+        assert not bool(torch.isnan(y).any()) and not bool((y == 7.0).any())     # every output written, no poison
+        if first is None:
+            first = y.clone()
+        assert torch.equal(y, first), hex(fill)
+    stream = torch.cuda.Stream()
+    ws = torch.empty((need,), dtype=torch.uint8, device=DEV)
+    y = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        dmr.dmr_qlinear_forward(layer, xd, out=y, workspace=ws)
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for _ in range(3):
+                dmr.dmr_qlinear_forward(layer, xd, out=y, workspace=ws)
+        for _ in range(4):
+            y.fill_(7.0)
+            graph.replay()
+            stream.synchronize()
+            assert torch.equal(y, first)
+    torch.cuda.synchronize()
+
+
 def test_int4_tiled_gemm_refuses_a_short_workspace():
     K, N, M = 256, 2192, 2200
     need = dmr.dmr_qlinear_workspace_bytes(M, K, N)
