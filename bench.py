@@ -348,6 +348,7 @@ def layer_sweep(args, dmr, synth, torch, dev):
     stream = torch.cuda.Stream()
 
     def timeit(fn, iters):
+        torch.cuda.synchronize()          # the inputs were prepared on the default stream
         with torch.cuda.stream(stream):
             for i in range(3):
                 fn(i)
@@ -421,6 +422,7 @@ def w3_sweep(args, dmr, synth, torch, dev):
     stream = torch.cuda.Stream()
 
     def timeit(fn, iters):
+        torch.cuda.synchronize()          # the inputs were prepared on the default stream
         with torch.cuda.stream(stream):
             for i in range(3):
                 fn(i)
@@ -500,6 +502,7 @@ def launch_floor(args, dmr, synth, torch, dev):
     sink = torch.empty(4096 * 256, dtype=torch.int32, device=dev)
 
     def graph_us(fn):
+        torch.cuda.synchronize()          # the inputs were prepared on the default stream
         with torch.cuda.stream(stream):
             for i in range(5):
                 fn(i)
