@@ -31,6 +31,7 @@ def test_graph_replays_match_eager(K, N, M):
         eager.append((dmr.dmr_qlinear_forward(layer, xi, out_dtype=torch.float32).clone(),
                       dmr.dmr_qlinear_bf16_forward(wb, xi, out_dtype=torch.float32).clone()))
     stream = torch.cuda.Stream()
+    torch.cuda.synchronize()        # what ran on the default stream so far shares buffers with what follows
     with torch.cuda.stream(stream):
         dmr.dmr_qlinear_forward(layer, x, out=y4, workspace=ws4)            # warm-up outside the capture
         dmr.dmr_qlinear_bf16_forward(wb, x, out=y16, workspace=ws16)
@@ -65,6 +66,7 @@ def test_graph_replays_fused_chain_link():
     want = dmr.dmr_qlinear_forward_fused(layer, dmr.DMR_PRO_RMSNORM, x, gamma=gamma, eps=1e-6, residual=res,
                                          workspace=ws).clone()
     stream = torch.cuda.Stream()
+    torch.cuda.synchronize()        # what ran on the default stream so far shares buffers with what follows
     with torch.cuda.stream(stream):
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=stream):
